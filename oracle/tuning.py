@@ -1,0 +1,180 @@
+"""Host-side definitions around the workgroup-size sweep (TEST INFRASTRUCTURE ONLY).
+
+Written from the paper's definitions, in plain Python, one function per definition:
+legality (Section 3.1, Eq. 1-2), oracle workgroup size (Section 4.1, Eq. 3), the evaluation
+metrics `performance` and `speedup` (Section 7), the fallback handlers of Algorithm 1 and a
+nearest-neighbour classifier standing in for `classify(f(s))`.
+
+A workgroup size is a pair (w_r, w_c).  Eq. 1's comparison `w < W_max(s)` is read on the
+number of work-items, non-strictly: w_r * w_c <= W_max(s).
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, Iterable, List, Optional, Sequence, Tuple
+
+WG = Tuple[int, int]
+
+
+# ---- enumeration (Section 5) ------------------------------------------------------------
+
+def enumerate_sizes(mode: str, max_threads: int) -> List[WG]:
+    """All (w_r, w_c) with w_r * w_c <= max_threads, both drawn from
+    "pow2": {1, 2, 4, ...};  "even": {2, 4, ..., 64} (multiples of two)."""
+    if mode == "pow2":
+        vals = [1 << k for k in range(0, 32) if (1 << k) <= max_threads]
+    elif mode == "even":
+        vals = [2 * k for k in range(1, 33)]
+    else:
+        raise ValueError(mode)
+    out = []
+    for r in vals:
+        for c in vals:
+            if r * c <= max_threads:
+                out.append((r, c))
+    return out
+
+
+# ---- legality (Section 3.1) ---------------------------------------------------------------
+
+def tile_elements(w: WG, halo: Sequence[int]) -> int:
+    """Elements of the local-memory tile of Section 2: the workgroup plus its perimeter
+    border region, (w_r + north + south) * (w_c + east + west)."""
+    n, s, e, we = halo
+    return (w[0] + n + s) * (w[1] + e + we)
+
+
+def is_legal(w: WG, w_max: int, refused: Iterable[WG] = ()) -> bool:
+    """Eq. 1: w in W_legal(s) iff it satisfies the size constraint and is not refused."""
+    wr, wc = w
+    if wr < 1 or wc < 1:
+        return False
+    if wr * wc > w_max:
+        return False
+    return (wr, wc) not in set(refused)
+
+
+def legal_set(candidates: Iterable[WG], w_max: int, refused: Iterable[WG] = ()) -> List[WG]:
+    ref = set(refused)
+    return [w for w in candidates if is_legal(w, w_max, ref)]
+
+
+def safe_set(legal_sets: Sequence[Iterable[WG]]) -> List[WG]:
+    """Eq. 2: sizes legal for every scenario."""
+    sets = [set(s) for s in legal_sets]
+    if not sets:
+        return []
+    common = set.intersection(*sets)
+    return sorted(common)
+
+
+# ---- sweep reductions (Eq. 3 and Section 7 metrics) ---------------------------------------
+
+def oracle_size(sizes: Sequence[WG], mean_ms: Sequence[float], ok: Sequence[bool]) -> int:
+    """Eq. 3: index of the legal size with the lowest mean runtime.  Ties: fewer work-items,
+    then smaller w_r, then first in the list.  -1 when nothing is legal."""
+    best = -1
+    for i, (w, t, good) in enumerate(zip(sizes, mean_ms, ok)):
+        if not good or t is None or math.isnan(t):
+            continue
+        if best < 0:
+            best = i
+            continue
+        tb, wb = mean_ms[best], sizes[best]
+        key_i = (t, w[0] * w[1], w[0])
+        key_b = (tb, wb[0] * wb[1], wb[0])
+        if key_i < key_b:
+            best = i
+    return best
+
+
+def performance(mean_ms: Sequence[float], ok: Sequence[bool], best: int) -> List[float]:
+    """p(s, w) = t(s, Omega(s)) / t(s, w), in (0, 1]; NaN for refused sizes."""
+    out = []
+    for t, good in zip(mean_ms, ok):
+        out.append(mean_ms[best] / t if (good and best >= 0) else float("nan"))
+    return out
+
+
+def speedup(t_fixed: float, t_w: float) -> float:
+    """Speedup of size w over a fixed size: t(s, fixed) / t(s, w)."""
+    return t_fixed / t_w
+
+
+def sweep_reduce(sizes: Sequence[WG], mean_ms: Sequence[float], ok: Sequence[bool],
+                 fixed: WG, fixed_ms: Optional[float] = None) -> Dict[str, object]:
+    """What a sweep reports: the oracle size, its speedup over the fixed size (NaN if the
+    fixed size was refused) and the oracle/worst ratio."""
+    best = oracle_size(sizes, mean_ms, ok)
+    t_fixed = fixed_ms
+    if t_fixed is None:
+        for w, t, good in zip(sizes, mean_ms, ok):
+            if tuple(w) == tuple(fixed) and good:
+                t_fixed = t
+    res = {"best_index": best, "speedup_over_fixed": float("nan"), "best_over_worst": float("nan")}
+    if best >= 0:
+        if t_fixed is not None and not math.isnan(t_fixed):
+            res["speedup_over_fixed"] = speedup(t_fixed, mean_ms[best])
+        worst = max(t for t, good in zip(mean_ms, ok) if good)
+        res["best_over_worst"] = worst / mean_ms[best]
+    return res
+
+
+def baseline_size(perf_by_scenario: Sequence[Dict[WG, float]], safe: Sequence[WG]) -> Optional[WG]:
+    """Algorithm 1, Baseline handler: the safe size with the highest geometric mean of
+    p(s, w) over the training scenarios."""
+    best_w, best_g = None, -1.0
+    for w in safe:
+        logs = [math.log(p[w]) for p in perf_by_scenario]
+        g = math.exp(sum(logs) / len(logs))
+        if g > best_g:
+            best_w, best_g = w, g
+    return best_w
+
+
+# ---- Algorithm 1: classification with the NearestNeighbour fallback ------------------------
+
+def nearest_legal(w: WG, candidates: Sequence[WG]) -> Optional[WG]:
+    """The candidate with the lowest Euclidean distance to w (first one wins ties, as the
+    strict `d < d_min` of Algorithm 1 implies)."""
+    d_min, closest = math.inf, None
+    for c in candidates:
+        d = math.sqrt((c[0] - w[0]) ** 2 + (c[1] - w[1]) ** 2)
+        if d < d_min:
+            d_min, closest = d, c
+    return closest
+
+
+def predict_nearest_neighbour(predicted: WG, candidates: Sequence[WG], w_max: int,
+                              refused: Iterable[WG] = ()) -> Optional[WG]:
+    """Algorithm 1, NearestNeighbour: keep the classifier's size if legal, else move to the
+    closest size that satisfies the constraints and is not known to be refused."""
+    ref = set(refused)
+    w = tuple(predicted)
+    pool = [c for c in candidates if c[0] >= 1 and c[1] >= 1 and c[0] * c[1] <= w_max and c not in ref]
+    while not is_legal(w, w_max, ref):
+        if not pool:
+            return None
+        w = nearest_legal(w, pool)
+    return w
+
+
+def classify_1nn(train_x: Sequence[Sequence[float]], train_w: Sequence[WG],
+                 x: Sequence[float]) -> WG:
+    """classify(f(s)): label of the nearest training scenario.  Each feature is scaled by its
+    range over the training set (a constant feature carries no distance); Euclidean metric;
+    the first nearest wins ties."""
+    nf = len(x)
+    lo = [min(row[j] for row in train_x) for j in range(nf)]
+    hi = [max(row[j] for row in train_x) for j in range(nf)]
+    best, d_best = -1, math.inf
+    for i, row in enumerate(train_x):
+        d = 0.0
+        for j in range(nf):
+            span = hi[j] - lo[j]
+            if span > 0.0:
+                z = (row[j] - x[j]) / span
+                d += z * z
+        if d < d_best:
+            best, d_best = i, d
+    return tuple(train_w[best])

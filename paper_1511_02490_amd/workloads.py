@@ -1,0 +1,165 @@
+"""Seeded synthetic workloads for the 2D stencil skeleton.
+
+This module only *makes data*: grids, weight tables and workgroup-size lists that
+are handed, unchanged, to whichever implementation is being run.  It holds none of
+the stencil arithmetic (no border resolution, no customising function) and imports
+neither the HIP binding nor the CPU oracle, so both can be fed from it without
+sharing any of the method's code.
+
+The paper (Section 5) measures synthetic stencils and four reference applications
+(Gaussian blur, Game of Life, heat equation, Canny) on 512^2..4096^2 matrices of
+int / float / double, and prints neither the inputs nor the customising functions.
+The five workloads below stand in for them: same kinds of kernels (Table 2), same
+matrix sizes (plus one 8192^2 grid that does not fit the last-level cache), values
+drawn from a seeded generator.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Tuple
+
+import numpy as np
+
+BASE_SEED = 151102490
+
+# Kernel names (strings on purpose: each side maps them to its own constants).
+WEIGHTED_SUM = "weighted_sum"
+LIFE = "life"
+HEAT = "heat"
+SINCOS = "sincos"
+
+
+@dataclass
+class Workload:
+    """One scenario: a grid, a stencil shape, a border mode and a customising function."""
+
+    name: str
+    rows: int
+    cols: int
+    dtype: str                      # "f32" or "u8"
+    halo: Tuple[int, int, int, int]  # (north, south, east, west)
+    border: str                     # "clamp" | "wrap" | "constant"
+    pad: float                      # padding value for "constant"
+    kernel: str
+    iters: int
+    seed: int
+    sweep: str                      # "list" | "pow2" | "even"
+    weights: np.ndarray | None = None   # (N+S+1, E+W+1) float32, row-major
+    scalars: Tuple[float, ...] = ()
+    sweep_list: List[Tuple[int, int]] = field(default_factory=list)
+
+    @property
+    def cells(self) -> int:
+        return self.rows * self.cols
+
+    @property
+    def bytes_per_cell_update(self) -> int:
+        """One read and one write of a cell per application of the stencil."""
+        return 2 * (4 if self.dtype == "f32" else 1)
+
+    def grid(self) -> np.ndarray:
+        return make_grid(self)
+
+    def wg_sizes(self, max_threads: int = 1024) -> List[Tuple[int, int]]:
+        if self.sweep == "list":
+            return list(self.sweep_list)
+        return enumerate_wg(self.sweep, max_threads)
+
+
+def enumerate_wg(mode: str, max_threads: int = 1024) -> List[Tuple[int, int]]:
+    """Workgroup-size lists swept per scenario (Section 5: every (w_r, w_c) up to the
+    maximum workgroup size).
+
+    "pow2": w_r, w_c powers of two, w_r*w_c <= max_threads  (66 pairs for 1024).
+    "even": w_r, w_c in {2,4,..,64},  w_r*w_c <= max_threads (590 pairs for 1024).
+    """
+    if mode == "pow2":
+        vals = []
+        v = 1
+        while v <= max_threads:
+            vals.append(v)
+            v *= 2
+    elif mode == "even":
+        vals = list(range(2, 65, 2))
+    else:
+        raise ValueError(mode)
+    return [(r, c) for r in vals for c in vals if r * c <= max_threads]
+
+
+def gaussian_weights(radius: int, sigma: float) -> np.ndarray:
+    """(2*radius+1)^2 table: outer product of exp(-k^2 / (2 sigma^2)), k = -radius..radius,
+    normalised to sum 1 in float64, then rounded once to float32.  That float32 table is
+    the data both implementations receive."""
+    k = np.arange(-radius, radius + 1, dtype=np.float64)
+    g = np.exp(-(k * k) / (2.0 * sigma * sigma))
+    w = np.outer(g, g)
+    w /= w.sum()
+    return np.ascontiguousarray(w.astype(np.float32))
+
+
+def binomial3_weights() -> np.ndarray:
+    """[1,2,1]^T [1,2,1] / 16, exact in float32."""
+    b = np.array([1.0, 2.0, 1.0])
+    return np.ascontiguousarray((np.outer(b, b) / 16.0).astype(np.float32))
+
+
+def make_grid(w: "Workload") -> np.ndarray:
+    rng = np.random.default_rng(w.seed)
+    shape = (w.rows, w.cols)
+    if w.kernel == LIFE:
+        return np.ascontiguousarray((rng.random(shape, dtype=np.float32) < 0.3).astype(np.uint8))
+    if w.kernel == HEAT:
+        u = rng.random(shape, dtype=np.float32) * np.float32(100.0)
+        side = min(32, w.rows, w.cols)
+        n_sq = 64
+        tops = rng.integers(0, w.rows - side + 1, size=n_sq)
+        lefts = rng.integers(0, w.cols - side + 1, size=n_sq)
+        for t, l in zip(tops, lefts):           # overlaps allowed; written after the fill
+            u[t:t + side, l:l + side] = np.float32(1000.0)
+        return np.ascontiguousarray(u)
+    if w.kernel == SINCOS:
+        return np.ascontiguousarray(rng.random(shape, dtype=np.float32) * np.float32(2.0) - np.float32(1.0))
+    return np.ascontiguousarray(rng.random(shape, dtype=np.float32))
+
+
+def sincos_weights(halo: Tuple[int, int, int, int], seed: int) -> np.ndarray:
+    n, s, e, w = halo
+    rng = np.random.default_rng(seed)
+    return np.ascontiguousarray(rng.random((n + s + 1, e + w + 1), dtype=np.float32))
+
+
+def config(index: int, rows: int | None = None, cols: int | None = None,
+           iters: int | None = None) -> Workload:
+    """Workload C1..C5 (index 0..4).  rows/cols/iters override the full size, which is how
+    the parity tests get a small grid of the same recipe."""
+    seed = BASE_SEED + index
+    if index == 0:
+        wl = Workload("C1 gaussian3x3 256x256 f32 clamp", 256, 256, "f32", (1, 1, 1, 1), "clamp", 0.0,
+                      WEIGHTED_SUM, 1, seed, "list", weights=binomial3_weights(),
+                      sweep_list=[(8, 8), (16, 16), (32, 8), (64, 4), (8, 32), (4, 64)])
+    elif index == 1:
+        wl = Workload("C2 gaussian5x5 2048x2048 f32 clamp", 2048, 2048, "f32", (2, 2, 2, 2), "clamp", 0.0,
+                      WEIGHTED_SUM, 1, seed, "pow2", weights=gaussian_weights(2, 1.0))
+    elif index == 2:
+        wl = Workload("C3 life 4096x4096 u8 wrap x100", 4096, 4096, "u8", (1, 1, 1, 1), "wrap", 0.0,
+                      LIFE, 100, seed, "pow2")
+    elif index == 3:
+        wl = Workload("C4 heat 4096x4096 f32 wrap x1000", 4096, 4096, "f32", (1, 1, 1, 1), "wrap", 0.0,
+                      HEAT, 1000, seed, "pow2", scalars=(0.2,))
+    elif index == 4:
+        halo = (1, 5, 3, 0)
+        wl = Workload("C5 sincos N1S5E3W0 8192x8192 f32 const0", 8192, 8192, "f32", halo, "constant", 0.0,
+                      SINCOS, 1, seed, "even", weights=sincos_weights(halo, seed + 1000))
+    else:
+        raise ValueError("config index must be 0..4")
+    if rows is not None:
+        wl.rows = rows
+    if cols is not None:
+        wl.cols = cols
+    if iters is not None:
+        wl.iters = iters
+    return wl
+
+
+def all_configs() -> Dict[str, Workload]:
+    return {"C%d" % (i + 1): config(i) for i in range(5)}
