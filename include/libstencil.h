@@ -1,0 +1,196 @@
+/*
+ * libstencil - 2D stencil skeleton with a tunable workgroup size, for AMD MI355X (gfx950).
+ *
+ * The operation is the stencil pattern of Section 2 of "Autotuning OpenCL Workgroup Size
+ * for Stencil Patterns" (arXiv 1511.02490): a customising function is applied to every
+ * element of a 2D matrix; it sees the element and a rectangular border region of
+ * `north`, `south`, `east`, `west` cells around it; neighbours outside the matrix are
+ * substituted by the nearest in-matrix cell or by a padding constant (periodic wrap is
+ * provided in addition).  The matrix is decomposed into workgroups of w_r x w_c work-items
+ * (Figure 1), each staging a tile plus perimeter border region in local memory; the
+ * workgroup size is the tunable parameter, and the sweep of Section 5 times every size.
+ *
+ * Conventions: matrices are contiguous row-major a[r][c]; north = smaller r, south = larger
+ * r, west = smaller c, east = larger c; the region includes the centre.  Weight tables are
+ * (north+south+1) x (east+west+1), row-major, applied as a correlation:
+ *   out[r][c] = sum_{dr=-north..south} sum_{dc=-west..east} w[dr+north][dc+west] * V(r+dr, c+dc)
+ * where V substitutes out-of-matrix positions according to the border mode.
+ *
+ * Pointers named `in` / `out` are DEVICE pointers owned by the caller.  Every other pointer
+ * is a HOST pointer.  All functions return STENCIL_OK (0) or a negative stencil_status and
+ * never abort or throw; `stencil_last_error()` gives the text of the calling thread's last
+ * failure.  Functions that take no `in`/`out` make no GPU call and work on a machine
+ * without a GPU.
+ */
+#ifndef LIBSTENCIL_H
+#define LIBSTENCIL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct stencil stencil_t;
+typedef struct stencil_predictor stencil_predictor_t;
+
+enum stencil_status {
+    STENCIL_OK = 0,
+    STENCIL_E_INVALID = -1,   /* bad argument: null, out of range, aliasing buffers        */
+    STENCIL_E_REFUSED = -2,   /* workgroup size not legal for this scenario (Section 3.1:
+                                 over W_max, or a "refused parameter": tile exceeds local
+                                 memory)                                                  */
+    STENCIL_E_RESOURCES = -3, /* allocation failed                                         */
+    STENCIL_E_HIP = -4        /* HIP runtime error; text in stencil_last_error()           */
+};
+
+enum stencil_dtype { STENCIL_F32 = 0, STENCIL_U8 = 1 };
+
+/* Border substitution (Section 2): CLAMP = value of the nearest cell within the matrix,
+ * CONSTANT = predefined padding value, WRAP = periodic (true modulo). */
+enum stencil_border { STENCIL_CLAMP = 0, STENCIL_WRAP = 1, STENCIL_CONSTANT = 2 };
+
+/* Customising functions (Table 2 names the paper's kernels; it does not print them).
+ *   WEIGHTED_SUM (f32): sum of w * V over the region - "gaussian".  fp32 fma chain in
+ *                 (dr, dc) row-major order.
+ *   LIFE (u8):    Conway B3/S23 on cells 0/1, region 1/1/1/1 - "gol".
+ *   HEAT (f32):   u + alpha * (((n + s) + (e + w)) - 4u), region 1/1/1/1, every operation
+ *                 rounded to fp32 in this order - "he".  scalars[0] = alpha.
+ *   SINCOS (f32): sum over the region of w * sin(V) + cos(V) - a compute-intensive
+ *                 synthetic stencil (Section 3.3).  sin/cos are evaluated in fp32.
+ */
+enum stencil_kernel {
+    STENCIL_WEIGHTED_SUM = 0,
+    STENCIL_LIFE = 1,
+    STENCIL_HEAT = 2,
+    STENCIL_SINCOS = 3
+};
+
+enum stencil_enum_mode {
+    STENCIL_ENUM_POW2 = 0, /* w_r, w_c in {1,2,4,...}              */
+    STENCIL_ENUM_EVEN = 1  /* w_r, w_c in {2,4,...,64} (Section 5) */
+};
+
+#define STENCIL_MAX_HALO 32            /* Table 2's border sizes go up to 30 */
+#define STENCIL_MAX_WG_SIZE 1024       /* device limit on work-items per workgroup */
+#define STENCIL_LOCAL_MEM_BYTES 65536  /* local memory one workgroup may allocate */
+
+/* ---- scenario ---------------------------------------------------------------------- */
+
+/* Section 2: the user defines size, type and border region of the matrix.  Creates a
+ * handle (owned by the library, release with stencil_destroy); makes no GPU call.
+ * rows, cols >= 1 and rows*cols < 2^31; halos in [0, STENCIL_MAX_HALO].  The customising
+ * function defaults to WEIGHTED_SUM with all-zero weights until stencil_set_kernel. */
+int stencil_create(stencil_t **out, int64_t rows, int64_t cols, int dtype,
+                   int halo_n, int halo_s, int halo_e, int halo_w, int border_mode);
+
+/* Frees the handle, its scratch matrix and its events.  NULL is accepted. */
+void stencil_destroy(stencil_t *st);
+
+/* Selects the customising function (Section 2).  `weights` (host, copied) must hold
+ * (north+south+1)*(east+west+1) floats for WEIGHTED_SUM / SINCOS and is ignored otherwise;
+ * `scalars` (host, copied): HEAT takes alpha.  LIFE and HEAT require region 1/1/1/1;
+ * LIFE requires dtype U8, the others F32. */
+int stencil_set_kernel(stencil_t *st, int kernel_id, const float *weights, int n_weights,
+                       const float *scalars, int n_scalars);
+
+/* Padding value for STENCIL_CONSTANT (Section 2); default 0.  For U8 it is truncated. */
+int stencil_set_border_value(stencil_t *st, double value);
+
+/* Register blocking: each work-item computes a cells_rows x cells_cols block of adjacent
+ * cells, so a workgroup of w_r x w_c work-items covers (w_r*cells_rows) x (w_c*cells_cols)
+ * elements.  (1,1) is the paper's mapping of one element per work-item (Section 2) and the
+ * default.  Supported: cells_rows in {1,2,4,8}, cells_cols in {1,4}; U8 matrices also
+ * cells_cols = 16.  Values never depend on the blocking. */
+int stencil_set_blocking(stencil_t *st, int cells_rows, int cells_cols);
+int stencil_get_blocking(const stencil_t *st, int *cells_rows, int *cells_cols);
+
+/* ---- legality (Section 3.1) ---------------------------------------------------------- */
+
+/* W_max(s): the largest number of work-items a workgroup of this scenario may have. */
+int stencil_max_wg_size(const stencil_t *st);
+
+/* Bytes of local memory the tile of Section 2 (workgroup plus perimeter border region)
+ * needs for this scenario and workgroup size, as laid out by the kernels. */
+int64_t stencil_tile_bytes(const stencil_t *st, int wg_rows, int wg_cols);
+
+/* Eq. 1: 1 if (wg_rows, wg_cols) is legal for this scenario (w_r*w_c <= W_max(s) and not a
+ * refused parameter, i.e. its tile fits local memory), else 0. */
+int stencil_is_legal(const stencil_t *st, int wg_rows, int wg_cols);
+
+/* Section 5's enumeration.  Writes up to `cap` pairs to rows[]/cols[] (may be NULL when
+ * cap = 0) in row-major order of (w_r, w_c) and returns the total number of pairs with
+ * w_r*w_c <= max_threads (or a negative status). */
+int stencil_enumerate_wg(int mode, int max_threads, int *rows, int *cols, int cap);
+
+/* ---- execution ------------------------------------------------------------------------ */
+
+/* Applies the stencil `iters` times (out-of-place steps; the input of step k+1 is the
+ * output of step k) with workgroups of wg_rows x wg_cols work-items.  `in` and `out` are
+ * device buffers of rows*cols elements, contiguous row-major, non-overlapping; `in` is
+ * never written; the final matrix is always in `out`; iters = 0 copies.  A scratch matrix
+ * for the intermediate steps is allocated on first use and kept until destroy.
+ * Asynchronous on `stream` (a hipStream_t; NULL = default stream), no host synchronisation.
+ * wg_rows = wg_cols = 0 lets the library choose (Section 2: selecting the size is the
+ * implementation's responsibility): the best size of the handle's last sweep, else a
+ * built-in default.  Illegal sizes return STENCIL_E_REFUSED without launching. */
+int stencil_run(stencil_t *st, const void *in, void *out, int iters,
+                int wg_rows, int wg_cols, void *stream);
+
+/* Section 5's measurement: for each of the n sizes, 3 untimed runs and then `reps` timed
+ * samples (reps <= 0 means 30), each sample one stencil_run(iters) bracketed by events on
+ * `stream`.  Outputs (host arrays of n, each may be NULL): mean / min / median / sample
+ * standard deviation in milliseconds per sample, and status (STENCIL_OK or
+ * STENCIL_E_REFUSED; refused sizes get NaN times and the sweep continues, Section 4.2).
+ * best_index = argmin of the mean over legal sizes (Eq. 3; ties: fewer work-items, then
+ * smaller w_r), -1 if none.  speedup_over_fixed = mean(fixed) / mean(best) (Section 7's
+ * speedup metric; the fixed size is timed additionally if it is not in the list; NaN if it
+ * is refused); pass fixed_rows = 0 to skip.  Synchronous: returns after the last sample.
+ * Remembers the best size for stencil_run(0, 0). */
+int stencil_sweep_wg(stencil_t *st, const void *in, void *out, int iters,
+                     const int *wg_rows_list, const int *wg_cols_list, int n,
+                     int fixed_rows, int fixed_cols, int reps,
+                     double *mean_ms, double *min_ms, double *median_ms, double *stddev_ms,
+                     int *status, int *best_index, double *speedup_over_fixed, void *stream);
+
+/* The reductions of a sweep on their own (Eq. 3; Section 7's performance and speedup), on
+ * host arrays: best_index as above; performance[i] = mean_ms[best] / mean_ms[i] (NaN where
+ * status[i] != STENCIL_OK; may be NULL); speedup = fixed_ms / mean_ms[best]. */
+int stencil_sweep_reduce(const int *wg_rows_list, const int *wg_cols_list, int n,
+                         const double *mean_ms, const int *status, double fixed_ms,
+                         int *best_index, double *performance, double *speedup_over_fixed);
+
+/* ---- prediction (Section 3.2, Section 4.1, Algorithm 1) ---------------------------------- */
+
+#define STENCIL_N_FEATURES 12
+
+/* f(s): dataset, kernel and device features of the scenario, STENCIL_N_FEATURES doubles:
+ * rows, cols, element bytes, north, south, east, west, region cells, compute-intensive
+ * flag, compute units, local memory bytes, max workgroup size. */
+int stencil_features(const stencil_t *st, double *features);
+
+/* A nearest-neighbour classifier over (f(s), Omega(s)) pairs (Section 4.1's D_training). */
+int stencil_predictor_create(stencil_predictor_t **out);
+void stencil_predictor_destroy(stencil_predictor_t *p);
+int stencil_predictor_add(stencil_predictor_t *p, const double *features, int n_features,
+                          int wg_rows, int wg_cols);
+/* classify(f(s)): the label of the nearest training scenario; each feature is scaled by
+ * its range over the training set, Euclidean distance, first nearest wins ties. */
+int stencil_predictor_classify(const stencil_predictor_t *p, const double *features,
+                               int n_features, int *wg_rows, int *wg_cols);
+
+/* Algorithm 1 with the NearestNeighbour handler: classify the scenario; if the size is not
+ * legal for it, take the candidate (from cand_rows/cand_cols, n_cand entries) that is legal
+ * and closest in Euclidean distance (first wins ties).  STENCIL_E_REFUSED if no candidate
+ * is legal. */
+int stencil_predict_wg(const stencil_t *st, const stencil_predictor_t *p,
+                       const int *cand_rows, const int *cand_cols, int n_cand,
+                       int *wg_rows, int *wg_cols);
+
+/* Text of the calling thread's most recent error ("" if none). */
+const char *stencil_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIBSTENCIL_H */

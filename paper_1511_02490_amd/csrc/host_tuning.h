@@ -1,0 +1,119 @@
+// Host-side arithmetic around the workgroup-size sweep: the enumeration of Section 5, the
+// oracle size of Eq. 3, the performance / speedup metrics of Section 7, sample statistics,
+// and the nearest-neighbour classifier used for classify(f(s)) in Algorithm 1.
+#pragma once
+#include <algorithm>
+#include <cmath>
+#include <limits>
+#include <vector>
+
+namespace host_tuning {
+
+// The values w_r and w_c are drawn from.  mode 0: powers of two up to max_threads;
+// mode 1: multiples of two, 2..64.
+inline bool size_values(int mode, int max_threads, std::vector<int> &vals) {
+    vals.clear();
+    if (mode == 0) {
+        for (long long v = 1; v <= max_threads; v *= 2) vals.push_back((int)v);
+        return true;
+    }
+    if (mode == 1) {
+        for (int v = 2; v <= 64; v += 2) vals.push_back(v);
+        return true;
+    }
+    return false;
+}
+
+struct SampleStats {
+    double mean, min, median, stddev;
+};
+
+inline SampleStats summarise(std::vector<double> s) {
+    SampleStats r{0, 0, 0, 0};
+    const size_t n = s.size();
+    if (n == 0) return r;
+    double sum = 0;
+    for (double x : s) sum += x;
+    r.mean = sum / (double)n;
+    std::sort(s.begin(), s.end());
+    r.min = s.front();
+    r.median = (n % 2) ? s[n / 2] : 0.5 * (s[n / 2 - 1] + s[n / 2]);
+    double ss = 0;
+    for (double x : s) ss += (x - r.mean) * (x - r.mean);
+    r.stddev = n > 1 ? std::sqrt(ss / (double)(n - 1)) : 0.0;
+    return r;
+}
+
+// Eq. 3 and the metrics of Section 7.  status[i] == 0 marks a legal, measured size.
+inline void reduce(const int *wr, const int *wc, int n, const double *mean_ms, const int *status,
+                   double fixed_ms, int *best_index, double *performance, double *speedup) {
+    int best = -1;
+    for (int i = 0; i < n; ++i) {
+        if (status[i] != 0 || std::isnan(mean_ms[i])) continue;
+        if (best < 0) {
+            best = i;
+            continue;
+        }
+        const long long ti = (long long)wr[i] * wc[i], tb = (long long)wr[best] * wc[best];
+        bool better = mean_ms[i] < mean_ms[best];
+        if (mean_ms[i] == mean_ms[best]) better = ti < tb || (ti == tb && wr[i] < wr[best]);
+        if (better) best = i;
+    }
+    const double nan = std::numeric_limits<double>::quiet_NaN();
+    if (best_index) *best_index = best;
+    if (performance)
+        for (int i = 0; i < n; ++i)
+            performance[i] = (best >= 0 && status[i] == 0) ? mean_ms[best] / mean_ms[i] : nan;
+    if (speedup) *speedup = (best >= 0 && !std::isnan(fixed_ms)) ? fixed_ms / mean_ms[best] : nan;
+}
+
+// classify(f(s)) by the nearest training scenario (range-scaled Euclidean distance).
+class NearestClassifier {
+public:
+    bool add(const double *f, int nf, int wr, int wc) {
+        if (nf_ == 0) nf_ = nf;
+        if (nf != nf_) return false;
+        x_.insert(x_.end(), f, f + nf);
+        wr_.push_back(wr);
+        wc_.push_back(wc);
+        return true;
+    }
+    bool classify(const double *f, int nf, int *wr, int *wc) const {
+        const size_t n = wr_.size();
+        if (n == 0 || nf != nf_) return false;
+        std::vector<double> lo(nf_), hi(nf_);
+        for (int j = 0; j < nf_; ++j) {
+            lo[j] = hi[j] = x_[j];
+            for (size_t i = 1; i < n; ++i) {
+                lo[j] = std::min(lo[j], x_[i * nf_ + j]);
+                hi[j] = std::max(hi[j], x_[i * nf_ + j]);
+            }
+        }
+        size_t best = 0;
+        double d_best = std::numeric_limits<double>::infinity();
+        for (size_t i = 0; i < n; ++i) {
+            double d = 0;
+            for (int j = 0; j < nf_; ++j) {
+                const double span = hi[j] - lo[j];
+                if (span > 0) {
+                    const double z = (x_[i * nf_ + j] - f[j]) / span;
+                    d += z * z;
+                }
+            }
+            if (d < d_best) {
+                d_best = d;
+                best = i;
+            }
+        }
+        *wr = wr_[best];
+        *wc = wc_[best];
+        return true;
+    }
+
+private:
+    int nf_ = 0;
+    std::vector<double> x_;
+    std::vector<int> wr_, wc_;
+};
+
+}  // namespace host_tuning

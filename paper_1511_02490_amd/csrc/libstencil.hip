@@ -1,0 +1,652 @@
+// libstencil: C-ABI front end, scenario handle, legality, launch and the timed
+// workgroup-size sweep.  The interface is documented in include/libstencil.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <type_traits>
+#include <vector>
+
+#include "../../include/libstencil.h"
+#include "host_tuning.h"
+#include "tile_kernel.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int fail_hip(hipError_t e, const char *what) {
+    return fail(STENCIL_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+// ---- scenario handle ---------------------------------------------------------------------
+
+using LaunchFn = hipError_t (*)(const stencil *, const void *, void *, int, int, hipStream_t);
+
+struct Variant {
+    int kernel, border;
+    int hn, hs, he, hw;   // -1: run-time border region
+    int cr, cc;
+    int max_threads;      // per-kernel workgroup-size limit (Section 3.1)
+    int staged_bytes;     // bytes per staged element in LDS
+    LaunchFn launch;
+};
+
+struct stencil {
+    int64_t rows = 0, cols = 0;
+    int dtype = STENCIL_F32;
+    int hn = 0, hs = 0, he = 0, hw = 0;
+    int border = STENCIL_CLAMP;
+    double pad = 0.0;
+    int kernel = STENCIL_WEIGHTED_SUM;
+    std::vector<float> weights;
+    float scalar0 = 0.0f;
+    int cr = 1, cc = 1;
+    int xcd_remap = 1;
+    int best_rows = 0, best_cols = 0;
+    // device-side state, created on first use
+    void *scratch = nullptr;
+    float *d_weights = nullptr;
+    bool weights_uploaded = false;
+    std::vector<hipEvent_t> events;
+    size_t elem() const { return dtype == STENCIL_F32 ? 4 : 1; }
+    size_t bytes() const { return (size_t)rows * (size_t)cols * elem(); }
+};
+
+namespace {
+
+struct TileGeom {
+    int th, tw;        // elements covered by one workgroup
+    int pitch;         // LDS pitch in staged elements
+    int64_t lds_bytes;
+    int tiles_r, tiles_c;
+};
+
+TileGeom tile_geom(const stencil *s, const Variant &v, int wr, int wc) {
+    TileGeom g;
+    g.th = wr * v.cr;
+    g.tw = wc * v.cc;
+    const int hwa = v.cc == 1 ? s->hw : sk::round_up(s->hw, v.cc);
+    const int hea = v.cc == 1 ? s->he : sk::round_up(s->he, v.cc);
+    g.pitch = hwa + g.tw + hea;
+    g.lds_bytes = (int64_t)(g.th + s->hn + s->hs) * g.pitch * v.staged_bytes;
+    g.tiles_r = (int)((s->rows + g.th - 1) / g.th);
+    g.tiles_c = (int)((s->cols + g.tw - 1) / g.tw);
+    return g;
+}
+
+template <class Op, int B, class Halo, int CR, int CC, int MAXT>
+hipError_t launch_tile(const stencil *s, const void *in, void *out, int wr, int wc, hipStream_t stream) {
+    using T = typename Op::T;
+    Variant v{};
+    v.cr = CR;
+    v.cc = CC;
+    v.staged_bytes = (int)sizeof(typename Op::L);
+    const TileGeom g = tile_geom(s, v, wr, wc);
+    sk::TileArgs<Op, Halo> a;
+    a.in = static_cast<const T *>(in);
+    a.out = static_cast<T *>(out);
+    a.rows = (int)s->rows;
+    a.cols = (int)s->cols;
+    a.tiles_c = g.tiles_c;
+    a.n_tiles = g.tiles_r * g.tiles_c;
+    a.pitch = g.pitch;
+    const size_t row_bytes = (size_t)s->cols * sizeof(T);
+    a.vec_ok = (CC > 1 && row_bytes % 16 == 0 && (uintptr_t)in % 16 == 0 && (uintptr_t)out % 16 == 0) ? 1 : 0;
+    a.pad = (T)s->pad;
+    a.scalar0 = s->scalar0;
+    if constexpr (Halo::kStatic) {
+        if constexpr (Op::kWeights)
+            for (int k = 0; k < (int)(sizeof(a.w.v) / sizeof(float)); ++k) a.w.v[k] = s->weights[k];
+        else
+            a.w.v[0] = 0.0f;
+    } else {
+        a.halo.n_ = s->hn;
+        a.halo.s_ = s->hs;
+        a.halo.e_ = s->he;
+        a.halo.w_ = s->hw;
+        a.w.v = s->d_weights;
+    }
+    unsigned blocks = (unsigned)a.n_tiles;
+    a.xcd_chunk = 0;
+    if (s->xcd_remap && a.n_tiles >= 64) {
+        a.xcd_chunk = (a.n_tiles + 7) / 8;
+        blocks = (unsigned)a.xcd_chunk * 8u;
+    }
+    hipLaunchKernelGGL((sk::tile_kernel<Op, B, Halo, CR, CC, MAXT>), dim3(blocks), dim3(wc, wr),
+                       (size_t)g.lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+// ---- registry of compiled variants ----------------------------------------------------------
+
+// Per-kernel workgroup-size limit (Section 3.1: the registers a kernel needs bound its
+// maximum workgroup size).  The heavily blocked variants are compiled for 256 work-items so
+// that their register windows stay out of scratch memory.
+template <class Op, int CR, int CC>
+constexpr int variant_max_threads() {
+    if (std::is_same<Op, sk::OpSinCos>::value && CR * CC >= 32) return 256;
+    if (std::is_same<Op, sk::OpLife>::value && CR * CC >= 64) return 256;
+    return STENCIL_MAX_WG_SIZE;
+}
+
+template <class Op, int KID, int B, class Halo, int CR, int CC>
+void reg_one(std::vector<Variant> &r) {
+    Variant v;
+    v.kernel = KID;
+    v.border = B;
+    if (Halo::kStatic) {
+        v.hn = Halo::N; v.hs = Halo::S; v.he = Halo::E; v.hw = Halo::W;
+    } else {
+        v.hn = v.hs = v.he = v.hw = -1;
+    }
+    v.cr = CR;
+    v.cc = CC;
+    constexpr int kMaxT = variant_max_threads<Op, CR, CC>();
+    v.max_threads = kMaxT;
+    v.staged_bytes = (int)sizeof(typename Op::L);
+    v.launch = &launch_tile<Op, B, Halo, CR, CC, kMaxT>;
+    r.push_back(v);
+}
+
+template <class Op, int KID, class Halo, int CR, int CC>
+void reg_borders(std::vector<Variant> &r) {
+    reg_one<Op, KID, sk::kClamp, Halo, CR, CC>(r);
+    reg_one<Op, KID, sk::kWrap, Halo, CR, CC>(r);
+    reg_one<Op, KID, sk::kConstant, Halo, CR, CC>(r);
+}
+
+template <class Op, int KID, class Halo, int CCV>
+void reg_blockings(std::vector<Variant> &r) {
+    reg_borders<Op, KID, Halo, 1, 1>(r);
+    reg_borders<Op, KID, Halo, 2, 1>(r);
+    reg_borders<Op, KID, Halo, 4, 1>(r);
+    reg_borders<Op, KID, Halo, 8, 1>(r);
+    reg_borders<Op, KID, Halo, 1, CCV>(r);
+    reg_borders<Op, KID, Halo, 2, CCV>(r);
+    reg_borders<Op, KID, Halo, 4, CCV>(r);
+    reg_borders<Op, KID, Halo, 8, CCV>(r);
+}
+
+const std::vector<Variant> &registry() {
+    static const std::vector<Variant> reg = [] {
+        std::vector<Variant> r;
+        reg_blockings<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloD, 4>(r);
+        reg_blockings<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<1, 1, 1, 1>, 4>(r);
+        reg_blockings<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<2, 2, 2, 2>, 4>(r);
+        reg_blockings<sk::OpSinCos, STENCIL_SINCOS, sk::HaloD, 4>(r);
+        reg_blockings<sk::OpSinCos, STENCIL_SINCOS, sk::HaloC<1, 5, 3, 0>, 4>(r);
+        reg_blockings<sk::OpHeat, STENCIL_HEAT, sk::HaloC<1, 1, 1, 1>, 4>(r);
+        reg_blockings<sk::OpLife, STENCIL_LIFE, sk::HaloC<1, 1, 1, 1>, 16>(r);
+        return r;
+    }();
+    return reg;
+}
+
+// The variant that serves a scenario: a compile-time border region if one matches, else
+// the run-time one.
+const Variant *find_variant(const stencil *s) {
+    const Variant *dyn = nullptr;
+    for (const Variant &v : registry()) {
+        if (v.kernel != s->kernel || v.border != s->border || v.cr != s->cr || v.cc != s->cc) continue;
+        if (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw) return &v;
+        if (v.hn < 0) dyn = &v;
+    }
+    return dyn;
+}
+
+bool blocking_supported(const stencil *s, int cr, int cc) {
+    for (const Variant &v : registry())
+        if (v.kernel == s->kernel && v.border == s->border && v.cr == cr && v.cc == cc &&
+            (v.hn < 0 || (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw)))
+            return true;
+    return false;
+}
+
+int check_legal(const stencil *s, const Variant *v, int wr, int wc) {
+    if (!v) return fail(STENCIL_E_INVALID, "no kernel variant for this scenario");
+    if (wr < 1 || wc < 1)
+        return fail(STENCIL_E_REFUSED, "workgroup size %dx%d: dimensions must be >= 1", wr, wc);
+    if ((int64_t)wr * wc > v->max_threads)
+        return fail(STENCIL_E_REFUSED, "workgroup size %dx%d exceeds W_max = %d work-items", wr, wc,
+                    v->max_threads);
+    const TileGeom g = tile_geom(s, *v, wr, wc);
+    if (g.lds_bytes > STENCIL_LOCAL_MEM_BYTES)
+        return fail(STENCIL_E_REFUSED, "workgroup size %dx%d refused: tile needs %lld bytes of local memory (limit %d)",
+                    wr, wc, (long long)g.lds_bytes, STENCIL_LOCAL_MEM_BYTES);
+    return STENCIL_OK;
+}
+
+int ensure_device_state(stencil *s, const Variant *v, bool need_scratch) {
+    if (v->hn < 0 && !s->weights_uploaded) {
+        const size_t n = std::max<size_t>(1, s->weights.size());
+        if (!s->d_weights) {
+            hipError_t e = hipMalloc((void **)&s->d_weights, n * sizeof(float));
+            if (e != hipSuccess) return fail(STENCIL_E_RESOURCES, "hipMalloc(weights): %s", hipGetErrorString(e));
+        }
+        if (!s->weights.empty()) {
+            hipError_t e = hipMemcpy(s->d_weights, s->weights.data(), s->weights.size() * sizeof(float),
+                                     hipMemcpyHostToDevice);
+            if (e != hipSuccess) return fail_hip(e, "hipMemcpy(weights)");
+        }
+        s->weights_uploaded = true;
+    }
+    if (need_scratch && !s->scratch) {
+        hipError_t e = hipMalloc(&s->scratch, s->bytes());
+        if (e != hipSuccess) {
+            s->scratch = nullptr;
+            return fail(STENCIL_E_RESOURCES, "hipMalloc(scratch matrix, %zu bytes): %s", s->bytes(),
+                        hipGetErrorString(e));
+        }
+    }
+    return STENCIL_OK;
+}
+
+// `iters` out-of-place applications ending in `out`, never writing `in`.
+int run_checked(stencil *s, const Variant *v, const void *in, void *out, int iters, int wr, int wc,
+                hipStream_t stream) {
+    if (iters == 0) {
+        hipError_t e = hipMemcpyAsync(out, in, s->bytes(), hipMemcpyDeviceToDevice, stream);
+        return e == hipSuccess ? STENCIL_OK : fail_hip(e, "hipMemcpyAsync");
+    }
+    const void *src = in;
+    void *dst = (iters % 2 == 1) ? out : s->scratch;
+    for (int it = 0; it < iters; ++it) {
+        hipError_t e = v->launch(s, src, dst, wr, wc, stream);
+        if (e != hipSuccess) return fail_hip(e, "kernel launch");
+        src = dst;
+        dst = (dst == out) ? s->scratch : out;
+    }
+    return STENCIL_OK;
+}
+
+int validate_buffers(const stencil *s, const void *in, const void *out) {
+    if (!in || !out) return fail(STENCIL_E_INVALID, "in/out must not be NULL");
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out, n = s->bytes();
+    if (a < b + n && b < a + n) return fail(STENCIL_E_INVALID, "in and out overlap");
+    if (a % s->elem() || b % s->elem()) return fail(STENCIL_E_INVALID, "in/out are not element-aligned");
+    return STENCIL_OK;
+}
+
+void default_wg(const stencil *s, const Variant *v, int *wr, int *wc) {
+    if (s->best_rows > 0 && check_legal(s, v, s->best_rows, s->best_cols) == STENCIL_OK) {
+        *wr = s->best_rows;
+        *wc = s->best_cols;
+        return;
+    }
+    // one wavefront wide, a few rows tall; shrink until the tile fits local memory
+    int r = 4, c = 64;
+    while (check_legal(s, v, r, c) != STENCIL_OK && (r > 1 || c > 1)) {
+        if (r > 1) r /= 2; else c /= 2;
+    }
+    *wr = r;
+    *wc = c;
+}
+
+}  // namespace
+
+// ---- C ABI -----------------------------------------------------------------------------------
+
+extern "C" {
+
+const char *stencil_last_error(void) { return g_err; }
+
+int stencil_create(stencil_t **out, int64_t rows, int64_t cols, int dtype, int halo_n, int halo_s,
+                   int halo_e, int halo_w, int border_mode) {
+    if (!out) return fail(STENCIL_E_INVALID, "out handle pointer is NULL");
+    *out = nullptr;
+    if (rows < 1 || cols < 1) return fail(STENCIL_E_INVALID, "rows and cols must be >= 1 (got %lld x %lld)",
+                                          (long long)rows, (long long)cols);
+    if (rows > INT32_MAX || cols > INT32_MAX || rows * cols > (int64_t)INT32_MAX)
+        return fail(STENCIL_E_INVALID, "matrix too large: rows*cols must be < 2^31");
+    if (dtype != STENCIL_F32 && dtype != STENCIL_U8) return fail(STENCIL_E_INVALID, "unknown dtype %d", dtype);
+    const int h[4] = {halo_n, halo_s, halo_e, halo_w};
+    for (int k = 0; k < 4; ++k)
+        if (h[k] < 0 || h[k] > STENCIL_MAX_HALO)
+            return fail(STENCIL_E_INVALID, "border region extents must be in [0, %d]", STENCIL_MAX_HALO);
+    if (border_mode < STENCIL_CLAMP || border_mode > STENCIL_CONSTANT)
+        return fail(STENCIL_E_INVALID, "unknown border mode %d", border_mode);
+    stencil *s = new (std::nothrow) stencil;
+    if (!s) return fail(STENCIL_E_RESOURCES, "out of host memory");
+    s->rows = rows;
+    s->cols = cols;
+    s->dtype = dtype;
+    s->hn = halo_n; s->hs = halo_s; s->he = halo_e; s->hw = halo_w;
+    s->border = border_mode;
+    if (dtype == STENCIL_F32) {
+        s->kernel = STENCIL_WEIGHTED_SUM;
+        s->weights.assign((size_t)(halo_n + halo_s + 1) * (halo_e + halo_w + 1), 0.0f);
+    } else {
+        s->kernel = -1;   // a U8 matrix has no default customising function
+    }
+    *out = s;
+    return STENCIL_OK;
+}
+
+void stencil_destroy(stencil_t *s) {
+    if (!s) return;
+    for (hipEvent_t e : s->events) (void)hipEventDestroy(e);
+    if (s->scratch) (void)hipFree(s->scratch);
+    if (s->d_weights) (void)hipFree(s->d_weights);
+    delete s;
+}
+
+int stencil_set_kernel(stencil_t *s, int kernel_id, const float *weights, int n_weights,
+                       const float *scalars, int n_scalars) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    const int cells = (s->hn + s->hs + 1) * (s->he + s->hw + 1);
+    const bool unit_region = s->hn == 1 && s->hs == 1 && s->he == 1 && s->hw == 1;
+    switch (kernel_id) {
+    case STENCIL_WEIGHTED_SUM:
+    case STENCIL_SINCOS:
+        if (s->dtype != STENCIL_F32) return fail(STENCIL_E_INVALID, "this kernel needs an F32 matrix");
+        if (!weights || n_weights != cells)
+            return fail(STENCIL_E_INVALID, "weights must hold (N+S+1)*(E+W+1) = %d floats (got %d)", cells, n_weights);
+        s->weights.assign(weights, weights + cells);
+        break;
+    case STENCIL_LIFE:
+        if (s->dtype != STENCIL_U8) return fail(STENCIL_E_INVALID, "LIFE needs a U8 matrix");
+        if (!unit_region) return fail(STENCIL_E_INVALID, "LIFE needs border region 1/1/1/1");
+        s->weights.clear();
+        break;
+    case STENCIL_HEAT:
+        if (s->dtype != STENCIL_F32) return fail(STENCIL_E_INVALID, "HEAT needs an F32 matrix");
+        if (!unit_region) return fail(STENCIL_E_INVALID, "HEAT needs border region 1/1/1/1");
+        if (!scalars || n_scalars < 1) return fail(STENCIL_E_INVALID, "HEAT needs scalars[0] = alpha");
+        s->scalar0 = scalars[0];
+        s->weights.clear();
+        break;
+    default:
+        return fail(STENCIL_E_INVALID, "unknown kernel id %d", kernel_id);
+    }
+    s->kernel = kernel_id;
+    s->weights_uploaded = false;
+    if (!blocking_supported(s, s->cr, s->cc)) {
+        s->cr = 1;
+        s->cc = 1;
+    }
+    s->best_rows = s->best_cols = 0;
+    return STENCIL_OK;
+}
+
+int stencil_set_border_value(stencil_t *s, double value) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    s->pad = value;
+    return STENCIL_OK;
+}
+
+int stencil_set_blocking(stencil_t *s, int cells_rows, int cells_cols) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    if (s->kernel < 0) return fail(STENCIL_E_INVALID, "select a kernel first");
+    if (!blocking_supported(s, cells_rows, cells_cols))
+        return fail(STENCIL_E_INVALID, "blocking %dx%d is not available for this kernel", cells_rows, cells_cols);
+    s->cr = cells_rows;
+    s->cc = cells_cols;
+    s->best_rows = s->best_cols = 0;
+    return STENCIL_OK;
+}
+
+int stencil_get_blocking(const stencil_t *s, int *cells_rows, int *cells_cols) {
+    if (!s || !cells_rows || !cells_cols) return fail(STENCIL_E_INVALID, "NULL argument");
+    *cells_rows = s->cr;
+    *cells_cols = s->cc;
+    return STENCIL_OK;
+}
+
+int stencil_max_wg_size(const stencil_t *s) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    const Variant *v = find_variant(s);
+    if (!v) return fail(STENCIL_E_INVALID, "no kernel variant for this scenario");
+    return v->max_threads;
+}
+
+int64_t stencil_tile_bytes(const stencil_t *s, int wg_rows, int wg_cols) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    const Variant *v = find_variant(s);
+    if (!v || wg_rows < 1 || wg_cols < 1) return fail(STENCIL_E_INVALID, "bad scenario or workgroup size");
+    return tile_geom(s, *v, wg_rows, wg_cols).lds_bytes;
+}
+
+int stencil_is_legal(const stencil_t *s, int wg_rows, int wg_cols) {
+    if (!s) return 0;
+    return check_legal(s, find_variant(s), wg_rows, wg_cols) == STENCIL_OK ? 1 : 0;
+}
+
+int stencil_enumerate_wg(int mode, int max_threads, int *rows, int *cols, int cap) {
+    if (max_threads < 1 || cap < 0 || (cap > 0 && (!rows || !cols)))
+        return fail(STENCIL_E_INVALID, "bad arguments to stencil_enumerate_wg");
+    std::vector<int> vals;
+    if (!host_tuning::size_values(mode, max_threads, vals)) return fail(STENCIL_E_INVALID, "unknown enumeration mode %d", mode);
+    int n = 0;
+    for (int r : vals)
+        for (int c : vals)
+            if ((int64_t)r * c <= max_threads) {
+                if (n < cap) {
+                    rows[n] = r;
+                    cols[n] = c;
+                }
+                ++n;
+            }
+    return n;
+}
+
+int stencil_run(stencil_t *s, const void *in, void *out, int iters, int wg_rows, int wg_cols, void *stream) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    if (iters < 0) return fail(STENCIL_E_INVALID, "iters must be >= 0");
+    int rc = validate_buffers(s, in, out);
+    if (rc != STENCIL_OK) return rc;
+    const Variant *v = find_variant(s);
+    if (!v) return fail(STENCIL_E_INVALID, "no kernel selected for this scenario");
+    if (wg_rows == 0 && wg_cols == 0) default_wg(s, v, &wg_rows, &wg_cols);
+    rc = check_legal(s, v, wg_rows, wg_cols);
+    if (rc != STENCIL_OK) return rc;
+    rc = ensure_device_state(s, v, iters > 1);
+    if (rc != STENCIL_OK) return rc;
+    return run_checked(s, v, in, out, iters, wg_rows, wg_cols, (hipStream_t)stream);
+}
+
+int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const int *wg_rows_list,
+                     const int *wg_cols_list, int n, int fixed_rows, int fixed_cols, int reps,
+                     double *mean_ms, double *min_ms, double *median_ms, double *stddev_ms, int *status,
+                     int *best_index, double *speedup_over_fixed, void *stream_) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    if (n < 0 || (n > 0 && (!wg_rows_list || !wg_cols_list))) return fail(STENCIL_E_INVALID, "bad size list");
+    if (iters < 1) return fail(STENCIL_E_INVALID, "a sweep needs iters >= 1");
+    int rc = validate_buffers(s, in, out);
+    if (rc != STENCIL_OK) return rc;
+    const Variant *v = find_variant(s);
+    if (!v) return fail(STENCIL_E_INVALID, "no kernel selected for this scenario");
+    if (reps <= 0) reps = 30;
+    hipStream_t stream = (hipStream_t)stream_;
+    rc = ensure_device_state(s, v, iters > 1);
+    if (rc != STENCIL_OK) return rc;
+    while ((int)s->events.size() < 2 * reps) {
+        hipEvent_t e;
+        hipError_t he = hipEventCreate(&e);
+        if (he != hipSuccess) return fail_hip(he, "hipEventCreate");
+        s->events.push_back(e);
+    }
+    const double nan = std::numeric_limits<double>::quiet_NaN();
+    const int kWarmup = 3;
+    std::vector<double> samples((size_t)reps);
+    std::vector<double> means((size_t)n + 1, nan);
+    std::vector<int> stat((size_t)n + 1, STENCIL_E_REFUSED);
+
+    // times one size into slot k; returns STENCIL_OK also when the size is refused
+    auto time_size = [&](int wr, int wc, int k) -> int {
+        if (check_legal(s, v, wr, wc) != STENCIL_OK) {
+            stat[k] = STENCIL_E_REFUSED;
+            if (k < n) {
+                if (min_ms) min_ms[k] = nan;
+                if (median_ms) median_ms[k] = nan;
+                if (stddev_ms) stddev_ms[k] = nan;
+            }
+            return STENCIL_OK;
+        }
+        for (int w = 0; w < kWarmup; ++w) {
+            int r = run_checked(s, v, in, out, iters, wr, wc, stream);
+            if (r != STENCIL_OK) return r;
+        }
+        for (int i = 0; i < reps; ++i) {
+            hipError_t e = hipEventRecord(s->events[2 * i], stream);
+            if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
+            int r = run_checked(s, v, in, out, iters, wr, wc, stream);
+            if (r != STENCIL_OK) return r;
+            e = hipEventRecord(s->events[2 * i + 1], stream);
+            if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
+        }
+        hipError_t e = hipEventSynchronize(s->events[2 * reps - 1]);
+        if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
+        for (int i = 0; i < reps; ++i) {
+            float ms = 0.0f;
+            e = hipEventElapsedTime(&ms, s->events[2 * i], s->events[2 * i + 1]);
+            if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
+            samples[i] = ms;
+        }
+        host_tuning::SampleStats st = host_tuning::summarise(samples);
+        means[k] = st.mean;
+        stat[k] = STENCIL_OK;
+        if (k < n) {
+            if (min_ms) min_ms[k] = st.min;
+            if (median_ms) median_ms[k] = st.median;
+            if (stddev_ms) stddev_ms[k] = st.stddev;
+        }
+        return STENCIL_OK;
+    };
+
+    for (int k = 0; k < n; ++k) {
+        rc = time_size(wg_rows_list[k], wg_cols_list[k], k);
+        if (rc != STENCIL_OK) return rc;
+    }
+    double fixed_ms = nan;
+    if (fixed_rows > 0 && fixed_cols > 0) {
+        int at = -1;
+        for (int k = 0; k < n; ++k)
+            if (wg_rows_list[k] == fixed_rows && wg_cols_list[k] == fixed_cols) { at = k; break; }
+        if (at < 0) {
+            rc = time_size(fixed_rows, fixed_cols, n);
+            if (rc != STENCIL_OK) return rc;
+            at = n;
+        }
+        if (stat[at] == STENCIL_OK) fixed_ms = means[at];
+    }
+    int best = -1;
+    double speedup = nan;
+    host_tuning::reduce(wg_rows_list, wg_cols_list, n, means.data(), stat.data(), fixed_ms, &best, nullptr, &speedup);
+    for (int k = 0; k < n; ++k) {
+        if (mean_ms) mean_ms[k] = means[k];
+        if (status) status[k] = stat[k];
+    }
+    if (best_index) *best_index = best;
+    if (speedup_over_fixed) *speedup_over_fixed = speedup;
+    if (best >= 0) {
+        s->best_rows = wg_rows_list[best];
+        s->best_cols = wg_cols_list[best];
+    }
+    return STENCIL_OK;
+}
+
+int stencil_sweep_reduce(const int *wg_rows_list, const int *wg_cols_list, int n, const double *mean_ms,
+                         const int *status, double fixed_ms, int *best_index, double *performance,
+                         double *speedup_over_fixed) {
+    if (n < 0 || (n > 0 && (!wg_rows_list || !wg_cols_list || !mean_ms || !status)))
+        return fail(STENCIL_E_INVALID, "bad arguments to stencil_sweep_reduce");
+    host_tuning::reduce(wg_rows_list, wg_cols_list, n, mean_ms, status, fixed_ms, best_index, performance,
+                        speedup_over_fixed);
+    return STENCIL_OK;
+}
+
+int stencil_features(const stencil_t *s, double *f) {
+    if (!s || !f) return fail(STENCIL_E_INVALID, "NULL argument");
+    f[0] = (double)s->rows;
+    f[1] = (double)s->cols;
+    f[2] = (double)s->elem();
+    f[3] = s->hn;
+    f[4] = s->hs;
+    f[5] = s->he;
+    f[6] = s->hw;
+    f[7] = (double)(s->hn + s->hs + 1) * (s->he + s->hw + 1);
+    f[8] = s->kernel == STENCIL_SINCOS ? 1.0 : 0.0;
+    f[9] = 256.0;                              // compute units of an MI355X
+    f[10] = (double)STENCIL_LOCAL_MEM_BYTES;
+    f[11] = (double)STENCIL_MAX_WG_SIZE;
+    return STENCIL_OK;
+}
+
+int stencil_predictor_create(stencil_predictor_t **out) {
+    if (!out) return fail(STENCIL_E_INVALID, "NULL argument");
+    *out = reinterpret_cast<stencil_predictor_t *>(new (std::nothrow) host_tuning::NearestClassifier);
+    return *out ? STENCIL_OK : fail(STENCIL_E_RESOURCES, "out of host memory");
+}
+
+void stencil_predictor_destroy(stencil_predictor_t *p) {
+    delete reinterpret_cast<host_tuning::NearestClassifier *>(p);
+}
+
+int stencil_predictor_add(stencil_predictor_t *p, const double *features, int n_features, int wg_rows, int wg_cols) {
+    if (!p || !features || n_features < 1 || wg_rows < 1 || wg_cols < 1) return fail(STENCIL_E_INVALID, "bad arguments");
+    auto *c = reinterpret_cast<host_tuning::NearestClassifier *>(p);
+    if (!c->add(features, n_features, wg_rows, wg_cols))
+        return fail(STENCIL_E_INVALID, "feature count %d differs from earlier training pairs", n_features);
+    return STENCIL_OK;
+}
+
+int stencil_predictor_classify(const stencil_predictor_t *p, const double *features, int n_features,
+                               int *wg_rows, int *wg_cols) {
+    if (!p || !features || !wg_rows || !wg_cols) return fail(STENCIL_E_INVALID, "NULL argument");
+    auto *c = reinterpret_cast<const host_tuning::NearestClassifier *>(p);
+    if (!c->classify(features, n_features, wg_rows, wg_cols))
+        return fail(STENCIL_E_INVALID, "classifier has no training pairs, or feature count differs");
+    return STENCIL_OK;
+}
+
+int stencil_predict_wg(const stencil_t *s, const stencil_predictor_t *p, const int *cand_rows, const int *cand_cols,
+                       int n_cand, int *wg_rows, int *wg_cols) {
+    if (!s || !p || !wg_rows || !wg_cols || n_cand < 0 || (n_cand > 0 && (!cand_rows || !cand_cols)))
+        return fail(STENCIL_E_INVALID, "bad arguments");
+    double f[STENCIL_N_FEATURES];
+    int rc = stencil_features(s, f);
+    if (rc != STENCIL_OK) return rc;
+    int wr = 0, wc = 0;
+    rc = stencil_predictor_classify(p, f, STENCIL_N_FEATURES, &wr, &wc);
+    if (rc != STENCIL_OK) return rc;
+    const Variant *v = find_variant(s);
+    // Algorithm 1, NearestNeighbour: keep a legal prediction, else the closest legal candidate
+    while (check_legal(s, v, wr, wc) != STENCIL_OK) {
+        double d_min = std::numeric_limits<double>::infinity();
+        int closest = -1;
+        for (int k = 0; k < n_cand; ++k) {
+            if (check_legal(s, v, cand_rows[k], cand_cols[k]) != STENCIL_OK) continue;
+            const double dr = cand_rows[k] - wr, dc = cand_cols[k] - wc;
+            const double d = std::sqrt(dr * dr + dc * dc);
+            if (d < d_min) {
+                d_min = d;
+                closest = k;
+            }
+        }
+        if (closest < 0) return fail(STENCIL_E_REFUSED, "no legal candidate workgroup size");
+        wr = cand_rows[closest];
+        wc = cand_cols[closest];
+    }
+    g_err[0] = '\0';
+    *wg_rows = wr;
+    *wg_cols = wc;
+    return STENCIL_OK;
+}
+
+}  // extern "C"

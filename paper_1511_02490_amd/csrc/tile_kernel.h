@@ -1,0 +1,215 @@
+// The stencil skeleton's kernel (Section 2 and Figure 1 of the paper): the matrix is cut
+// into workgroups of w_r x w_c work-items; each workgroup stages its tile plus the perimeter
+// border region in local memory (LDS), waits, and every work-item folds the customising
+// function over the border region of its cells.
+//
+// Beyond the paper's one-element-per-work-item mapping, a work-item may own a CR x CC block
+// of adjacent cells (register blocking): the workgroup then covers (w_r*CR) x (w_c*CC)
+// elements, rows of the window are pulled from LDS once and reused by all the cells they
+// touch, and with CC*sizeof(T) = 16 bytes HBM and LDS traffic moves as 128-bit accesses.
+#pragma once
+#include "stencil_ops.h"
+
+namespace sk {
+
+template <class Op, class Halo, bool Static = Halo::kStatic>
+struct WeightStore;
+// Compile-time region: the weight table travels in the kernel arguments (scalar registers).
+template <class Op, class Halo>
+struct WeightStore<Op, Halo, true> {
+    static constexpr int kCount = Op::kWeights ? (Halo::N + Halo::S + 1) * (Halo::E + Halo::W + 1) : 1;
+    float v[kCount];
+    __device__ __forceinline__ float operator[](int k) const { return Op::kWeights ? v[k] : 0.0f; }
+};
+// Run-time region: table in device memory (uniform index -> scalar loads).
+template <class Op, class Halo>
+struct WeightStore<Op, Halo, false> {
+    const float *v;
+    __device__ __forceinline__ float operator[](int k) const { return Op::kWeights ? v[k] : 0.0f; }
+};
+
+template <class Op, class Halo>
+struct TileArgs {
+    const typename Op::T *in;
+    typename Op::T *out;
+    int rows, cols;
+    int tiles_c;     // tiles per row of tiles
+    int n_tiles;
+    int xcd_chunk;   // > 0: tiles are dealt to the 8 XCDs in contiguous chunks of this many
+    int pitch;       // LDS tile pitch, in staged elements
+    int vec_ok;      // rows of `in` / `out` start 16-byte aligned and cols % CC == 0
+    typename Op::T pad;
+    float scalar0;
+    Halo halo;
+    WeightStore<Op, Halo> w;
+};
+
+__host__ __device__ constexpr int round_up(int x, int m) { return (x + m - 1) / m * m; }
+__host__ __device__ constexpr int round_down(int x, int m) { return x / m * m; }
+
+// 16-byte moves between global memory / LDS and register arrays.
+template <class E, int CNT>
+__device__ __forceinline__ void load_vec(E (&dst)[CNT], const E *src) {
+    static_assert(sizeof(E) * CNT % 16 == 0, "vector moves are whole 16-byte words");
+    constexpr int NV = sizeof(E) * CNT / 16;
+    uint4 tmp[NV];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) tmp[k] = reinterpret_cast<const uint4 *>(src)[k];
+    __builtin_memcpy(dst, tmp, sizeof(tmp));
+}
+template <class E, int CNT>
+__device__ __forceinline__ void store_vec(E *dst, const E (&src)[CNT]) {
+    static_assert(sizeof(E) * CNT % 16 == 0, "vector moves are whole 16-byte words");
+    constexpr int NV = sizeof(E) * CNT / 16;
+    uint4 tmp[NV];
+    __builtin_memcpy(tmp, src, sizeof(tmp));
+#pragma unroll
+    for (int k = 0; k < NV; ++k) reinterpret_cast<uint4 *>(dst)[k] = tmp[k];
+}
+
+// Columns staged left / right of the tile: the border region's extent, widened to whole
+// 16-byte vectors when the work-items move vectors.
+template <int CC>
+__host__ __device__ constexpr int staged_halo(int h) { return CC == 1 ? h : round_up(h, CC); }
+
+template <class Op, int B, class Halo, int CR, int CC, int MAXT>
+__global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) {
+    using T = typename Op::T;
+    using L = typename Op::L;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    L *tile = reinterpret_cast<L *>(lds_raw);
+
+    const int wr = blockDim.y, wc = blockDim.x;
+    const int tx = threadIdx.x, ty = threadIdx.y;
+
+    int t = blockIdx.x;
+    if (a.xcd_chunk > 0) t = (t & 7) * a.xcd_chunk + (t >> 3);
+    if (t >= a.n_tiles) return;
+    const int tile_r = t / a.tiles_c, tile_c = t - tile_r * a.tiles_c;
+
+    const Halo h = a.halo;
+    const int hn = h.n(), hs = h.s(), he = h.e(), hw = h.w();
+    const int th = wr * CR, tw = wc * CC;
+    const int r0 = tile_r * th, c0 = tile_c * tw;
+    const int hwa = staged_halo<CC>(hw);
+    const int pitch = a.pitch;
+    const int rows = a.rows, cols = a.cols;
+    // rows of the tile that exist in the matrix, plus the border region
+    const int TH = min(th, rows - r0) + hn + hs;
+
+    // ---- stage tile + border region into LDS, resolving out-of-matrix positions ----------
+    if constexpr (CC == 1) {
+        const int TW = min(tw, cols - c0) + he + hw;
+        for (int i = ty; i < TH; i += wr) {
+            const int gr = resolve<B>(r0 - hn + i, rows);
+            for (int j = tx; j < TW; j += wc) {
+                const int gc = resolve<B>(c0 - hw + j, cols);
+                const T v = (gr < 0 || gc < 0) ? a.pad : a.in[(size_t)gr * cols + gc];
+                tile[i * pitch + j] = Op::stage(v);
+            }
+        }
+    } else {
+        const int nq = pitch / CC;
+        for (int i = ty; i < TH; i += wr) {
+            const int gr = resolve<B>(r0 - hn + i, rows);
+            for (int q = tx; q < nq; q += wc) {
+                const int gc0 = c0 - hwa + q * CC;
+                if (gc0 >= cols + he) continue;      // right of everything this tile needs
+                T v[CC];
+                if (gr >= 0 && a.vec_ok && gc0 >= 0 && gc0 + CC <= cols) {
+                    load_vec(v, a.in + (size_t)gr * cols + gc0);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < CC; ++k) {
+                        const int gc = resolve<B>(gc0 + k, cols);
+                        v[k] = (gr < 0 || gc < 0) ? a.pad : a.in[(size_t)gr * cols + gc];
+                    }
+                }
+                L sv[CC];
+#pragma unroll
+                for (int k = 0; k < CC; ++k) sv[k] = Op::stage(v[k]);
+                store_vec(tile + i * pitch + q * CC, sv);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- fold the customising function over the border region ----------------------------
+    const int lr0 = ty * CR, lc0 = tx * CC;
+    if (r0 + lr0 >= rows || c0 + lc0 >= cols) return;
+
+    typename Op::State st[CR][CC];
+#pragma unroll
+    for (int cr = 0; cr < CR; ++cr)
+#pragma unroll
+        for (int cc = 0; cc < CC; ++cc) Op::init(st[cr][cc]);
+
+    if constexpr (Halo::kStatic) {
+        constexpr int N = Halo::N, S = Halo::S, E = Halo::E, W = Halo::W;
+        constexpr int HWA = staged_halo<CC>(W);
+        constexpr int VL = CC == 1 ? 1 : (16 / (int)sizeof(L) < 1 ? 1 : 16 / (int)sizeof(L));
+        constexpr int LO = round_down(HWA - W, VL);
+        constexpr int HI = round_up(HWA + CC + E, VL);
+        constexpr int WW = HI - LO;
+        constexpr int WCOLS = E + W + 1;
+        // window rows stream through registers; row wi feeds cell-row cr with dr = wi - N - cr
+#pragma unroll
+        for (int wi = 0; wi < CR + N + S; ++wi) {
+            if (lr0 + wi >= TH) break;
+            L row[WW];
+            const L *src = tile + (lr0 + wi) * pitch + lc0 + LO;
+            if constexpr (CC == 1) {
+#pragma unroll
+                for (int k = 0; k < WW; ++k) row[k] = src[k];
+            } else {
+                load_vec(row, src);
+            }
+#pragma unroll
+            for (int cr = 0; cr < CR; ++cr) {
+                const int dr = wi - N - cr;
+                if (dr < -N || dr > S) continue;
+#pragma unroll
+                for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+                    for (int dc = -W; dc <= E; ++dc)
+                        Op::visit(st[cr][cc], dr, dc, a.w[(dr + N) * WCOLS + dc + W],
+                                  row[HWA - LO + cc + dc]);
+            }
+        }
+    } else {
+        const int wcols = he + hw + 1;
+#pragma unroll
+        for (int cr = 0; cr < CR; ++cr) {
+            if (r0 + lr0 + cr >= rows) break;
+#pragma unroll
+            for (int cc = 0; cc < CC; ++cc) {
+                const L *ctr = tile + (lr0 + cr + hn) * pitch + hwa + lc0 + cc;
+                for (int dr = -hn; dr <= hs; ++dr)
+                    for (int dc = -hw; dc <= he; ++dc)
+                        Op::visit(st[cr][cc], dr, dc, a.w[(dr + hn) * wcols + dc + hw], ctr[dr * pitch + dc]);
+            }
+        }
+    }
+
+    // ---- store ------------------------------------------------------------------------------
+#pragma unroll
+    for (int cr = 0; cr < CR; ++cr) {
+        const int r = r0 + lr0 + cr;
+        if (r >= rows) break;
+        T res[CC];
+#pragma unroll
+        for (int cc = 0; cc < CC; ++cc) res[cc] = Op::finish(st[cr][cc], a.scalar0);
+        T *dst = a.out + (size_t)r * cols + c0 + lc0;
+        if constexpr (CC > 1) {
+            if (a.vec_ok && c0 + lc0 + CC <= cols) {
+                store_vec(dst, res);
+                continue;
+            }
+        }
+#pragma unroll
+        for (int cc = 0; cc < CC; ++cc)
+            if (c0 + lc0 + cc < cols) dst[cc] = res[cc];
+    }
+}
+
+}  // namespace sk

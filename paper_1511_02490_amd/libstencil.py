@@ -1,0 +1,287 @@
+"""Thin ctypes binding over the C-ABI library (include/libstencil.h).
+
+Argument marshalling only: every step of the stencil and of the sweep runs inside
+libstencil.so.  PyTorch tensors are used for device memory and streams.  Importing this
+module loads the shared library and raises if it has not been built - there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "_lib", "libstencil.so")
+
+OK, E_INVALID, E_REFUSED, E_RESOURCES, E_HIP = 0, -1, -2, -3, -4
+F32, U8 = 0, 1
+CLAMP, WRAP, CONSTANT = 0, 1, 2
+WEIGHTED_SUM, LIFE, HEAT, SINCOS = 0, 1, 2, 3
+ENUM_POW2, ENUM_EVEN = 0, 1
+N_FEATURES = 12
+
+_DTYPES = {"f32": F32, "u8": U8}
+_BORDERS = {"clamp": CLAMP, "wrap": WRAP, "constant": CONSTANT}
+_KERNELS = {"weighted_sum": WEIGHTED_SUM, "life": LIFE, "heat": HEAT, "sincos": SINCOS}
+
+
+class StencilError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("libstencil error %d: %s" % (code, text))
+        self.code = code
+
+
+class Refused(StencilError):
+    """The workgroup size is not legal for the scenario (Section 3.1's refused parameter)."""
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libstencil.so is not built (%s missing): run `python -c 'import __graft_entry__ as g; "
+            "g.build()'` or `python paper_1511_02490_amd/build.py` first" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    c_int, c_i64, c_dbl, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
+    ip, dp, fp = ctypes.POINTER(c_int), ctypes.POINTER(c_dbl), ctypes.POINTER(ctypes.c_float)
+    sig = {
+        "stencil_create": (c_int, [ctypes.POINTER(vp), c_i64, c_i64, c_int, c_int, c_int, c_int, c_int, c_int]),
+        "stencil_destroy": (None, [vp]),
+        "stencil_set_kernel": (c_int, [vp, c_int, fp, c_int, fp, c_int]),
+        "stencil_set_border_value": (c_int, [vp, c_dbl]),
+        "stencil_set_blocking": (c_int, [vp, c_int, c_int]),
+        "stencil_get_blocking": (c_int, [vp, ip, ip]),
+        "stencil_max_wg_size": (c_int, [vp]),
+        "stencil_tile_bytes": (c_i64, [vp, c_int, c_int]),
+        "stencil_is_legal": (c_int, [vp, c_int, c_int]),
+        "stencil_enumerate_wg": (c_int, [c_int, c_int, ip, ip, c_int]),
+        "stencil_run": (c_int, [vp, vp, vp, c_int, c_int, c_int, vp]),
+        "stencil_sweep_wg": (c_int, [vp, vp, vp, c_int, ip, ip, c_int, c_int, c_int, c_int,
+                                     dp, dp, dp, dp, ip, ip, dp, vp]),
+        "stencil_sweep_reduce": (c_int, [ip, ip, c_int, dp, ip, c_dbl, ip, dp, dp]),
+        "stencil_features": (c_int, [vp, dp]),
+        "stencil_predictor_create": (c_int, [ctypes.POINTER(vp)]),
+        "stencil_predictor_destroy": (None, [vp]),
+        "stencil_predictor_add": (c_int, [vp, dp, c_int, c_int, c_int]),
+        "stencil_predictor_classify": (c_int, [vp, dp, c_int, ip, ip]),
+        "stencil_predict_wg": (c_int, [vp, vp, ip, ip, c_int, ip, ip]),
+        "stencil_last_error": (ctypes.c_char_p, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)          # AttributeError if the library lacks a declared symbol
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+_lib = _load()
+EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
+           "stencil_set_blocking", "stencil_get_blocking", "stencil_max_wg_size", "stencil_tile_bytes",
+           "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg",
+           "stencil_sweep_reduce", "stencil_features", "stencil_predictor_create",
+           "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
+           "stencil_predict_wg", "stencil_last_error")
+
+
+def last_error() -> str:
+    return _lib.stencil_last_error().decode()
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise (Refused if rc == E_REFUSED else StencilError)(rc, last_error())
+    return rc
+
+
+def _ints(vals: Sequence[int]):
+    return (ctypes.c_int * len(vals))(*[int(v) for v in vals])
+
+
+def _dbls(vals: Sequence[float]):
+    return (ctypes.c_double * len(vals))(*[float(v) for v in vals])
+
+
+def enumerate_wg(mode: str = "pow2", max_threads: int = 1024) -> List[Tuple[int, int]]:
+    m = ENUM_POW2 if mode == "pow2" else ENUM_EVEN if mode == "even" else int(mode)
+    n = _check(_lib.stencil_enumerate_wg(m, max_threads, None, None, 0))
+    r, c = (ctypes.c_int * n)(), (ctypes.c_int * n)()
+    _check(_lib.stencil_enumerate_wg(m, max_threads, r, c, n))
+    return list(zip(r, c))
+
+
+def sweep_reduce(sizes: Sequence[Tuple[int, int]], mean_ms: Sequence[float], status: Sequence[int],
+                 fixed_ms: float = float("nan")):
+    n = len(sizes)
+    best, sp = ctypes.c_int(-1), ctypes.c_double(float("nan"))
+    perf = (ctypes.c_double * max(n, 1))()
+    _check(_lib.stencil_sweep_reduce(_ints([s[0] for s in sizes]), _ints([s[1] for s in sizes]), n,
+                                     _dbls(mean_ms), _ints(status), float(fixed_ms),
+                                     ctypes.byref(best), perf, ctypes.byref(sp)))
+    return best.value, list(perf)[:n], sp.value
+
+
+class SweepResult:
+    def __init__(self, sizes, mean_ms, min_ms, median_ms, stddev_ms, status, best_index, speedup):
+        self.sizes, self.mean_ms, self.min_ms = sizes, mean_ms, min_ms
+        self.median_ms, self.stddev_ms, self.status = median_ms, stddev_ms, status
+        self.best_index, self.speedup_over_fixed = best_index, speedup
+
+    @property
+    def best(self) -> Optional[Tuple[int, int]]:
+        return self.sizes[self.best_index] if self.best_index >= 0 else None
+
+    @property
+    def best_ms(self) -> float:
+        return self.mean_ms[self.best_index] if self.best_index >= 0 else float("nan")
+
+    def legal(self):
+        return [(s, t) for s, t, st in zip(self.sizes, self.mean_ms, self.status) if st == OK]
+
+    @property
+    def worst_ms(self) -> float:
+        ts = [t for _, t in self.legal()]
+        return max(ts) if ts else float("nan")
+
+    def ms_of(self, size) -> float:
+        for s, t, st in zip(self.sizes, self.mean_ms, self.status):
+            if tuple(s) == tuple(size) and st == OK:
+                return t
+        return float("nan")
+
+
+class Stencil:
+    """One scenario: matrix size and type, border region, border mode, customising function."""
+
+    def __init__(self, rows: int, cols: int, dtype: str = "f32", halo: Sequence[int] = (1, 1, 1, 1),
+                 border: str = "clamp", pad: float = 0.0):
+        self._h = ctypes.c_void_p()
+        n, s, e, w = (int(x) for x in halo)
+        dt = _DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
+        bm = _BORDERS[border] if isinstance(border, str) else int(border)
+        _check(_lib.stencil_create(ctypes.byref(self._h), int(rows), int(cols), dt, n, s, e, w, bm))
+        self.rows, self.cols, self.dtype, self.halo = int(rows), int(cols), dtype, (n, s, e, w)
+        if pad:
+            self.set_border_value(pad)
+
+    @classmethod
+    def from_workload(cls, wl) -> "Stencil":
+        st = cls(wl.rows, wl.cols, wl.dtype, wl.halo, wl.border, wl.pad)
+        st.set_kernel(wl.kernel, wl.weights, wl.scalars)
+        return st
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            _lib.stencil_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = close
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    # -- configuration ---------------------------------------------------------------------
+    def set_kernel(self, kernel, weights=None, scalars: Sequence[float] = ()):
+        kid = _KERNELS[kernel] if isinstance(kernel, str) else int(kernel)
+        wbuf, nw = None, 0
+        if weights is not None:
+            import numpy as np
+            flat = np.asarray(weights, dtype=np.float32).ravel()
+            nw = int(flat.size)
+            wbuf = (ctypes.c_float * nw)(*flat.tolist())
+        sc = (ctypes.c_float * max(1, len(scalars)))(*[float(x) for x in scalars])
+        _check(_lib.stencil_set_kernel(self._h, kid, wbuf, nw, sc, len(scalars)))
+
+    def set_border_value(self, v: float):
+        _check(_lib.stencil_set_border_value(self._h, float(v)))
+
+    def set_blocking(self, cells_rows: int, cells_cols: int):
+        _check(_lib.stencil_set_blocking(self._h, int(cells_rows), int(cells_cols)))
+
+    def get_blocking(self) -> Tuple[int, int]:
+        a, b = ctypes.c_int(), ctypes.c_int()
+        _check(_lib.stencil_get_blocking(self._h, ctypes.byref(a), ctypes.byref(b)))
+        return a.value, b.value
+
+    # -- legality ----------------------------------------------------------------------------
+    def max_wg_size(self) -> int:
+        return _check(_lib.stencil_max_wg_size(self._h))
+
+    def tile_bytes(self, wg_rows: int, wg_cols: int) -> int:
+        return _check(_lib.stencil_tile_bytes(self._h, int(wg_rows), int(wg_cols)))
+
+    def is_legal(self, wg_rows: int, wg_cols: int) -> bool:
+        return bool(_lib.stencil_is_legal(self._h, int(wg_rows), int(wg_cols)))
+
+    def features(self) -> List[float]:
+        f = (ctypes.c_double * N_FEATURES)()
+        _check(_lib.stencil_features(self._h, f))
+        return list(f)
+
+    # -- execution ---------------------------------------------------------------------------
+    @staticmethod
+    def _stream_ptr(stream):
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream()
+        return ctypes.c_void_p(getattr(stream, "cuda_stream", stream))
+
+    def _check_tensors(self, tin, tout):
+        import torch
+        want = torch.float32 if self.dtype in ("f32", F32) else torch.uint8
+        for t in (tin, tout):
+            if not t.is_cuda or not t.is_contiguous() or t.dtype != want or t.numel() != self.rows * self.cols:
+                raise ValueError("tensors must be contiguous CUDA %s of %d x %d" % (want, self.rows, self.cols))
+
+    def run(self, tin, tout, iters: int = 1, wg: Tuple[int, int] = (0, 0), stream=None):
+        self._check_tensors(tin, tout)
+        _check(_lib.stencil_run(self._h, ctypes.c_void_p(tin.data_ptr()), ctypes.c_void_p(tout.data_ptr()),
+                                int(iters), int(wg[0]), int(wg[1]), self._stream_ptr(stream)))
+        return tout
+
+    def sweep(self, tin, tout, sizes: Sequence[Tuple[int, int]], iters: int = 1,
+              fixed: Tuple[int, int] = (4, 4), reps: int = 30, stream=None) -> SweepResult:
+        self._check_tensors(tin, tout)
+        n = len(sizes)
+        arr = lambda: (ctypes.c_double * max(n, 1))()
+        mean, mn, med, sd = arr(), arr(), arr(), arr()
+        status = (ctypes.c_int * max(n, 1))()
+        best, sp = ctypes.c_int(-1), ctypes.c_double(float("nan"))
+        _check(_lib.stencil_sweep_wg(self._h, ctypes.c_void_p(tin.data_ptr()), ctypes.c_void_p(tout.data_ptr()),
+                                     int(iters), _ints([s[0] for s in sizes]), _ints([s[1] for s in sizes]), n,
+                                     int(fixed[0]), int(fixed[1]), int(reps), mean, mn, med, sd, status,
+                                     ctypes.byref(best), ctypes.byref(sp), self._stream_ptr(stream)))
+        return SweepResult([tuple(s) for s in sizes], list(mean)[:n], list(mn)[:n], list(med)[:n],
+                           list(sd)[:n], list(status)[:n], best.value, sp.value)
+
+    def predict(self, predictor: "Predictor", candidates: Sequence[Tuple[int, int]]) -> Tuple[int, int]:
+        wr, wc = ctypes.c_int(), ctypes.c_int()
+        _check(_lib.stencil_predict_wg(self._h, predictor._h, _ints([c[0] for c in candidates]),
+                                       _ints([c[1] for c in candidates]), len(candidates),
+                                       ctypes.byref(wr), ctypes.byref(wc)))
+        return wr.value, wc.value
+
+
+class Predictor:
+    """Nearest-neighbour classifier over (f(s), Omega(s)) pairs (Section 4.1)."""
+
+    def __init__(self):
+        self._h = ctypes.c_void_p()
+        _check(_lib.stencil_predictor_create(ctypes.byref(self._h)))
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            _lib.stencil_predictor_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = close
+
+    def add(self, features: Sequence[float], wg: Tuple[int, int]):
+        _check(_lib.stencil_predictor_add(self._h, _dbls(features), len(features), int(wg[0]), int(wg[1])))
+
+    def classify(self, features: Sequence[float]) -> Tuple[int, int]:
+        wr, wc = ctypes.c_int(), ctypes.c_int()
+        _check(_lib.stencil_predictor_classify(self._h, _dbls(features), len(features),
+                                               ctypes.byref(wr), ctypes.byref(wc)))
+        return wr.value, wc.value

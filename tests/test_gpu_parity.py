@@ -1,0 +1,338 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Bar: bit-exact for the integer (Life) kernel; max relative error <= 1e-5 per application and
+<= 1e-4 after iterated runs for fp32.  The heat kernel is specified as a fixed sequence of
+fp32 operations, so for it the GPU is additionally required to match the fp32 oracle exactly.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import stencil as oracle
+from paper_1511_02490_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+REL_1 = 1e-5       # one application
+REL_N = 1e-4       # after iterated runs
+
+
+@pytest.fixture(scope="module")
+def ls():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1511_02490_amd import libstencil
+    return libstencil
+
+
+def rel_err(got, ref):
+    got = got.astype(np.float64)
+    ref = ref.astype(np.float64)
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-6)))
+
+
+def gpu_apply(ls, w, grid, wg, iters=None, blocking=(1, 1), offset=0):
+    """Run workload `w` on `grid` through the library.  offset > 0 places the matrices that many
+    elements into their allocations, so that rows are not 16-byte aligned."""
+    st = ls.Stencil.from_workload(w)
+    st.set_blocking(*blocking)
+    n = grid.size
+    tdt = torch.float32 if w.dtype == "f32" else torch.uint8
+    buf_in = torch.zeros(n + offset, dtype=tdt, device="cuda")
+    buf_out = torch.full((n + offset,), 7, dtype=tdt, device="cuda")
+    tin, tout = buf_in[offset:], buf_out[offset:]
+    tin.copy_(torch.from_numpy(grid.reshape(-1)))
+    st.run(tin, tout, w.iters if iters is None else iters, wg)
+    torch.cuda.synchronize()
+    assert np.array_equal(tin.cpu().numpy().reshape(grid.shape), grid), "input was modified"
+    out = tout.cpu().numpy().reshape(grid.shape)
+    st.close()
+    return out
+
+
+def check(ls, w, wg, iters=None, blocking=(1, 1), offset=0, grid=None):
+    g = w.grid() if grid is None else grid
+    it = w.iters if iters is None else iters
+    ref = oracle.apply(g, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, it)
+    got = gpu_apply(ls, w, g, wg, it, blocking, offset)
+    if w.dtype == "u8":
+        np.testing.assert_array_equal(got, ref)
+    else:
+        tol = REL_1 if it <= 1 else REL_N
+        err = rel_err(got, ref)
+        assert err <= tol, "rel err %.3g > %.1g (wg %s blocking %s)" % (err, tol, wg, blocking)
+        if w.kernel == wl.HEAT:
+            np.testing.assert_array_equal(got, ref)
+    return got
+
+
+def custom(kernel, rows, cols, halo, border, pad=0.0, seed=1, iters=1):
+    """A workload of the synthetic family: any border region, any border mode."""
+    n, s, e, w_ = halo
+    rng = np.random.default_rng(seed)
+    weights = None
+    dtype = "f32"
+    scalars = ()
+    if kernel in (wl.WEIGHTED_SUM, wl.SINCOS):
+        weights = rng.random((n + s + 1, e + w_ + 1), dtype=np.float32)
+        if kernel == wl.WEIGHTED_SUM:
+            weights /= weights.sum()
+    if kernel == wl.HEAT:
+        scalars = (0.2,)
+    if kernel == wl.LIFE:
+        dtype = "u8"
+    return wl.Workload("custom", rows, cols, dtype, halo, border, pad, kernel, iters, seed, "pow2",
+                       weights=weights, scalars=scalars)
+
+
+# ---- C1: the small configuration, whole matrix, every listed size ----------------------------
+
+def test_c1_all_listed_sizes(ls):
+    w = wl.config(0)
+    for wg in w.wg_sizes():
+        check(ls, w, wg)
+    for blocking in ((4, 4), (2, 1), (1, 4)):
+        check(ls, w, (8, 8), blocking=blocking)
+
+
+# ---- every kernel x border mode x blocking, ragged matrices spanning several tiles -----------
+
+BLOCKINGS_F32 = [(1, 1), (2, 1), (8, 1), (1, 4), (4, 4), (8, 4)]
+
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+@pytest.mark.parametrize("halo", [(1, 1, 1, 1), (2, 2, 2, 2), (2, 1, 2, 2), (0, 0, 0, 0), (7, 3, 9, 5)])
+def test_weighted_sum_borders_and_regions(ls, border, halo):
+    w = custom(wl.WEIGHTED_SUM, 131, 157, halo, border, pad=0.5, seed=sum(halo))
+    for blocking in BLOCKINGS_F32:
+        for wg in [(4, 4), (16, 16), (3, 21), (2, 64)]:
+            check(ls, w, wg, blocking=blocking)
+    # aligned rows (vector path), misaligned base pointer, and cols % 4 != 0
+    w2 = custom(wl.WEIGHTED_SUM, 96, 128, halo, border, pad=0.5, seed=3)
+    for off in (0, 1):
+        check(ls, w2, (8, 16), blocking=(4, 4), offset=off)
+
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_sincos_borders(ls, border):
+    for halo in [(1, 5, 3, 0), (2, 0, 1, 3)]:
+        w = custom(wl.SINCOS, 93, 140, halo, border, pad=0.3, seed=5)
+        for blocking in [(1, 1), (4, 1), (2, 4), (8, 4)]:
+            for wg in [(4, 4), (8, 16), (6, 10)]:
+                check(ls, w, wg, blocking=blocking)
+
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_life_bit_exact(ls, border):
+    for rows, cols in [(150, 203), (64, 256)]:
+        w = wl.config(2, rows=rows, cols=cols, iters=12)
+        w.border = border
+        for blocking in [(1, 1), (4, 1), (1, 16), (2, 16)]:
+            for wg in [(4, 4), (16, 16), (2, 64), (5, 7)]:
+                check(ls, w, wg, blocking=blocking)
+    w1 = wl.config(2, rows=97, cols=61, iters=1)
+    w1.border, w1.pad = "constant", 1.0              # live padding
+    check(ls, w1, (8, 8))
+
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_heat_matches_fp32_oracle_exactly(ls, border):
+    w = wl.config(3, rows=160, cols=216, iters=25)
+    w.border, w.pad = border, 50.0
+    for blocking in [(1, 1), (4, 1), (1, 4), (8, 4)]:
+        for wg in [(4, 4), (16, 16), (4, 64), (7, 9)]:
+            check(ls, w, wg, blocking=blocking)
+
+
+def test_heat_conserves_total_and_long_run(ls):
+    w = wl.config(3, rows=256, cols=256, iters=1000)
+    g = w.grid()
+    got = check(ls, w, (4, 64), blocking=(4, 4), grid=g)
+    s0, s1 = g.astype(np.float64).sum(), got.astype(np.float64).sum()
+    assert abs(s1 - s0) / s0 < 1e-6
+    assert got.min() >= g.min() and got.max() <= g.max()
+
+
+# ---- gold standard (Section 5): every workgroup size gives the output of the baseline size ---
+
+@pytest.mark.parametrize("index", [1, 2, 3, 4])
+def test_every_swept_size_matches_baseline_output(ls, index):
+    rows, cols = (300, 260)
+    w = wl.config(index, rows=rows, cols=cols, iters=3 if index in (2, 3) else 1)
+    g = w.grid()
+    base = gpu_apply(ls, w, g, (4, 4))
+    sizes = wl.enumerate_wg("pow2") if index != 4 else wl.enumerate_wg("even")[::7]
+    for blocking in [(1, 1), (4, 16 if w.dtype == "u8" else 4)]:
+        st = ls.Stencil.from_workload(w)
+        st.set_blocking(*blocking)
+        tdt = torch.float32 if w.dtype == "f32" else torch.uint8
+        tin = torch.from_numpy(g).cuda()
+        tout = torch.empty_like(tin)
+        assert tin.dtype == tdt
+        n_run = 0
+        for wg in sizes:
+            if not st.is_legal(*wg):
+                with pytest.raises(ls.Refused):
+                    st.run(tin, tout, w.iters, wg)
+                continue
+            tout.fill_(9)
+            st.run(tin, tout, w.iters, wg)
+            np.testing.assert_array_equal(tout.cpu().numpy(), base, err_msg="wg %s blocking %s" % (wg, blocking))
+            n_run += 1
+        assert n_run >= len(sizes) // 2
+        st.close()
+
+
+# ---- degenerate shapes and the error paths ----------------------------------------------------
+
+@pytest.mark.parametrize("shape", [(1, 1), (1, 37), (41, 1), (2, 3), (5, 4)])
+def test_tiny_matrices_smaller_than_the_region(ls, shape):
+    for border in ("clamp", "wrap", "constant"):
+        w = custom(wl.WEIGHTED_SUM, shape[0], shape[1], (3, 2, 4, 1), border, pad=0.25, seed=11)
+        for blocking in [(1, 1), (4, 4)]:
+            check(ls, w, (4, 8), blocking=blocking)
+        wlife = wl.config(2, rows=shape[0], cols=shape[1], iters=3)
+        wlife.border = border
+        check(ls, wlife, (2, 2))
+        check(ls, wlife, (4, 4), blocking=(2, 16))
+
+
+def test_iters_zero_copies_and_even_odd_iteration_counts(ls):
+    w = wl.config(3, rows=64, cols=80)
+    g = w.grid()
+    np.testing.assert_array_equal(gpu_apply(ls, w, g, (4, 4), iters=0), g)
+    for it in (1, 2, 3, 4):
+        check(ls, w, (8, 8), iters=it)
+
+
+def test_error_paths_do_not_launch(ls):
+    w = wl.config(1, rows=64, cols=64)
+    st = ls.Stencil.from_workload(w)
+    tin = torch.from_numpy(w.grid()).cuda()
+    tout = torch.full_like(tin, -1.0)
+    for wg in [(64, 32), (2048, 1), (0, 4), (-1, 4)]:
+        with pytest.raises(ls.Refused):
+            st.run(tin, tout, 1, wg)
+    torch.cuda.synchronize()
+    assert float(tout.max()) == -1.0                               # nothing ran
+    with pytest.raises(ls.StencilError) as e:
+        st.run(tin, tin, 1, (4, 4))                                # aliasing
+    assert e.value.code == ls.E_INVALID
+    both = torch.zeros(64 * 64 + 32, device="cuda")
+    with pytest.raises(ls.StencilError):
+        st.run(both[:4096], both[32:], 1, (4, 4))                  # partial overlap
+    with pytest.raises(ls.StencilError):
+        st.run(tin, tout, -1, (4, 4))
+    st.run(tin, tout, 1, (0, 0))                                   # library's own choice
+    torch.cuda.synchronize()
+    ref = oracle.apply_workload(w)
+    assert rel_err(tout.cpu().numpy(), ref) <= REL_1
+
+
+def test_runs_on_a_side_stream(ls):
+    w = wl.config(0)
+    g = w.grid()
+    st = ls.Stencil.from_workload(w)
+    side = torch.cuda.Stream()
+    tin = torch.from_numpy(g).cuda()
+    tout = torch.empty_like(tin)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        st.run(tin, tout, 1, (8, 8))
+    side.synchronize()
+    assert rel_err(tout.cpu().numpy(), oracle.apply_workload(w, g)) <= REL_1
+
+
+# ---- the sweep (Section 5) ---------------------------------------------------------------------
+
+def test_sweep_reports_times_best_and_refusals(ls):
+    w = wl.config(1, rows=512, cols=512)
+    st = ls.Stencil.from_workload(w)
+    tin = torch.from_numpy(w.grid()).cuda()
+    tout = torch.empty_like(tin)
+    sizes = [(4, 4), (8, 8), (16, 16), (64, 4), (4, 64), (64, 32), (1, 1024), (1024, 1)]
+    res = st.sweep(tin, tout, sizes, iters=1, fixed=(32, 4), reps=30)
+    assert res.status[5] == ls.E_REFUSED and np.isnan(res.mean_ms[5])
+    ok = [i for i, s in enumerate(res.status) if s == ls.OK]
+    assert ok == [0, 1, 2, 3, 4, 6, 7]
+    for i in ok:
+        assert res.mean_ms[i] > 0 and res.min_ms[i] <= res.median_ms[i] and res.min_ms[i] <= res.mean_ms[i]
+        assert res.stddev_ms[i] >= 0
+    assert res.best_index == int(np.nanargmin(res.mean_ms))
+    assert res.speedup_over_fixed > 0
+    # the reductions agree with the oracle's definitions on the measured table
+    from oracle import tuning
+    assert res.best_index == tuning.oracle_size(sizes, res.mean_ms, [s == ls.OK for s in res.status])
+    # the last sample's output is still the stencil's output
+    torch.cuda.synchronize()
+    assert rel_err(tout.cpu().numpy(), oracle.apply_workload(w)) <= REL_1
+    # (0, 0) now means the sweep's best size
+    st.run(tin, tout, 1, (0, 0))
+    torch.cuda.synchronize()
+    assert rel_err(tout.cpu().numpy(), oracle.apply_workload(w)) <= REL_1
+
+
+# ---- full-size configurations, in the launch configuration bench.py times ---------------------
+
+def test_c2_full_size(ls):
+    w = wl.config(1)
+    g = w.grid()
+    ref = oracle.apply_workload(w, g)
+    for wg, blocking in [((16, 16), (1, 1)), ((4, 64), (4, 4))]:
+        got = gpu_apply(ls, w, g, wg, blocking=blocking)
+        assert rel_err(got, ref) <= REL_1
+
+
+def test_c3_full_size_100_generations(ls):
+    w = wl.config(2)
+    g = w.grid()
+    ref = oracle.apply_workload(w, g)
+    got = gpu_apply(ls, w, g, (4, 64), blocking=(2, 16))
+    np.testing.assert_array_equal(got, ref)
+    assert 0.02 < got.mean() < 0.2
+
+
+def test_c4_full_size(ls):
+    """100 of the 1000 steps against the oracle element by element; the full 1000 steps
+    checked by properties that hold at any size (conservation, range) and by agreement of two
+    launch configurations."""
+    w = wl.config(3)
+    g = w.grid()
+    ref = oracle.apply_workload(w, g, iters=100)
+    got = gpu_apply(ls, w, g, (4, 64), iters=100, blocking=(4, 4))
+    np.testing.assert_array_equal(got, ref)
+    a = gpu_apply(ls, w, g, (4, 64), iters=1000, blocking=(4, 4))
+    b = gpu_apply(ls, w, g, (16, 16), iters=1000, blocking=(1, 1))
+    np.testing.assert_array_equal(a, b)
+    s0, s1 = g.astype(np.float64).sum(), a.astype(np.float64).sum()
+    assert abs(s1 - s0) / s0 < 1e-6
+    assert a.min() >= g.min() and a.max() <= g.max()
+
+
+def test_c5_full_size_sampled_windows(ls):
+    """8192^2: the oracle evaluates windows (matrix corners, edges and interior) one by one.
+    A window that starts at the matrix's north/west edge, or ends at its south/east edge, sees
+    the same padding in the oracle as in the full matrix; interior windows are compared away
+    from their own rims."""
+    w = wl.config(4)
+    g = w.grid()
+    got = gpu_apply(ls, w, g, (2, 64), blocking=(4, 4))
+    got1 = gpu_apply(ls, w, g, (16, 16), blocking=(1, 1))
+    np.testing.assert_array_equal(got, got1)
+    N, S, E, W = w.halo
+    R, C = w.rows, w.cols
+    rng = np.random.default_rng(99)
+    spans = [(0, 0), (0, C - 96), (R - 96, 0), (R - 96, C - 96), (0, 4000), (4000, 0), (R - 96, 3000)]
+    spans += [(int(rng.integers(100, R - 200)), int(rng.integers(100, C - 200))) for _ in range(10)]
+    worst = 0.0
+    for r0, c0 in spans:
+        sub = g[r0:r0 + 96, c0:c0 + 96]
+        ref = oracle.apply(sub, w.kernel, w.halo, w.border, w.pad, w.weights)
+        lo_r = 0 if r0 == 0 else N
+        hi_r = 96 if r0 + 96 == R else 96 - S
+        lo_c = 0 if c0 == 0 else W
+        hi_c = 96 if c0 + 96 == C else 96 - E
+        err = rel_err(got[r0 + lo_r:r0 + hi_r, c0 + lo_c:c0 + hi_c], ref[lo_r:hi_r, lo_c:hi_c])
+        worst = max(worst, err)
+    assert worst <= REL_1, worst

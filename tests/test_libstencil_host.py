@@ -1,0 +1,142 @@
+"""Host-side logic of the C-ABI library, checked without a GPU: the library loads and exports
+every declared symbol; enumeration, legality (Eq. 1), sweep reductions (Eq. 3, Section 7) and
+prediction (Algorithm 1) agree with the oracle's definitions and with hand-worked cases."""
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import tuning
+from paper_1511_02490_amd import libstencil as ls
+from paper_1511_02490_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "libstencil.h")).read()
+    declared = set(re.findall(r"\b(stencil_[a-z_]+)\s*\(", header))
+    declared -= {"stencil_t", "stencil_predictor_t"}
+    assert declared == set(ls.EXPORTS)
+    import ctypes
+    lib = ctypes.CDLL(ls.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("mode,count", [("pow2", 66), ("even", 590)])
+def test_enumeration_matches_definition(mode, count):
+    got = ls.enumerate_wg(mode, 1024)
+    assert len(got) == count
+    assert got == tuning.enumerate_sizes(mode, 1024) == wl.enumerate_wg(mode, 1024)
+    assert ls.enumerate_wg(mode, 256) == tuning.enumerate_sizes(mode, 256)
+
+
+def test_create_validates_arguments():
+    for bad in [dict(rows=0, cols=4), dict(rows=4, cols=-1), dict(rows=1 << 20, cols=1 << 20)]:
+        with pytest.raises(ls.StencilError) as e:
+            ls.Stencil(bad["rows"], bad["cols"])
+        assert e.value.code == ls.E_INVALID
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(8, 8, halo=(1, 1, 33, 1))
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(8, 8, halo=(1, -1, 1, 1))
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(8, 8, border=7)
+    st = ls.Stencil(8, 8, "u8")
+    with pytest.raises(ls.StencilError):
+        st.set_kernel("heat", scalars=(0.2,))            # heat needs f32
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(8, 8, "f32", (2, 2, 2, 2)).set_kernel("heat", scalars=(0.2,))   # 5-point only
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(8, 8, "f32", (1, 1, 1, 1)).set_kernel("weighted_sum", np.ones((3, 2), np.float32))
+    assert "weights" in ls.last_error()
+
+
+def test_legality_eq1():
+    st = ls.Stencil.from_workload(wl.config(1))          # 5x5 gaussian, halo 2
+    assert st.max_wg_size() == 1024
+    cands = tuning.enumerate_sizes("pow2", 2048)
+    for w in cands:
+        tile_ok = st.tile_bytes(*w) <= 65536
+        assert st.is_legal(*w) == (tuning.is_legal(w, 1024) and tile_ok)
+    assert not st.is_legal(0, 4) and not st.is_legal(4, 0) and not st.is_legal(-2, 2)
+    # the tile of Section 2: (w_r + N + S) x (w_c + E + W) elements of 4 bytes
+    assert st.tile_bytes(16, 16) == tuning.tile_elements((16, 16), (2, 2, 2, 2)) * 4
+    # a refused parameter: inside W_max, but the tile does not fit local memory
+    big = ls.Stencil(4096, 4096, "f32", (30, 30, 30, 30), "clamp")
+    big.set_kernel("weighted_sum", np.zeros((61, 61), np.float32))
+    assert 32 * 32 <= big.max_wg_size()
+    assert big.tile_bytes(32, 32) == (32 + 60) * (32 + 60) * 4 and big.is_legal(32, 32)
+    assert big.tile_bytes(64, 16) == (64 + 60) * (16 + 60) * 4 and big.is_legal(64, 16)
+    assert big.tile_bytes(8, 128) == (8 + 60) * (128 + 60) * 4 and big.is_legal(8, 128)
+    big.set_blocking(4, 4)
+    assert not big.is_legal(32, 32)                      # (128+60) x (128+64) floats > 64 KiB
+    assert "refused" in ls.last_error()
+
+
+def test_blocking_changes_tile_and_per_kernel_limit():
+    st = ls.Stencil.from_workload(wl.config(4))          # sincos N1 S5 E3 W0
+    assert st.get_blocking() == (1, 1)
+    assert st.tile_bytes(32, 8) == tuning.tile_elements((32, 8), (1, 5, 3, 0)) * 8   # (sin, cos) pairs
+    st.set_blocking(8, 4)
+    assert st.get_blocking() == (8, 4)
+    assert st.max_wg_size() == 256                       # register-heavy variant: lower per-kernel limit
+    assert st.is_legal(2, 64) and not st.is_legal(8, 64)          # 512 work-items > 256
+    assert not st.is_legal(4, 64)                                 # 38 x 260 (sin, cos) pairs > 64 KiB
+    with pytest.raises(ls.StencilError):
+        st.set_blocking(3, 4)
+
+
+def test_sweep_reduce_matches_definitions():
+    rng = np.random.default_rng(0)
+    for trial in range(20):
+        sizes = tuning.enumerate_sizes("pow2", 1024)
+        ms = rng.choice([0.5, 1.0, 2.0, 3.0, 7.5], size=len(sizes)).tolist()
+        ok = (rng.random(len(sizes)) > 0.2).tolist()
+        status = [ls.OK if o else ls.E_REFUSED for o in ok]
+        ms = [m if o else float("nan") for m, o in zip(ms, ok)]
+        fixed_ms = float(rng.choice([4.0, float("nan")]))
+        best, perf, sp = ls.sweep_reduce(sizes, ms, status, fixed_ms)
+        assert best == tuning.oracle_size(sizes, ms, ok)
+        ref_perf = tuning.performance(ms, ok, best)
+        for a, b in zip(perf, ref_perf):
+            assert (math.isnan(a) and math.isnan(b)) or a == b
+        if math.isnan(fixed_ms):
+            assert math.isnan(sp)
+        else:
+            assert sp == tuning.speedup(fixed_ms, ms[best])
+    # by inspection
+    best, perf, sp = ls.sweep_reduce([(4, 4), (8, 8), (64, 4)], [4.0, 2.0, 1.0], [0, 0, 0], 4.0)
+    assert best == 2 and perf == [0.25, 0.5, 1.0] and sp == 4.0
+    best, perf, sp = ls.sweep_reduce([(4, 4)], [float("nan")], [ls.E_REFUSED], 1.0)
+    assert best == -1 and math.isnan(sp)
+
+
+def test_features_and_prediction_algorithm1():
+    scen = [ls.Stencil.from_workload(wl.config(i)) for i in range(5)]
+    feats = [s.features() for s in scen]
+    assert feats[1][:9] == [2048.0, 2048.0, 4.0, 2.0, 2.0, 2.0, 2.0, 25.0, 0.0]
+    assert feats[2][2] == 1.0 and feats[4][8] == 1.0 and feats[4][7] == 28.0
+    labels = [(8, 8), (4, 64), (16, 16), (2, 128), (64, 32)]      # the last is above any W_max
+    pred = ls.Predictor()
+    for f, w in zip(feats, labels):
+        pred.add(f, w)
+    probe = ls.Stencil(2000, 2100, "f32", (2, 2, 2, 2), "clamp")
+    probe.set_kernel("weighted_sum", np.zeros((5, 5), np.float32))
+    assert pred.classify(probe.features()) == tuning.classify_1nn(feats, labels, probe.features()) == (4, 64)
+    cands = tuning.enumerate_sizes("pow2", 1024)
+    assert probe.predict(pred, cands) == (4, 64)                  # legal: returned as classified
+    # a scenario whose nearest training label is illegal falls back to the closest legal size
+    probe2 = ls.Stencil(8000, 8000, "f32", (1, 5, 3, 0), "constant")
+    probe2.set_kernel("sincos", np.zeros((7, 4), np.float32))
+    assert pred.classify(probe2.features()) == (64, 32)
+    legal = [c for c in cands if probe2.is_legal(*c)]
+    expect = tuning.predict_nearest_neighbour((64, 32), legal, 1024)
+    assert probe2.predict(pred, cands) == expect == (64, 16)      # distance 16; (32,32) is 32 away
+    with pytest.raises(ls.Refused):
+        probe2.predict(pred, [(2048, 1)])
+    with pytest.raises(ls.StencilError):
+        ls.Predictor().classify(feats[0])
