@@ -28,12 +28,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# blocking tried besides the paper's one-element-per-work-item mapping, per kernel
-TUNED_BLOCKINGS = {
-    "weighted_sum": [(4, 4), (8, 4), (2, 4)],
-    "heat": [(4, 4), (8, 4), (2, 4)],
-    "sincos": [(4, 4), (2, 4), (8, 4)],
-    "life": [(2, 16), (4, 16), (1, 16)],
+# mappings swept besides the paper's one element per work-item with a local-memory tile:
+# (staging, cells_rows, cells_cols)
+MAPPINGS = {
+    "weighted_sum": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("direct", 1, 4), ("direct", 2, 4)],
+    "heat": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("direct", 1, 4), ("direct", 2, 4)],
+    "sincos": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("local", 8, 4)],
+    "life": [("local", 1, 1), ("local", 1, 16), ("local", 2, 16), ("direct", 1, 16), ("direct", 2, 16)],
 }
 
 
@@ -42,7 +43,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = per-workload default)")
     ap.add_argument("--warmup", type=int, default=-1)
-    ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--reps", type=int, default=30, help="timed samples per workgroup size in the sweep")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -76,8 +77,9 @@ def cpu_baseline(wl_mod, w, target_seconds):
     import numpy as np
     threads = oracle.max_threads()
     g = w.grid()
-    rows_cal = min(w.rows, 256)
+    rows_cal = min(w.rows, 1024)
     sub = np.ascontiguousarray(g[:rows_cal])
+    oracle.apply(sub[:64], w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1)   # load, spawn threads
     t0 = time.perf_counter()
     oracle.apply(sub, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1)
     t_cal = max(time.perf_counter() - t0, 1e-4)
@@ -132,20 +134,19 @@ def main():
     st = ls.Stencil.from_workload(w)
     t_sweep0 = time.perf_counter()
     sweeps = {}
-    best = None   # (ms, blocking, wg)
-    blockings = [(1, 1)] + TUNED_BLOCKINGS[w.kernel]
-    for blocking in blockings:
-        st.set_blocking(*blocking)
+    best = None   # (ms, mapping, wg)
+    for mapping in MAPPINGS[w.kernel]:
+        st.set_mapping(*mapping)
         res = st.sweep(tin, tout, sizes, iters=burst, fixed=(4, 4), reps=args.reps)
         summ, _ = sweep_summary(res, cells_per_sample)
         summ["w_max"] = st.max_wg_size()
-        sweeps["%dx%d" % blocking] = summ
+        sweeps["%s %dx%d" % mapping] = summ
         if res.best and (best is None or res.best_ms < best[0]):
-            best = (res.best_ms, blocking, res.best)
+            best = (res.best_ms, mapping, res.best)
     sweep_seconds = time.perf_counter() - t_sweep0
     assert best is not None, "no legal workgroup size"
     _, blocking, wg = best
-    st.set_blocking(*blocking)
+    st.set_mapping(*blocking)
 
     # predictor (Algorithm 1): trained on the other workloads' features with this run's best
     # sizes unknown, it can only be scored when sweeps of several scenarios exist; here it is
@@ -157,7 +158,6 @@ def main():
             pred.add(other.features(), (4, 64))
             other.close()
     pwg = st.predict(pred, sizes)
-    st.set_blocking(*blocking)
     t_pred = None
     if st.is_legal(*pwg):
         r1 = st.sweep(tin, tout, [pwg], iters=burst, fixed=(0, 0), reps=args.reps)
@@ -184,7 +184,8 @@ def main():
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                "kernel": "tile_kernel<%s> blocking %dx%d wg %dx%d" % (w.kernel, blocking[0], blocking[1], wg[0], wg[1]),
+                "kernel": "%s_kernel<%s> %dx%d cells/work-item, wg %dx%d" % (
+                    "tile" if blocking[0] == "local" else "direct", w.kernel, blocking[1], blocking[2], wg[0], wg[1]),
                 "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg_bytes}
 
     out = {
@@ -194,7 +195,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "rows": w.rows, "cols": w.cols, "iters": w.iters,
                    "halo_nsew": list(w.halo), "border": w.border, "best_wg": list(wg),
-                   "cells_per_work_item": list(blocking), "sweep_burst": burst, "sweep_reps": args.reps},
+                   "staging": blocking[0], "cells_per_work_item": list(blocking[1:]),
+                   "sweep_burst": burst, "sweep_reps": args.reps},
         "roofline": roofline,
         "sweep": {"seconds": sweep_seconds, "by_blocking": sweeps,
                   "predicted_wg": list(pwg),

@@ -97,13 +97,29 @@ int stencil_set_kernel(stencil_t *st, int kernel_id, const float *weights, int n
 /* Padding value for STENCIL_CONSTANT (Section 2); default 0.  For U8 it is truncated. */
 int stencil_set_border_value(stencil_t *st, double value);
 
-/* Register blocking: each work-item computes a cells_rows x cells_cols block of adjacent
- * cells, so a workgroup of w_r x w_c work-items covers (w_r*cells_rows) x (w_c*cells_cols)
- * elements.  (1,1) is the paper's mapping of one element per work-item (Section 2) and the
- * default.  Supported: cells_rows in {1,2,4,8}, cells_cols in {1,4}; U8 matrices also
- * cells_cols = 16.  Values never depend on the blocking. */
-int stencil_set_blocking(stencil_t *st, int cells_rows, int cells_cols);
-int stencil_get_blocking(const stencil_t *st, int *cells_rows, int *cells_cols);
+/* How elements map to work-items and where the window is staged.
+ *   staging: STENCIL_STAGING_LOCAL  - the paper's scheme (Section 2): the workgroup's tile plus
+ *            perimeter border region is staged in local memory, then every work-item reads
+ *            its window from there.  Available for every scenario; the default.
+ *            STENCIL_STAGING_DIRECT - nothing is staged: work-items read their windows from
+ *            global memory as 16-byte vectors and rely on the L1/L2 caches for the overlap.
+ *            Available for WEIGHTED_SUM with regions 1/1/1/1 and 2/2/2/2, HEAT and LIFE;
+ *            needs no local memory, so no size is refused for its tile.
+ *   cells_rows x cells_cols: block of adjacent cells one work-item computes (register
+ *            blocking); a workgroup of w_r x w_c work-items covers (w_r*cells_rows) x
+ *            (w_c*cells_cols) elements.  (1,1) is the paper's one element per work-item.
+ *            LOCAL: cells_rows in {1,2,4,8}, cells_cols in {1,4} (F32) or {1,16} (U8);
+ *            DIRECT: cells_rows in {1,2,4}, cells_cols = 4 (F32) or 16 (U8).
+ * Output values never depend on the mapping.  Heavily blocked variants have a lower per-kernel
+ * W_max (Section 3.1), see stencil_max_wg_size. */
+enum stencil_staging { STENCIL_STAGING_LOCAL = 0, STENCIL_STAGING_DIRECT = 1 };
+int stencil_set_mapping(stencil_t *st, int staging, int cells_rows, int cells_cols);
+int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int *cells_cols);
+
+/* Launch options.  STENCIL_OPT_XCD_REMAP (default 1): workgroups are numbered so that each of
+ * the eight XCDs (each with its own L2) works on one contiguous band of tiles. */
+enum stencil_option { STENCIL_OPT_XCD_REMAP = 0 };
+int stencil_set_option(stencil_t *st, int option, int value);
 
 /* ---- legality (Section 3.1) ---------------------------------------------------------- */
 

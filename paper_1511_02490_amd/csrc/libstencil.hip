@@ -14,6 +14,7 @@
 
 #include "../../include/libstencil.h"
 #include "host_tuning.h"
+#include "direct_kernel.h"
 #include "tile_kernel.h"
 
 namespace {
@@ -39,6 +40,7 @@ int fail_hip(hipError_t e, const char *what) {
 using LaunchFn = hipError_t (*)(const stencil *, const void *, void *, int, int, hipStream_t);
 
 struct Variant {
+    int staging;          // STENCIL_STAGING_LOCAL or STENCIL_STAGING_DIRECT
     int kernel, border;
     int hn, hs, he, hw;   // -1: run-time border region
     int cr, cc;
@@ -56,6 +58,7 @@ struct stencil {
     int kernel = STENCIL_WEIGHTED_SUM;
     std::vector<float> weights;
     float scalar0 = 0.0f;
+    int staging = STENCIL_STAGING_LOCAL;
     int cr = 1, cc = 1;
     int xcd_remap = 1;
     int best_rows = 0, best_cols = 0;
@@ -84,16 +87,21 @@ TileGeom tile_geom(const stencil *s, const Variant &v, int wr, int wc) {
     const int hwa = v.cc == 1 ? s->hw : sk::round_up(s->hw, v.cc);
     const int hea = v.cc == 1 ? s->he : sk::round_up(s->he, v.cc);
     g.pitch = hwa + g.tw + hea;
-    g.lds_bytes = (int64_t)(g.th + s->hn + s->hs) * g.pitch * v.staged_bytes;
+    g.lds_bytes = v.staging == STENCIL_STAGING_DIRECT
+                      ? 0
+                      : (int64_t)(g.th + s->hn + s->hs) * g.pitch * v.staged_bytes;
     g.tiles_r = (int)((s->rows + g.th - 1) / g.th);
     g.tiles_c = (int)((s->cols + g.tw - 1) / g.tw);
     return g;
 }
 
-template <class Op, int B, class Halo, int CR, int CC, int MAXT>
-hipError_t launch_tile(const stencil *s, const void *in, void *out, int wr, int wc, hipStream_t stream) {
+// Kernel arguments and grid for one launch; `blocks` is the grid size.
+template <class Op, class Halo, int CR, int CC>
+sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, void *out, int wr, int wc,
+                                 unsigned *blocks, size_t *lds_bytes) {
     using T = typename Op::T;
     Variant v{};
+    v.staging = staging;
     v.cr = CR;
     v.cc = CC;
     v.staged_bytes = (int)sizeof(typename Op::L);
@@ -122,14 +130,41 @@ hipError_t launch_tile(const stencil *s, const void *in, void *out, int wr, int 
         a.halo.w_ = s->hw;
         a.w.v = s->d_weights;
     }
-    unsigned blocks = (unsigned)a.n_tiles;
+    *blocks = (unsigned)a.n_tiles;
     a.xcd_chunk = 0;
     if (s->xcd_remap && a.n_tiles >= 64) {
         a.xcd_chunk = (a.n_tiles + 7) / 8;
-        blocks = (unsigned)a.xcd_chunk * 8u;
+        *blocks = (unsigned)a.xcd_chunk * 8u;
     }
-    hipLaunchKernelGGL((sk::tile_kernel<Op, B, Halo, CR, CC, MAXT>), dim3(blocks), dim3(wc, wr),
-                       (size_t)g.lds_bytes, stream, a);
+    *lds_bytes = (size_t)g.lds_bytes;
+    return a;
+}
+
+template <class Op, int B, class Halo, int CR, int CC, int MAXT>
+hipError_t launch_tile(const stencil *s, const void *in, void *out, int wr, int wc, hipStream_t stream) {
+    unsigned blocks;
+    size_t lds;
+    const auto a = make_args<Op, Halo, CR, CC>(s, STENCIL_STAGING_LOCAL, in, out, wr, wc, &blocks, &lds);
+    hipLaunchKernelGGL((sk::tile_kernel<Op, B, Halo, CR, CC, MAXT>), dim3(blocks), dim3(wc, wr), lds, stream, a);
+    return hipGetLastError();
+}
+
+template <class Op, int B, class Halo, int CR, int CC, int MAXT>
+hipError_t launch_direct(const stencil *s, const void *in, void *out, int wr, int wc, hipStream_t stream) {
+    unsigned blocks;
+    size_t lds;
+    const auto a = make_args<Op, Halo, CR, CC>(s, STENCIL_STAGING_DIRECT, in, out, wr, wc, &blocks, &lds);
+    hipLaunchKernelGGL((sk::direct_kernel<Op, B, Halo, CR, CC, MAXT>), dim3(blocks), dim3(wc, wr), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int B, int CR, int MAXT>
+hipError_t launch_life_direct(const stencil *s, const void *in, void *out, int wr, int wc, hipStream_t stream) {
+    unsigned blocks;
+    size_t lds;
+    const auto a = make_args<sk::OpLife, sk::HaloC<1, 1, 1, 1>, CR, 16>(s, STENCIL_STAGING_DIRECT, in, out, wr, wc,
+                                                                        &blocks, &lds);
+    hipLaunchKernelGGL((sk::life_direct_kernel<B, CR, MAXT>), dim3(blocks), dim3(wc, wr), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -148,6 +183,7 @@ constexpr int variant_max_threads() {
 template <class Op, int KID, int B, class Halo, int CR, int CC>
 void reg_one(std::vector<Variant> &r) {
     Variant v;
+    v.staging = STENCIL_STAGING_LOCAL;
     v.kernel = KID;
     v.border = B;
     if (Halo::kStatic) {
@@ -162,6 +198,56 @@ void reg_one(std::vector<Variant> &r) {
     v.staged_bytes = (int)sizeof(typename Op::L);
     v.launch = &launch_tile<Op, B, Halo, CR, CC, kMaxT>;
     r.push_back(v);
+}
+
+template <class Op, int KID, int B, class Halo, int CR, int CC>
+void reg_direct_one(std::vector<Variant> &r) {
+    Variant v;
+    v.staging = STENCIL_STAGING_DIRECT;
+    v.kernel = KID;
+    v.border = B;
+    v.hn = Halo::N; v.hs = Halo::S; v.he = Halo::E; v.hw = Halo::W;
+    v.cr = CR;
+    v.cc = CC;
+    v.max_threads = STENCIL_MAX_WG_SIZE;
+    v.staged_bytes = 0;
+    v.launch = &launch_direct<Op, B, Halo, CR, CC, STENCIL_MAX_WG_SIZE>;
+    r.push_back(v);
+}
+
+template <class Op, int KID, class Halo, int CC>
+void reg_direct(std::vector<Variant> &r) {
+    reg_direct_one<Op, KID, sk::kClamp, Halo, 1, CC>(r);
+    reg_direct_one<Op, KID, sk::kWrap, Halo, 1, CC>(r);
+    reg_direct_one<Op, KID, sk::kConstant, Halo, 1, CC>(r);
+    reg_direct_one<Op, KID, sk::kClamp, Halo, 2, CC>(r);
+    reg_direct_one<Op, KID, sk::kWrap, Halo, 2, CC>(r);
+    reg_direct_one<Op, KID, sk::kConstant, Halo, 2, CC>(r);
+    reg_direct_one<Op, KID, sk::kClamp, Halo, 4, CC>(r);
+    reg_direct_one<Op, KID, sk::kWrap, Halo, 4, CC>(r);
+    reg_direct_one<Op, KID, sk::kConstant, Halo, 4, CC>(r);
+}
+
+template <int B, int CR>
+void reg_life_direct_one(std::vector<Variant> &r) {
+    Variant v;
+    v.staging = STENCIL_STAGING_DIRECT;
+    v.kernel = STENCIL_LIFE;
+    v.border = B;
+    v.hn = v.hs = v.he = v.hw = 1;
+    v.cr = CR;
+    v.cc = 16;
+    v.max_threads = STENCIL_MAX_WG_SIZE;
+    v.staged_bytes = 0;
+    v.launch = &launch_life_direct<B, CR, STENCIL_MAX_WG_SIZE>;
+    r.push_back(v);
+}
+
+template <int CR>
+void reg_life_direct(std::vector<Variant> &r) {
+    reg_life_direct_one<sk::kClamp, CR>(r);
+    reg_life_direct_one<sk::kWrap, CR>(r);
+    reg_life_direct_one<sk::kConstant, CR>(r);
 }
 
 template <class Op, int KID, class Halo, int CR, int CC>
@@ -193,6 +279,12 @@ const std::vector<Variant> &registry() {
         reg_blockings<sk::OpSinCos, STENCIL_SINCOS, sk::HaloC<1, 5, 3, 0>, 4>(r);
         reg_blockings<sk::OpHeat, STENCIL_HEAT, sk::HaloC<1, 1, 1, 1>, 4>(r);
         reg_blockings<sk::OpLife, STENCIL_LIFE, sk::HaloC<1, 1, 1, 1>, 16>(r);
+        reg_direct<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<1, 1, 1, 1>, 4>(r);
+        reg_direct<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<2, 2, 2, 2>, 4>(r);
+        reg_direct<sk::OpHeat, STENCIL_HEAT, sk::HaloC<1, 1, 1, 1>, 4>(r);
+        reg_life_direct<1>(r);
+        reg_life_direct<2>(r);
+        reg_life_direct<4>(r);
         return r;
     }();
     return reg;
@@ -203,16 +295,18 @@ const std::vector<Variant> &registry() {
 const Variant *find_variant(const stencil *s) {
     const Variant *dyn = nullptr;
     for (const Variant &v : registry()) {
-        if (v.kernel != s->kernel || v.border != s->border || v.cr != s->cr || v.cc != s->cc) continue;
+        if (v.kernel != s->kernel || v.border != s->border || v.cr != s->cr || v.cc != s->cc ||
+            v.staging != s->staging)
+            continue;
         if (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw) return &v;
         if (v.hn < 0) dyn = &v;
     }
     return dyn;
 }
 
-bool blocking_supported(const stencil *s, int cr, int cc) {
+bool mapping_supported(const stencil *s, int staging, int cr, int cc) {
     for (const Variant &v : registry())
-        if (v.kernel == s->kernel && v.border == s->border && v.cr == cr && v.cc == cc &&
+        if (v.kernel == s->kernel && v.border == s->border && v.staging == staging && v.cr == cr && v.cc == cc &&
             (v.hn < 0 || (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw)))
             return true;
     return false;
@@ -376,7 +470,8 @@ int stencil_set_kernel(stencil_t *s, int kernel_id, const float *weights, int n_
     }
     s->kernel = kernel_id;
     s->weights_uploaded = false;
-    if (!blocking_supported(s, s->cr, s->cc)) {
+    if (!mapping_supported(s, s->staging, s->cr, s->cc)) {
+        s->staging = STENCIL_STAGING_LOCAL;
         s->cr = 1;
         s->cc = 1;
     }
@@ -390,22 +485,36 @@ int stencil_set_border_value(stencil_t *s, double value) {
     return STENCIL_OK;
 }
 
-int stencil_set_blocking(stencil_t *s, int cells_rows, int cells_cols) {
+int stencil_set_mapping(stencil_t *s, int staging, int cells_rows, int cells_cols) {
     if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
     if (s->kernel < 0) return fail(STENCIL_E_INVALID, "select a kernel first");
-    if (!blocking_supported(s, cells_rows, cells_cols))
-        return fail(STENCIL_E_INVALID, "blocking %dx%d is not available for this kernel", cells_rows, cells_cols);
+    if (!mapping_supported(s, staging, cells_rows, cells_cols))
+        return fail(STENCIL_E_INVALID, "mapping (staging %d, %dx%d cells per work-item) is not available for this scenario",
+                    staging, cells_rows, cells_cols);
+    s->staging = staging;
     s->cr = cells_rows;
     s->cc = cells_cols;
     s->best_rows = s->best_cols = 0;
     return STENCIL_OK;
 }
 
-int stencil_get_blocking(const stencil_t *s, int *cells_rows, int *cells_cols) {
-    if (!s || !cells_rows || !cells_cols) return fail(STENCIL_E_INVALID, "NULL argument");
+int stencil_get_mapping(const stencil_t *s, int *staging, int *cells_rows, int *cells_cols) {
+    if (!s || !staging || !cells_rows || !cells_cols) return fail(STENCIL_E_INVALID, "NULL argument");
+    *staging = s->staging;
     *cells_rows = s->cr;
     *cells_cols = s->cc;
     return STENCIL_OK;
+}
+
+int stencil_set_option(stencil_t *s, int option, int value) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    switch (option) {
+    case STENCIL_OPT_XCD_REMAP:
+        s->xcd_remap = value ? 1 : 0;
+        return STENCIL_OK;
+    default:
+        return fail(STENCIL_E_INVALID, "unknown option %d", option);
+    }
 }
 
 int stencil_max_wg_size(const stencil_t *s) {

@@ -19,6 +19,9 @@ F32, U8 = 0, 1
 CLAMP, WRAP, CONSTANT = 0, 1, 2
 WEIGHTED_SUM, LIFE, HEAT, SINCOS = 0, 1, 2, 3
 ENUM_POW2, ENUM_EVEN = 0, 1
+STAGING_LOCAL, STAGING_DIRECT = 0, 1
+OPT_XCD_REMAP = 0
+_STAGINGS = {"local": STAGING_LOCAL, "direct": STAGING_DIRECT}
 N_FEATURES = 12
 
 _DTYPES = {"f32": F32, "u8": U8}
@@ -49,8 +52,9 @@ def _load() -> ctypes.CDLL:
         "stencil_destroy": (None, [vp]),
         "stencil_set_kernel": (c_int, [vp, c_int, fp, c_int, fp, c_int]),
         "stencil_set_border_value": (c_int, [vp, c_dbl]),
-        "stencil_set_blocking": (c_int, [vp, c_int, c_int]),
-        "stencil_get_blocking": (c_int, [vp, ip, ip]),
+        "stencil_set_mapping": (c_int, [vp, c_int, c_int, c_int]),
+        "stencil_get_mapping": (c_int, [vp, ip, ip, ip]),
+        "stencil_set_option": (c_int, [vp, c_int, c_int]),
         "stencil_max_wg_size": (c_int, [vp]),
         "stencil_tile_bytes": (c_i64, [vp, c_int, c_int]),
         "stencil_is_legal": (c_int, [vp, c_int, c_int]),
@@ -75,7 +79,7 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
-           "stencil_set_blocking", "stencil_get_blocking", "stencil_max_wg_size", "stencil_tile_bytes",
+           "stencil_set_mapping", "stencil_get_mapping", "stencil_set_option", "stencil_max_wg_size", "stencil_tile_bytes",
            "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg",
            "stencil_sweep_reduce", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
@@ -196,13 +200,24 @@ class Stencil:
     def set_border_value(self, v: float):
         _check(_lib.stencil_set_border_value(self._h, float(v)))
 
+    def set_mapping(self, staging="local", cells_rows: int = 1, cells_cols: int = 1):
+        sg = _STAGINGS[staging] if isinstance(staging, str) else int(staging)
+        _check(_lib.stencil_set_mapping(self._h, sg, int(cells_rows), int(cells_cols)))
+
     def set_blocking(self, cells_rows: int, cells_cols: int):
-        _check(_lib.stencil_set_blocking(self._h, int(cells_rows), int(cells_cols)))
+        """Register blocking under the current staging."""
+        self.set_mapping(self.get_mapping()[0], cells_rows, cells_cols)
+
+    def get_mapping(self) -> Tuple[int, int, int]:
+        a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        _check(_lib.stencil_get_mapping(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+        return a.value, b.value, c.value
 
     def get_blocking(self) -> Tuple[int, int]:
-        a, b = ctypes.c_int(), ctypes.c_int()
-        _check(_lib.stencil_get_blocking(self._h, ctypes.byref(a), ctypes.byref(b)))
-        return a.value, b.value
+        return self.get_mapping()[1:]
+
+    def set_option(self, option: int, value: int):
+        _check(_lib.stencil_set_option(self._h, int(option), int(value)))
 
     # -- legality ----------------------------------------------------------------------------
     def max_wg_size(self) -> int:

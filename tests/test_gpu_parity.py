@@ -32,11 +32,19 @@ def rel_err(got, ref):
     return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-6)))
 
 
+def set_mapping(st, blocking):
+    """blocking = (cells_rows, cells_cols) under local-memory staging, or ("direct", cr, cc)."""
+    if len(blocking) == 3:
+        st.set_mapping(*blocking)
+    else:
+        st.set_mapping("local", *blocking)
+
+
 def gpu_apply(ls, w, grid, wg, iters=None, blocking=(1, 1), offset=0):
     """Run workload `w` on `grid` through the library.  offset > 0 places the matrices that many
     elements into their allocations, so that rows are not 16-byte aligned."""
     st = ls.Stencil.from_workload(w)
-    st.set_blocking(*blocking)
+    set_mapping(st, blocking)
     n = grid.size
     tdt = torch.float32 if w.dtype == "f32" else torch.uint8
     buf_in = torch.zeros(n + offset, dtype=tdt, device="cuda")
@@ -99,19 +107,27 @@ def test_c1_all_listed_sizes(ls):
 # ---- every kernel x border mode x blocking, ragged matrices spanning several tiles -----------
 
 BLOCKINGS_F32 = [(1, 1), (2, 1), (8, 1), (1, 4), (4, 4), (8, 4)]
+DIRECT_F32 = [("direct", 1, 4), ("direct", 2, 4), ("direct", 4, 4)]
+DIRECT_U8 = [("direct", 1, 16), ("direct", 2, 16), ("direct", 4, 16)]
 
 
 @pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
 @pytest.mark.parametrize("halo", [(1, 1, 1, 1), (2, 2, 2, 2), (2, 1, 2, 2), (0, 0, 0, 0), (7, 3, 9, 5)])
 def test_weighted_sum_borders_and_regions(ls, border, halo):
     w = custom(wl.WEIGHTED_SUM, 131, 157, halo, border, pad=0.5, seed=sum(halo))
-    for blocking in BLOCKINGS_F32:
+    direct = DIRECT_F32 if halo in [(1, 1, 1, 1), (2, 2, 2, 2)] else []
+    for blocking in BLOCKINGS_F32 + direct:
         for wg in [(4, 4), (16, 16), (3, 21), (2, 64)]:
             check(ls, w, wg, blocking=blocking)
     # aligned rows (vector path), misaligned base pointer, and cols % 4 != 0
     w2 = custom(wl.WEIGHTED_SUM, 96, 128, halo, border, pad=0.5, seed=3)
     for off in (0, 1):
-        check(ls, w2, (8, 16), blocking=(4, 4), offset=off)
+        for blocking in [(4, 4)] + direct[:2]:
+            check(ls, w2, (8, 16), blocking=blocking, offset=off)
+    if not direct:
+        st = ls.Stencil.from_workload(w)
+        with pytest.raises(ls.StencilError):
+            st.set_mapping("direct", 1, 4)                  # no direct variant for this region
 
 
 @pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
@@ -128,27 +144,35 @@ def test_life_bit_exact(ls, border):
     for rows, cols in [(150, 203), (64, 256)]:
         w = wl.config(2, rows=rows, cols=cols, iters=12)
         w.border = border
-        for blocking in [(1, 1), (4, 1), (1, 16), (2, 16)]:
+        for blocking in [(1, 1), (4, 1), (1, 16), (2, 16)] + DIRECT_U8:
             for wg in [(4, 4), (16, 16), (2, 64), (5, 7)]:
                 check(ls, w, wg, blocking=blocking)
-    w1 = wl.config(2, rows=97, cols=61, iters=1)
-    w1.border, w1.pad = "constant", 1.0              # live padding
-    check(ls, w1, (8, 8))
+    for shape in [(97, 61), (80, 96)]:
+        w1 = wl.config(2, rows=shape[0], cols=shape[1], iters=2)
+        w1.border, w1.pad = "constant", 1.0              # live padding
+        check(ls, w1, (8, 8))
+        check(ls, w1, (8, 8), blocking=("direct", 2, 16))
+        check(ls, w1, (8, 8), blocking=("direct", 1, 16), offset=3)
 
 
 @pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
 def test_heat_matches_fp32_oracle_exactly(ls, border):
     w = wl.config(3, rows=160, cols=216, iters=25)
     w.border, w.pad = border, 50.0
-    for blocking in [(1, 1), (4, 1), (1, 4), (8, 4)]:
+    for blocking in [(1, 1), (4, 1), (1, 4), (8, 4)] + DIRECT_F32:
         for wg in [(4, 4), (16, 16), (4, 64), (7, 9)]:
             check(ls, w, wg, blocking=blocking)
+    w2 = wl.config(3, rows=61, cols=83, iters=5)          # cols % 4 != 0: element-wise path
+    w2.border, w2.pad = border, 50.0
+    check(ls, w2, (4, 16), blocking=("direct", 2, 4))
 
 
 def test_heat_conserves_total_and_long_run(ls):
     w = wl.config(3, rows=256, cols=256, iters=1000)
     g = w.grid()
     got = check(ls, w, (4, 64), blocking=(4, 4), grid=g)
+    got2 = check(ls, w, (4, 64), blocking=("direct", 1, 4), grid=g)
+    np.testing.assert_array_equal(got, got2)
     s0, s1 = g.astype(np.float64).sum(), got.astype(np.float64).sum()
     assert abs(s1 - s0) / s0 < 1e-6
     assert got.min() >= g.min() and got.max() <= g.max()
@@ -163,9 +187,11 @@ def test_every_swept_size_matches_baseline_output(ls, index):
     g = w.grid()
     base = gpu_apply(ls, w, g, (4, 4))
     sizes = wl.enumerate_wg("pow2") if index != 4 else wl.enumerate_wg("even")[::7]
-    for blocking in [(1, 1), (4, 16 if w.dtype == "u8" else 4)]:
+    vec = 16 if w.dtype == "u8" else 4
+    mappings = [(1, 1), (4, vec)] + ([("direct", 1, vec), ("direct", 4, vec)] if index != 4 else [])
+    for blocking in mappings:
         st = ls.Stencil.from_workload(w)
-        st.set_blocking(*blocking)
+        set_mapping(st, blocking)
         tdt = torch.float32 if w.dtype == "f32" else torch.uint8
         tin = torch.from_numpy(g).cuda()
         tout = torch.empty_like(tin)
@@ -196,6 +222,12 @@ def test_tiny_matrices_smaller_than_the_region(ls, shape):
         wlife.border = border
         check(ls, wlife, (2, 2))
         check(ls, wlife, (4, 4), blocking=(2, 16))
+        check(ls, wlife, (4, 4), blocking=("direct", 2, 16))
+        wheat = wl.config(3, rows=shape[0], cols=shape[1], iters=3)
+        wheat.border = border
+        check(ls, wheat, (4, 4), blocking=("direct", 1, 4))
+        w3 = custom(wl.WEIGHTED_SUM, shape[0], shape[1], (2, 2, 2, 2), border, pad=0.25, seed=12)
+        check(ls, w3, (2, 8), blocking=("direct", 4, 4))
 
 
 def test_iters_zero_copies_and_even_odd_iteration_counts(ls):
@@ -279,7 +311,7 @@ def test_c2_full_size(ls):
     w = wl.config(1)
     g = w.grid()
     ref = oracle.apply_workload(w, g)
-    for wg, blocking in [((16, 16), (1, 1)), ((4, 64), (4, 4))]:
+    for wg, blocking in [((16, 16), (1, 1)), ((4, 64), (4, 4)), ((4, 64), ("direct", 1, 4))]:
         got = gpu_apply(ls, w, g, wg, blocking=blocking)
         assert rel_err(got, ref) <= REL_1
 
@@ -289,6 +321,8 @@ def test_c3_full_size_100_generations(ls):
     g = w.grid()
     ref = oracle.apply_workload(w, g)
     got = gpu_apply(ls, w, g, (4, 64), blocking=(2, 16))
+    np.testing.assert_array_equal(got, ref)
+    got = gpu_apply(ls, w, g, (4, 64), blocking=("direct", 1, 16))
     np.testing.assert_array_equal(got, ref)
     assert 0.02 < got.mean() < 0.2
 
@@ -302,7 +336,9 @@ def test_c4_full_size(ls):
     ref = oracle.apply_workload(w, g, iters=100)
     got = gpu_apply(ls, w, g, (4, 64), iters=100, blocking=(4, 4))
     np.testing.assert_array_equal(got, ref)
-    a = gpu_apply(ls, w, g, (4, 64), iters=1000, blocking=(4, 4))
+    got = gpu_apply(ls, w, g, (4, 64), iters=100, blocking=("direct", 1, 4))
+    np.testing.assert_array_equal(got, ref)
+    a = gpu_apply(ls, w, g, (4, 64), iters=1000, blocking=("direct", 1, 4))
     b = gpu_apply(ls, w, g, (16, 16), iters=1000, blocking=(1, 1))
     np.testing.assert_array_equal(a, b)
     s0, s1 = g.astype(np.float64).sum(), a.astype(np.float64).sum()

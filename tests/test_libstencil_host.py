@@ -72,6 +72,8 @@ def test_legality_eq1():
     assert big.tile_bytes(32, 32) == (32 + 60) * (32 + 60) * 4 and big.is_legal(32, 32)
     assert big.tile_bytes(64, 16) == (64 + 60) * (16 + 60) * 4 and big.is_legal(64, 16)
     assert big.tile_bytes(8, 128) == (8 + 60) * (128 + 60) * 4 and big.is_legal(8, 128)
+    with pytest.raises(ls.StencilError):
+        big.set_mapping("direct", 1, 4)                  # no cache-staged variant for a 30-cell region
     big.set_blocking(4, 4)
     assert not big.is_legal(32, 32)                      # (128+60) x (128+64) floats > 64 KiB
     assert "refused" in ls.last_error()
@@ -88,6 +90,13 @@ def test_blocking_changes_tile_and_per_kernel_limit():
     assert not st.is_legal(4, 64)                                 # 38 x 260 (sin, cos) pairs > 64 KiB
     with pytest.raises(ls.StencilError):
         st.set_blocking(3, 4)
+    # cache-staged mapping: no tile in local memory, nothing refused below W_max
+    heat = ls.Stencil.from_workload(wl.config(3))
+    heat.set_mapping("direct", 1, 4)
+    assert heat.get_mapping() == (ls.STAGING_DIRECT, 1, 4)
+    assert heat.tile_bytes(32, 32) == 0 and heat.is_legal(1, 1024) and not heat.is_legal(2, 1024)
+    heat.set_mapping("local", 8, 4)
+    assert heat.tile_bytes(32, 32) == (256 + 2) * (128 + 8) * 4 and not heat.is_legal(32, 32)
 
 
 def test_sweep_reduce_matches_definitions():
