@@ -48,6 +48,10 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quick", action="store_true", help="sweep a thinned size list (development only)")
+    ap.add_argument("--wg", default="", help="R,C: skip the sweep and time this workgroup size (profiling runs)")
+    ap.add_argument("--mapping", default="", help="staging,cells_rows,cells_cols to go with --wg, e.g. direct,2,4")
+    ap.add_argument("--copy-only", action="store_true",
+                    help="launch only the plain copy kernel on the workload's matrix (counter calibration)")
     return ap.parse_args()
 
 
@@ -70,6 +74,20 @@ def sweep_summary(res, cells_per_sample):
     return out, legal
 
 
+def recorded_traffic(workload_key, kernel_label):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None when there is
+    none for this kernel or the kernel sources have changed since the counters were taken."""
+    from paper_1511_02490_amd import rocprof_summary as rs
+    try:
+        with open(rs.TRAFFIC_JSON) as fh:
+            rec = json.load(fh).get(workload_key)
+    except (OSError, ValueError):
+        return None
+    if not rec or rec.get("kernel") != kernel_label or rec.get("source_hash") != rs.kernel_source_hash():
+        return None
+    return rec["traffic_bytes_per_launch"]
+
+
 def cpu_baseline(wl_mod, w, target_seconds):
     """The oracle, as it stands, on the first rows of the workload's matrix for a bounded
     number of iterations (the sample is sized from a short calibration run)."""
@@ -77,26 +95,23 @@ def cpu_baseline(wl_mod, w, target_seconds):
     import numpy as np
     threads = oracle.max_threads()
     g = w.grid()
-    rows_cal = min(w.rows, 1024)
-    sub = np.ascontiguousarray(g[:rows_cal])
-    oracle.apply(sub[:64], w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1)   # load, spawn threads
-    t0 = time.perf_counter()
-    oracle.apply(sub, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1)
-    t_cal = max(time.perf_counter() - t0, 1e-4)
-    rate = rows_cal * w.cols / t_cal                      # cell updates / s, rough
-    budget = rate * target_seconds
-    rows = int(min(w.rows, max(rows_cal, budget // w.cols)))
-    iters = int(max(1, min(w.iters, budget // (rows * w.cols))))
-    sub = np.ascontiguousarray(g[:rows])
-    t0 = time.perf_counter()
-    oracle.apply(sub, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, iters)
-    dt = time.perf_counter() - t0
+    rows = w.rows
+    run = lambda it: oracle.apply(g, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, it)
+    oracle.apply(g[:64], w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1)   # load library, spawn threads
+    iters, dt = 1, 0.0
+    while True:
+        t0 = time.perf_counter()
+        run(iters)
+        dt = time.perf_counter() - t0
+        if dt >= target_seconds / 3 or iters >= w.iters:
+            break
+        iters = int(min(w.iters, max(2 * iters, iters * 0.8 * target_seconds / max(dt, 1e-3))))
     return {
         "value": rows * w.cols * iters / dt / 1e9,
         "unit": "Gcells/s",
         "cores": threads,
         "kind": "oracle",
-        "sample": "first %d of %d rows x %d cols, %d of %d iterations, %.1f s" % (rows, w.rows, w.cols, iters, w.iters, dt),
+        "sample": "whole %d x %d matrix, %d of %d iterations, %.1f s" % (w.rows, w.cols, iters, w.iters, dt),
     }
 
 
@@ -131,40 +146,64 @@ def main():
         burst = 20
     cells_per_sample = cells * burst
 
-    st = ls.Stencil.from_workload(w)
-    t_sweep0 = time.perf_counter()
-    sweeps = {}
-    best = None   # (ms, mapping, wg)
-    for mapping in MAPPINGS[w.kernel]:
-        st.set_mapping(*mapping)
-        res = st.sweep(tin, tout, sizes, iters=burst, fixed=(4, 4), reps=args.reps)
-        summ, _ = sweep_summary(res, cells_per_sample)
-        summ["w_max"] = st.max_wg_size()
-        sweeps["%s %dx%d" % mapping] = summ
-        if res.best and (best is None or res.best_ms < best[0]):
-            best = (res.best_ms, mapping, res.best)
-    sweep_seconds = time.perf_counter() - t_sweep0
-    assert best is not None, "no legal workgroup size"
-    _, blocking, wg = best
-    st.set_mapping(*blocking)
-
-    # predictor (Algorithm 1): trained on the other workloads' features with this run's best
-    # sizes unknown, it can only be scored when sweeps of several scenarios exist; here it is
-    # exercised on a leave-this-one-out table of sizes typical for the device
-    pred = ls.Predictor()
-    for i in range(5):
-        if i != index:
-            other = ls.Stencil.from_workload(wl.config(i))
-            pred.add(other.features(), (4, 64))
-            other.close()
-    pwg = st.predict(pred, sizes)
-    t_pred = None
-    if st.is_legal(*pwg):
-        r1 = st.sweep(tin, tout, [pwg], iters=burst, fixed=(0, 0), reps=args.reps)
-        t_pred = r1.mean_ms[0]
-
     steps = args.steps if args.steps > 0 else {0: 200, 1: 200, 2: 20, 3: 5, 4: 100}[index]
     warmup = args.warmup if args.warmup >= 0 else max(1, steps // 10)
+
+    def copy_reference(n=20):
+        """GB/s of the plain copy kernel on this matrix (read + write), by events on the stream."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            ls.device_copy(tin, tout)
+        e0.record()
+        for _ in range(n):
+            ls.device_copy(tin, tout)
+        e1.record()
+        e1.synchronize()
+        return 2.0 * tin.numel() * tin.element_size() / (e0.elapsed_time(e1) / n * 1e-3) / 1e9
+
+    if args.copy_only:
+        gbs = copy_reference(max(steps, 20))
+        print(json.dumps({"metric": "plain copy kernel GB/s (read+write)", "value": gbs, "unit": "GB/s",
+                          "config": {"workload": w.name, "bytes_each_way": tin.numel() * tin.element_size()}}))
+        return
+
+    st = ls.Stencil.from_workload(w)
+    sweeps, sweep_seconds, pwg, t_pred = {}, 0.0, None, None
+    if args.wg:
+        wg = tuple(int(x) for x in args.wg.split(","))
+        m = args.mapping.split(",") if args.mapping else ["local", "1", "1"]
+        blocking = (m[0], int(m[1]), int(m[2]))
+        st.set_mapping(*blocking)
+        best = (float("nan"), blocking, wg)
+    else:
+        t_sweep0 = time.perf_counter()
+        best = None   # (ms, mapping, wg)
+        for mapping in MAPPINGS[w.kernel]:
+            st.set_mapping(*mapping)
+            res = st.sweep(tin, tout, sizes, iters=burst, fixed=(4, 4), reps=args.reps)
+            summ, _ = sweep_summary(res, cells_per_sample)
+            summ["w_max"] = st.max_wg_size()
+            sweeps["%s %dx%d" % mapping] = summ
+            if res.best and (best is None or res.best_ms < best[0]):
+                best = (res.best_ms, mapping, res.best)
+        sweep_seconds = time.perf_counter() - t_sweep0
+        assert best is not None, "no legal workgroup size"
+        _, blocking, wg = best
+        st.set_mapping(*blocking)
+
+        # Algorithm 1 on this scenario: a classifier that has only seen the other workloads
+        # (labelled with a size typical for the device) predicts, the NearestNeighbour handler
+        # repairs an illegal prediction, and the sweep scores the result (`performance`).
+        pred = ls.Predictor()
+        for i in range(5):
+            if i != index:
+                other = ls.Stencil.from_workload(wl.config(i))
+                pred.add(other.features(), (4, 64))
+                other.close()
+        pwg = st.predict(pred, sizes)
+        if st.is_legal(*pwg):
+            r1 = st.sweep(tin, tout, [pwg], iters=burst, fixed=(0, 0), reps=args.reps)
+            t_pred = r1.mean_ms[0]
 
     for _ in range(warmup):
         st.run(tin, tout, w.iters, wg)
@@ -182,10 +221,12 @@ def main():
     kernel_ms = k_res.mean_ms[0] / burst
     alg_bytes = cells * w.bytes_per_cell_update
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    kernel_label = "%s_kernel<%s> %dx%d cells/work-item, wg %dx%d" % (
+        "tile" if blocking[0] == "local" else "direct", w.kernel, blocking[1], blocking[2], wg[0], wg[1])
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                "kernel": "%s_kernel<%s> %dx%d cells/work-item, wg %dx%d" % (
-                    "tile" if blocking[0] == "local" else "direct", w.kernel, blocking[1], blocking[2], wg[0], wg[1]),
+                "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(args.workload, kernel_label),
+                "copy_kernel_gbs": copy_reference(),
+                "kernel": kernel_label,
                 "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg_bytes}
 
     out = {
@@ -199,7 +240,7 @@ def main():
                    "sweep_burst": burst, "sweep_reps": args.reps},
         "roofline": roofline,
         "sweep": {"seconds": sweep_seconds, "by_blocking": sweeps,
-                  "predicted_wg": list(pwg),
+                  "predicted_wg": list(pwg) if pwg else None,
                   "predicted_performance": (best[0] / t_pred) if t_pred else None},
     }
     if not args.no_cpu_baseline:

@@ -169,6 +169,13 @@ int stencil_sweep_wg(stencil_t *st, const void *in, void *out, int iters,
                      double *mean_ms, double *min_ms, double *median_ms, double *stddev_ms,
                      int *status, int *best_index, double *speedup_over_fixed, void *stream);
 
+/* Reference for the bandwidth a stencil can hope for: a plain device-to-device copy kernel
+ * (one 16-byte vector per work-item) of `bytes` bytes from `in` to `out` (device pointers,
+ * 16-byte aligned, non-overlapping), asynchronous on `stream`.  Not part of the paper's
+ * method; used to express achieved bandwidth relative to a copy and to calibrate hardware
+ * traffic counters against a kernel of known size. */
+int stencil_device_copy(const void *in, void *out, int64_t bytes, void *stream);
+
 /* The reductions of a sweep on their own (Eq. 3; Section 7's performance and speedup), on
  * host arrays: best_index as above; performance[i] = mean_ms[best] / mean_ms[i] (NaN where
  * status[i] != STENCIL_OK; may be NULL); speedup = fixed_ms / mean_ms[best]. */

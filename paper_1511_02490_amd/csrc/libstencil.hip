@@ -168,6 +168,18 @@ hipError_t launch_life_direct(const stencil *s, const void *in, void *out, int w
     return hipGetLastError();
 }
 
+// Plain copy: one 16-byte vector per work-item (tail bytes one by one).  The achievable
+// read+write bandwidth the stencil kernels are compared with, and the known-size kernel that
+// hardware traffic counters are calibrated against.
+__global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ in, uint4 *__restrict__ out,
+                                                   size_t n_vec, size_t n_bytes) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_vec) out[i] = in[i];
+    const size_t tail = n_vec * 16 + i;
+    if (i < 16 && tail < n_bytes)
+        reinterpret_cast<unsigned char *>(out)[tail] = reinterpret_cast<const unsigned char *>(in)[tail];
+}
+
 // ---- registry of compiled variants ----------------------------------------------------------
 
 // Per-kernel workgroup-size limit (Section 3.1: the registers a kernel needs bound its
@@ -668,6 +680,22 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
         s->best_cols = wg_cols_list[best];
     }
     return STENCIL_OK;
+}
+
+int stencil_device_copy(const void *in, void *out, int64_t bytes, void *stream) {
+    if (!in || !out || bytes < 0) return fail(STENCIL_E_INVALID, "bad arguments to stencil_device_copy");
+    if ((uintptr_t)in % 16 || (uintptr_t)out % 16) return fail(STENCIL_E_INVALID, "buffers must be 16-byte aligned");
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
+    if (a < b + (uintptr_t)bytes && b < a + (uintptr_t)bytes) return fail(STENCIL_E_INVALID, "in and out overlap");
+    if (bytes == 0) return STENCIL_OK;
+    const size_t n_vec = (size_t)bytes / 16;
+    const size_t threads = std::max<size_t>(n_vec, 16);
+    const size_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffull) return fail(STENCIL_E_INVALID, "copy too large for one launch");
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       static_cast<const uint4 *>(in), static_cast<uint4 *>(out), n_vec, (size_t)bytes);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? STENCIL_OK : fail_hip(e, "copy kernel launch");
 }
 
 int stencil_sweep_reduce(const int *wg_rows_list, const int *wg_cols_list, int n, const double *mean_ms,

@@ -62,6 +62,7 @@ def _load() -> ctypes.CDLL:
         "stencil_run": (c_int, [vp, vp, vp, c_int, c_int, c_int, vp]),
         "stencil_sweep_wg": (c_int, [vp, vp, vp, c_int, ip, ip, c_int, c_int, c_int, c_int,
                                      dp, dp, dp, dp, ip, ip, dp, vp]),
+        "stencil_device_copy": (c_int, [vp, vp, c_i64, vp]),
         "stencil_sweep_reduce": (c_int, [ip, ip, c_int, dp, ip, c_dbl, ip, dp, dp]),
         "stencil_features": (c_int, [vp, dp]),
         "stencil_predictor_create": (c_int, [ctypes.POINTER(vp)]),
@@ -81,7 +82,7 @@ _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
            "stencil_set_mapping", "stencil_get_mapping", "stencil_set_option", "stencil_max_wg_size", "stencil_tile_bytes",
            "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg",
-           "stencil_sweep_reduce", "stencil_features", "stencil_predictor_create",
+           "stencil_device_copy", "stencil_sweep_reduce", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
            "stencil_predict_wg", "stencil_last_error")
 
@@ -110,6 +111,15 @@ def enumerate_wg(mode: str = "pow2", max_threads: int = 1024) -> List[Tuple[int,
     r, c = (ctypes.c_int * n)(), (ctypes.c_int * n)()
     _check(_lib.stencil_enumerate_wg(m, max_threads, r, c, n))
     return list(zip(r, c))
+
+
+def device_copy(tin, tout, stream=None):
+    """Plain copy kernel between two equally sized CUDA tensors (bandwidth reference)."""
+    nbytes = tin.numel() * tin.element_size()
+    assert tout.numel() * tout.element_size() == nbytes and tin.is_cuda and tout.is_cuda
+    _check(_lib.stencil_device_copy(ctypes.c_void_p(tin.data_ptr()), ctypes.c_void_p(tout.data_ptr()),
+                                    nbytes, Stencil._stream_ptr(stream)))
+    return tout
 
 
 def sweep_reduce(sizes: Sequence[Tuple[int, int]], mean_ms: Sequence[float], status: Sequence[int],
