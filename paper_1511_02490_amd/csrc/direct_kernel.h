@@ -13,7 +13,7 @@ namespace sk {
 // Window row `gr_raw` for the CC cells starting at column c0: W values to the west, the CC
 // cells, E values to the east, border-resolved.
 template <class Op, int B, int CC, int W, int E>
-__device__ __forceinline__ void fetch_row(typename Op::L (&row)[W + CC + E], const typename Op::T *in, int gr_raw,
+__device__ __forceinline__ void fetch_row(typename Op::V (&row)[W + CC + E], const typename Op::T *in, int gr_raw,
                                           int c0, int rows, int cols, bool fast_cols, typename Op::T pad) {
     using T = typename Op::T;
     static_assert(W <= CC && E <= CC, "direct kernels reach at most one vector to each side");
@@ -47,7 +47,11 @@ __device__ __forceinline__ void fetch_row(typename Op::L (&row)[W + CC + E], con
         }
     }
 #pragma unroll
-    for (int k = 0; k < W + CC + E; ++k) row[k] = Op::stage(v[k]);
+    for (int k = 0; k < W + CC + E; ++k) {
+        typename Op::L parts[Op::kPlanes];
+        Op::stage(v[k], parts);
+        row[k] = Op::combine(parts);
+    }
 }
 
 // Work-item (ty, tx) of workgroup (tile_r, tile_c) owns rows (tile_r*w_r + ty)*CR .. +CR-1 and
@@ -56,7 +60,7 @@ template <class Op, int B, class Halo, int CR, int CC, int MAXT>
 __global__ __launch_bounds__(MAXT) void direct_kernel(const TileArgs<Op, Halo> a) {
     static_assert(Halo::kStatic, "direct kernels are compiled per border region");
     using T = typename Op::T;
-    using L = typename Op::L;
+    using V = typename Op::V;
     constexpr int N = Halo::N, S = Halo::S, E = Halo::E, W = Halo::W;
     constexpr int WCOLS = E + W + 1;
 
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(MAXT) void direct_kernel(const TileArgs<Op, Halo> a
         // the first cell-row this window row feeds; stop once that lies below the matrix
         const int first_cr = wi - N - S > 0 ? wi - N - S : 0;
         if (r0 + first_cr >= rows) break;
-        L row[W + CC + E];
+        V row[W + CC + E];
         fetch_row<Op, B, CC, W, E>(row, a.in, r0 - N + wi, c0, rows, cols, fast_cols, a.pad);
 #pragma unroll
         for (int cr = 0; cr < CR; ++cr) {
@@ -90,9 +94,9 @@ __global__ __launch_bounds__(MAXT) void direct_kernel(const TileArgs<Op, Halo> a
             if (dr < -N || dr > S) continue;
 #pragma unroll
             for (int cc = 0; cc < CC; ++cc)
-#pragma unroll
-                for (int dc = -W; dc <= E; ++dc)
-                    Op::visit(st[cr][cc], dr, dc, a.w[(dr + N) * WCOLS + dc + W], row[W + cc + dc]);
+                fold_row<Op>(
+                    st[cr][cc], dr, W, E, [&](int dc) { return a.w[(dr + N) * WCOLS + dc + W]; },
+                    [&](int dc) { return row[W + cc + dc]; });
         }
     }
 

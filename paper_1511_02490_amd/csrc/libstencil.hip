@@ -104,7 +104,7 @@ sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, 
     v.staging = staging;
     v.cr = CR;
     v.cc = CC;
-    v.staged_bytes = (int)sizeof(typename Op::L);
+    v.staged_bytes = (int)sizeof(typename Op::L) * Op::kPlanes;
     const TileGeom g = tile_geom(s, v, wr, wc);
     sk::TileArgs<Op, Halo> a;
     a.in = static_cast<const T *>(in);
@@ -114,6 +114,11 @@ sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, 
     a.tiles_c = g.tiles_c;
     a.n_tiles = g.tiles_r * g.tiles_c;
     a.pitch = g.pitch;
+    a.plane = (g.th + s->hn + s->hs) * g.pitch;
+    {
+        const unsigned items = (unsigned)(g.pitch / CC);   // vectors (elements when CC = 1) per staged row
+        a.stage_magic = (unsigned)((0x100000000ull + items - 1) / items);
+    }
     const size_t row_bytes = (size_t)s->cols * sizeof(T);
     a.vec_ok = (CC > 1 && row_bytes % 16 == 0 && (uintptr_t)in % 16 == 0 && (uintptr_t)out % 16 == 0) ? 1 : 0;
     a.pad = (T)s->pad;
@@ -207,7 +212,7 @@ void reg_one(std::vector<Variant> &r) {
     v.cc = CC;
     constexpr int kMaxT = variant_max_threads<Op, CR, CC>();
     v.max_threads = kMaxT;
-    v.staged_bytes = (int)sizeof(typename Op::L);
+    v.staged_bytes = (int)sizeof(typename Op::L) * Op::kPlanes;
     v.launch = &launch_tile<Op, B, Halo, CR, CC, kMaxT>;
     r.push_back(v);
 }

@@ -3,6 +3,10 @@
 // value) for every cell of the region -> finish.  The fold order is what fixes each output
 // bit-for-bit, whatever workgroup size or register blocking the kernel is launched with
 // (the paper's gold-standard check, Section 5, compares every workgroup size against one).
+//
+// Each function names: T, the matrix element; V, what the fold consumes per cell (T itself,
+// or something computed from it once per cell); kPlanes and L: V is kept in local memory as
+// kPlanes separate planes of L, so that neighbouring lanes read neighbouring addresses.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -47,13 +51,22 @@ struct HaloD {
 
 // ---- weighted sum ("gaussian" of Table 2): fp32 fma chain ---------------------------------
 struct OpWeightedSum {
-    using T = float;      // matrix element
-    using L = float;      // what is staged in local memory
+    static constexpr bool kRowFold = false;
+    using T = float;
+    using L = float;
+    using V = float;
+    static constexpr int kPlanes = 1;
     static constexpr bool kWeights = true;
     struct State { float acc; };
-    __device__ static __forceinline__ L stage(T v) { return v; }
+    __device__ static __forceinline__ void stage(T v, L (&out)[1]) { out[0] = v; }
+    __device__ static __forceinline__ V combine(const L (&p)[1]) { return p[0]; }
+    template <int CC>
+    __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[1][CC]) {
+#pragma unroll
+        for (int k = 0; k < CC; ++k) out[0][k] = v[k];
+    }
     __device__ static __forceinline__ void init(State &s) { s.acc = 0.0f; }
-    __device__ static __forceinline__ void visit(State &s, int, int, float w, L v) {
+    __device__ static __forceinline__ void visit(State &s, int, int, float w, V v) {
         s.acc = __fmaf_rn(w, v, s.acc);
     }
     __device__ static __forceinline__ T finish(const State &s, float) { return s.acc; }
@@ -61,13 +74,22 @@ struct OpWeightedSum {
 
 // ---- Conway's Game of Life, B3/S23 ("gol") -------------------------------------------------
 struct OpLife {
+    static constexpr bool kRowFold = false;
     using T = uint8_t;
     using L = uint8_t;
+    using V = uint8_t;
+    static constexpr int kPlanes = 1;
     static constexpr bool kWeights = false;
     struct State { int n; int self; };
-    __device__ static __forceinline__ L stage(T v) { return v; }
+    __device__ static __forceinline__ void stage(T v, L (&out)[1]) { out[0] = v; }
+    __device__ static __forceinline__ V combine(const L (&p)[1]) { return p[0]; }
+    template <int CC>
+    __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[1][CC]) {
+#pragma unroll
+        for (int k = 0; k < CC; ++k) out[0][k] = v[k];
+    }
     __device__ static __forceinline__ void init(State &s) { s.n = 0; s.self = 0; }
-    __device__ static __forceinline__ void visit(State &s, int dr, int dc, float, L v) {
+    __device__ static __forceinline__ void visit(State &s, int dr, int dc, float, V v) {
         if (dr == 0 && dc == 0) s.self = v; else s.n += v;
     }
     __device__ static __forceinline__ T finish(const State &s, float) {
@@ -78,13 +100,22 @@ struct OpLife {
 // ---- heat equation, explicit 5-point step ("he") --------------------------------------------
 // u' = u + alpha * (((n + s) + (e + w)) - 4u), each operation rounded to fp32, in that order.
 struct OpHeat {
+    static constexpr bool kRowFold = false;
     using T = float;
     using L = float;
+    using V = float;
+    static constexpr int kPlanes = 1;
     static constexpr bool kWeights = false;
     struct State { float n, w, u, e, s; };
-    __device__ static __forceinline__ L stage(T v) { return v; }
+    __device__ static __forceinline__ void stage(T v, L (&out)[1]) { out[0] = v; }
+    __device__ static __forceinline__ V combine(const L (&p)[1]) { return p[0]; }
+    template <int CC>
+    __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[1][CC]) {
+#pragma unroll
+        for (int k = 0; k < CC; ++k) out[0][k] = v[k];
+    }
     __device__ static __forceinline__ void init(State &s) { s.n = s.w = s.u = s.e = s.s = 0.0f; }
-    __device__ static __forceinline__ void visit(State &s, int dr, int dc, float, L v) {
+    __device__ static __forceinline__ void visit(State &s, int dr, int dc, float, V v) {
         if (dr == -1 && dc == 0) s.n = v;
         else if (dr == 0 && dc == -1) s.w = v;
         else if (dr == 0 && dc == 0) s.u = v;
@@ -102,23 +133,83 @@ struct OpHeat {
 
 // ---- compute-intensive synthetic stencil: sum of w * sin(x) + cos(x) over the region ------
 // sin and cos are evaluated once per staged cell (fp32) and kept side by side in local
-// memory; the fold keeps one fma chain for the sines and one sum for the cosines.
+// memory (one plane each).  The fold keeps one fma chain for the sines; the cosines of one region row are
+// summed pairwise from the west end ((c0 + c1) + (c2 + c3) + ...), so that neighbouring
+// cells of one work-item share their pair sums, and the row sums are added north to south.
+
+// sin and cos of x in fp32, absolute error below 2e-7 for |x| <= 2^16: x / (2 pi) is formed
+// as a two-term product (1 / (2 pi) split into an fp32 head and tail, fma for the exact
+// partial products), its integer part is dropped, and the hardware sine / cosine (which take
+// their argument in turns) finish the job.
+__device__ __forceinline__ void sincos_small_f32(float x, float &sn_out, float &cs_out) {
+    const float kInv2PiHi = 0.15915493667125702f, kInv2PiLo = 6.4206383e-09f;
+    const float hi = __fmul_rn(x, kInv2PiHi);
+    const float lo = __fmaf_rn(x, kInv2PiLo, __fmaf_rn(x, kInv2PiHi, -hi));
+    const float turns = __fadd_rn(__fsub_rn(hi, rintf(hi)), lo);
+    sn_out = __builtin_amdgcn_sinf(turns);
+    cs_out = __builtin_amdgcn_cosf(turns);
+}
+constexpr float kSinCosSmallLimit = 65536.0f;   // beyond this (or NaN) the library routine is used
+
 struct OpSinCos {
     using T = float;
-    using L = float2;     // (sin x, cos x)
+    using L = float;
+    using V = float2;     // (sin x, cos x)
+    static constexpr int kPlanes = 2;   // a plane of sines and a plane of cosines
     static constexpr bool kWeights = true;
+    static constexpr bool kRowFold = true;
     struct State { float s, c; };
-    __device__ static __forceinline__ L stage(T v) {
-        float sn, cs;
-        sincosf(v, &sn, &cs);
-        return make_float2(sn, cs);
+    __device__ static __forceinline__ void stage(T v, L (&out)[2]) {
+        if (__builtin_expect(fabsf(v) <= kSinCosSmallLimit, 1))
+            sincos_small_f32(v, out[0], out[1]);
+        else
+            sincosf(v, &out[0], &out[1]);
     }
+    // CC cells at once: one range test for all of them
+    template <int CC>
+    __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[2][CC]) {
+        // sum of magnitudes <= limit implies each is; NaN or Inf anywhere makes the test fail
+        float mag = fabsf(v[0]);
+#pragma unroll
+        for (int k = 1; k < CC; ++k) mag = __fadd_rn(mag, fabsf(v[k]));
+        if (__builtin_expect(mag <= kSinCosSmallLimit, 1)) {
+#pragma unroll
+            for (int k = 0; k < CC; ++k) sincos_small_f32(v[k], out[0][k], out[1][k]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < CC; ++k) sincosf(v[k], &out[0][k], &out[1][k]);
+        }
+    }
+    __device__ static __forceinline__ V combine(const L (&p)[2]) { return make_float2(p[0], p[1]); }
     __device__ static __forceinline__ void init(State &s) { s.s = 0.0f; s.c = 0.0f; }
-    __device__ static __forceinline__ void visit(State &s, int, int, float w, L v) {
-        s.s = __fmaf_rn(w, v.x, s.s);
-        s.c = __fadd_rn(s.c, v.y);
+    // one row of the region: w(dc) and v(dc) give weight and staged value at column offset dc
+    template <class WAcc, class VAcc>
+    __device__ static __forceinline__ void visit_row(State &s, int, int W, int E, WAcc w, VAcc v) {
+        for (int dc = -W; dc <= E; ++dc) s.s = __fmaf_rn(w(dc), v(dc).x, s.s);
+        int dc = -W;
+        float h;
+        if (dc + 1 <= E) {
+            h = __fadd_rn(v(dc).y, v(dc + 1).y);
+            dc += 2;
+        } else {
+            h = v(dc).y;
+            dc += 1;
+        }
+        for (; dc + 1 <= E; dc += 2) h = __fadd_rn(h, __fadd_rn(v(dc).y, v(dc + 1).y));
+        if (dc <= E) h = __fadd_rn(h, v(dc).y);
+        s.c = __fadd_rn(s.c, h);
     }
     __device__ static __forceinline__ T finish(const State &s, float) { return __fadd_rn(s.s, s.c); }
 };
+
+// One row of the region folded into a cell's state.
+template <class Op, class WAcc, class VAcc>
+__device__ __forceinline__ void fold_row(typename Op::State &st, int dr, int W, int E, WAcc w, VAcc v) {
+    if constexpr (Op::kRowFold) {
+        Op::visit_row(st, dr, W, E, w, v);
+    } else {
+        for (int dc = -W; dc <= E; ++dc) Op::visit(st, dr, dc, w(dc), v(dc));
+    }
+}
 
 }  // namespace sk

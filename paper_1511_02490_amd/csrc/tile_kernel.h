@@ -37,6 +37,8 @@ struct TileArgs {
     int n_tiles;
     int xcd_chunk;   // > 0: tiles are dealt to the 8 XCDs in contiguous chunks of this many
     int pitch;       // LDS tile pitch, in staged elements
+    int plane;       // elements per LDS plane (tile rows x pitch)
+    unsigned stage_magic;   // ceil(2^32 / items per staged row): tid / items by one multiply
     int vec_ok;      // rows of `in` / `out` start 16-byte aligned and cols % CC == 0
     typename Op::T pad;
     float scalar0;
@@ -76,8 +78,9 @@ template <class Op, int B, class Halo, int CR, int CC, int MAXT>
 __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) {
     using T = typename Op::T;
     using L = typename Op::L;
+    constexpr int NP = Op::kPlanes;
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    L *tile = reinterpret_cast<L *>(lds_raw);
+    L *tile = reinterpret_cast<L *>(lds_raw);   // NP planes of a.plane elements each
 
     const int wr = blockDim.y, wc = blockDim.x;
     const int tx = threadIdx.x, ty = threadIdx.y;
@@ -98,37 +101,48 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
     const int TH = min(th, rows - r0) + hn + hs;
 
     // ---- stage tile + border region into LDS, resolving out-of-matrix positions ----------
-    if constexpr (CC == 1) {
-        const int TW = min(tw, cols - c0) + he + hw;
-        for (int i = ty; i < TH; i += wr) {
+    // The staged rows are walked as one linear sequence of vectors (elements when CC = 1),
+    // work-item k taking items k, k + w_r*w_c, ...: the halo columns then cost a fraction of a
+    // pass instead of a whole extra pass with most lanes idle.
+    {
+        const int n_items = pitch / CC;   // per staged row
+        const int nthreads = wr * wc, tid = ty * wc + tx;
+        int i = (int)__umulhi((unsigned)tid, a.stage_magic);   // tid / n_items
+        int q = tid - i * n_items;
+        const int di = (int)__umulhi((unsigned)nthreads, a.stage_magic), dq = nthreads - di * n_items;
+        while (i < TH) {
             const int gr = resolve<B>(r0 - hn + i, rows);
-            for (int j = tx; j < TW; j += wc) {
-                const int gc = resolve<B>(c0 - hw + j, cols);
+            if constexpr (CC == 1) {
+                const int gc = resolve<B>(c0 - hw + q, cols);
                 const T v = (gr < 0 || gc < 0) ? a.pad : a.in[(size_t)gr * cols + gc];
-                tile[i * pitch + j] = Op::stage(v);
-            }
-        }
-    } else {
-        const int nq = pitch / CC;
-        for (int i = ty; i < TH; i += wr) {
-            const int gr = resolve<B>(r0 - hn + i, rows);
-            for (int q = tx; q < nq; q += wc) {
+                L sv[NP];
+                Op::stage(v, sv);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) tile[p * a.plane + i * pitch + q] = sv[p];
+            } else {
                 const int gc0 = c0 - hwa + q * CC;
-                if (gc0 >= cols + he) continue;      // right of everything this tile needs
-                T v[CC];
-                if (gr >= 0 && a.vec_ok && gc0 >= 0 && gc0 + CC <= cols) {
-                    load_vec(v, a.in + (size_t)gr * cols + gc0);
-                } else {
+                if (gc0 < cols + he) {   // else: right of everything this tile needs
+                    T v[CC];
+                    if (gr >= 0 && a.vec_ok && gc0 >= 0 && gc0 + CC <= cols) {
+                        load_vec(v, a.in + (size_t)gr * cols + gc0);
+                    } else {
 #pragma unroll
-                    for (int k = 0; k < CC; ++k) {
-                        const int gc = resolve<B>(gc0 + k, cols);
-                        v[k] = (gr < 0 || gc < 0) ? a.pad : a.in[(size_t)gr * cols + gc];
+                        for (int k = 0; k < CC; ++k) {
+                            const int gc = resolve<B>(gc0 + k, cols);
+                            v[k] = (gr < 0 || gc < 0) ? a.pad : a.in[(size_t)gr * cols + gc];
+                        }
                     }
-                }
-                L sv[CC];
+                    L sv[NP][CC];
+                    Op::template stage_vec<CC>(v, sv);
 #pragma unroll
-                for (int k = 0; k < CC; ++k) sv[k] = Op::stage(v[k]);
-                store_vec(tile + i * pitch + q * CC, sv);
+                    for (int p = 0; p < NP; ++p) store_vec(tile + p * a.plane + i * pitch + q * CC, sv[p]);
+                }
+            }
+            i += di;
+            q += dq;
+            if (q >= n_items) {
+                q -= n_items;
+                ++i;
             }
         }
     }
@@ -156,24 +170,32 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
 #pragma unroll
         for (int wi = 0; wi < CR + N + S; ++wi) {
             if (lr0 + wi >= TH) break;
-            L row[WW];
-            const L *src = tile + (lr0 + wi) * pitch + lc0 + LO;
-            if constexpr (CC == 1) {
+            L row[NP][WW];
 #pragma unroll
-                for (int k = 0; k < WW; ++k) row[k] = src[k];
-            } else {
-                load_vec(row, src);
+            for (int p = 0; p < NP; ++p) {
+                const L *src = tile + p * a.plane + (lr0 + wi) * pitch + lc0 + LO;
+                if constexpr (CC == 1) {
+#pragma unroll
+                    for (int k = 0; k < WW; ++k) row[p][k] = src[k];
+                } else {
+                    load_vec(row[p], src);
+                }
             }
+            auto value_at = [&](int i) {
+                L parts[NP];
+#pragma unroll
+                for (int p = 0; p < NP; ++p) parts[p] = row[p][i];
+                return Op::combine(parts);
+            };
 #pragma unroll
             for (int cr = 0; cr < CR; ++cr) {
                 const int dr = wi - N - cr;
                 if (dr < -N || dr > S) continue;
 #pragma unroll
                 for (int cc = 0; cc < CC; ++cc)
-#pragma unroll
-                    for (int dc = -W; dc <= E; ++dc)
-                        Op::visit(st[cr][cc], dr, dc, a.w[(dr + N) * WCOLS + dc + W],
-                                  row[HWA - LO + cc + dc]);
+                    fold_row<Op>(
+                        st[cr][cc], dr, W, E, [&](int dc) { return a.w[(dr + N) * WCOLS + dc + W]; },
+                        [&](int dc) { return value_at(HWA - LO + cc + dc); });
             }
         }
     } else {
@@ -185,8 +207,14 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
             for (int cc = 0; cc < CC; ++cc) {
                 const L *ctr = tile + (lr0 + cr + hn) * pitch + hwa + lc0 + cc;
                 for (int dr = -hn; dr <= hs; ++dr)
-                    for (int dc = -hw; dc <= he; ++dc)
-                        Op::visit(st[cr][cc], dr, dc, a.w[(dr + hn) * wcols + dc + hw], ctr[dr * pitch + dc]);
+                    fold_row<Op>(
+                        st[cr][cc], dr, hw, he, [&](int dc) { return a.w[(dr + hn) * wcols + dc + hw]; },
+                        [&](int dc) {
+                            L parts[NP];
+#pragma unroll
+                            for (int p = 0; p < NP; ++p) parts[p] = ctr[p * a.plane + dr * pitch + dc];
+                            return Op::combine(parts);
+                        });
             }
         }
     }
