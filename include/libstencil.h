@@ -73,7 +73,7 @@ enum stencil_enum_mode {
 
 #define STENCIL_MAX_HALO 32            /* Table 2's border sizes go up to 30 */
 #define STENCIL_MAX_WG_SIZE 1024       /* device limit on work-items per workgroup */
-#define STENCIL_LOCAL_MEM_BYTES 65536  /* local memory one workgroup may allocate */
+#define STENCIL_LOCAL_MEM_BYTES 163840 /* local memory one workgroup may allocate (160 KiB) */
 
 /* ---- scenario ---------------------------------------------------------------------- */
 

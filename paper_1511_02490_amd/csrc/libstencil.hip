@@ -150,6 +150,19 @@ hipError_t launch_tile(const stencil *s, const void *in, void *out, int wr, int 
     unsigned blocks;
     size_t lds;
     const auto a = make_args<Op, Halo, CR, CC>(s, STENCIL_STAGING_LOCAL, in, out, wr, wc, &blocks, &lds);
+    // tiles above 64 KiB need the kernel's dynamic local-memory limit raised once (per device)
+    static thread_local int raised_on = -1;
+    if (lds > 65536) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (raised_on != dev) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&sk::tile_kernel<Op, B, Halo, CR, CC, MAXT>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, STENCIL_LOCAL_MEM_BYTES);
+            if (e != hipSuccess) return e;
+            raised_on = dev;
+        }
+    }
     hipLaunchKernelGGL((sk::tile_kernel<Op, B, Halo, CR, CC, MAXT>), dim3(blocks), dim3(wc, wr), lds, stream, a);
     return hipGetLastError();
 }

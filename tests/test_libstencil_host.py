@@ -60,7 +60,7 @@ def test_legality_eq1():
     assert st.max_wg_size() == 1024
     cands = tuning.enumerate_sizes("pow2", 2048)
     for w in cands:
-        tile_ok = st.tile_bytes(*w) <= 65536
+        tile_ok = st.tile_bytes(*w) <= 160 * 1024
         assert st.is_legal(*w) == (tuning.is_legal(w, 1024) and tile_ok)
     assert not st.is_legal(0, 4) and not st.is_legal(4, 0) and not st.is_legal(-2, 2)
     # the tile of Section 2: (w_r + N + S) x (w_c + E + W) elements of 4 bytes
@@ -75,7 +75,8 @@ def test_legality_eq1():
     with pytest.raises(ls.StencilError):
         big.set_mapping("direct", 1, 4)                  # no cache-staged variant for a 30-cell region
     big.set_blocking(4, 4)
-    assert not big.is_legal(32, 32)                      # (128+60) x (128+64) floats > 64 KiB
+    assert big.tile_bytes(32, 32) == (128 + 60) * (128 + 64) * 4 and big.is_legal(32, 32)
+    assert big.tile_bytes(128, 8) == (512 + 60) * (32 + 64) * 4 and not big.is_legal(128, 8)   # > 160 KiB
     assert "refused" in ls.last_error()
 
 
@@ -87,7 +88,7 @@ def test_blocking_changes_tile_and_per_kernel_limit():
     assert st.get_blocking() == (8, 4)
     assert st.max_wg_size() == 256                       # register-heavy variant: lower per-kernel limit
     assert st.is_legal(2, 64) and not st.is_legal(8, 64)          # 512 work-items > 256
-    assert not st.is_legal(4, 64)                                 # 38 x 260 (sin, cos) pairs > 64 KiB
+    assert st.tile_bytes(4, 64) == 38 * 260 * 8 and st.is_legal(4, 64)   # sine plane + cosine plane
     with pytest.raises(ls.StencilError):
         st.set_blocking(3, 4)
     # cache-staged mapping: no tile in local memory, nothing refused below W_max
@@ -96,7 +97,8 @@ def test_blocking_changes_tile_and_per_kernel_limit():
     assert heat.get_mapping() == (ls.STAGING_DIRECT, 1, 4)
     assert heat.tile_bytes(32, 32) == 0 and heat.is_legal(1, 1024) and not heat.is_legal(2, 1024)
     heat.set_mapping("local", 8, 4)
-    assert heat.tile_bytes(32, 32) == (256 + 2) * (128 + 8) * 4 and not heat.is_legal(32, 32)
+    assert heat.tile_bytes(32, 32) == (256 + 2) * (128 + 8) * 4 and heat.is_legal(32, 32)
+    assert heat.tile_bytes(128, 8) == (1024 + 2) * (32 + 8) * 4 and not heat.is_legal(128, 8)   # > 160 KiB
 
 
 def test_sweep_reduce_matches_definitions():
