@@ -105,6 +105,12 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            global memory as 16-byte vectors and rely on the L1/L2 caches for the overlap.
  *            Available for WEIGHTED_SUM with regions 1/1/1/1 and 2/2/2/2, HEAT and LIFE;
  *            needs no local memory, so no size is refused for its tile.
+ *            STENCIL_STAGING_TEMPORAL - temporal blocking for iterated runs: one launch stages
+ *            the tile plus a border region STENCIL_OPT_TEMPORAL_DEPTH cells deep in local
+ *            memory and advances it by that many applications before writing it back, so a
+ *            stencil_run of `iters` applications takes ceil(iters / depth) launches.
+ *            Available for HEAT and for WEIGHTED_SUM with region 1/1/1/1; cells_cols = 4,
+ *            cells_rows in {1,2,4,8}.
  *   cells_rows x cells_cols: block of adjacent cells one work-item computes (register
  *            blocking); a workgroup of w_r x w_c work-items covers (w_r*cells_rows) x
  *            (w_c*cells_cols) elements.  (1,1) is the paper's one element per work-item.
@@ -112,13 +118,16 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            DIRECT: cells_rows in {1,2,4}, cells_cols = 4 (F32) or 16 (U8).
  * Output values never depend on the mapping.  Heavily blocked variants have a lower per-kernel
  * W_max (Section 3.1), see stencil_max_wg_size. */
-enum stencil_staging { STENCIL_STAGING_LOCAL = 0, STENCIL_STAGING_DIRECT = 1 };
+enum stencil_staging { STENCIL_STAGING_LOCAL = 0, STENCIL_STAGING_DIRECT = 1, STENCIL_STAGING_TEMPORAL = 2 };
 int stencil_set_mapping(stencil_t *st, int staging, int cells_rows, int cells_cols);
 int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int *cells_cols);
 
 /* Launch options.  STENCIL_OPT_XCD_REMAP (default 1): workgroups are numbered so that each of
- * the eight XCDs (each with its own L2) works on one contiguous band of tiles. */
-enum stencil_option { STENCIL_OPT_XCD_REMAP = 0 };
+ * the eight XCDs (each with its own L2) works on one contiguous band of tiles.
+ * STENCIL_OPT_TEMPORAL_DEPTH (default 2, 1..STENCIL_MAX_TEMPORAL_DEPTH): applications fused
+ * into one launch under STENCIL_STAGING_TEMPORAL. */
+#define STENCIL_MAX_TEMPORAL_DEPTH 4
+enum stencil_option { STENCIL_OPT_XCD_REMAP = 0, STENCIL_OPT_TEMPORAL_DEPTH = 1 };
 int stencil_set_option(stencil_t *st, int option, int value);
 
 /* ---- legality (Section 3.1) ---------------------------------------------------------- */

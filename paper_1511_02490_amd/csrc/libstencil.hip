@@ -15,6 +15,7 @@
 #include "../../include/libstencil.h"
 #include "host_tuning.h"
 #include "direct_kernel.h"
+#include "temporal_kernel.h"
 #include "tile_kernel.h"
 
 namespace {
@@ -37,10 +38,11 @@ int fail_hip(hipError_t e, const char *what) {
 
 // ---- scenario handle ---------------------------------------------------------------------
 
-using LaunchFn = hipError_t (*)(const stencil *, const void *, void *, int, int, hipStream_t);
+// (scenario, in, out, wg_rows, wg_cols, applications fused into this launch, stream)
+using LaunchFn = hipError_t (*)(const stencil *, const void *, void *, int, int, int, hipStream_t);
 
 struct Variant {
-    int staging;          // STENCIL_STAGING_LOCAL or STENCIL_STAGING_DIRECT
+    int staging;          // STENCIL_STAGING_LOCAL, _DIRECT or _TEMPORAL
     int kernel, border;
     int hn, hs, he, hw;   // -1: run-time border region
     int cr, cc;
@@ -61,6 +63,7 @@ struct stencil {
     int staging = STENCIL_STAGING_LOCAL;
     int cr = 1, cc = 1;
     int xcd_remap = 1;
+    int temporal_depth = 2;   // applications per launch under STENCIL_STAGING_TEMPORAL
     int best_rows = 0, best_cols = 0;
     // device-side state, created on first use
     void *scratch = nullptr;
@@ -76,6 +79,7 @@ namespace {
 struct TileGeom {
     int th, tw;        // elements covered by one workgroup
     int pitch;         // LDS pitch in staged elements
+    int plane;         // staged elements per LDS plane
     int64_t lds_bytes;
     int tiles_r, tiles_c;
 };
@@ -87,9 +91,17 @@ TileGeom tile_geom(const stencil *s, const Variant &v, int wr, int wc) {
     const int hwa = v.cc == 1 ? s->hw : sk::round_up(s->hw, v.cc);
     const int hea = v.cc == 1 ? s->he : sk::round_up(s->he, v.cc);
     g.pitch = hwa + g.tw + hea;
-    g.lds_bytes = v.staging == STENCIL_STAGING_DIRECT
-                      ? 0
-                      : (int64_t)(g.th + s->hn + s->hs) * g.pitch * v.staged_bytes;
+    g.plane = (g.th + s->hn + s->hs) * g.pitch;
+    g.lds_bytes = (int64_t)g.plane * v.staged_bytes;
+    if (v.staging == STENCIL_STAGING_DIRECT) {
+        g.plane = 0;
+        g.lds_bytes = 0;
+    } else if (v.staging == STENCIL_STAGING_TEMPORAL) {
+        // tile + `depth` rows above and below, one vector left and right; two buffers
+        g.pitch = g.tw + 2 * v.cc;
+        g.plane = (g.th + 2 * s->temporal_depth) * g.pitch;
+        g.lds_bytes = 2 * (int64_t)g.plane * v.staged_bytes;
+    }
     g.tiles_r = (int)((s->rows + g.th - 1) / g.th);
     g.tiles_c = (int)((s->cols + g.tw - 1) / g.tw);
     return g;
@@ -114,7 +126,7 @@ sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, 
     a.tiles_c = g.tiles_c;
     a.n_tiles = g.tiles_r * g.tiles_c;
     a.pitch = g.pitch;
-    a.plane = (g.th + s->hn + s->hs) * g.pitch;
+    a.plane = g.plane;
     {
         const unsigned items = (unsigned)(g.pitch / CC);   // vectors (elements when CC = 1) per staged row
         a.stage_magic = (unsigned)((0x100000000ull + items - 1) / items);
@@ -145,30 +157,51 @@ sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, 
     return a;
 }
 
+// Tiles above 64 KiB need the kernel's dynamic local-memory limit raised, once per kernel and
+// device; `raised_on` remembers the device it was last done on.
+hipError_t allow_large_tiles(const void *kernel, size_t lds, int *raised_on) {
+    if (lds <= 65536) return hipSuccess;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (*raised_on != dev) {
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, STENCIL_LOCAL_MEM_BYTES);
+        if (e != hipSuccess) return e;
+        *raised_on = dev;
+    }
+    return hipSuccess;
+}
+
+template <class Op, int B, int CR, int MAXT>
+hipError_t launch_temporal(const stencil *s, const void *in, void *out, int wr, int wc, int depth,
+                           hipStream_t stream) {
+    using Halo = sk::HaloC<1, 1, 1, 1>;
+    unsigned blocks;
+    size_t lds;
+    const auto a = make_args<Op, Halo, CR, 4>(s, STENCIL_STAGING_TEMPORAL, in, out, wr, wc, &blocks, &lds);
+    static thread_local int raised_on = -1;
+    hipError_t e = allow_large_tiles(reinterpret_cast<const void *>(&sk::temporal_kernel<Op, B, CR, MAXT>), lds,
+                                     &raised_on);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((sk::temporal_kernel<Op, B, CR, MAXT>), dim3(blocks), dim3(wc, wr), lds, stream, a, depth);
+    return hipGetLastError();
+}
+
 template <class Op, int B, class Halo, int CR, int CC, int MAXT>
-hipError_t launch_tile(const stencil *s, const void *in, void *out, int wr, int wc, hipStream_t stream) {
+hipError_t launch_tile(const stencil *s, const void *in, void *out, int wr, int wc, int, hipStream_t stream) {
     unsigned blocks;
     size_t lds;
     const auto a = make_args<Op, Halo, CR, CC>(s, STENCIL_STAGING_LOCAL, in, out, wr, wc, &blocks, &lds);
-    // tiles above 64 KiB need the kernel's dynamic local-memory limit raised once (per device)
     static thread_local int raised_on = -1;
-    if (lds > 65536) {
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        if (raised_on != dev) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&sk::tile_kernel<Op, B, Halo, CR, CC, MAXT>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, STENCIL_LOCAL_MEM_BYTES);
-            if (e != hipSuccess) return e;
-            raised_on = dev;
-        }
-    }
+    hipError_t e = allow_large_tiles(reinterpret_cast<const void *>(&sk::tile_kernel<Op, B, Halo, CR, CC, MAXT>),
+                                     lds, &raised_on);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((sk::tile_kernel<Op, B, Halo, CR, CC, MAXT>), dim3(blocks), dim3(wc, wr), lds, stream, a);
     return hipGetLastError();
 }
 
 template <class Op, int B, class Halo, int CR, int CC, int MAXT>
-hipError_t launch_direct(const stencil *s, const void *in, void *out, int wr, int wc, hipStream_t stream) {
+hipError_t launch_direct(const stencil *s, const void *in, void *out, int wr, int wc, int, hipStream_t stream) {
     unsigned blocks;
     size_t lds;
     const auto a = make_args<Op, Halo, CR, CC>(s, STENCIL_STAGING_DIRECT, in, out, wr, wc, &blocks, &lds);
@@ -177,7 +210,7 @@ hipError_t launch_direct(const stencil *s, const void *in, void *out, int wr, in
 }
 
 template <int B, int CR, int MAXT>
-hipError_t launch_life_direct(const stencil *s, const void *in, void *out, int wr, int wc, hipStream_t stream) {
+hipError_t launch_life_direct(const stencil *s, const void *in, void *out, int wr, int wc, int, hipStream_t stream) {
     unsigned blocks;
     size_t lds;
     const auto a = make_args<sk::OpLife, sk::HaloC<1, 1, 1, 1>, CR, 16>(s, STENCIL_STAGING_DIRECT, in, out, wr, wc,
@@ -258,6 +291,28 @@ void reg_direct(std::vector<Variant> &r) {
     reg_direct_one<Op, KID, sk::kConstant, Halo, 4, CC>(r);
 }
 
+template <class Op, int KID, int B, int CR>
+void reg_temporal_one(std::vector<Variant> &r) {
+    Variant v;
+    v.staging = STENCIL_STAGING_TEMPORAL;
+    v.kernel = KID;
+    v.border = B;
+    v.hn = v.hs = v.he = v.hw = 1;
+    v.cr = CR;
+    v.cc = 4;
+    v.max_threads = STENCIL_MAX_WG_SIZE;
+    v.staged_bytes = 4;
+    v.launch = &launch_temporal<Op, B, CR, STENCIL_MAX_WG_SIZE>;
+    r.push_back(v);
+}
+
+template <class Op, int KID, int CR>
+void reg_temporal(std::vector<Variant> &r) {
+    reg_temporal_one<Op, KID, sk::kClamp, CR>(r);
+    reg_temporal_one<Op, KID, sk::kWrap, CR>(r);
+    reg_temporal_one<Op, KID, sk::kConstant, CR>(r);
+}
+
 template <int B, int CR>
 void reg_life_direct_one(std::vector<Variant> &r) {
     Variant v;
@@ -312,6 +367,14 @@ const std::vector<Variant> &registry() {
         reg_direct<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<1, 1, 1, 1>, 4>(r);
         reg_direct<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<2, 2, 2, 2>, 4>(r);
         reg_direct<sk::OpHeat, STENCIL_HEAT, sk::HaloC<1, 1, 1, 1>, 4>(r);
+        reg_temporal<sk::OpHeat, STENCIL_HEAT, 1>(r);
+        reg_temporal<sk::OpHeat, STENCIL_HEAT, 2>(r);
+        reg_temporal<sk::OpHeat, STENCIL_HEAT, 4>(r);
+        reg_temporal<sk::OpHeat, STENCIL_HEAT, 8>(r);
+        reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 1>(r);
+        reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 2>(r);
+        reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 4>(r);
+        reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 8>(r);
         reg_life_direct<1>(r);
         reg_life_direct<2>(r);
         reg_life_direct<4>(r);
@@ -388,11 +451,17 @@ int run_checked(stencil *s, const Variant *v, const void *in, void *out, int ite
         hipError_t e = hipMemcpyAsync(out, in, s->bytes(), hipMemcpyDeviceToDevice, stream);
         return e == hipSuccess ? STENCIL_OK : fail_hip(e, "hipMemcpyAsync");
     }
+    // `per` applications per launch; the launches alternate between `out` and the scratch
+    // matrix so that the last one lands in `out`
+    const int per = v->staging == STENCIL_STAGING_TEMPORAL ? s->temporal_depth : 1;
+    const int launches = (iters + per - 1) / per;
     const void *src = in;
-    void *dst = (iters % 2 == 1) ? out : s->scratch;
-    for (int it = 0; it < iters; ++it) {
-        hipError_t e = v->launch(s, src, dst, wr, wc, stream);
+    void *dst = (launches % 2 == 1) ? out : s->scratch;
+    for (int done = 0; done < iters;) {
+        const int now = std::min(per, iters - done);
+        hipError_t e = v->launch(s, src, dst, wr, wc, now, stream);
         if (e != hipSuccess) return fail_hip(e, "kernel launch");
+        done += now;
         src = dst;
         dst = (dst == out) ? s->scratch : out;
     }
@@ -541,6 +610,12 @@ int stencil_set_option(stencil_t *s, int option, int value) {
     switch (option) {
     case STENCIL_OPT_XCD_REMAP:
         s->xcd_remap = value ? 1 : 0;
+        return STENCIL_OK;
+    case STENCIL_OPT_TEMPORAL_DEPTH:
+        if (value < 1 || value > STENCIL_MAX_TEMPORAL_DEPTH)
+            return fail(STENCIL_E_INVALID, "temporal depth must be in [1, %d]", STENCIL_MAX_TEMPORAL_DEPTH);
+        s->temporal_depth = value;
+        s->best_rows = s->best_cols = 0;
         return STENCIL_OK;
     default:
         return fail(STENCIL_E_INVALID, "unknown option %d", option);

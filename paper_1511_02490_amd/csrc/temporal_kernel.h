@@ -1,0 +1,140 @@
+// Temporal blocking for iterated stencils with the 1/1/1/1 border region: one launch
+// advances the matrix by `depth` applications (1 <= depth <= 4).  The workgroup stages its tile
+// plus a border region `depth` cells deep (rows) and one 16-byte vector wide (columns) in local
+// memory, then ping-pongs between two LDS buffers: after application k the values within k
+// cells of the staged rim are stale, and after `depth` applications exactly the tile itself is
+// still right and is written out.  HBM traffic per application falls by the depth; the price is
+// the redundant rim work and one barrier per application.
+//
+// Out-of-matrix positions inside the staged tile are re-resolved after every application: a
+// periodic copy evolves like its original (nothing to do), a padded position is set back to the
+// padding value, a clamped position is copied from the nearest in-matrix cell's new value.
+// The per-cell arithmetic is the same fold as in the single-application kernels, so results
+// are bit-identical to `depth` separate launches.
+#pragma once
+#include "tile_kernel.h"
+
+namespace sk {
+
+// One application for the four cells of vector q in tile row i, read from `src`.
+template <class Op>
+__device__ __forceinline__ void temporal_quad(typename Op::T (&res)[4], const float *src, int pitch, int nq, int i, int q,
+                                              const WeightStore<Op, HaloC<1, 1, 1, 1>> &w, float scalar0) {
+    typename Op::State st[4];
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) Op::init(st[cc]);
+#pragma unroll
+    for (int dr = -1; dr <= 1; ++dr) {
+        const float *rp = src + (i + dr) * pitch + q * 4;
+        float row[6];
+        float ctr[4];
+        load_vec(ctr, rp);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) row[1 + k] = ctr[k];
+        row[0] = q > 0 ? rp[-1] : ctr[0];            // beyond the staged rim: any value will do
+        row[5] = q < nq - 1 ? rp[4] : ctr[3];
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+            fold_row<Op>(
+                st[cc], dr, 1, 1, [&](int dc) { return w[(dr + 1) * 3 + dc + 1]; },
+                [&](int dc) { return row[1 + cc + dc]; });
+    }
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) res[cc] = Op::finish(st[cc], scalar0);
+}
+
+template <class Op, int B, int CR, int MAXT>
+__global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC<1, 1, 1, 1>> a, const int depth) {
+    using T = typename Op::T;
+    static_assert(Op::kPlanes == 1 && sizeof(T) == 4 && sizeof(typename Op::L) == 4, "fp32, one plane");
+    constexpr int CC = 4, HC = 4;   // cells per vector; staged columns each side of the tile
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    float *src = reinterpret_cast<float *>(lds_raw);
+    float *dst = src + a.plane;
+
+    const int wr = blockDim.y, wc = blockDim.x;
+    const int tx = threadIdx.x, ty = threadIdx.y;
+    const int tid = ty * wc + tx, nthreads = wr * wc;
+
+    int t = blockIdx.x;
+    if (a.xcd_chunk > 0) t = (t & 7) * a.xcd_chunk + (t >> 3);
+    if (t >= a.n_tiles) return;
+    const int tile_r = t / a.tiles_c, tile_c = t - tile_r * a.tiles_c;
+    const int rows = a.rows, cols = a.cols, pitch = a.pitch, nq = pitch / CC;
+    const int th = wr * CR, tw = wc * CC;
+    const int r0 = tile_r * th, c0 = tile_c * tw;
+    const int row_first = r0 - depth, col_first = c0 - HC;
+    const int ER = min(th, rows - r0) + 2 * depth;   // staged rows in use
+
+    stage_tile<Op, B, CC>(src, a.plane, pitch, a.in, rows, cols, row_first, col_first, ER, cols + HC, a.pad,
+                          a.vec_ok, a.stage_magic, tid, nthreads);
+    __syncthreads();
+
+    // does the staged tile reach outside the matrix?  (same answer for the whole workgroup)
+    const bool at_border = row_first < 0 || row_first + ER > rows || col_first < 0 || col_first + pitch > cols;
+    const int di = (int)__umulhi((unsigned)nthreads, a.stage_magic), dq = nthreads - di * nq;
+
+    for (int k = 1; k < depth; ++k) {
+        // application k on tile rows [k, ER - k): everything that can still be right
+        int i = k + (int)__umulhi((unsigned)tid, a.stage_magic);
+        int q = tid - (i - k) * nq;
+        while (i < ER - k) {
+            T res[CC];
+            temporal_quad<Op>(res, src, pitch, nq, i, q, a.w, a.scalar0);
+            if (B == kConstant && at_border) {
+                const int gr = row_first + i;
+#pragma unroll
+                for (int cc = 0; cc < CC; ++cc) {
+                    const int gc = col_first + q * CC + cc;
+                    if ((unsigned)gr >= (unsigned)rows || (unsigned)gc >= (unsigned)cols) res[cc] = a.pad;
+                }
+            }
+            store_vec(dst + i * pitch + q * CC, res);
+            i += di;
+            q += dq;
+            if (q >= nq) {
+                q -= nq;
+                ++i;
+            }
+        }
+        __syncthreads();
+        if (B == kClamp && at_border) {
+            // clamped positions take the new value of the nearest in-matrix cell
+            for (int idx = tid; idx < (ER - 2 * k) * pitch; idx += nthreads) {
+                const int i2 = k + idx / pitch, j2 = idx % pitch;
+                const int gr = row_first + i2, gc = col_first + j2;
+                if ((unsigned)gr >= (unsigned)rows || (unsigned)gc >= (unsigned)cols) {
+                    const int ci = min(max(gr, 0), rows - 1) - row_first, cj = min(max(gc, 0), cols - 1) - col_first;
+                    // the nearest cell lies inside the staged tile whenever this position can
+                    // still influence the tile's own cells; stale rim positions may skip it
+                    if (ci >= k && ci < ER - k && cj >= 0 && cj < pitch) dst[i2 * pitch + j2] = dst[ci * pitch + cj];
+                }
+            }
+            __syncthreads();
+        }
+        float *tmp = src;
+        src = dst;
+        dst = tmp;
+    }
+
+    // last application: the tile's own cells, straight to global memory
+    const int c = c0 + tx * CC;
+    if (c >= cols) return;
+#pragma unroll
+    for (int cr = 0; cr < CR; ++cr) {
+        const int r = r0 + ty * CR + cr;
+        if (r >= rows) break;
+        T res[CC];
+        temporal_quad<Op>(res, src, pitch, nq, depth + ty * CR + cr, 1 + tx, a.w, a.scalar0);
+        T *out = a.out + (size_t)r * cols + c;
+        if (a.vec_ok && c + CC <= cols) {
+            store_vec(out, res);
+        } else {
+#pragma unroll
+            for (int cc = 0; cc < CC; ++cc)
+                if (c + cc < cols) out[cc] = res[cc];
+        }
+    }
+}
+
+}  // namespace sk

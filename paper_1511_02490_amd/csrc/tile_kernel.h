@@ -74,6 +74,62 @@ __device__ __forceinline__ void store_vec(E *dst, const E (&src)[CNT]) {
 template <int CC>
 __host__ __device__ constexpr int staged_halo(int h) { return CC == 1 ? h : round_up(h, CC); }
 
+// Stages `n_rows` rows of a tile into LDS with border resolution (Section 2).  Tile row i is
+// matrix row row_first + i, tile column j is matrix column col_first + j; each plane of the
+// staged values has `pitch` elements per row.  The rows are walked as one linear sequence of
+// 16-byte vectors (single elements when CC = 1), work-item k taking items k, k + n, k + 2n, ...
+// so that the halo columns cost a fraction of a pass rather than a whole extra pass with most
+// lanes idle.  Vectors starting at or beyond matrix column `col_end` are not needed and skipped.
+// `magic` = ceil(2^32 / (pitch / CC)) turns the one division into a multiply.
+template <class Op, int B, int CC>
+__device__ __forceinline__ void stage_tile(typename Op::L *tile, int plane, int pitch, const typename Op::T *in,
+                                           int rows, int cols, int row_first, int col_first, int n_rows,
+                                           int col_end, typename Op::T pad, int vec_ok, unsigned magic, int tid,
+                                           int nthreads) {
+    using T = typename Op::T;
+    using L = typename Op::L;
+    constexpr int NP = Op::kPlanes;
+    const int n_items = pitch / CC;   // per staged row
+    int i = (int)__umulhi((unsigned)tid, magic);
+    int q = tid - i * n_items;
+    const int di = (int)__umulhi((unsigned)nthreads, magic), dq = nthreads - di * n_items;
+    while (i < n_rows) {
+        const int gr = resolve<B>(row_first + i, rows);
+        if constexpr (CC == 1) {
+            const int gc = resolve<B>(col_first + q, cols);
+            const T v = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
+            L sv[NP];
+            Op::stage(v, sv);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) tile[p * plane + i * pitch + q] = sv[p];
+        } else {
+            const int gc0 = col_first + q * CC;
+            if (gc0 < col_end) {
+                T v[CC];
+                if (gr >= 0 && vec_ok && gc0 >= 0 && gc0 + CC <= cols) {
+                    load_vec(v, in + (size_t)gr * cols + gc0);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < CC; ++k) {
+                        const int gc = resolve<B>(gc0 + k, cols);
+                        v[k] = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
+                    }
+                }
+                L sv[NP][CC];
+                Op::template stage_vec<CC>(v, sv);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) store_vec(tile + p * plane + i * pitch + q * CC, sv[p]);
+            }
+        }
+        i += di;
+        q += dq;
+        if (q >= n_items) {
+            q -= n_items;
+            ++i;
+        }
+    }
+}
+
 template <class Op, int B, class Halo, int CR, int CC, int MAXT>
 __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) {
     using T = typename Op::T;
@@ -100,52 +156,8 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
     // rows of the tile that exist in the matrix, plus the border region
     const int TH = min(th, rows - r0) + hn + hs;
 
-    // ---- stage tile + border region into LDS, resolving out-of-matrix positions ----------
-    // The staged rows are walked as one linear sequence of vectors (elements when CC = 1),
-    // work-item k taking items k, k + w_r*w_c, ...: the halo columns then cost a fraction of a
-    // pass instead of a whole extra pass with most lanes idle.
-    {
-        const int n_items = pitch / CC;   // per staged row
-        const int nthreads = wr * wc, tid = ty * wc + tx;
-        int i = (int)__umulhi((unsigned)tid, a.stage_magic);   // tid / n_items
-        int q = tid - i * n_items;
-        const int di = (int)__umulhi((unsigned)nthreads, a.stage_magic), dq = nthreads - di * n_items;
-        while (i < TH) {
-            const int gr = resolve<B>(r0 - hn + i, rows);
-            if constexpr (CC == 1) {
-                const int gc = resolve<B>(c0 - hw + q, cols);
-                const T v = (gr < 0 || gc < 0) ? a.pad : a.in[(size_t)gr * cols + gc];
-                L sv[NP];
-                Op::stage(v, sv);
-#pragma unroll
-                for (int p = 0; p < NP; ++p) tile[p * a.plane + i * pitch + q] = sv[p];
-            } else {
-                const int gc0 = c0 - hwa + q * CC;
-                if (gc0 < cols + he) {   // else: right of everything this tile needs
-                    T v[CC];
-                    if (gr >= 0 && a.vec_ok && gc0 >= 0 && gc0 + CC <= cols) {
-                        load_vec(v, a.in + (size_t)gr * cols + gc0);
-                    } else {
-#pragma unroll
-                        for (int k = 0; k < CC; ++k) {
-                            const int gc = resolve<B>(gc0 + k, cols);
-                            v[k] = (gr < 0 || gc < 0) ? a.pad : a.in[(size_t)gr * cols + gc];
-                        }
-                    }
-                    L sv[NP][CC];
-                    Op::template stage_vec<CC>(v, sv);
-#pragma unroll
-                    for (int p = 0; p < NP; ++p) store_vec(tile + p * a.plane + i * pitch + q * CC, sv[p]);
-                }
-            }
-            i += di;
-            q += dq;
-            if (q >= n_items) {
-                q -= n_items;
-                ++i;
-            }
-        }
-    }
+    stage_tile<Op, B, CC>(tile, a.plane, pitch, a.in, rows, cols, r0 - hn, c0 - hwa, TH, cols + he, a.pad,
+                          a.vec_ok, a.stage_magic, ty * wc + tx, wr * wc);
     __syncthreads();
 
     // ---- fold the customising function over the border region ----------------------------

@@ -65,7 +65,8 @@ def main():
     ap.add_argument("--kernel", required=True, help="substring naming the stencil kernel")
     ap.add_argument("--title", default="")
     ap.add_argument("--command", default="", help="the bench.py arguments the three runs used")
-    ap.add_argument("--record", default="", help="key under which to store the traffic in profiles/traffic.json")
+    ap.add_argument("--record", action="store_true",
+                    help="store the traffic in profiles/traffic.json under the kernel's label")
     a = ap.parse_args()
     d, p = a.dir, a.prefix
 
@@ -134,13 +135,13 @@ def main():
         if os.path.exists(TRAFFIC_JSON):
             with open(TRAFFIC_JSON) as fh:
                 rec = json.load(fh)
-        rec[a.record] = {"kernel": roof["kernel"], "traffic_bytes_per_launch": traffic,
+        rec[roof["kernel"]] = {"workload": bench["config"]["workload"], "traffic_bytes_per_launch": traffic,
                          "fetch_kib": f_kib, "write_kib": w_kib, "fetch_scale": f_scale, "write_scale": w_scale,
                          "source_hash": kernel_source_hash()}
         with open(TRAFFIC_JSON, "w") as fh:
             json.dump(rec, fh, indent=1, sort_keys=True)
             fh.write("\n")
-        print("recorded %s in %s" % (a.record, TRAFFIC_JSON), file=sys.stderr)
+        print("recorded %r in %s" % (roof["kernel"], TRAFFIC_JSON), file=sys.stderr)
 
 
 if __name__ == "__main__":

@@ -33,8 +33,12 @@ def rel_err(got, ref):
 
 
 def set_mapping(st, blocking):
-    """blocking = (cells_rows, cells_cols) under local-memory staging, or ("direct", cr, cc)."""
-    if len(blocking) == 3:
+    """blocking = (cells_rows, cells_cols) under local-memory staging, ("direct", cr, cc), or
+    ("temporal", cr, cc, depth)."""
+    if len(blocking) == 4:
+        st.set_mapping(*blocking[:3])
+        st.set_option(1, blocking[3])          # STENCIL_OPT_TEMPORAL_DEPTH
+    elif len(blocking) == 3:
         st.set_mapping(*blocking)
     else:
         st.set_mapping("local", *blocking)
@@ -176,6 +180,43 @@ def test_heat_conserves_total_and_long_run(ls):
     s0, s1 = g.astype(np.float64).sum(), got.astype(np.float64).sum()
     assert abs(s1 - s0) / s0 < 1e-6
     assert got.min() >= g.min() and got.max() <= g.max()
+
+
+# ---- temporal blocking: several applications per launch ------------------------------------
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_temporal_blocking_heat_bit_exact(ls, border):
+    for rows, cols, iters in [(160, 216, 13), (61, 83, 7), (128, 256, 8)]:
+        w = wl.config(3, rows=rows, cols=cols, iters=iters)
+        w.border, w.pad = border, 50.0
+        for depth in (1, 2, 3, 4):
+            for cr, wg in [(1, (4, 16)), (2, (4, 64)), (4, (2, 8)), (8, (3, 5)), (4, (16, 16))]:
+                check(ls, w, wg, blocking=("temporal", cr, 4, depth))
+
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_temporal_blocking_weighted_sum_and_tiny(ls, border):
+    w = custom(wl.WEIGHTED_SUM, 90, 117, (1, 1, 1, 1), border, pad=0.4, seed=21, iters=9)
+    for depth in (2, 4):
+        check(ls, w, (4, 16), blocking=("temporal", 2, 4, depth))
+        check(ls, w, (8, 8), blocking=("temporal", 4, 4, depth), offset=1)
+    for shape in [(1, 1), (1, 9), (7, 1), (3, 4), (5, 6)]:      # smaller than the staged rim
+        wt = wl.config(3, rows=shape[0], cols=shape[1], iters=6)
+        wt.border, wt.pad = border, 20.0
+        check(ls, wt, (2, 4), blocking=("temporal", 2, 4, 4))
+        check(ls, wt, (2, 4), blocking=("temporal", 1, 4, 3))
+
+
+def test_temporal_blocking_not_offered_for_other_regions(ls):
+    st = ls.Stencil.from_workload(wl.config(1))                    # 5x5 region
+    with pytest.raises(ls.StencilError):
+        st.set_mapping("temporal", 2, 4)
+    st2 = ls.Stencil.from_workload(wl.config(3))
+    st2.set_mapping("temporal", 2, 4)
+    with pytest.raises(ls.StencilError):
+        st2.set_option(1, 5)                                       # depth limit is 4
+    st2.set_option(1, 4)
+    assert st2.tile_bytes(4, 16) == 2 * (8 + 8) * (64 + 8) * 4     # two buffers, rim 4 rows / 1 vector
 
 
 # ---- gold standard (Section 5): every workgroup size gives the output of the baseline size ---
@@ -338,7 +379,11 @@ def test_c4_full_size(ls):
     np.testing.assert_array_equal(got, ref)
     got = gpu_apply(ls, w, g, (4, 64), iters=100, blocking=("direct", 1, 4))
     np.testing.assert_array_equal(got, ref)
+    got = gpu_apply(ls, w, g, (4, 64), iters=100, blocking=("temporal", 4, 4, 4))
+    np.testing.assert_array_equal(got, ref)
+    c = gpu_apply(ls, w, g, (8, 32), iters=1000, blocking=("temporal", 2, 4, 3))
     a = gpu_apply(ls, w, g, (4, 64), iters=1000, blocking=("direct", 1, 4))
+    np.testing.assert_array_equal(a, c)
     b = gpu_apply(ls, w, g, (16, 16), iters=1000, blocking=(1, 1))
     np.testing.assert_array_equal(a, b)
     s0, s1 = g.astype(np.float64).sum(), a.astype(np.float64).sum()
