@@ -127,30 +127,41 @@ struct LifeRow {
     uint32_t l, r;   // the cell west of w[0]'s first byte, the cell east of w[3]'s last byte
 };
 
+// Loads one row of 16 cells.  The cells just west and east of them are the neighbouring lanes'
+// last and first cells: `lane_w` / `lane_e` say whether that lane belongs to the same wavefront
+// and the same matrix row and is executing this call too (then a cross-lane move fetches the
+// byte); otherwise the cell is read from memory with the border rule.
 template <int B>
 __device__ __forceinline__ LifeRow life_fetch(const uint8_t *in, int gr_raw, int c0, int rows, int cols,
-                                              bool fast_cols, uint8_t pad) {
+                                              bool fast_cols, uint8_t pad, bool lane_w, bool lane_e) {
     LifeRow x;
     const int gr = resolve<B>(gr_raw, rows);
     if (gr >= 0 && fast_cols) {
-        const uint8_t *p = in + (size_t)gr * cols + c0;
-        const uint4 v = *reinterpret_cast<const uint4 *>(p);
+        const uint4 v = *reinterpret_cast<const uint4 *>(in + (size_t)gr * cols + c0);
         x.w[0] = v.x; x.w[1] = v.y; x.w[2] = v.z; x.w[3] = v.w;
-        x.l = p[-1];
-        x.r = p[16];
     } else {
-        uint8_t b[18];
 #pragma unroll
-        for (int k = 0; k < 18; ++k) {
-            const int gc = resolve<B>(c0 - 1 + k, cols);
-            b[k] = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
+        for (int k = 0; k < 4; ++k) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int gc = resolve<B>(c0 + 4 * k + b, cols);
+                const uint32_t cell = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
+                word |= cell << (8 * b);
+            }
+            x.w[k] = word;
         }
-        x.l = b[0];
-        x.r = b[17];
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            x.w[k] = (uint32_t)b[1 + 4 * k] | ((uint32_t)b[2 + 4 * k] << 8) | ((uint32_t)b[3 + 4 * k] << 16) |
-                     ((uint32_t)b[4 + 4 * k] << 24);
+    }
+    // every lane that is here takes part in both moves
+    x.l = (uint32_t)__shfl_up((int)x.w[3], 1) >> 24;
+    x.r = (uint32_t)__shfl_down((int)x.w[0], 1) & 0xffu;
+    if (!lane_w) {
+        const int gc = resolve<B>(c0 - 1, cols);
+        x.l = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
+    }
+    if (!lane_e) {
+        const int gc = resolve<B>(c0 + 16, cols);
+        x.r = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
     }
     return x;
 }
@@ -166,15 +177,20 @@ __global__ __launch_bounds__(MAXT) void life_direct_kernel(const TileArgs<OpLife
     const int r0 = (tile_r * (int)blockDim.y + (int)threadIdx.y) * CR;
     const int c0 = (tile_c * (int)blockDim.x + (int)threadIdx.x) * CC;
     if (r0 >= rows || c0 >= cols) return;
-    const bool fast_cols = a.vec_ok && c0 >= 1 && c0 + CC + 1 <= cols;
+    const bool fast_cols = a.vec_ok && c0 + CC <= cols;
+    // the lanes one below / above hold the cells just west / east when they are work-items of
+    // the same workgroup row inside the same wavefront (and, to the east, inside the matrix)
+    const int lane = ((int)threadIdx.y * (int)blockDim.x + (int)threadIdx.x) & 63;
+    const bool lane_w = threadIdx.x > 0 && lane > 0;
+    const bool lane_e = threadIdx.x + 1 < blockDim.x && lane < 63 && c0 + CC < cols;
 
-    LifeRow above = life_fetch<B>(a.in, r0 - 1, c0, rows, cols, fast_cols, a.pad);
-    LifeRow cur = life_fetch<B>(a.in, r0, c0, rows, cols, fast_cols, a.pad);
+    LifeRow above = life_fetch<B>(a.in, r0 - 1, c0, rows, cols, fast_cols, a.pad, lane_w, lane_e);
+    LifeRow cur = life_fetch<B>(a.in, r0, c0, rows, cols, fast_cols, a.pad, lane_w, lane_e);
 #pragma unroll
     for (int cr = 0; cr < CR; ++cr) {
         const int r = r0 + cr;
         if (r >= rows) break;
-        const LifeRow below = life_fetch<B>(a.in, r + 1, c0, rows, cols, fast_cols, a.pad);
+        const LifeRow below = life_fetch<B>(a.in, r + 1, c0, rows, cols, fast_cols, a.pad, lane_w, lane_e);
         uint32_t v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) v[k] = above.w[k] + cur.w[k] + below.w[k];   // column sums
