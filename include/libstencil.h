@@ -192,6 +192,12 @@ int stencil_sweep_reduce(const int *wg_rows_list, const int *wg_cols_list, int n
                          const double *mean_ms, const int *status, double fixed_ms,
                          int *best_index, double *performance, double *speedup_over_fixed);
 
+/* Algorithm 1's Baseline handler (also the "best fixed workgroup size" the paper's speedups
+ * are quoted against): `performance` is n_scenarios x n_sizes, row-major, p(s, w) as returned by
+ * stencil_sweep_reduce with NaN where w is not legal for s.  best_index = the size that is legal
+ * for every scenario (W_safe, Eq. 2) with the highest geometric mean of p, or -1 if none is. */
+int stencil_baseline_wg(const double *performance, int n_scenarios, int n_sizes, int *best_index);
+
 /* ---- prediction (Section 3.2, Section 4.1, Algorithm 1) ---------------------------------- */
 
 #define STENCIL_N_FEATURES 12

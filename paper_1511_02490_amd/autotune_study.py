@@ -1,0 +1,155 @@
+"""The paper's experiment in miniature, on one MI355X: sweep the workgroup-size space of a set
+of synthetic and real stencil scenarios (Section 5), then evaluate workgroup-size prediction
+(Algorithm 1: nearest-neighbour classifier over f(s) with the NearestNeighbour fallback) against
+the sweep's oracle sizes with the metrics of Section 7.
+
+    python -m paper_1511_02490_amd.autotune_study [--synthetic 32] [--reps 5] [--mapping local,1,1]
+
+Everything measured goes through the C ABI (sweeps, legality, features, predictor, baseline);
+this script only builds the scenario list and the tables.  Prints a markdown report.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import statistics
+import sys
+import time
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--synthetic", type=int, default=32)
+    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--mapping", default="local,1,1")
+    ap.add_argument("--json", default="", help="also write the raw tables here")
+    a = ap.parse_args()
+
+    import torch
+    from paper_1511_02490_amd import libstencil as ls
+    from paper_1511_02490_amd import workloads as wl
+
+    m = a.mapping.split(",")
+    mapping = (m[0], int(m[1]), int(m[2]))
+    sizes = ls.enumerate_wg("pow2", 1024)
+    scen = wl.synthetic_scenarios(a.synthetic) + wl.real_scenarios()
+    kind = ["synthetic"] * a.synthetic + ["real"] * (len(scen) - a.synthetic)
+
+    feats, times, status = [], [], []
+    t0 = time.perf_counter()
+    for w in scen:
+        st = ls.Stencil.from_workload(w)
+        try:
+            st.set_mapping(*mapping)
+        except ls.StencilError:
+            st.set_mapping("local", 1, 1)
+        tin = torch.from_numpy(w.grid()).cuda()
+        tout = torch.empty_like(tin)
+        res = st.sweep(tin, tout, sizes, iters=max(1, min(w.iters, 10)), fixed=(0, 0), reps=a.reps)
+        feats.append(st.features())
+        times.append(res.mean_ms)
+        status.append(res.status)
+        st.close()
+        del tin, tout
+        print("swept %-44s best %-10s %.4f ms  refused %d" % (w.name, res.best, res.best_ms,
+                                                             sum(1 for s in res.status if s != 0)),
+              file=sys.stderr, flush=True)
+    sweep_s = time.perf_counter() - t0
+
+    n_s, n_w = len(scen), len(sizes)
+    nan = float("nan")
+    oracle, perf = [], []
+    for i in range(n_s):
+        b, p, _ = ls.sweep_reduce(sizes, times[i], status[i], nan)
+        oracle.append(b)
+        perf.append(p)
+    base = ls.baseline_wg(perf)                      # best fixed size that is legal everywhere
+    idx = {s: j for j, s in enumerate(sizes)}
+
+    def evaluate(train, test, predictor_kind):
+        rows = []
+        for i in test:
+            tr = [k for k in train if k != i]
+            if predictor_kind == "zeror":
+                j = base
+                legal_first = True
+            else:
+                pred = ls.Predictor()
+                for k in tr:
+                    pred.add(feats[k], sizes[oracle[k]])
+                raw = pred.classify(feats[i])
+                st = ls.Stencil.from_workload(scen[i])
+                try:
+                    st.set_mapping(*mapping)
+                except ls.StencilError:
+                    st.set_mapping("local", 1, 1)
+                legal_first = st.is_legal(*raw)
+                j = idx[st.predict(pred, sizes)]
+                st.close()
+                pred.close()
+            t = times[i][j]
+            rows.append({"scenario": scen[i].name, "oracle": sizes[oracle[i]], "predicted": sizes[j],
+                         "accurate": j == oracle[i], "valid_first": legal_first, "performance": perf[i][j],
+                         "speedup_over_baseline": times[i][base] / t,
+                         "speedup_over_4x4": times[i][idx[(4, 4)]] / t if status[i][idx[(4, 4)]] == 0 else nan,
+                         "speedup_over_32x4": times[i][idx[(32, 4)]] / t if status[i][idx[(32, 4)]] == 0 else nan})
+        return rows
+
+    def summary(rows):
+        f = lambda key: [r[key] for r in rows if not math.isnan(r[key])]
+        return {"n": len(rows), "accuracy": sum(r["accurate"] for r in rows) / len(rows),
+                "valid_first": sum(r["valid_first"] for r in rows) / len(rows),
+                "mean_performance": statistics.mean(f("performance")),
+                "median_speedup_over_baseline": statistics.median(f("speedup_over_baseline")),
+                "mean_speedup_over_baseline": statistics.mean(f("speedup_over_baseline")),
+                "median_speedup_over_4x4": statistics.median(f("speedup_over_4x4")),
+                "median_speedup_over_32x4": statistics.median(f("speedup_over_32x4"))}
+
+    all_i = list(range(n_s))
+    syn = [i for i in all_i if kind[i] == "synthetic"]
+    real = [i for i in all_i if kind[i] == "real"]
+    parts = {"leave-one-out, 1-NN + NearestNeighbour": evaluate(all_i, all_i, "1nn"),
+             "synthetic -> real, 1-NN + NearestNeighbour": evaluate(syn, real, "1nn"),
+             "ZeroR (always the baseline size)": evaluate(all_i, all_i, "zeror")}
+
+    worst_over_best = [max(t for t, s in zip(times[i], status[i]) if s == 0) / times[i][oracle[i]] for i in all_i]
+    distinct = len({oracle[i] for i in all_i})
+    refused = sum(1 for i in all_i for s in status[i] if s != 0)
+    print("# Workgroup-size autotuning study on one MI355X")
+    print()
+    print("Mapping `%s %dx%d`; %d scenarios (%d synthetic, %d real), %d workgroup sizes each (powers of two,"
+          " product <= 1024), %d samples per size; sweep time %.0f s." % (mapping + (n_s, len(syn), len(real), n_w, a.reps, sweep_s)))
+    print()
+    print("* distinct oracle sizes: %d of %d scenarios; most common: %s" % (
+        distinct, n_s, max(set(oracle), key=oracle.count) and sizes[max(set(oracle), key=oracle.count)]))
+    print("* oracle over worst size: mean %.1fx (min %.2fx, max %.1fx)" % (
+        statistics.mean(worst_over_best), min(worst_over_best), max(worst_over_best)))
+    print("* refused test cases: %d of %d (%.1f %%)" % (refused, n_s * n_w, 100.0 * refused / (n_s * n_w)))
+    print("* baseline (best size legal for every scenario, by geometric mean of performance): %s, reaching"
+          " %.0f %% of the oracle's performance on average" % (
+              sizes[base] if base >= 0 else None, 100 * statistics.mean(perf[i][base] for i in all_i)))
+    print()
+    print("| evaluation | n | accuracy | legal at first try | mean performance (of oracle) | median speedup over baseline | mean | median over 4x4 | median over 32x4 |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for name, rows in parts.items():
+        s = summary(rows)
+        print("| %s | %d | %.0f %% | %.0f %% | %.0f %% | %.2fx | %.2fx | %.2fx | %.2fx |" % (
+            name, s["n"], 100 * s["accuracy"], 100 * s["valid_first"], 100 * s["mean_performance"],
+            s["median_speedup_over_baseline"], s["mean_speedup_over_baseline"], s["median_speedup_over_4x4"],
+            s["median_speedup_over_32x4"]))
+    print()
+    print("| scenario | oracle size | oracle ms | predicted (leave-one-out) | performance |")
+    print("|---|---|---|---|---|")
+    for i, r in enumerate(parts["leave-one-out, 1-NN + NearestNeighbour"]):
+        print("| %s | %dx%d | %.4f | %dx%d | %.2f |" % (r["scenario"], r["oracle"][0], r["oracle"][1],
+                                                       times[i][oracle[i]], r["predicted"][0], r["predicted"][1],
+                                                       r["performance"]))
+    if a.json:
+        with open(a.json, "w") as fh:
+            json.dump({"sizes": sizes, "scenarios": [w.name for w in scen], "times_ms": times, "status": status,
+                       "features": feats}, fh)
+
+
+if __name__ == "__main__":
+    main()

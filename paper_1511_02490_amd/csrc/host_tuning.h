@@ -67,6 +67,27 @@ inline void reduce(const int *wr, const int *wc, int n, const double *mean_ms, c
     if (speedup) *speedup = (best >= 0 && !std::isnan(fixed_ms)) ? fixed_ms / mean_ms[best] : nan;
 }
 
+// Algorithm 1's Baseline handler: among the sizes legal for every scenario (W_safe, Eq. 2), the
+// one with the highest geometric mean of p(s, w).  perf is n_scen x n_sizes, row-major, NaN
+// where a size is not legal for a scenario.  Returns -1 if no size is safe.
+inline int baseline_index(const double *perf, int n_scen, int n_sizes) {
+    int best = -1;
+    double best_log = 0;
+    for (int j = 0; j < n_sizes; ++j) {
+        double sum_log = 0;
+        bool safe = n_scen > 0;
+        for (int i = 0; i < n_scen && safe; ++i) {
+            const double p = perf[(size_t)i * n_sizes + j];
+            if (std::isnan(p) || p <= 0) safe = false; else sum_log += std::log(p);
+        }
+        if (safe && (best < 0 || sum_log > best_log)) {
+            best = j;
+            best_log = sum_log;
+        }
+    }
+    return best;
+}
+
 // classify(f(s)) by the nearest training scenario (range-scaled Euclidean distance).
 class NearestClassifier {
 public:

@@ -801,6 +801,13 @@ int stencil_sweep_reduce(const int *wg_rows_list, const int *wg_cols_list, int n
     return STENCIL_OK;
 }
 
+int stencil_baseline_wg(const double *performance, int n_scenarios, int n_sizes, int *best_index) {
+    if (!performance || !best_index || n_scenarios < 1 || n_sizes < 1)
+        return fail(STENCIL_E_INVALID, "bad arguments to stencil_baseline_wg");
+    *best_index = host_tuning::baseline_index(performance, n_scenarios, n_sizes);
+    return STENCIL_OK;
+}
+
 int stencil_features(const stencil_t *s, double *f) {
     if (!s || !f) return fail(STENCIL_E_INVALID, "NULL argument");
     f[0] = (double)s->rows;

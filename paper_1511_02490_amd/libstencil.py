@@ -64,6 +64,7 @@ def _load() -> ctypes.CDLL:
                                      dp, dp, dp, dp, ip, ip, dp, vp]),
         "stencil_device_copy": (c_int, [vp, vp, c_i64, vp]),
         "stencil_sweep_reduce": (c_int, [ip, ip, c_int, dp, ip, c_dbl, ip, dp, dp]),
+        "stencil_baseline_wg": (c_int, [dp, c_int, c_int, ip]),
         "stencil_features": (c_int, [vp, dp]),
         "stencil_predictor_create": (c_int, [ctypes.POINTER(vp)]),
         "stencil_predictor_destroy": (None, [vp]),
@@ -82,7 +83,7 @@ _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
            "stencil_set_mapping", "stencil_get_mapping", "stencil_set_option", "stencil_max_wg_size", "stencil_tile_bytes",
            "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg",
-           "stencil_device_copy", "stencil_sweep_reduce", "stencil_features", "stencil_predictor_create",
+           "stencil_device_copy", "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
            "stencil_predict_wg", "stencil_last_error")
 
@@ -131,6 +132,16 @@ def sweep_reduce(sizes: Sequence[Tuple[int, int]], mean_ms: Sequence[float], sta
                                      _dbls(mean_ms), _ints(status), float(fixed_ms),
                                      ctypes.byref(best), perf, ctypes.byref(sp)))
     return best.value, list(perf)[:n], sp.value
+
+
+def baseline_wg(performance: Sequence[Sequence[float]]) -> int:
+    """Index of the best safe fixed size (Algorithm 1, Baseline) for a scenarios x sizes table of
+    p(s, w) with NaN for illegal sizes; -1 if no size is legal everywhere."""
+    n_s, n_w = len(performance), len(performance[0])
+    flat = [float(x) for row in performance for x in row]
+    best = ctypes.c_int(-1)
+    _check(_lib.stencil_baseline_wg(_dbls(flat), n_s, n_w, ctypes.byref(best)))
+    return best.value
 
 
 class SweepResult:

@@ -163,3 +163,52 @@ def config(index: int, rows: int | None = None, cols: int | None = None,
 
 def all_configs() -> Dict[str, Workload]:
     return {"C%d" % (i + 1): config(i) for i in range(5)}
+
+
+# ---- scenario sets for the autotuning study (Section 3.3 / Section 5) -------------------------
+
+def synthetic_scenarios(n: int, seed: int = BASE_SEED + 100) -> List[Workload]:
+    """Synthetic stencils after the paper's template (Section 3.3): four shape parameters, and a
+    boolean complexity - lightweight (a weighted sum) or compute-intensive (w sin x + cos x per
+    region cell) - on the paper's matrix sizes.  Border extents are drawn from 0..8 (up to 30,
+    Table 2's limit, on the smallest matrix only, so that one-work-item workgroups stay
+    affordable); border mode and values are random."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for k in range(n):
+        heavy = bool(rng.integers(0, 2))
+        big = (not heavy) and rng.random() < 0.2
+        if big:
+            side = 512
+            halo = tuple(int(h) for h in rng.integers(4, 31, size=4))
+        else:
+            side = int(rng.choice([512, 1024, 2048, 4096] if not heavy else [512, 1024, 2048]))
+            halo = tuple(int(h) for h in rng.integers(0, 9 if not heavy else 6, size=4))
+        border = str(rng.choice(["clamp", "wrap", "constant"]))
+        n_, s_, e_, w_ = halo
+        weights = rng.random((n_ + s_ + 1, e_ + w_ + 1), dtype=np.float32)
+        if not heavy:
+            weights /= weights.sum()
+        name = "syn-%s-%02d %dx%d N%dS%dE%dW%d %s" % ("b" if heavy else "a", k, side, side, n_, s_, e_, w_, border)
+        out.append(Workload(name, side, side, "f32", halo, border, 0.5, SINCOS if heavy else WEIGHTED_SUM, 1,
+                            seed + 1 + k, "pow2", weights=np.ascontiguousarray(weights)))
+    return out
+
+
+def real_scenarios() -> List[Workload]:
+    """The reference applications of Section 5 that this build defines (Gaussian blur, Game of
+    Life, heat equation) on the paper's four matrix sizes."""
+    out = []
+    for side in (512, 1024, 2048, 4096):
+        for radius in (1, 2):
+            w = config(1 if radius == 2 else 0, rows=side, cols=side)
+            w.name = "gaussian%dx%d %dx%d" % (2 * radius + 1, 2 * radius + 1, side, side)
+            w.sweep = "pow2"
+            out.append(w)
+        g = config(2, rows=side, cols=side, iters=10)
+        g.name = "gol %dx%d" % (side, side)
+        out.append(g)
+        h = config(3, rows=side, cols=side, iters=10)
+        h.name = "he %dx%d" % (side, side)
+        out.append(h)
+    return out

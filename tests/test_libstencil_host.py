@@ -151,3 +151,26 @@ def test_features_and_prediction_algorithm1():
         probe2.predict(pred, [(2048, 1)])
     with pytest.raises(ls.StencilError):
         ls.Predictor().classify(feats[0])
+
+
+def test_baseline_handler_matches_definition():
+    sizes = [(4, 4), (8, 8), (64, 4)]
+    nan = float("nan")
+    perf = [[0.5, 1.0, nan], [0.5, 0.16, 1.0]]
+    # (64,4) is not safe; geometric means 0.5 vs 0.4
+    assert ls.baseline_wg(perf) == 0
+    dicts = [{w: p for w, p in zip(sizes, row) if not math.isnan(p)} for row in perf]
+    safe = tuning.safe_set([list(d) for d in dicts])
+    assert sizes[ls.baseline_wg(perf)] == tuning.baseline_size(dicts, safe)
+    perf[1][1] = 0.36
+    assert ls.baseline_wg(perf) == 1
+    assert ls.baseline_wg([[nan, 1.0], [1.0, nan]]) == -1
+    rng = np.random.default_rng(3)
+    for _ in range(20):
+        table = rng.uniform(0.05, 1.0, size=(6, 9))
+        table[rng.random(table.shape) < 0.1] = np.nan
+        dicts = [{j: p for j, p in enumerate(row) if not np.isnan(p)} for row in table]
+        safe = tuning.safe_set([list(d) for d in dicts])
+        expect = tuning.baseline_size(dicts, safe)
+        got = ls.baseline_wg(table.tolist())
+        assert (got == -1 and expect is None) or got == expect
