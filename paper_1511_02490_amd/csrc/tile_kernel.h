@@ -153,8 +153,9 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
     const int hwa = staged_halo<CC>(hw);
     const int pitch = a.pitch;
     const int rows = a.rows, cols = a.cols;
-    // rows of the tile that exist in the matrix, plus the border region
-    const int TH = min(th, rows - r0) + hn + hs;
+    // the whole tile height is staged, also where the last tile hangs over the matrix edge (those
+    // rows resolve like any other out-of-matrix row): no window row ever needs a range check
+    const int TH = th + hn + hs;
 
     stage_tile<Op, B, CC>(tile, a.plane, pitch, a.in, rows, cols, r0 - hn, c0 - hwa, TH, cols + he, a.pad,
                           a.vec_ok, a.stage_magic, ty * wc + tx, wr * wc);
@@ -181,7 +182,6 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
         // window rows stream through registers; row wi feeds cell-row cr with dr = wi - N - cr
 #pragma unroll
         for (int wi = 0; wi < CR + N + S; ++wi) {
-            if (lr0 + wi >= TH) break;
             L row[NP][WW];
 #pragma unroll
             for (int p = 0; p < NP; ++p) {
