@@ -37,7 +37,9 @@ MAPPINGS = {
              ("temporal", 2, 4, 2), ("temporal", 4, 4, 2), ("temporal", 4, 4, 3), ("temporal", 2, 4, 4),
              ("temporal", 4, 4, 4), ("temporal", 8, 4, 4)],
     "sincos": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("local", 8, 4)],
-    "life": [("local", 1, 1), ("local", 1, 16), ("local", 2, 16), ("direct", 1, 16), ("direct", 2, 16)],
+    "life": [("local", 1, 1), ("local", 1, 16), ("local", 2, 16), ("direct", 1, 16), ("direct", 2, 16),
+             ("temporal", 2, 16, 2), ("temporal", 4, 16, 2), ("temporal", 2, 16, 4), ("temporal", 4, 16, 4),
+             ("temporal", 8, 16, 4)],
 }
 
 

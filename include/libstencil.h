@@ -109,8 +109,8 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            the tile plus a border region STENCIL_OPT_TEMPORAL_DEPTH cells deep in local
  *            memory and advances it by that many applications before writing it back, so a
  *            stencil_run of `iters` applications takes ceil(iters / depth) launches.
- *            Available for HEAT and for WEIGHTED_SUM with region 1/1/1/1; cells_cols = 4,
- *            cells_rows in {1,2,4,8}.
+ *            Available for HEAT and WEIGHTED_SUM with region 1/1/1/1 (cells_cols = 4) and
+ *            for LIFE (cells_cols = 16); cells_rows in {1,2,4,8}.
  *   cells_rows x cells_cols: block of adjacent cells one work-item computes (register
  *            blocking); a workgroup of w_r x w_c work-items covers (w_r*cells_rows) x
  *            (w_c*cells_cols) elements.  (1,1) is the paper's one element per work-item.

@@ -127,6 +127,26 @@ struct LifeRow {
     uint32_t l, r;   // the cell west of w[0]'s first byte, the cell east of w[3]'s last byte
 };
 
+// Next generation of the 16 cells of `cur`, given the rows above and below.
+__device__ __forceinline__ void life_rule(uint32_t (&o)[4], const LifeRow &above, const LifeRow &cur,
+                                          const LifeRow &below) {
+    uint32_t v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = above.w[k] + cur.w[k] + below.w[k];   // column sums
+    const uint32_t vl = above.l + cur.l + below.l, vr = above.r + cur.r + below.r;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t west = (v[k] << 8) | (k == 0 ? vl : (v[k - 1] >> 24));
+        const uint32_t east = (v[k] >> 8) | ((k == 3 ? vr : v[k + 1]) << 24);
+        const uint32_t s = v[k] + west + east;        // 3x3 block sums, <= 9 per byte
+        const uint32_t n = s - cur.w[k];              // neighbours only
+        uint32_t x = (n | cur.w[k]) ^ 0x03030303u;    // zero byte <=> alive next
+        x |= x >> 2;
+        x |= x >> 1;
+        o[k] = ~x & 0x01010101u;
+    }
+}
+
 // Loads one row of 16 cells.  The cells just west and east of them are the neighbouring lanes'
 // last and first cells: `lane_w` / `lane_e` say whether that lane belongs to the same wavefront
 // and the same matrix row and is executing this call too (then a cross-lane move fetches the
@@ -191,22 +211,8 @@ __global__ __launch_bounds__(MAXT) void life_direct_kernel(const TileArgs<OpLife
         const int r = r0 + cr;
         if (r >= rows) break;
         const LifeRow below = life_fetch<B>(a.in, r + 1, c0, rows, cols, fast_cols, a.pad, lane_w, lane_e);
-        uint32_t v[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = above.w[k] + cur.w[k] + below.w[k];   // column sums
-        const uint32_t vl = above.l + cur.l + below.l, vr = above.r + cur.r + below.r;
         uint32_t o[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t west = (v[k] << 8) | (k == 0 ? vl : (v[k - 1] >> 24));
-            const uint32_t east = (v[k] >> 8) | ((k == 3 ? vr : v[k + 1]) << 24);
-            const uint32_t s = v[k] + west + east;        // 3x3 block sums, <= 9 per byte
-            const uint32_t n = s - cur.w[k];              // neighbours only
-            uint32_t x = (n | cur.w[k]) ^ 0x03030303u;    // zero byte <=> alive next
-            x |= x >> 2;
-            x |= x >> 1;
-            o[k] = ~x & 0x01010101u;
-        }
+        life_rule(o, above, cur, below);
         uint8_t *dst = a.out + (size_t)r * cols + c0;
         if (a.vec_ok && c0 + CC <= cols) {
             *reinterpret_cast<uint4 *>(dst) = make_uint4(o[0], o[1], o[2], o[3]);

@@ -187,6 +187,21 @@ hipError_t launch_temporal(const stencil *s, const void *in, void *out, int wr, 
     return hipGetLastError();
 }
 
+template <int B, int CR, int MAXT>
+hipError_t launch_life_temporal(const stencil *s, const void *in, void *out, int wr, int wc, int depth,
+                                hipStream_t stream) {
+    unsigned blocks;
+    size_t lds;
+    const auto a = make_args<sk::OpLife, sk::HaloC<1, 1, 1, 1>, CR, 16>(s, STENCIL_STAGING_TEMPORAL, in, out, wr, wc,
+                                                                        &blocks, &lds);
+    static thread_local int raised_on = -1;
+    hipError_t e = allow_large_tiles(reinterpret_cast<const void *>(&sk::life_temporal_kernel<B, CR, MAXT>), lds,
+                                     &raised_on);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((sk::life_temporal_kernel<B, CR, MAXT>), dim3(blocks), dim3(wc, wr), lds, stream, a, depth);
+    return hipGetLastError();
+}
+
 template <class Op, int B, class Halo, int CR, int CC, int MAXT>
 hipError_t launch_tile(const stencil *s, const void *in, void *out, int wr, int wc, int, hipStream_t stream) {
     unsigned blocks;
@@ -314,6 +329,28 @@ void reg_temporal(std::vector<Variant> &r) {
 }
 
 template <int B, int CR>
+void reg_life_temporal_one(std::vector<Variant> &r) {
+    Variant v;
+    v.staging = STENCIL_STAGING_TEMPORAL;
+    v.kernel = STENCIL_LIFE;
+    v.border = B;
+    v.hn = v.hs = v.he = v.hw = 1;
+    v.cr = CR;
+    v.cc = 16;
+    v.max_threads = STENCIL_MAX_WG_SIZE;
+    v.staged_bytes = 1;
+    v.launch = &launch_life_temporal<B, CR, STENCIL_MAX_WG_SIZE>;
+    r.push_back(v);
+}
+
+template <int CR>
+void reg_life_temporal(std::vector<Variant> &r) {
+    reg_life_temporal_one<sk::kClamp, CR>(r);
+    reg_life_temporal_one<sk::kWrap, CR>(r);
+    reg_life_temporal_one<sk::kConstant, CR>(r);
+}
+
+template <int B, int CR>
 void reg_life_direct_one(std::vector<Variant> &r) {
     Variant v;
     v.staging = STENCIL_STAGING_DIRECT;
@@ -375,6 +412,10 @@ const std::vector<Variant> &registry() {
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 2>(r);
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 4>(r);
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 8>(r);
+        reg_life_temporal<1>(r);
+        reg_life_temporal<2>(r);
+        reg_life_temporal<4>(r);
+        reg_life_temporal<8>(r);
         reg_life_direct<1>(r);
         reg_life_direct<2>(r);
         reg_life_direct<4>(r);

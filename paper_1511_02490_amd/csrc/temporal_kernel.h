@@ -12,6 +12,7 @@
 // The per-cell arithmetic is the same fold as in the single-application kernels, so results
 // are bit-identical to `depth` separate launches.
 #pragma once
+#include "direct_kernel.h"
 #include "tile_kernel.h"
 
 namespace sk {
@@ -133,6 +134,111 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
 #pragma unroll
             for (int cc = 0; cc < CC; ++cc)
                 if (c + cc < cols) out[cc] = res[cc];
+        }
+    }
+}
+
+// ---- Game of Life, several generations per launch ------------------------------------------
+// Same scheme on packed bytes: 16 cells per vector, a rim of `depth` rows and one vector.
+
+// Row i, vector q of an LDS tile as a LifeRow (west / east cells from the adjoining words).
+__device__ __forceinline__ LifeRow life_lds_row(const uint8_t *src, int pitch, int nq, int i, int q) {
+    LifeRow x;
+    const uint8_t *p = src + i * pitch + q * 16;
+    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+    x.w[0] = v.x; x.w[1] = v.y; x.w[2] = v.z; x.w[3] = v.w;
+    x.l = q > 0 ? (*reinterpret_cast<const uint32_t *>(p - 4) >> 24) : 0u;       // beyond the rim: stale anyway
+    x.r = q < nq - 1 ? (*reinterpret_cast<const uint32_t *>(p + 16) & 0xffu) : 0u;
+    return x;
+}
+
+template <int B, int CR, int MAXT>
+__global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLife, HaloC<1, 1, 1, 1>> a,
+                                                             const int depth) {
+    constexpr int CC = 16, HC = 16;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    uint8_t *src = lds_raw;
+    uint8_t *dst = src + a.plane;
+
+    const int wr = blockDim.y, wc = blockDim.x;
+    const int tx = threadIdx.x, ty = threadIdx.y;
+    const int tid = ty * wc + tx, nthreads = wr * wc;
+
+    int t = blockIdx.x;
+    if (a.xcd_chunk > 0) t = (t & 7) * a.xcd_chunk + (t >> 3);
+    if (t >= a.n_tiles) return;
+    const int tile_r = t / a.tiles_c, tile_c = t - tile_r * a.tiles_c;
+    const int rows = a.rows, cols = a.cols, pitch = a.pitch, nq = pitch / CC;
+    const int th = wr * CR, tw = wc * CC;
+    const int r0 = tile_r * th, c0 = tile_c * tw;
+    const int row_first = r0 - depth, col_first = c0 - HC;
+    const int ER = min(th, rows - r0) + 2 * depth;
+
+    stage_tile<OpLife, B, CC>(src, a.plane, pitch, a.in, rows, cols, row_first, col_first, ER, cols + HC, a.pad,
+                              a.vec_ok, a.stage_magic, tid, nthreads);
+    __syncthreads();
+
+    const bool at_border = row_first < 0 || row_first + ER > rows || col_first < 0 || col_first + pitch > cols;
+    const int di = (int)__umulhi((unsigned)nthreads, a.stage_magic), dq = nthreads - di * nq;
+
+    for (int k = 1; k < depth; ++k) {
+        int i = k + (int)__umulhi((unsigned)tid, a.stage_magic);
+        int q = tid - (i - k) * nq;
+        while (i < ER - k) {
+            uint32_t o[4];
+            life_rule(o, life_lds_row(src, pitch, nq, i - 1, q), life_lds_row(src, pitch, nq, i, q),
+                      life_lds_row(src, pitch, nq, i + 1, q));
+            if (B == kConstant && at_border) {
+                const int gr = row_first + i;
+#pragma unroll
+                for (int b = 0; b < CC; ++b) {
+                    const int gc = col_first + q * CC + b;
+                    if ((unsigned)gr >= (unsigned)rows || (unsigned)gc >= (unsigned)cols)
+                        o[b >> 2] = (o[b >> 2] & ~(0xffu << (8 * (b & 3)))) | ((uint32_t)a.pad << (8 * (b & 3)));
+                }
+            }
+            *reinterpret_cast<uint4 *>(dst + i * pitch + q * CC) = make_uint4(o[0], o[1], o[2], o[3]);
+            i += di;
+            q += dq;
+            if (q >= nq) {
+                q -= nq;
+                ++i;
+            }
+        }
+        __syncthreads();
+        if (B == kClamp && at_border) {
+            for (int idx = tid; idx < (ER - 2 * k) * pitch; idx += nthreads) {
+                const int i2 = k + idx / pitch, j2 = idx % pitch;
+                const int gr = row_first + i2, gc = col_first + j2;
+                if ((unsigned)gr >= (unsigned)rows || (unsigned)gc >= (unsigned)cols) {
+                    const int ci = min(max(gr, 0), rows - 1) - row_first, cj = min(max(gc, 0), cols - 1) - col_first;
+                    if (ci >= k && ci < ER - k && cj >= 0 && cj < pitch) dst[i2 * pitch + j2] = dst[ci * pitch + cj];
+                }
+            }
+            __syncthreads();
+        }
+        uint8_t *tmp = src;
+        src = dst;
+        dst = tmp;
+    }
+
+    const int c = c0 + tx * CC;
+    if (c >= cols) return;
+#pragma unroll
+    for (int cr = 0; cr < CR; ++cr) {
+        const int r = r0 + ty * CR + cr;
+        if (r >= rows) break;
+        const int i = depth + ty * CR + cr, q = 1 + tx;
+        uint32_t o[4];
+        life_rule(o, life_lds_row(src, pitch, nq, i - 1, q), life_lds_row(src, pitch, nq, i, q),
+                  life_lds_row(src, pitch, nq, i + 1, q));
+        uint8_t *out = a.out + (size_t)r * cols + c;
+        if (a.vec_ok && c + CC <= cols) {
+            *reinterpret_cast<uint4 *>(out) = make_uint4(o[0], o[1], o[2], o[3]);
+        } else {
+#pragma unroll
+            for (int b = 0; b < CC; ++b)
+                if (c + b < cols) out[b] = (uint8_t)(o[b >> 2] >> (8 * (b & 3)));
         }
     }
 }

@@ -207,6 +207,24 @@ def test_temporal_blocking_weighted_sum_and_tiny(ls, border):
         check(ls, wt, (2, 4), blocking=("temporal", 1, 4, 3))
 
 
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_temporal_blocking_life_bit_exact(ls, border):
+    for rows, cols, iters in [(150, 203, 13), (64, 256, 8), (97, 61, 7)]:
+        w = wl.config(2, rows=rows, cols=cols, iters=iters)
+        w.border = border
+        for depth in (1, 2, 3, 4):
+            for cr, wg in [(1, (4, 16)), (2, (4, 64)), (4, (2, 8)), (8, (3, 5))]:
+                check(ls, w, wg, blocking=("temporal", cr, 16, depth))
+    w1 = wl.config(2, rows=80, cols=96, iters=6)
+    w1.border, w1.pad = "constant", 1.0                            # live padding
+    check(ls, w1, (4, 4), blocking=("temporal", 2, 16, 4))
+    check(ls, w1, (4, 4), blocking=("temporal", 2, 16, 3), offset=5)
+    for shape in [(1, 1), (1, 9), (7, 1), (3, 4), (5, 40)]:
+        wt = wl.config(2, rows=shape[0], cols=shape[1], iters=6)
+        wt.border = border
+        check(ls, wt, (2, 4), blocking=("temporal", 2, 16, 4))
+
+
 def test_temporal_blocking_not_offered_for_other_regions(ls):
     st = ls.Stencil.from_workload(wl.config(1))                    # 5x5 region
     with pytest.raises(ls.StencilError):
@@ -364,6 +382,8 @@ def test_c3_full_size_100_generations(ls):
     got = gpu_apply(ls, w, g, (4, 64), blocking=(2, 16))
     np.testing.assert_array_equal(got, ref)
     got = gpu_apply(ls, w, g, (4, 64), blocking=("direct", 1, 16))
+    np.testing.assert_array_equal(got, ref)
+    got = gpu_apply(ls, w, g, (8, 16), blocking=("temporal", 4, 16, 4))
     np.testing.assert_array_equal(got, ref)
     assert 0.02 < got.mean() < 0.2
 
