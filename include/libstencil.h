@@ -217,12 +217,19 @@ int stencil_predictor_add(stencil_predictor_t *p, const double *features, int n_
 int stencil_predictor_classify(const stencil_predictor_t *p, const double *features,
                                int n_features, int *wg_rows, int *wg_cols);
 
-/* Algorithm 1 with the NearestNeighbour handler: classify the scenario; if the size is not
- * legal for it, take the candidate (from cand_rows/cand_cols, n_cand entries) that is legal
- * and closest in Euclidean distance (first wins ties).  STENCIL_E_REFUSED if no candidate
- * is legal. */
+/* Algorithm 1: classify the scenario; a legal size is returned as classified, otherwise the
+ * fallback handler chooses among the candidates (cand_rows/cand_cols, n_cand entries) that are
+ * legal for the scenario:
+ *   STENCIL_FALLBACK_NEAREST  - the one closest to the prediction in Euclidean distance (first
+ *                               wins ties);
+ *   STENCIL_FALLBACK_BASELINE - (baseline_rows, baseline_cols), e.g. from stencil_baseline_wg;
+ *   STENCIL_FALLBACK_RANDOM   - the (random mod count)-th legal candidate in list order; the
+ *                               caller supplies the random number.
+ * STENCIL_E_REFUSED if the handler has nothing legal to offer. */
+enum stencil_fallback { STENCIL_FALLBACK_NEAREST = 0, STENCIL_FALLBACK_BASELINE = 1, STENCIL_FALLBACK_RANDOM = 2 };
 int stencil_predict_wg(const stencil_t *st, const stencil_predictor_t *p,
                        const int *cand_rows, const int *cand_cols, int n_cand,
+                       int handler, int baseline_rows, int baseline_cols, uint64_t random,
                        int *wg_rows, int *wg_cols);
 
 /* Text of the calling thread's most recent error ("" if none). */

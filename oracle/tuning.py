@@ -159,6 +159,24 @@ def predict_nearest_neighbour(predicted: WG, candidates: Sequence[WG], w_max: in
     return w
 
 
+def predict_baseline(predicted: WG, baseline: WG, w_max: int, refused: Iterable[WG] = ()) -> Optional[WG]:
+    """Algorithm 1, Baseline: keep a legal prediction, else fall back to the baseline size."""
+    ref = set(refused)
+    if is_legal(tuple(predicted), w_max, ref):
+        return tuple(predicted)
+    return tuple(baseline) if is_legal(tuple(baseline), w_max, ref) else None
+
+
+def predict_random(predicted: WG, candidates: Sequence[WG], w_max: int, refused: Iterable[WG], random: int) -> Optional[WG]:
+    """Algorithm 1, Random: keep a legal prediction, else a random size among those expected to be
+    legal; the draw is passed in (`random` modulo the number of legal candidates, in list order)."""
+    ref = set(refused)
+    if is_legal(tuple(predicted), w_max, ref):
+        return tuple(predicted)
+    pool = [c for c in candidates if is_legal(c, w_max, ref)]
+    return pool[random % len(pool)] if pool else None
+
+
 def classify_1nn(train_x: Sequence[Sequence[float]], train_w: Sequence[WG],
                  x: Sequence[float]) -> WG:
     """classify(f(s)): label of the nearest training scenario.  Each feature is scaled by its

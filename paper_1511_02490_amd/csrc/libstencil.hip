@@ -894,9 +894,12 @@ int stencil_predictor_classify(const stencil_predictor_t *p, const double *featu
 }
 
 int stencil_predict_wg(const stencil_t *s, const stencil_predictor_t *p, const int *cand_rows, const int *cand_cols,
-                       int n_cand, int *wg_rows, int *wg_cols) {
+                       int n_cand, int handler, int baseline_rows, int baseline_cols, uint64_t random,
+                       int *wg_rows, int *wg_cols) {
     if (!s || !p || !wg_rows || !wg_cols || n_cand < 0 || (n_cand > 0 && (!cand_rows || !cand_cols)))
         return fail(STENCIL_E_INVALID, "bad arguments");
+    if (handler < STENCIL_FALLBACK_NEAREST || handler > STENCIL_FALLBACK_RANDOM)
+        return fail(STENCIL_E_INVALID, "unknown fallback handler %d", handler);
     double f[STENCIL_N_FEATURES];
     int rc = stencil_features(s, f);
     if (rc != STENCIL_OK) return rc;
@@ -904,22 +907,36 @@ int stencil_predict_wg(const stencil_t *s, const stencil_predictor_t *p, const i
     rc = stencil_predictor_classify(p, f, STENCIL_N_FEATURES, &wr, &wc);
     if (rc != STENCIL_OK) return rc;
     const Variant *v = find_variant(s);
-    // Algorithm 1, NearestNeighbour: keep a legal prediction, else the closest legal candidate
-    while (check_legal(s, v, wr, wc) != STENCIL_OK) {
-        double d_min = std::numeric_limits<double>::infinity();
-        int closest = -1;
-        for (int k = 0; k < n_cand; ++k) {
-            if (check_legal(s, v, cand_rows[k], cand_cols[k]) != STENCIL_OK) continue;
-            const double dr = cand_rows[k] - wr, dc = cand_cols[k] - wc;
-            const double d = std::sqrt(dr * dr + dc * dc);
-            if (d < d_min) {
-                d_min = d;
-                closest = k;
+    // Algorithm 1: a legal prediction is kept; otherwise the handler chooses
+    if (check_legal(s, v, wr, wc) != STENCIL_OK) {
+        if (handler == STENCIL_FALLBACK_BASELINE) {
+            if (check_legal(s, v, baseline_rows, baseline_cols) != STENCIL_OK)
+                return fail(STENCIL_E_REFUSED, "the baseline size %dx%d is not legal for this scenario", baseline_rows,
+                            baseline_cols);
+            wr = baseline_rows;
+            wc = baseline_cols;
+        } else {
+            std::vector<int> legal;
+            for (int k = 0; k < n_cand; ++k)
+                if (check_legal(s, v, cand_rows[k], cand_cols[k]) == STENCIL_OK) legal.push_back(k);
+            if (legal.empty()) return fail(STENCIL_E_REFUSED, "no legal candidate workgroup size");
+            int pick = legal[0];
+            if (handler == STENCIL_FALLBACK_RANDOM) {
+                pick = legal[(size_t)(random % legal.size())];
+            } else {
+                double d_min = std::numeric_limits<double>::infinity();
+                for (int k : legal) {
+                    const double dr = cand_rows[k] - wr, dc = cand_cols[k] - wc;
+                    const double d = std::sqrt(dr * dr + dc * dc);
+                    if (d < d_min) {
+                        d_min = d;
+                        pick = k;
+                    }
+                }
             }
+            wr = cand_rows[pick];
+            wc = cand_cols[pick];
         }
-        if (closest < 0) return fail(STENCIL_E_REFUSED, "no legal candidate workgroup size");
-        wr = cand_rows[closest];
-        wc = cand_cols[closest];
     }
     g_err[0] = '\0';
     *wg_rows = wr;

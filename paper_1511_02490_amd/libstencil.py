@@ -70,7 +70,7 @@ def _load() -> ctypes.CDLL:
         "stencil_predictor_destroy": (None, [vp]),
         "stencil_predictor_add": (c_int, [vp, dp, c_int, c_int, c_int]),
         "stencil_predictor_classify": (c_int, [vp, dp, c_int, ip, ip]),
-        "stencil_predict_wg": (c_int, [vp, vp, ip, ip, c_int, ip, ip]),
+        "stencil_predict_wg": (c_int, [vp, vp, ip, ip, c_int, c_int, c_int, c_int, ctypes.c_uint64, ip, ip]),
         "stencil_last_error": (ctypes.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -291,10 +291,14 @@ class Stencil:
         return SweepResult([tuple(s) for s in sizes], list(mean)[:n], list(mn)[:n], list(med)[:n],
                            list(sd)[:n], list(status)[:n], best.value, sp.value)
 
-    def predict(self, predictor: "Predictor", candidates: Sequence[Tuple[int, int]]) -> Tuple[int, int]:
+    def predict(self, predictor: "Predictor", candidates: Sequence[Tuple[int, int]], handler: str = "nearest",
+                baseline: Tuple[int, int] = (0, 0), random: int = 0) -> Tuple[int, int]:
+        """Algorithm 1 with the chosen fallback handler ("nearest", "baseline" or "random")."""
         wr, wc = ctypes.c_int(), ctypes.c_int()
+        h = {"nearest": 0, "baseline": 1, "random": 2}[handler]
         _check(_lib.stencil_predict_wg(self._h, predictor._h, _ints([c[0] for c in candidates]),
-                                       _ints([c[1] for c in candidates]), len(candidates),
+                                       _ints([c[1] for c in candidates]), len(candidates), h,
+                                       int(baseline[0]), int(baseline[1]), int(random),
                                        ctypes.byref(wr), ctypes.byref(wc)))
         return wr.value, wc.value
 

@@ -335,6 +335,36 @@ def test_runs_on_a_side_stream(ls):
     assert rel_err(tout.cpu().numpy(), oracle.apply_workload(w, g)) <= REL_1
 
 
+def test_iterated_run_inside_a_hip_graph(ls):
+    """An iterated stencil_run is only kernel launches once its scratch matrix exists, so it can
+    be captured into a HIP graph; every replay must reproduce the eager result."""
+    w = wl.config(3, rows=192, cols=256, iters=9)
+    g = w.grid()
+    ref = oracle.apply_workload(w, g)
+    for blocking in [("direct", 2, 4), ("temporal", 2, 4, 4)]:
+        st = ls.Stencil.from_workload(w)
+        set_mapping(st, blocking)
+        tin = torch.from_numpy(g).cuda()
+        tout = torch.zeros_like(tin)
+        st.run(tin, tout, w.iters, (4, 16))                     # eager: allocates the scratch matrix
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(tout.cpu().numpy(), ref)
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                st.run(tin, tout, w.iters, (4, 16), stream=side)
+        torch.cuda.synchronize()
+        for replay in range(3):
+            tout.fill_(-1.0)                                    # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(tout.cpu().numpy(), ref, err_msg="replay %d %s" % (replay, blocking))
+        st.close()
+
+
 # ---- the sweep (Section 5) ---------------------------------------------------------------------
 
 def test_sweep_reports_times_best_and_refusals(ls):

@@ -147,6 +147,16 @@ def test_features_and_prediction_algorithm1():
     legal = [c for c in cands if probe2.is_legal(*c)]
     expect = tuning.predict_nearest_neighbour((64, 32), legal, 1024)
     assert probe2.predict(pred, cands) == expect == (64, 16)      # distance 16; (32,32) is 32 away
+    # the other two handlers of Algorithm 1
+    refused = [c for c in cands if not probe2.is_legal(*c)]
+    assert probe2.predict(pred, cands, "baseline", baseline=(4, 4)) == tuning.predict_baseline((64, 32), (4, 4), 1024, refused) == (4, 4)
+    assert probe.predict(pred, cands, "baseline", baseline=(4, 4)) == (4, 64)      # legal prediction is kept
+    with pytest.raises(ls.Refused):
+        probe2.predict(pred, cands, "baseline", baseline=(64, 64))
+    for draw in (0, 7, 12345678901234567):
+        got = probe2.predict(pred, cands, "random", random=draw)
+        assert got == tuning.predict_random((64, 32), cands, 1024, refused, draw) and probe2.is_legal(*got)
+    assert probe.predict(pred, cands, "random", random=99) == (4, 64)
     with pytest.raises(ls.Refused):
         probe2.predict(pred, [(2048, 1)])
     with pytest.raises(ls.StencilError):

@@ -108,3 +108,15 @@ def test_1nn_classifier_by_hand():
     # a feature that is constant over the training set carries no distance
     X2 = [(5.0, 1.0), (5.0, 2.0)]
     assert tuning.classify_1nn(X2, [(4, 4), (8, 8)], (500.0, 1.9)) == (8, 8)
+
+
+def test_baseline_and_random_handlers_by_hand():
+    cands = [(4, 4), (32, 4), (16, 64)]
+    assert tuning.predict_baseline((8, 8), (4, 4), 1024) == (8, 8)
+    assert tuning.predict_baseline((64, 32), (4, 4), 1024) == (4, 4)
+    assert tuning.predict_baseline((64, 32), (4, 4), 1024, refused=[(4, 4)]) is None
+    assert tuning.predict_random((8, 8), cands, 1024, [], 5) == (8, 8)
+    # legal pool in list order: (4,4), (16,64) once (32,4) is refused; draw 3 -> index 1
+    assert tuning.predict_random((64, 32), cands, 1024, [(32, 4)], 3) == (16, 64)
+    assert tuning.predict_random((64, 32), cands, 1024, [(32, 4)], 4) == (4, 4)
+    assert tuning.predict_random((64, 32), [], 1024, [], 4) is None
