@@ -100,7 +100,7 @@ TileGeom tile_geom(const stencil *s, const Variant &v, int wr, int wc) {
         // tile + `depth` rows above and below, one vector left and right; two buffers
         g.pitch = g.tw + 2 * v.cc;
         g.plane = (g.th + 2 * s->temporal_depth) * g.pitch;
-        g.lds_bytes = 2 * (int64_t)g.plane * v.staged_bytes;
+        g.lds_bytes = 2 * (int64_t)g.plane * v.staged_bytes + 32;   // + one spare vector at each end
     }
     g.tiles_r = (int)((s->rows + g.th - 1) / g.th);
     g.tiles_c = (int)((s->cols + g.tw - 1) / g.tw);

@@ -17,23 +17,26 @@
 
 namespace sk {
 
-// One application for the four cells of vector q in tile row i, read from `src`.
+// One application for the four cells at `ctr_row` (a 16-byte aligned position in an LDS
+// buffer, not in its first or last row).  The cells west and east of the vector are read from
+// the adjoining words; at the two ends of a staged row those words belong to the neighbouring
+// row - values that only ever reach rim cells which are stale by then.
 template <class Op>
-__device__ __forceinline__ void temporal_quad(typename Op::T (&res)[4], const float *src, int pitch, int nq, int i, int q,
+__device__ __forceinline__ void temporal_quad(typename Op::T (&res)[4], const float *ctr_row, int pitch,
                                               const WeightStore<Op, HaloC<1, 1, 1, 1>> &w, float scalar0) {
     typename Op::State st[4];
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) Op::init(st[cc]);
 #pragma unroll
     for (int dr = -1; dr <= 1; ++dr) {
-        const float *rp = src + (i + dr) * pitch + q * 4;
+        const float *rp = ctr_row + dr * pitch;
         float row[6];
         float ctr[4];
         load_vec(ctr, rp);
 #pragma unroll
         for (int k = 0; k < 4; ++k) row[1 + k] = ctr[k];
-        row[0] = q > 0 ? rp[-1] : ctr[0];            // beyond the staged rim: any value will do
-        row[5] = q < nq - 1 ? rp[4] : ctr[3];
+        row[0] = rp[-1];
+        row[5] = rp[4];
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc)
             fold_row<Op>(
@@ -50,7 +53,9 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
     static_assert(Op::kPlanes == 1 && sizeof(T) == 4 && sizeof(typename Op::L) == 4, "fp32, one plane");
     constexpr int CC = 4, HC = 4;   // cells per vector; staged columns each side of the tile
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    float *src = reinterpret_cast<float *>(lds_raw);
+    // [one spare vector][buffer][buffer][one spare vector]: the reads one word before a row's
+    // first vector and one word after its last stay inside the allocation
+    float *src = reinterpret_cast<float *>(lds_raw) + CC;
     float *dst = src + a.plane;
 
     const int wr = blockDim.y, wc = blockDim.x;
@@ -79,9 +84,10 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
         // application k on tile rows [k, ER - k): everything that can still be right
         int i = k + (int)__umulhi((unsigned)tid, a.stage_magic);
         int q = tid - (i - k) * nq;
+        int off = i * pitch + q * CC;   // walks with (i, q)
         while (i < ER - k) {
             T res[CC];
-            temporal_quad<Op>(res, src, pitch, nq, i, q, a.w, a.scalar0);
+            temporal_quad<Op>(res, src + off, pitch, a.w, a.scalar0);
             if (B == kConstant && at_border) {
                 const int gr = row_first + i;
 #pragma unroll
@@ -90,12 +96,13 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
                     if ((unsigned)gr >= (unsigned)rows || (unsigned)gc >= (unsigned)cols) res[cc] = a.pad;
                 }
             }
-            store_vec(dst + i * pitch + q * CC, res);
+            store_vec(dst + off, res);
             i += di;
             q += dq;
+            off += di * pitch + dq * CC;
             if (q >= nq) {
                 q -= nq;
-                ++i;
+                ++i;            // (i, q) -> (i + 1, q - nq): the same linear offset
             }
         }
         __syncthreads();
@@ -126,7 +133,7 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
         const int r = r0 + ty * CR + cr;
         if (r >= rows) break;
         T res[CC];
-        temporal_quad<Op>(res, src, pitch, nq, depth + ty * CR + cr, 1 + tx, a.w, a.scalar0);
+        temporal_quad<Op>(res, src + (depth + ty * CR + cr) * pitch + (1 + tx) * CC, pitch, a.w, a.scalar0);
         T *out = a.out + (size_t)r * cols + c;
         if (a.vec_ok && c + CC <= cols) {
             store_vec(out, res);
@@ -141,14 +148,15 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
 // ---- Game of Life, several generations per launch ------------------------------------------
 // Same scheme on packed bytes: 16 cells per vector, a rim of `depth` rows and one vector.
 
-// Row i, vector q of an LDS tile as a LifeRow (west / east cells from the adjoining words).
-__device__ __forceinline__ LifeRow life_lds_row(const uint8_t *src, int pitch, int nq, int i, int q) {
+// The 16 cells at `p` (a 16-byte aligned position in an LDS buffer) as a LifeRow; the cells west
+// and east of them come from the adjoining words (at the ends of a staged row: from the
+// neighbouring row, which only stale rim cells ever see).
+__device__ __forceinline__ LifeRow life_lds_row(const uint8_t *p) {
     LifeRow x;
-    const uint8_t *p = src + i * pitch + q * 16;
     const uint4 v = *reinterpret_cast<const uint4 *>(p);
     x.w[0] = v.x; x.w[1] = v.y; x.w[2] = v.z; x.w[3] = v.w;
-    x.l = q > 0 ? (*reinterpret_cast<const uint32_t *>(p - 4) >> 24) : 0u;       // beyond the rim: stale anyway
-    x.r = q < nq - 1 ? (*reinterpret_cast<const uint32_t *>(p + 16) & 0xffu) : 0u;
+    x.l = *reinterpret_cast<const uint32_t *>(p - 4) >> 24;
+    x.r = *reinterpret_cast<const uint32_t *>(p + 16) & 0xffu;
     return x;
 }
 
@@ -157,7 +165,7 @@ __global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLi
                                                              const int depth) {
     constexpr int CC = 16, HC = 16;
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    uint8_t *src = lds_raw;
+    uint8_t *src = lds_raw + CC;   // one spare vector before and after the two buffers
     uint8_t *dst = src + a.plane;
 
     const int wr = blockDim.y, wc = blockDim.x;
@@ -184,10 +192,10 @@ __global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLi
     for (int k = 1; k < depth; ++k) {
         int i = k + (int)__umulhi((unsigned)tid, a.stage_magic);
         int q = tid - (i - k) * nq;
+        int off = i * pitch + q * CC;
         while (i < ER - k) {
             uint32_t o[4];
-            life_rule(o, life_lds_row(src, pitch, nq, i - 1, q), life_lds_row(src, pitch, nq, i, q),
-                      life_lds_row(src, pitch, nq, i + 1, q));
+            life_rule(o, life_lds_row(src + off - pitch), life_lds_row(src + off), life_lds_row(src + off + pitch));
             if (B == kConstant && at_border) {
                 const int gr = row_first + i;
 #pragma unroll
@@ -197,9 +205,10 @@ __global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLi
                         o[b >> 2] = (o[b >> 2] & ~(0xffu << (8 * (b & 3)))) | ((uint32_t)a.pad << (8 * (b & 3)));
                 }
             }
-            *reinterpret_cast<uint4 *>(dst + i * pitch + q * CC) = make_uint4(o[0], o[1], o[2], o[3]);
+            *reinterpret_cast<uint4 *>(dst + off) = make_uint4(o[0], o[1], o[2], o[3]);
             i += di;
             q += dq;
+            off += di * pitch + dq * CC;
             if (q >= nq) {
                 q -= nq;
                 ++i;
@@ -228,10 +237,9 @@ __global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLi
     for (int cr = 0; cr < CR; ++cr) {
         const int r = r0 + ty * CR + cr;
         if (r >= rows) break;
-        const int i = depth + ty * CR + cr, q = 1 + tx;
+        const uint8_t *p = src + (depth + ty * CR + cr) * pitch + (1 + tx) * CC;
         uint32_t o[4];
-        life_rule(o, life_lds_row(src, pitch, nq, i - 1, q), life_lds_row(src, pitch, nq, i, q),
-                  life_lds_row(src, pitch, nq, i + 1, q));
+        life_rule(o, life_lds_row(p - pitch), life_lds_row(p), life_lds_row(p + pitch));
         uint8_t *out = a.out + (size_t)r * cols + c;
         if (a.vec_ok && c + CC <= cols) {
             *reinterpret_cast<uint4 *>(out) = make_uint4(o[0], o[1], o[2], o[3]);
