@@ -116,6 +116,7 @@ def leave_one_out_prediction(ls, wl, torch, index, mapping_of, reps):
         o = wl.config(i)
         st = ls.Stencil.from_workload(o)
         st.set_mapping(*mapping_of(o))
+        st.set_option(ls.OPT_SWEEP_CUTOFF, 300)      # training sweeps: adaptive sampling
         a = torch.from_numpy(o.grid()).cuda()
         b = torch.empty_like(a)
         res = st.sweep(a, b, o.wg_sizes(), iters=sweep_burst(o), fixed=(0, 0), reps=reps)

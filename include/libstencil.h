@@ -125,9 +125,14 @@ int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int 
 /* Launch options.  STENCIL_OPT_XCD_REMAP (default 1): workgroups are numbered so that each of
  * the eight XCDs (each with its own L2) works on one contiguous band of tiles.
  * STENCIL_OPT_TEMPORAL_DEPTH (default 2, 1..STENCIL_MAX_TEMPORAL_DEPTH): applications fused
- * into one launch under STENCIL_STAGING_TEMPORAL. */
+ * into one launch under STENCIL_STAGING_TEMPORAL.
+ * STENCIL_OPT_SWEEP_CUTOFF (default 0 = off; otherwise a percentage >= 100): adaptive sampling
+ * for stencil_sweep_wg, after the paper's closing remarks on minimising the observations needed
+ * to tell bad sizes from good ones: every size first gets one warm-up and two samples; only the
+ * sizes whose two-sample mean is within cutoff/100 times the best one are then sampled in full
+ * (3 warm-ups + `reps` samples); the others keep their two-sample statistics. */
 #define STENCIL_MAX_TEMPORAL_DEPTH 4
-enum stencil_option { STENCIL_OPT_XCD_REMAP = 0, STENCIL_OPT_TEMPORAL_DEPTH = 1 };
+enum stencil_option { STENCIL_OPT_XCD_REMAP = 0, STENCIL_OPT_TEMPORAL_DEPTH = 1, STENCIL_OPT_SWEEP_CUTOFF = 2 };
 int stencil_set_option(stencil_t *st, int option, int value);
 
 /* ---- legality (Section 3.1) ---------------------------------------------------------- */

@@ -64,6 +64,7 @@ struct stencil {
     int cr = 1, cc = 1;
     int xcd_remap = 1;
     int temporal_depth = 2;   // applications per launch under STENCIL_STAGING_TEMPORAL
+    int sweep_cutoff_pct = 0; // > 0: sizes slower than this percentage of the best so far are cut short
     int best_rows = 0, best_cols = 0;
     // device-side state, created on first use
     void *scratch = nullptr;
@@ -652,6 +653,11 @@ int stencil_set_option(stencil_t *s, int option, int value) {
     case STENCIL_OPT_XCD_REMAP:
         s->xcd_remap = value ? 1 : 0;
         return STENCIL_OK;
+    case STENCIL_OPT_SWEEP_CUTOFF:
+        if (value < 0 || (value > 0 && value < 100))
+            return fail(STENCIL_E_INVALID, "sweep cutoff is a percentage >= 100, or 0 to sample every size fully");
+        s->sweep_cutoff_pct = value;
+        return STENCIL_OK;
     case STENCIL_OPT_TEMPORAL_DEPTH:
         if (value < 1 || value > STENCIL_MAX_TEMPORAL_DEPTH)
             return fail(STENCIL_E_INVALID, "temporal depth must be in [1, %d]", STENCIL_MAX_TEMPORAL_DEPTH);
@@ -739,11 +745,13 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
     const double nan = std::numeric_limits<double>::quiet_NaN();
     const int kWarmup = 3;
     std::vector<double> samples((size_t)reps);
+
     std::vector<double> means((size_t)n + 1, nan);
     std::vector<int> stat((size_t)n + 1, STENCIL_E_REFUSED);
 
     // times one size into slot k; returns STENCIL_OK also when the size is refused
-    auto time_size = [&](int wr, int wc, int k) -> int {
+    // probe_only: one warm-up and two samples instead of three warm-ups and `reps` samples
+    auto time_size = [&](int wr, int wc, int k, bool probe_only) -> int {
         if (check_legal(s, v, wr, wc) != STENCIL_OK) {
             stat[k] = STENCIL_E_REFUSED;
             if (k < n) {
@@ -753,29 +761,43 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
             }
             return STENCIL_OK;
         }
-        for (int w = 0; w < kWarmup; ++w) {
+        // samples [from, to) into the event pairs, then wait for them and read the times
+        auto take = [&](int from, int to) -> int {
+            for (int i = from; i < to; ++i) {
+                hipError_t e = hipEventRecord(s->events[2 * i], stream);
+                if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
+                int r = run_checked(s, v, in, out, iters, wr, wc, stream);
+                if (r != STENCIL_OK) return r;
+                e = hipEventRecord(s->events[2 * i + 1], stream);
+                if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
+            }
+            if (to > from) {
+                hipError_t e = hipEventSynchronize(s->events[2 * to - 1]);
+                if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
+            }
+            for (int i = from; i < to; ++i) {
+                float ms = 0.0f;
+                hipError_t e = hipEventElapsedTime(&ms, s->events[2 * i], s->events[2 * i + 1]);
+                if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
+                samples[i] = ms;
+            }
+            return STENCIL_OK;
+        };
+        const int taken = probe_only ? std::min(2, reps) : reps;
+        for (int w = 0; w < (probe_only ? 1 : kWarmup); ++w) {
             int r = run_checked(s, v, in, out, iters, wr, wc, stream);
             if (r != STENCIL_OK) return r;
         }
-        for (int i = 0; i < reps; ++i) {
-            hipError_t e = hipEventRecord(s->events[2 * i], stream);
-            if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
-            int r = run_checked(s, v, in, out, iters, wr, wc, stream);
+        {
+            int r = take(0, taken);
             if (r != STENCIL_OK) return r;
-            e = hipEventRecord(s->events[2 * i + 1], stream);
-            if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
         }
-        hipError_t e = hipEventSynchronize(s->events[2 * reps - 1]);
-        if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
-        for (int i = 0; i < reps; ++i) {
-            float ms = 0.0f;
-            e = hipEventElapsedTime(&ms, s->events[2 * i], s->events[2 * i + 1]);
-            if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
-            samples[i] = ms;
-        }
+        samples.resize((size_t)taken);
         host_tuning::SampleStats st = host_tuning::summarise(samples);
+        samples.resize((size_t)reps);
         means[k] = st.mean;
         stat[k] = STENCIL_OK;
+
         if (k < n) {
             if (min_ms) min_ms[k] = st.min;
             if (median_ms) median_ms[k] = st.median;
@@ -784,9 +806,24 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
         return STENCIL_OK;
     };
 
-    for (int k = 0; k < n; ++k) {
-        rc = time_size(wg_rows_list[k], wg_cols_list[k], k);
-        if (rc != STENCIL_OK) return rc;
+    if (s->sweep_cutoff_pct > 0 && reps > 2) {
+        // adaptive sampling: probe every size, then sample fully only those within reach of the best
+        double best_probe = std::numeric_limits<double>::infinity();
+        for (int k = 0; k < n; ++k) {
+            rc = time_size(wg_rows_list[k], wg_cols_list[k], k, true);
+            if (rc != STENCIL_OK) return rc;
+            if (stat[k] == STENCIL_OK) best_probe = std::min(best_probe, means[k]);
+        }
+        for (int k = 0; k < n; ++k) {
+            if (stat[k] != STENCIL_OK || means[k] * 100.0 > best_probe * s->sweep_cutoff_pct) continue;
+            rc = time_size(wg_rows_list[k], wg_cols_list[k], k, false);
+            if (rc != STENCIL_OK) return rc;
+        }
+    } else {
+        for (int k = 0; k < n; ++k) {
+            rc = time_size(wg_rows_list[k], wg_cols_list[k], k, false);
+            if (rc != STENCIL_OK) return rc;
+        }
     }
     double fixed_ms = nan;
     if (fixed_rows > 0 && fixed_cols > 0) {
@@ -794,7 +831,7 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
         for (int k = 0; k < n; ++k)
             if (wg_rows_list[k] == fixed_rows && wg_cols_list[k] == fixed_cols) { at = k; break; }
         if (at < 0) {
-            rc = time_size(fixed_rows, fixed_cols, n);
+            rc = time_size(fixed_rows, fixed_cols, n, false);
             if (rc != STENCIL_OK) return rc;
             at = n;
         }

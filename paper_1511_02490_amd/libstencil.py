@@ -20,7 +20,7 @@ CLAMP, WRAP, CONSTANT = 0, 1, 2
 WEIGHTED_SUM, LIFE, HEAT, SINCOS = 0, 1, 2, 3
 ENUM_POW2, ENUM_EVEN = 0, 1
 STAGING_LOCAL, STAGING_DIRECT, STAGING_TEMPORAL = 0, 1, 2
-OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH = 0, 1
+OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF = 0, 1, 2
 _STAGINGS = {"local": STAGING_LOCAL, "direct": STAGING_DIRECT, "temporal": STAGING_TEMPORAL}
 N_FEATURES = 12
 

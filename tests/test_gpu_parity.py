@@ -394,6 +394,29 @@ def test_sweep_reports_times_best_and_refusals(ls):
     assert rel_err(tout.cpu().numpy(), oracle.apply_workload(w)) <= REL_1
 
 
+def test_sweep_with_adaptive_sampling_finds_the_same_best(ls):
+    import time
+    w = wl.config(3, rows=1024, cols=1024)
+    st = ls.Stencil.from_workload(w)
+    tin = torch.from_numpy(w.grid()).cuda()
+    tout = torch.empty_like(tin)
+    sizes = wl.enumerate_wg("pow2")
+    t0 = time.perf_counter()
+    full = st.sweep(tin, tout, sizes, iters=4, reps=30)
+    t_full = time.perf_counter() - t0
+    st.set_option(ls.OPT_SWEEP_CUTOFF, 300)
+    t0 = time.perf_counter()
+    cut = st.sweep(tin, tout, sizes, iters=4, reps=30)
+    t_cut = time.perf_counter() - t0
+    assert cut.status == full.status
+    # the landscape is flat at the top: the adaptive sweep's winner must be as good as the full one's
+    assert full.ms_of(cut.best) <= 1.1 * full.best_ms
+    assert cut.best_ms <= 1.15 * full.best_ms
+    assert t_cut < 0.7 * t_full
+    with pytest.raises(ls.StencilError):
+        st.set_option(ls.OPT_SWEEP_CUTOFF, 50)
+
+
 # ---- full-size configurations, in the launch configuration bench.py times ---------------------
 
 def test_c2_full_size(ls):
