@@ -17,26 +17,50 @@
 
 namespace sk {
 
-// One application for the four cells at `ctr_row` (a 16-byte aligned position in an LDS
-// buffer, not in its first or last row).  The cells west and east of the vector are read from
-// the adjoining words; at the two ends of a staged row those words belong to the neighbouring
-// row - values that only ever reach rim cells which are stale by then.
+// Cross-lane moves inside a wavefront: the value the lane one below / one above holds.
+// (Lane 0 has no lane below and lane 63 none above; they get 0 and must look elsewhere.)
+__device__ __forceinline__ uint32_t from_lane_below(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint32_t from_lane_above(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xf, 0xf, false);
+}
+
+// Rows of an item handled by one work-item per pass through a time step: the window rolls down
+// over them, so R + 2 LDS rows are read for R rows written.
+constexpr int kTemporalRows = 2;
+
+// Four cells of one LDS row plus the cells west and east of them.  Work-items with consecutive
+// ids hold consecutive vectors of a row, so the two neighbours normally sit in the adjacent
+// lanes; where they do not (first / last lane of a wavefront, or the caller says so) the
+// adjoining LDS words are read instead.  At the two ends of a staged row the "neighbour" is
+// whatever lies beside it in memory - values that only ever reach rim cells that are stale.
+struct QuadRow {
+    float v[4];
+    float w, e;
+};
+__device__ __forceinline__ QuadRow load_quad_row(const float *rp, bool west_in_lane, bool east_in_lane) {
+    QuadRow r;
+    load_vec(r.v, rp);
+    r.w = __uint_as_float(from_lane_below(__float_as_uint(r.v[3])));
+    r.e = __uint_as_float(from_lane_above(__float_as_uint(r.v[0])));
+    if (!west_in_lane) r.w = rp[-1];
+    if (!east_in_lane) r.e = rp[4];
+    return r;
+}
+
+// One application for the four cells of `mid`, given the rows above and below.
 template <class Op>
-__device__ __forceinline__ void temporal_quad(typename Op::T (&res)[4], const float *ctr_row, int pitch,
-                                              const WeightStore<Op, HaloC<1, 1, 1, 1>> &w, float scalar0) {
+__device__ __forceinline__ void temporal_quad(typename Op::T (&res)[4], const QuadRow &up, const QuadRow &mid,
+                                              const QuadRow &dn, const WeightStore<Op, HaloC<1, 1, 1, 1>> &w,
+                                              float scalar0) {
     typename Op::State st[4];
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) Op::init(st[cc]);
 #pragma unroll
     for (int dr = -1; dr <= 1; ++dr) {
-        const float *rp = ctr_row + dr * pitch;
-        float row[6];
-        float ctr[4];
-        load_vec(ctr, rp);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) row[1 + k] = ctr[k];
-        row[0] = rp[-1];
-        row[5] = rp[4];
+        const QuadRow &q = dr < 0 ? up : (dr == 0 ? mid : dn);
+        const float row[6] = {q.w, q.v[0], q.v[1], q.v[2], q.v[3], q.e};
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc)
             fold_row<Op>(
@@ -52,6 +76,7 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
     using T = typename Op::T;
     static_assert(Op::kPlanes == 1 && sizeof(T) == 4 && sizeof(typename Op::L) == 4, "fp32, one plane");
     constexpr int CC = 4, HC = 4;   // cells per vector; staged columns each side of the tile
+    constexpr int R = kTemporalRows;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     // [one spare vector][buffer][buffer][one spare vector]: the reads one word before a row's
     // first vector and one word after its last stay inside the allocation
@@ -61,6 +86,7 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
     const int wr = blockDim.y, wc = blockDim.x;
     const int tx = threadIdx.x, ty = threadIdx.y;
     const int tid = ty * wc + tx, nthreads = wr * wc;
+    const int lane = tid & 63;
 
     int t = blockIdx.x;
     if (a.xcd_chunk > 0) t = (t & 7) * a.xcd_chunk + (t >> 3);
@@ -78,31 +104,48 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
 
     // does the staged tile reach outside the matrix?  (same answer for the whole workgroup)
     const bool at_border = row_first < 0 || row_first + ER > rows || col_first < 0 || col_first + pitch > cols;
-    const int di = (int)__umulhi((unsigned)nthreads, a.stage_magic), dq = nthreads - di * nq;
+    // items of a time step: groups of R rows x vectors of a row, walked linearly by work-item id;
+    // the next item sits in the next lane unless this is the wavefront's or the workgroup's last
+    const bool next_in_lane = lane < 63 && tid + 1 < nthreads;
+    const int dg = (int)__umulhi((unsigned)nthreads, a.stage_magic), dq = nthreads - dg * nq;
 
     for (int k = 1; k < depth; ++k) {
         // application k on tile rows [k, ER - k): everything that can still be right
-        int i = k + (int)__umulhi((unsigned)tid, a.stage_magic);
-        int q = tid - (i - k) * nq;
-        int off = i * pitch + q * CC;   // walks with (i, q)
-        while (i < ER - k) {
-            T res[CC];
-            temporal_quad<Op>(res, src + off, pitch, a.w, a.scalar0);
-            if (B == kConstant && at_border) {
-                const int gr = row_first + i;
+        const int n_groups = (ER - 2 * k + R - 1) / R;
+        int g = (int)__umulhi((unsigned)tid, a.stage_magic);
+        int q = tid - g * nq;
+        int off = (k + g * R) * pitch + q * CC;   // walks with (g, q)
+        while (g < n_groups) {
+            const int i0 = k + g * R;
+            const float *rp = src + off;
+            QuadRow up = load_quad_row(rp - pitch, lane > 0, next_in_lane);
+            QuadRow mid = load_quad_row(rp, lane > 0, next_in_lane);
 #pragma unroll
-                for (int cc = 0; cc < CC; ++cc) {
-                    const int gc = col_first + q * CC + cc;
-                    if ((unsigned)gr >= (unsigned)rows || (unsigned)gc >= (unsigned)cols) res[cc] = a.pad;
+            for (int rr = 0; rr < R; ++rr) {
+                const int i = i0 + rr;
+                if (i >= ER - k) break;
+                const QuadRow dn = load_quad_row(rp + (rr + 1) * pitch, lane > 0, next_in_lane);
+                T res[CC];
+                temporal_quad<Op>(res, up, mid, dn, a.w, a.scalar0);
+                if (B == kConstant && at_border) {
+                    const int gr = row_first + i;
+#pragma unroll
+                    for (int cc = 0; cc < CC; ++cc) {
+                        const int gc = col_first + q * CC + cc;
+                        if ((unsigned)gr >= (unsigned)rows || (unsigned)gc >= (unsigned)cols) res[cc] = a.pad;
+                    }
                 }
+                store_vec(dst + off + rr * pitch, res);
+                up = mid;
+                mid = dn;
             }
-            store_vec(dst + off, res);
-            i += di;
+            g += dg;
             q += dq;
-            off += di * pitch + dq * CC;
-            if (q >= nq) {
+            off += dg * R * pitch + dq * CC;
+            if (q >= nq) {   // (g, q) -> (g + 1, q - nq)
                 q -= nq;
-                ++i;            // (i, q) -> (i + 1, q - nq): the same linear offset
+                ++g;
+                off += (R - 1) * pitch;
             }
         }
         __syncthreads();
@@ -125,23 +168,33 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
         dst = tmp;
     }
 
-    // last application: the tile's own cells, straight to global memory
+    // last application: the tile's own cells, straight to global memory.  Work-item (ty, tx) owns
+    // rows ty*CR.. and vector 1 + tx; its row neighbours are the adjacent lanes except at the two
+    // ends of the workgroup's row.
     const int c = c0 + tx * CC;
-    if (c >= cols) return;
+    const bool west_in_lane = lane > 0 && tx > 0, east_in_lane = lane < 63 && tx + 1 < wc;
+    const float *rp = src + (depth + ty * CR) * pitch + (1 + tx) * CC;
+    QuadRow up = load_quad_row(rp - pitch, west_in_lane, east_in_lane);
+    QuadRow mid = load_quad_row(rp, west_in_lane, east_in_lane);
 #pragma unroll
     for (int cr = 0; cr < CR; ++cr) {
         const int r = r0 + ty * CR + cr;
-        if (r >= rows) break;
-        T res[CC];
-        temporal_quad<Op>(res, src + (depth + ty * CR + cr) * pitch + (1 + tx) * CC, pitch, a.w, a.scalar0);
-        T *out = a.out + (size_t)r * cols + c;
-        if (a.vec_ok && c + CC <= cols) {
-            store_vec(out, res);
-        } else {
+        // (every lane keeps loading, so that lanes still at work find their neighbours' values)
+        const QuadRow dn = load_quad_row(rp + (cr + 1) * pitch, west_in_lane, east_in_lane);
+        if (r < rows && c < cols) {
+            T res[CC];
+            temporal_quad<Op>(res, up, mid, dn, a.w, a.scalar0);
+            T *out = a.out + (size_t)r * cols + c;
+            if (a.vec_ok && c + CC <= cols) {
+                store_vec(out, res);
+            } else {
 #pragma unroll
-            for (int cc = 0; cc < CC; ++cc)
-                if (c + cc < cols) out[cc] = res[cc];
+                for (int cc = 0; cc < CC; ++cc)
+                    if (c + cc < cols) out[cc] = res[cc];
+            }
         }
+        up = mid;
+        mid = dn;
     }
 }
 
@@ -149,14 +202,16 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
 // Same scheme on packed bytes: 16 cells per vector, a rim of `depth` rows and one vector.
 
 // The 16 cells at `p` (a 16-byte aligned position in an LDS buffer) as a LifeRow; the cells west
-// and east of them come from the adjoining words (at the ends of a staged row: from the
-// neighbouring row, which only stale rim cells ever see).
-__device__ __forceinline__ LifeRow life_lds_row(const uint8_t *p) {
+// and east of them come from the adjacent lanes, or from the adjoining LDS words where those
+// lanes do not hold them (see load_quad_row).
+__device__ __forceinline__ LifeRow life_lds_row(const uint8_t *p, bool west_in_lane, bool east_in_lane) {
     LifeRow x;
     const uint4 v = *reinterpret_cast<const uint4 *>(p);
     x.w[0] = v.x; x.w[1] = v.y; x.w[2] = v.z; x.w[3] = v.w;
-    x.l = *reinterpret_cast<const uint32_t *>(p - 4) >> 24;
-    x.r = *reinterpret_cast<const uint32_t *>(p + 16) & 0xffu;
+    x.l = from_lane_below(x.w[3]) >> 24;
+    x.r = from_lane_above(x.w[0]) & 0xffu;
+    if (!west_in_lane) x.l = *reinterpret_cast<const uint32_t *>(p - 4) >> 24;
+    if (!east_in_lane) x.r = *reinterpret_cast<const uint32_t *>(p + 16) & 0xffu;
     return x;
 }
 
@@ -164,6 +219,7 @@ template <int B, int CR, int MAXT>
 __global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLife, HaloC<1, 1, 1, 1>> a,
                                                              const int depth) {
     constexpr int CC = 16, HC = 16;
+    constexpr int R = kTemporalRows;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     uint8_t *src = lds_raw + CC;   // one spare vector before and after the two buffers
     uint8_t *dst = src + a.plane;
@@ -171,6 +227,7 @@ __global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLi
     const int wr = blockDim.y, wc = blockDim.x;
     const int tx = threadIdx.x, ty = threadIdx.y;
     const int tid = ty * wc + tx, nthreads = wr * wc;
+    const int lane = tid & 63;
 
     int t = blockIdx.x;
     if (a.xcd_chunk > 0) t = (t & 7) * a.xcd_chunk + (t >> 3);
@@ -187,31 +244,46 @@ __global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLi
     __syncthreads();
 
     const bool at_border = row_first < 0 || row_first + ER > rows || col_first < 0 || col_first + pitch > cols;
-    const int di = (int)__umulhi((unsigned)nthreads, a.stage_magic), dq = nthreads - di * nq;
+    const bool next_in_lane = lane < 63 && tid + 1 < nthreads;
+    const int dg = (int)__umulhi((unsigned)nthreads, a.stage_magic), dq = nthreads - dg * nq;
 
     for (int k = 1; k < depth; ++k) {
-        int i = k + (int)__umulhi((unsigned)tid, a.stage_magic);
-        int q = tid - (i - k) * nq;
-        int off = i * pitch + q * CC;
-        while (i < ER - k) {
-            uint32_t o[4];
-            life_rule(o, life_lds_row(src + off - pitch), life_lds_row(src + off), life_lds_row(src + off + pitch));
-            if (B == kConstant && at_border) {
-                const int gr = row_first + i;
+        const int n_groups = (ER - 2 * k + R - 1) / R;
+        int g = (int)__umulhi((unsigned)tid, a.stage_magic);
+        int q = tid - g * nq;
+        int off = (k + g * R) * pitch + q * CC;
+        while (g < n_groups) {
+            const int i0 = k + g * R;
+            const uint8_t *rp = src + off;
+            LifeRow up = life_lds_row(rp - pitch, lane > 0, next_in_lane);
+            LifeRow mid = life_lds_row(rp, lane > 0, next_in_lane);
 #pragma unroll
-                for (int b = 0; b < CC; ++b) {
-                    const int gc = col_first + q * CC + b;
-                    if ((unsigned)gr >= (unsigned)rows || (unsigned)gc >= (unsigned)cols)
-                        o[b >> 2] = (o[b >> 2] & ~(0xffu << (8 * (b & 3)))) | ((uint32_t)a.pad << (8 * (b & 3)));
+            for (int rr = 0; rr < R; ++rr) {
+                const int i = i0 + rr;
+                if (i >= ER - k) break;
+                const LifeRow dn = life_lds_row(rp + (rr + 1) * pitch, lane > 0, next_in_lane);
+                uint32_t o[4];
+                life_rule(o, up, mid, dn);
+                if (B == kConstant && at_border) {
+                    const int gr = row_first + i;
+#pragma unroll
+                    for (int b = 0; b < CC; ++b) {
+                        const int gc = col_first + q * CC + b;
+                        if ((unsigned)gr >= (unsigned)rows || (unsigned)gc >= (unsigned)cols)
+                            o[b >> 2] = (o[b >> 2] & ~(0xffu << (8 * (b & 3)))) | ((uint32_t)a.pad << (8 * (b & 3)));
+                    }
                 }
+                *reinterpret_cast<uint4 *>(dst + off + rr * pitch) = make_uint4(o[0], o[1], o[2], o[3]);
+                up = mid;
+                mid = dn;
             }
-            *reinterpret_cast<uint4 *>(dst + off) = make_uint4(o[0], o[1], o[2], o[3]);
-            i += di;
+            g += dg;
             q += dq;
-            off += di * pitch + dq * CC;
+            off += dg * R * pitch + dq * CC;
             if (q >= nq) {
                 q -= nq;
-                ++i;
+                ++g;
+                off += (R - 1) * pitch;
             }
         }
         __syncthreads();
@@ -232,22 +304,28 @@ __global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLi
     }
 
     const int c = c0 + tx * CC;
-    if (c >= cols) return;
+    const bool west_in_lane = lane > 0 && tx > 0, east_in_lane = lane < 63 && tx + 1 < wc;
+    const uint8_t *rp = src + (depth + ty * CR) * pitch + (1 + tx) * CC;
+    LifeRow up = life_lds_row(rp - pitch, west_in_lane, east_in_lane);
+    LifeRow mid = life_lds_row(rp, west_in_lane, east_in_lane);
 #pragma unroll
     for (int cr = 0; cr < CR; ++cr) {
         const int r = r0 + ty * CR + cr;
-        if (r >= rows) break;
-        const uint8_t *p = src + (depth + ty * CR + cr) * pitch + (1 + tx) * CC;
-        uint32_t o[4];
-        life_rule(o, life_lds_row(p - pitch), life_lds_row(p), life_lds_row(p + pitch));
-        uint8_t *out = a.out + (size_t)r * cols + c;
-        if (a.vec_ok && c + CC <= cols) {
-            *reinterpret_cast<uint4 *>(out) = make_uint4(o[0], o[1], o[2], o[3]);
-        } else {
+        const LifeRow dn = life_lds_row(rp + (cr + 1) * pitch, west_in_lane, east_in_lane);
+        if (r < rows && c < cols) {
+            uint32_t o[4];
+            life_rule(o, up, mid, dn);
+            uint8_t *out = a.out + (size_t)r * cols + c;
+            if (a.vec_ok && c + CC <= cols) {
+                *reinterpret_cast<uint4 *>(out) = make_uint4(o[0], o[1], o[2], o[3]);
+            } else {
 #pragma unroll
-            for (int b = 0; b < CC; ++b)
-                if (c + b < cols) out[b] = (uint8_t)(o[b >> 2] >> (8 * (b & 3)));
+                for (int b = 0; b < CC; ++b)
+                    if (c + b < cols) out[b] = (uint8_t)(o[b >> 2] >> (8 * (b & 3)));
+            }
         }
+        up = mid;
+        mid = dn;
     }
 }
 
