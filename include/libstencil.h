@@ -212,13 +212,21 @@ int stencil_baseline_wg(const double *performance, int n_scenarios, int n_sizes,
  * flag, compute units, local memory bytes, max workgroup size. */
 int stencil_features(const stencil_t *st, double *features);
 
-/* A nearest-neighbour classifier over (f(s), Omega(s)) pairs (Section 4.1's D_training). */
-int stencil_predictor_create(stencil_predictor_t **out);
+/* A classifier over (f(s), Omega(s)) pairs (Section 4.1's D_training):
+ *   STENCIL_CLASSIFIER_NEAREST - label of the nearest training scenario; each feature is scaled
+ *       by its range over the training set, Euclidean distance, first nearest wins ties;
+ *   STENCIL_CLASSIFIER_TREE    - decision tree (the paper's J48 is the fastest of its
+ *       classifiers): binary splits `feature <= threshold` by information gain over the
+ *       midpoints between consecutive distinct values (features in order, thresholds ascending,
+ *       first best wins), grown until pure; a leaf answers with its most frequent label;
+ *   STENCIL_CLASSIFIER_ZEROR   - always the most frequent label (the paper's dummy classifier). */
+enum stencil_classifier { STENCIL_CLASSIFIER_NEAREST = 0, STENCIL_CLASSIFIER_TREE = 1, STENCIL_CLASSIFIER_ZEROR = 2 };
+int stencil_predictor_create(stencil_predictor_t **out, int classifier);
 void stencil_predictor_destroy(stencil_predictor_t *p);
 int stencil_predictor_add(stencil_predictor_t *p, const double *features, int n_features,
                           int wg_rows, int wg_cols);
-/* classify(f(s)): the label of the nearest training scenario; each feature is scaled by
- * its range over the training set, Euclidean distance, first nearest wins ties. */
+/* classify(f(s)) with the classifier chosen at creation (a tree is grown on first use after
+ * the last added pair). */
 int stencil_predictor_classify(const stencil_predictor_t *p, const double *features,
                                int n_features, int *wg_rows, int *wg_cols);
 

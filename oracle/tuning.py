@@ -196,3 +196,80 @@ def classify_1nn(train_x: Sequence[Sequence[float]], train_w: Sequence[WG],
         if d < d_best:
             best, d_best = i, d
     return tuple(train_w[best])
+
+
+# ---- decision tree and ZeroR classifiers ---------------------------------------------------------
+
+def _label_counts(labels: Sequence[WG]):
+    """(label, count) in order of first appearance."""
+    out: List[List] = []
+    for w in labels:
+        for entry in out:
+            if entry[0] == w:
+                entry[1] += 1
+                break
+        else:
+            out.append([w, 1])
+    return out
+
+
+def _entropy(labels: Sequence[WG]) -> float:
+    h = 0.0
+    for _, c in _label_counts(labels):
+        p = c / len(labels)
+        h -= p * math.log2(p)
+    return h
+
+
+def _majority(labels: Sequence[WG]) -> WG:
+    counts = _label_counts(labels)
+    best = counts[0]
+    for entry in counts[1:]:
+        if entry[1] > best[1]:
+            best = entry
+    return best[0]
+
+
+def classify_zeror(train_w: Sequence[WG]) -> WG:
+    """The dummy classifier of Section 7: the most frequent training label (first among equals)."""
+    return _majority([tuple(w) for w in train_w])
+
+
+def grow_tree(train_x: Sequence[Sequence[float]], train_w: Sequence[WG]):
+    """Decision tree in the manner of the paper's J48 classifier: binary splits `x[j] <= t` chosen
+    by information gain, t over the midpoints between consecutive distinct values of feature j;
+    features in order, thresholds ascending, the first best split wins; grown until a node is
+    pure or no split gains.  Returns nested tuples: ("leaf", label) or ("split", j, t, left, right)."""
+    labels = [tuple(w) for w in train_w]
+
+    def grow(idx):
+        here = [labels[i] for i in idx]
+        h = _entropy(here)
+        if h <= 0:
+            return ("leaf", _majority(here))
+        best = None
+        best_gain = 0.0
+        for j in range(len(train_x[0])):
+            vals = sorted({train_x[i][j] for i in idx})
+            for a, b in zip(vals, vals[1:]):
+                t = 0.5 * (a + b)
+                left = [i for i in idx if train_x[i][j] <= t]
+                right = [i for i in idx if not train_x[i][j] <= t]
+                n = float(len(idx))
+                gain = h - (len(left) / n) * _entropy([labels[i] for i in left]) \
+                         - (len(right) / n) * _entropy([labels[i] for i in right])
+                if gain > best_gain:
+                    best_gain, best = gain, (j, t, left, right)
+        if best is None:
+            return ("leaf", _majority(here))
+        j, t, left, right = best
+        return ("split", j, t, grow(left), grow(right))
+
+    return grow(list(range(len(labels))))
+
+
+def classify_tree(tree, x: Sequence[float]) -> WG:
+    while tree[0] == "split":
+        _, j, t, left, right = tree
+        tree = left if x[j] <= t else right
+    return tree[1]

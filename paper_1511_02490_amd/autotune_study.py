@@ -1,6 +1,7 @@
 """The paper's experiment in miniature, on one MI355X: sweep the workgroup-size space of a set
 of synthetic and real stencil scenarios (Section 5), then evaluate workgroup-size prediction
-(Algorithm 1: nearest-neighbour classifier over f(s) with the NearestNeighbour fallback) against
+(Algorithm 1: nearest-neighbour and decision-tree classifiers over f(s) with the NearestNeighbour
+fallback) against
 the sweep's oracle sizes with the metrics of Section 7.
 
     python -m paper_1511_02490_amd.autotune_study [--synthetic 32] [--reps 5] [--mapping local,1,1]
@@ -75,7 +76,7 @@ def main():
                 j = base
                 legal_first = True
             else:
-                pred = ls.Predictor()
+                pred = ls.Predictor(predictor_kind)
                 for k in tr:
                     pred.add(feats[k], sizes[oracle[k]])
                 raw = pred.classify(feats[i])
@@ -109,8 +110,10 @@ def main():
     all_i = list(range(n_s))
     syn = [i for i in all_i if kind[i] == "synthetic"]
     real = [i for i in all_i if kind[i] == "real"]
-    parts = {"leave-one-out, 1-NN + NearestNeighbour": evaluate(all_i, all_i, "1nn"),
-             "synthetic -> real, 1-NN + NearestNeighbour": evaluate(syn, real, "1nn"),
+    parts = {"leave-one-out, 1-NN + NearestNeighbour": evaluate(all_i, all_i, "nearest"),
+             "leave-one-out, decision tree + NearestNeighbour": evaluate(all_i, all_i, "tree"),
+             "synthetic -> real, 1-NN + NearestNeighbour": evaluate(syn, real, "nearest"),
+             "synthetic -> real, decision tree + NearestNeighbour": evaluate(syn, real, "tree"),
              "ZeroR (always the baseline size)": evaluate(all_i, all_i, "zeror")}
 
     worst_over_best = [max(t for t, s in zip(times[i], status[i]) if s == 0) / times[i][oracle[i]] for i in all_i]

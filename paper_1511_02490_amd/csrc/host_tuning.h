@@ -88,20 +88,58 @@ inline int baseline_index(const double *perf, int n_scen, int n_sizes) {
     return best;
 }
 
-// classify(f(s)) by the nearest training scenario (range-scaled Euclidean distance).
-class NearestClassifier {
+// classify(f(s)) of Algorithm 1 over (f(s), Omega(s)) training pairs, three ways:
+//   kNearest - the label of the nearest training scenario (each feature scaled by its range
+//              over the training set, Euclidean distance, first nearest wins ties);
+//   kTree    - a decision tree in the manner of the paper's J48: binary splits `feature <=
+//              threshold` chosen by information gain over the midpoints between consecutive
+//              distinct values (features in order, thresholds ascending, first best wins), grown
+//              until a node is pure or nothing gains; a leaf answers with its most frequent
+//              label (the one seen first among equals);
+//   kZeroR   - always the most frequent label of the training set (the paper's dummy classifier).
+class Classifier {
 public:
+    enum Kind { kNearest = 0, kTree = 1, kZeroR = 2 };
+    explicit Classifier(int kind) : kind_(kind) {}
+
     bool add(const double *f, int nf, int wr, int wc) {
         if (nf_ == 0) nf_ = nf;
         if (nf != nf_) return false;
         x_.insert(x_.end(), f, f + nf);
         wr_.push_back(wr);
         wc_.push_back(wc);
+        built_ = false;
         return true;
     }
+
     bool classify(const double *f, int nf, int *wr, int *wc) const {
         const size_t n = wr_.size();
         if (n == 0 || nf != nf_) return false;
+        size_t pick = 0;
+        if (kind_ == kNearest) {
+            pick = nearest(f);
+        } else {
+            if (!built_) build();
+            int node = 0;
+            while (kind_ == kTree && nodes_[node].feature >= 0)
+                node = f[nodes_[node].feature] <= nodes_[node].threshold ? nodes_[node].left : nodes_[node].right;
+            pick = (size_t)nodes_[node].label_of;
+        }
+        *wr = wr_[pick];
+        *wc = wc_[pick];
+        return true;
+    }
+
+private:
+    struct Node {
+        int feature;        // -1: leaf
+        double threshold;
+        int left, right;
+        int label_of;       // a training pair carrying the leaf's label
+    };
+
+    size_t nearest(const double *f) const {
+        const size_t n = wr_.size();
         std::vector<double> lo(nf_), hi(nf_);
         for (int j = 0; j < nf_; ++j) {
             lo[j] = hi[j] = x_[j];
@@ -126,15 +164,102 @@ public:
                 best = i;
             }
         }
-        *wr = wr_[best];
-        *wc = wc_[best];
-        return true;
+        return best;
     }
 
-private:
+    bool same_label(int a, int b) const { return wr_[a] == wr_[b] && wc_[a] == wc_[b]; }
+
+    // label counts of a set of training pairs, labels in order of first appearance
+    void count(const std::vector<int> &idx, std::vector<int> &first, std::vector<int> &cnt) const {
+        first.clear();
+        cnt.clear();
+        for (int i : idx) {
+            size_t c = 0;
+            while (c < first.size() && !same_label(first[c], i)) ++c;
+            if (c == first.size()) {
+                first.push_back(i);
+                cnt.push_back(0);
+            }
+            ++cnt[c];
+        }
+    }
+
+    double entropy(const std::vector<int> &idx) const {
+        std::vector<int> first, cnt;
+        count(idx, first, cnt);
+        double h = 0;
+        for (int c : cnt) {
+            const double p = (double)c / (double)idx.size();
+            h -= p * std::log2(p);
+        }
+        return h;
+    }
+
+    int majority(const std::vector<int> &idx) const {
+        std::vector<int> first, cnt;
+        count(idx, first, cnt);
+        size_t best = 0;
+        for (size_t c = 1; c < cnt.size(); ++c)
+            if (cnt[c] > cnt[best]) best = c;
+        return first[best];
+    }
+
+    int grow(const std::vector<int> &idx) const {
+        const int me = (int)nodes_.size();
+        nodes_.push_back(Node{-1, 0.0, -1, -1, majority(idx)});
+        if (kind_ != kTree) return me;
+        const double h = entropy(idx);
+        if (h <= 0) return me;
+        double best_gain = 0;
+        int best_f = -1;
+        double best_t = 0;
+        std::vector<int> l, r;
+        for (int j = 0; j < nf_; ++j) {
+            std::vector<double> vals;
+            for (int i : idx) vals.push_back(x_[(size_t)i * nf_ + j]);
+            std::sort(vals.begin(), vals.end());
+            vals.erase(std::unique(vals.begin(), vals.end()), vals.end());
+            for (size_t k = 0; k + 1 < vals.size(); ++k) {
+                const double t = 0.5 * (vals[k] + vals[k + 1]);
+                l.clear();
+                r.clear();
+                for (int i : idx) (x_[(size_t)i * nf_ + j] <= t ? l : r).push_back(i);
+                const double n = (double)idx.size();
+                const double gain = h - ((double)l.size() / n) * entropy(l) - ((double)r.size() / n) * entropy(r);
+                if (gain > best_gain) {
+                    best_gain = gain;
+                    best_f = j;
+                    best_t = t;
+                }
+            }
+        }
+        if (best_f < 0) return me;
+        l.clear();
+        r.clear();
+        for (int i : idx) (x_[(size_t)i * nf_ + best_f] <= best_t ? l : r).push_back(i);
+        const int left = grow(l);
+        const int right = grow(r);
+        nodes_[me].feature = best_f;
+        nodes_[me].threshold = best_t;
+        nodes_[me].left = left;
+        nodes_[me].right = right;
+        return me;
+    }
+
+    void build() const {
+        nodes_.clear();
+        std::vector<int> all(wr_.size());
+        for (size_t i = 0; i < all.size(); ++i) all[i] = (int)i;
+        grow(all);
+        built_ = true;
+    }
+
+    int kind_;
     int nf_ = 0;
     std::vector<double> x_;
     std::vector<int> wr_, wc_;
+    mutable std::vector<Node> nodes_;
+    mutable bool built_ = false;
 };
 
 }  // namespace host_tuning

@@ -903,19 +903,22 @@ int stencil_features(const stencil_t *s, double *f) {
     return STENCIL_OK;
 }
 
-int stencil_predictor_create(stencil_predictor_t **out) {
+int stencil_predictor_create(stencil_predictor_t **out, int classifier) {
     if (!out) return fail(STENCIL_E_INVALID, "NULL argument");
-    *out = reinterpret_cast<stencil_predictor_t *>(new (std::nothrow) host_tuning::NearestClassifier);
+    *out = nullptr;
+    if (classifier < STENCIL_CLASSIFIER_NEAREST || classifier > STENCIL_CLASSIFIER_ZEROR)
+        return fail(STENCIL_E_INVALID, "unknown classifier %d", classifier);
+    *out = reinterpret_cast<stencil_predictor_t *>(new (std::nothrow) host_tuning::Classifier(classifier));
     return *out ? STENCIL_OK : fail(STENCIL_E_RESOURCES, "out of host memory");
 }
 
 void stencil_predictor_destroy(stencil_predictor_t *p) {
-    delete reinterpret_cast<host_tuning::NearestClassifier *>(p);
+    delete reinterpret_cast<host_tuning::Classifier *>(p);
 }
 
 int stencil_predictor_add(stencil_predictor_t *p, const double *features, int n_features, int wg_rows, int wg_cols) {
     if (!p || !features || n_features < 1 || wg_rows < 1 || wg_cols < 1) return fail(STENCIL_E_INVALID, "bad arguments");
-    auto *c = reinterpret_cast<host_tuning::NearestClassifier *>(p);
+    auto *c = reinterpret_cast<host_tuning::Classifier *>(p);
     if (!c->add(features, n_features, wg_rows, wg_cols))
         return fail(STENCIL_E_INVALID, "feature count %d differs from earlier training pairs", n_features);
     return STENCIL_OK;
@@ -924,7 +927,7 @@ int stencil_predictor_add(stencil_predictor_t *p, const double *features, int n_
 int stencil_predictor_classify(const stencil_predictor_t *p, const double *features, int n_features,
                                int *wg_rows, int *wg_cols) {
     if (!p || !features || !wg_rows || !wg_cols) return fail(STENCIL_E_INVALID, "NULL argument");
-    auto *c = reinterpret_cast<const host_tuning::NearestClassifier *>(p);
+    auto *c = reinterpret_cast<const host_tuning::Classifier *>(p);
     if (!c->classify(features, n_features, wg_rows, wg_cols))
         return fail(STENCIL_E_INVALID, "classifier has no training pairs, or feature count differs");
     return STENCIL_OK;

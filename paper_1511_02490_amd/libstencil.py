@@ -66,7 +66,7 @@ def _load() -> ctypes.CDLL:
         "stencil_sweep_reduce": (c_int, [ip, ip, c_int, dp, ip, c_dbl, ip, dp, dp]),
         "stencil_baseline_wg": (c_int, [dp, c_int, c_int, ip]),
         "stencil_features": (c_int, [vp, dp]),
-        "stencil_predictor_create": (c_int, [ctypes.POINTER(vp)]),
+        "stencil_predictor_create": (c_int, [ctypes.POINTER(vp), c_int]),
         "stencil_predictor_destroy": (None, [vp]),
         "stencil_predictor_add": (c_int, [vp, dp, c_int, c_int, c_int]),
         "stencil_predictor_classify": (c_int, [vp, dp, c_int, ip, ip]),
@@ -304,11 +304,12 @@ class Stencil:
 
 
 class Predictor:
-    """Nearest-neighbour classifier over (f(s), Omega(s)) pairs (Section 4.1)."""
+    """Classifier over (f(s), Omega(s)) pairs (Section 4.1): "nearest", "tree" or "zeror"."""
 
-    def __init__(self):
+    def __init__(self, classifier: str = "nearest"):
         self._h = ctypes.c_void_p()
-        _check(_lib.stencil_predictor_create(ctypes.byref(self._h)))
+        kind = {"nearest": 0, "tree": 1, "zeror": 2}[classifier]
+        _check(_lib.stencil_predictor_create(ctypes.byref(self._h), kind))
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:

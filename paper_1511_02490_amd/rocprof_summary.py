@@ -1,6 +1,6 @@
 """Condenses rocprofv3 output of a bench.py run into a short text summary and a traffic record.
 
-    python -m paper_1511_02490_amd.rocprof_summary --prefix c4 --dir gpurun_out/prof \
+    python -m paper_1511_02490_amd.rocprof_summary --prefix c4 --dir prof_out \
         --kernel direct_kernel --title "..." --command "..." > profiles/<name>.md
 
 expects <dir>/<prefix>_trace (from --kernel-trace --stats), <dir>/<prefix>_fetch (--pmc FETCH_SIZE)
@@ -98,8 +98,8 @@ def main():
     out.append("Commands (from the repository root on the GPU box; `cd /tmp && export TMPDIR=/tmp` first):")
     out.append("")
     for flags, tag in (("--kernel-trace --stats", "trace"), ("--pmc FETCH_SIZE", "fetch"), ("--pmc WRITE_SIZE", "write")):
-        out.append("    rocprofv3 %s --output-format csv -d gpurun_out/prof/%s_%s -o %s -- python3 bench.py %s"
-                   % (flags, p, tag, p, a.command))
+        out.append("    rocprofv3 %s --output-format csv -d %s/%s_%s -o %s -- python3 bench.py %s"
+                   % (flags, d.rstrip("/"), p, tag, p, a.command))
     out.append("")
     out.append("## Kernel trace (--kernel-trace --stats)")
     out.append("")

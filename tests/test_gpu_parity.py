@@ -321,6 +321,34 @@ def test_error_paths_do_not_launch(ls):
     assert rel_err(tout.cpu().numpy(), ref) <= REL_1
 
 
+def test_device_copy_and_workgroup_numbering_option(ls):
+    for n in (1, 15, 16, 17, 4096, 1000003):
+        a = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+        b = torch.zeros_like(a)
+        ls.device_copy(a, b)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b), n
+    x = torch.zeros(64, device="cuda")
+    with pytest.raises(ls.StencilError):
+        ls.device_copy(x[:32], x[16:48])                             # overlap
+    # the XCD-aware numbering of workgroups changes the schedule, never the values
+    w = wl.config(4, rows=200, cols=312)
+    g = w.grid()
+    outs = []
+    for remap in (1, 0):
+        st = ls.Stencil.from_workload(w)
+        st.set_mapping("local", 2, 4)
+        st.set_option(ls.OPT_XCD_REMAP, remap)
+        tin = torch.from_numpy(g).cuda()
+        tout = torch.empty_like(tin)
+        st.run(tin, tout, 1, (4, 8))                                # 25 x 10 tiles: above the remap threshold
+        torch.cuda.synchronize()
+        outs.append(tout.cpu().numpy())
+        st.close()
+    np.testing.assert_array_equal(outs[0], outs[1])
+    assert rel_err(outs[0], oracle.apply_workload(w, g)) <= REL_1
+
+
 def test_runs_on_a_side_stream(ls):
     w = wl.config(0)
     g = w.grid()
@@ -453,6 +481,8 @@ def test_c4_full_size(ls):
     got = gpu_apply(ls, w, g, (4, 64), iters=100, blocking=("direct", 1, 4))
     np.testing.assert_array_equal(got, ref)
     got = gpu_apply(ls, w, g, (4, 64), iters=100, blocking=("temporal", 4, 4, 4))
+    np.testing.assert_array_equal(got, ref)
+    got = gpu_apply(ls, w, g, (16, 16), iters=100, blocking=("temporal", 2, 4, 4))
     np.testing.assert_array_equal(got, ref)
     c = gpu_apply(ls, w, g, (8, 32), iters=1000, blocking=("temporal", 2, 4, 3))
     a = gpu_apply(ls, w, g, (4, 64), iters=1000, blocking=("direct", 1, 4))

@@ -184,3 +184,23 @@ def test_baseline_handler_matches_definition():
         expect = tuning.baseline_size(dicts, safe)
         got = ls.baseline_wg(table.tolist())
         assert (got == -1 and expect is None) or got == expect
+
+
+def test_tree_and_zeror_classifiers_match_definitions():
+    rng = np.random.default_rng(11)
+    labels_pool = [(64, 4), (8, 8), (16, 16), (4, 64), (32, 32)]
+    for trial in range(10):
+        n, nf = int(rng.integers(3, 40)), int(rng.integers(1, 6))
+        X = rng.integers(0, 6, size=(n, nf)).astype(float).tolist()      # repeated values and ties
+        W = [labels_pool[int(k)] for k in rng.integers(0, len(labels_pool), size=n)]
+        tree = tuning.grow_tree(X, W)
+        pt, pz = ls.Predictor("tree"), ls.Predictor("zeror")
+        for x, w in zip(X, W):
+            pt.add(x, w)
+            pz.add(x, w)
+        probes = rng.uniform(-1, 7, size=(30, nf)).tolist() + X
+        for x in probes:
+            assert pt.classify(x) == tuning.classify_tree(tree, x)
+            assert pz.classify(x) == tuning.classify_zeror(W)
+    with pytest.raises(ls.StencilError):
+        ls.Predictor("tree").classify([1.0])

@@ -120,3 +120,30 @@ def test_baseline_and_random_handlers_by_hand():
     assert tuning.predict_random((64, 32), cands, 1024, [(32, 4)], 3) == (16, 64)
     assert tuning.predict_random((64, 32), cands, 1024, [(32, 4)], 4) == (4, 4)
     assert tuning.predict_random((64, 32), [], 1024, [], 4) is None
+
+
+def test_decision_tree_by_hand():
+    """Four scenarios, two features.  Feature 0 separates {A, A} from {B, C} with gain 1 bit (the
+    parent has entropy 1.5 bits, the children 0 and 1); feature 1 cannot do better, so the root
+    splits on feature 0 at the midpoint 15; the right child then splits on feature 1 at 2.5."""
+    X = [(10.0, 1.0), (10.0, 9.0), (20.0, 2.0), (20.0, 3.0)]
+    A, B, C = (64, 4), (8, 8), (16, 16)
+    W = [A, A, B, C]
+    tree = tuning.grow_tree(X, W)
+    assert tree == ("split", 0, 15.0, ("leaf", A), ("split", 1, 2.5, ("leaf", B), ("leaf", C)))
+    assert tuning.classify_tree(tree, (12.0, 100.0)) == A
+    assert tuning.classify_tree(tree, (15.0, 0.0)) == A          # x <= t goes left
+    assert tuning.classify_tree(tree, (99.0, 2.5)) == B
+    assert tuning.classify_tree(tree, (99.0, 2.6)) == C
+    # identical features with different labels cannot be split: majority, first among equals
+    tree2 = tuning.grow_tree([(1.0,), (1.0,), (1.0,)], [B, A, A])
+    assert tree2 == ("leaf", A)
+    assert tuning.grow_tree([(1.0,), (1.0,)], [B, A]) == ("leaf", B)
+    # a training set is always classified back correctly when its features are distinct
+    import random
+    rnd = random.Random(5)
+    X3 = [(rnd.random(), rnd.random(), float(rnd.randrange(4))) for _ in range(40)]
+    W3 = [rnd.choice([A, B, C, (4, 64)]) for _ in range(40)]
+    t3 = tuning.grow_tree(X3, W3)
+    assert all(tuning.classify_tree(t3, x) == w for x, w in zip(X3, W3))
+    assert tuning.classify_zeror([B, A, A, B, C]) == B and tuning.classify_zeror([C, A, A]) == A
