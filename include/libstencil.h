@@ -33,6 +33,7 @@ extern "C" {
 
 typedef struct stencil stencil_t;
 typedef struct stencil_predictor stencil_predictor_t;
+typedef struct stencil_regressor stencil_regressor_t;
 
 enum stencil_status {
     STENCIL_OK = 0,
@@ -244,6 +245,29 @@ int stencil_predict_wg(const stencil_t *st, const stencil_predictor_t *p,
                        const int *cand_rows, const int *cand_cols, int n_cand,
                        int handler, int baseline_rows, int baseline_cols, uint64_t random,
                        int *wg_rows, int *wg_cols);
+
+/* ---- prediction with regressors (Sections 4.2 and 4.3, Algorithm 2) -------------------------- */
+
+/* R(f(s), w): a regressor over (f(s), w, y) tuples, y a runtime (Section 4.2) or the speedup of
+ * w over a baseline size (Section 4.3).  Nearest-neighbour regression: the prediction for (f, w)
+ * is the y of the tuple with the same w whose scenario is nearest to f (features scaled by their
+ * range over all tuples, Euclidean distance, first nearest wins ties); NaN if no tuple has w. */
+int stencil_regressor_create(stencil_regressor_t **out);
+void stencil_regressor_destroy(stencil_regressor_t *r);
+int stencil_regressor_add(stencil_regressor_t *r, const double *features, int n_features,
+                          int wg_rows, int wg_cols, double value);
+int stencil_regressor_predict(const stencil_regressor_t *r, const double *features, int n_features,
+                              int wg_rows, int wg_cols, double *value);
+
+/* Algorithm 2: among the candidates within W_max(s) that the regressor can price, take the one
+ * with the highest fitness of the prediction - STENCIL_FITNESS_RECIPROCAL (1/x, for predicted
+ * runtimes) or STENCIL_FITNESS_IDENTITY (for predicted speedups); if it turns out to be a refused
+ * parameter, strike it from the pool and take the next.  n_refused (may be NULL) = how many were
+ * struck.  STENCIL_E_REFUSED if the pool runs dry. */
+enum stencil_fitness { STENCIL_FITNESS_RECIPROCAL = 0, STENCIL_FITNESS_IDENTITY = 1 };
+int stencil_predict_wg_regression(const stencil_t *st, const stencil_regressor_t *r,
+                                  const int *cand_rows, const int *cand_cols, int n_cand, int fitness,
+                                  int *wg_rows, int *wg_cols, int *n_refused);
 
 /* Text of the calling thread's most recent error ("" if none). */
 const char *stencil_last_error(void);

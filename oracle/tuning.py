@@ -273,3 +273,54 @@ def classify_tree(tree, x: Sequence[float]) -> WG:
         _, j, t, left, right = tree
         tree = left if x[j] <= t else right
     return tree[1]
+
+
+# ---- Algorithm 2: classification by regression --------------------------------------------------
+
+def regress_1nn(train_x: Sequence[Sequence[float]], train_w: Sequence[WG], train_y: Sequence[float],
+                x: Sequence[float], w: WG) -> float:
+    """R(f(s), w): the y of the training tuple with the same w whose scenario is nearest to x
+    (features scaled by their range over all tuples; first nearest wins ties); NaN if none has w."""
+    nf = len(x)
+    lo = [min(row[j] for row in train_x) for j in range(nf)]
+    hi = [max(row[j] for row in train_x) for j in range(nf)]
+    best_y, d_best = float("nan"), math.inf
+    for row, wi, y in zip(train_x, train_w, train_y):
+        if tuple(wi) != tuple(w):
+            continue
+        d = 0.0
+        for j in range(nf):
+            span = hi[j] - lo[j]
+            if span > 0.0:
+                z = (row[j] - x[j]) / span
+                d += z * z
+        if d < d_best:
+            d_best, best_y = d, y
+    return best_y
+
+
+def predict_by_regression(predict, candidates: Sequence[WG], w_max: int, refused: Iterable[WG],
+                          fitness) -> Tuple[Optional[WG], int]:
+    """Algorithm 2.  `predict(w)` is R(f(s), w) for the scenario at hand, `fitness` the function
+    Delta (reciprocal for runtimes, identity for speedups).  Candidates are the sizes within
+    W_max; the best one by fitness is returned unless it is a refused parameter, in which case it
+    is struck from the pool and the next best taken.  Returns (size, number struck)."""
+    ref = set(refused)
+    pool = []
+    for c in candidates:
+        if c[0] >= 1 and c[1] >= 1 and c[0] * c[1] <= w_max:
+            y = predict(c)
+            if not math.isnan(y):
+                pool.append((c, fitness(y)))
+    struck = 0
+    while pool:
+        best = 0
+        for i in range(1, len(pool)):
+            if pool[i][1] > pool[best][1]:
+                best = i
+        w = pool[best][0]
+        if w not in ref:
+            return w, struck
+        struck += 1
+        del pool[best]
+    return None, struck

@@ -1,7 +1,7 @@
 """The paper's experiment in miniature, on one MI355X: sweep the workgroup-size space of a set
 of synthetic and real stencil scenarios (Section 5), then evaluate workgroup-size prediction
 (Algorithm 1: nearest-neighbour and decision-tree classifiers over f(s) with the NearestNeighbour
-fallback) against
+fallback; Algorithm 2: nearest-neighbour regressors on runtimes and on speedups) against
 the sweep's oracle sizes with the metrics of Section 7.
 
     python -m paper_1511_02490_amd.autotune_study [--synthetic 32] [--reps 5] [--mapping local,1,1]
@@ -97,6 +97,36 @@ def main():
                          "speedup_over_32x4": times[i][idx[(32, 4)]] / t if status[i][idx[(32, 4)]] == 0 else nan})
         return rows
 
+    def evaluate_regression(train, test, target):
+        """Algorithm 2 with the nearest-neighbour regressor trained on runtimes (target = "runtime",
+        fitness 1/x) or on speedups over the baseline size (target = "speedup", fitness x)."""
+        rows = []
+        for i in test:
+            reg = ls.Regressor()
+            for k in train:
+                if k == i:
+                    continue
+                for j, w in enumerate(sizes):
+                    if status[k][j] == 0:
+                        y = times[k][j] if target == "runtime" else times[k][base] / times[k][j]
+                        reg.add(feats[k], w, y)
+            st = ls.Stencil.from_workload(scen[i])
+            try:
+                st.set_mapping(*mapping)
+            except ls.StencilError:
+                st.set_mapping("local", 1, 1)
+            (wr, wc), struck = st.predict_regression(reg, sizes, "reciprocal" if target == "runtime" else "identity")
+            st.close()
+            reg.close()
+            j = idx[(wr, wc)]
+            t = times[i][j]
+            rows.append({"scenario": scen[i].name, "oracle": sizes[oracle[i]], "predicted": sizes[j],
+                         "accurate": j == oracle[i], "valid_first": struck == 0, "performance": perf[i][j],
+                         "speedup_over_baseline": times[i][base] / t,
+                         "speedup_over_4x4": times[i][idx[(4, 4)]] / t if status[i][idx[(4, 4)]] == 0 else nan,
+                         "speedup_over_32x4": times[i][idx[(32, 4)]] / t if status[i][idx[(32, 4)]] == 0 else nan})
+        return rows
+
     def summary(rows):
         f = lambda key: [r[key] for r in rows if not math.isnan(r[key])]
         return {"n": len(rows), "accuracy": sum(r["accurate"] for r in rows) / len(rows),
@@ -114,6 +144,9 @@ def main():
              "leave-one-out, decision tree + NearestNeighbour": evaluate(all_i, all_i, "tree"),
              "synthetic -> real, 1-NN + NearestNeighbour": evaluate(syn, real, "nearest"),
              "synthetic -> real, decision tree + NearestNeighbour": evaluate(syn, real, "tree"),
+             "leave-one-out, regressor on runtimes (Algorithm 2)": evaluate_regression(all_i, all_i, "runtime"),
+             "leave-one-out, regressor on speedups (Algorithm 2)": evaluate_regression(all_i, all_i, "speedup"),
+             "synthetic -> real, regressor on speedups (Algorithm 2)": evaluate_regression(syn, real, "speedup"),
              "ZeroR (always the baseline size)": evaluate(all_i, all_i, "zeror")}
 
     worst_over_best = [max(t for t, s in zip(times[i], status[i]) if s == 0) / times[i][oracle[i]] for i in all_i]

@@ -262,4 +262,55 @@ private:
     mutable bool built_ = false;
 };
 
+// R(f(s), w) of Algorithm 2 as a nearest-neighbour regressor over (f(s), w, y) tuples: the y of
+// the tuple with the same w whose scenario is nearest to f (features scaled by their range over
+// all tuples, Euclidean distance, first nearest wins ties); NaN if no tuple has this w.
+class Regressor {
+public:
+    bool add(const double *f, int nf, int wr, int wc, double y) {
+        if (nf_ == 0) nf_ = nf;
+        if (nf != nf_) return false;
+        x_.insert(x_.end(), f, f + nf);
+        wr_.push_back(wr);
+        wc_.push_back(wc);
+        y_.push_back(y);
+        return true;
+    }
+    int n_features() const { return nf_; }
+    double predict(const double *f, int wr, int wc) const {
+        const size_t n = y_.size();
+        std::vector<double> lo(nf_), hi(nf_);
+        for (int j = 0; j < nf_; ++j) {
+            lo[j] = hi[j] = n ? x_[j] : 0.0;
+            for (size_t i = 1; i < n; ++i) {
+                lo[j] = std::min(lo[j], x_[i * nf_ + j]);
+                hi[j] = std::max(hi[j], x_[i * nf_ + j]);
+            }
+        }
+        double best_y = std::numeric_limits<double>::quiet_NaN();
+        double d_best = std::numeric_limits<double>::infinity();
+        for (size_t i = 0; i < n; ++i) {
+            if (wr_[i] != wr || wc_[i] != wc) continue;
+            double d = 0;
+            for (int j = 0; j < nf_; ++j) {
+                const double span = hi[j] - lo[j];
+                if (span > 0) {
+                    const double z = (x_[i * nf_ + j] - f[j]) / span;
+                    d += z * z;
+                }
+            }
+            if (d < d_best) {
+                d_best = d;
+                best_y = y_[i];
+            }
+        }
+        return best_y;
+    }
+
+private:
+    int nf_ = 0;
+    std::vector<double> x_, y_;
+    std::vector<int> wr_, wc_;
+};
+
 }  // namespace host_tuning

@@ -984,4 +984,75 @@ int stencil_predict_wg(const stencil_t *s, const stencil_predictor_t *p, const i
     return STENCIL_OK;
 }
 
+int stencil_regressor_create(stencil_regressor_t **out) {
+    if (!out) return fail(STENCIL_E_INVALID, "NULL argument");
+    *out = reinterpret_cast<stencil_regressor_t *>(new (std::nothrow) host_tuning::Regressor);
+    return *out ? STENCIL_OK : fail(STENCIL_E_RESOURCES, "out of host memory");
+}
+
+void stencil_regressor_destroy(stencil_regressor_t *r) { delete reinterpret_cast<host_tuning::Regressor *>(r); }
+
+int stencil_regressor_add(stencil_regressor_t *r, const double *features, int n_features, int wg_rows, int wg_cols,
+                          double value) {
+    if (!r || !features || n_features < 1 || wg_rows < 1 || wg_cols < 1 || std::isnan(value))
+        return fail(STENCIL_E_INVALID, "bad arguments");
+    if (!reinterpret_cast<host_tuning::Regressor *>(r)->add(features, n_features, wg_rows, wg_cols, value))
+        return fail(STENCIL_E_INVALID, "feature count %d differs from earlier tuples", n_features);
+    return STENCIL_OK;
+}
+
+int stencil_regressor_predict(const stencil_regressor_t *r, const double *features, int n_features, int wg_rows,
+                              int wg_cols, double *value) {
+    if (!r || !features || !value) return fail(STENCIL_E_INVALID, "NULL argument");
+    auto *reg = reinterpret_cast<const host_tuning::Regressor *>(r);
+    if (reg->n_features() != n_features) return fail(STENCIL_E_INVALID, "regressor is empty, or feature count differs");
+    *value = reg->predict(features, wg_rows, wg_cols);
+    return STENCIL_OK;
+}
+
+int stencil_predict_wg_regression(const stencil_t *s, const stencil_regressor_t *r, const int *cand_rows,
+                                  const int *cand_cols, int n_cand, int fitness, int *wg_rows, int *wg_cols,
+                                  int *n_refused) {
+    if (!s || !r || !wg_rows || !wg_cols || n_cand < 0 || (n_cand > 0 && (!cand_rows || !cand_cols)))
+        return fail(STENCIL_E_INVALID, "bad arguments");
+    if (fitness != STENCIL_FITNESS_RECIPROCAL && fitness != STENCIL_FITNESS_IDENTITY)
+        return fail(STENCIL_E_INVALID, "unknown fitness function %d", fitness);
+    auto *reg = reinterpret_cast<const host_tuning::Regressor *>(r);
+    double f[STENCIL_N_FEATURES];
+    int rc = stencil_features(s, f);
+    if (rc != STENCIL_OK) return rc;
+    if (reg->n_features() != STENCIL_N_FEATURES) return fail(STENCIL_E_INVALID, "regressor is empty, or feature count differs");
+    const Variant *v = find_variant(s);
+    if (!v) return fail(STENCIL_E_INVALID, "no kernel variant for this scenario");
+    // Algorithm 2: candidates within W_max; best by fitness of the prediction; a refused
+    // parameter is struck from the pool and the next best taken
+    std::vector<int> pool;
+    std::vector<double> fit;
+    for (int k = 0; k < n_cand; ++k) {
+        if (cand_rows[k] < 1 || cand_cols[k] < 1 || (int64_t)cand_rows[k] * cand_cols[k] > v->max_threads) continue;
+        const double y = reg->predict(f, cand_rows[k], cand_cols[k]);
+        if (std::isnan(y)) continue;
+        pool.push_back(k);
+        fit.push_back(fitness == STENCIL_FITNESS_RECIPROCAL ? 1.0 / y : y);
+    }
+    int refused = 0;
+    while (!pool.empty()) {
+        size_t best = 0;
+        for (size_t i = 1; i < pool.size(); ++i)
+            if (fit[i] > fit[best]) best = i;
+        const int k = pool[best];
+        if (check_legal(s, v, cand_rows[k], cand_cols[k]) == STENCIL_OK) {
+            g_err[0] = '\0';
+            *wg_rows = cand_rows[k];
+            *wg_cols = cand_cols[k];
+            if (n_refused) *n_refused = refused;
+            return STENCIL_OK;
+        }
+        ++refused;
+        pool.erase(pool.begin() + (long)best);
+        fit.erase(fit.begin() + (long)best);
+    }
+    return fail(STENCIL_E_REFUSED, "no legal candidate workgroup size");
+}
+
 }  // extern "C"

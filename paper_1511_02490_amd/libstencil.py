@@ -71,6 +71,11 @@ def _load() -> ctypes.CDLL:
         "stencil_predictor_add": (c_int, [vp, dp, c_int, c_int, c_int]),
         "stencil_predictor_classify": (c_int, [vp, dp, c_int, ip, ip]),
         "stencil_predict_wg": (c_int, [vp, vp, ip, ip, c_int, c_int, c_int, c_int, ctypes.c_uint64, ip, ip]),
+        "stencil_regressor_create": (c_int, [ctypes.POINTER(vp)]),
+        "stencil_regressor_destroy": (None, [vp]),
+        "stencil_regressor_add": (c_int, [vp, dp, c_int, c_int, c_int, c_dbl]),
+        "stencil_regressor_predict": (c_int, [vp, dp, c_int, c_int, c_int, dp]),
+        "stencil_predict_wg_regression": (c_int, [vp, vp, ip, ip, c_int, c_int, ip, ip, ip]),
         "stencil_last_error": (ctypes.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -85,7 +90,9 @@ EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_s
            "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg",
            "stencil_device_copy", "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
-           "stencil_predict_wg", "stencil_last_error")
+           "stencil_predict_wg", "stencil_regressor_create", "stencil_regressor_destroy",
+           "stencil_regressor_add", "stencil_regressor_predict", "stencil_predict_wg_regression",
+           "stencil_last_error")
 
 
 def last_error() -> str:
@@ -291,6 +298,16 @@ class Stencil:
         return SweepResult([tuple(s) for s in sizes], list(mean)[:n], list(mn)[:n], list(med)[:n],
                            list(sd)[:n], list(status)[:n], best.value, sp.value)
 
+    def predict_regression(self, regressor: "Regressor", candidates: Sequence[Tuple[int, int]],
+                           fitness: str = "reciprocal") -> Tuple[Tuple[int, int], int]:
+        """Algorithm 2: ((wg_rows, wg_cols), number of refused candidates struck on the way)."""
+        wr, wc, nref = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        fit = {"reciprocal": 0, "identity": 1}[fitness]
+        _check(_lib.stencil_predict_wg_regression(self._h, regressor._h, _ints([c[0] for c in candidates]),
+                                                  _ints([c[1] for c in candidates]), len(candidates), fit,
+                                                  ctypes.byref(wr), ctypes.byref(wc), ctypes.byref(nref)))
+        return (wr.value, wc.value), nref.value
+
     def predict(self, predictor: "Predictor", candidates: Sequence[Tuple[int, int]], handler: str = "nearest",
                 baseline: Tuple[int, int] = (0, 0), random: int = 0) -> Tuple[int, int]:
         """Algorithm 1 with the chosen fallback handler ("nearest", "baseline" or "random")."""
@@ -301,6 +318,30 @@ class Stencil:
                                        int(baseline[0]), int(baseline[1]), int(random),
                                        ctypes.byref(wr), ctypes.byref(wc)))
         return wr.value, wc.value
+
+
+class Regressor:
+    """Nearest-neighbour regressor over (f(s), w, y) tuples (Sections 4.2 / 4.3)."""
+
+    def __init__(self):
+        self._h = ctypes.c_void_p()
+        _check(_lib.stencil_regressor_create(ctypes.byref(self._h)))
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            _lib.stencil_regressor_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = close
+
+    def add(self, features: Sequence[float], wg: Tuple[int, int], value: float):
+        _check(_lib.stencil_regressor_add(self._h, _dbls(features), len(features), int(wg[0]), int(wg[1]), float(value)))
+
+    def predict(self, features: Sequence[float], wg: Tuple[int, int]) -> float:
+        y = ctypes.c_double()
+        _check(_lib.stencil_regressor_predict(self._h, _dbls(features), len(features), int(wg[0]), int(wg[1]),
+                                              ctypes.byref(y)))
+        return y.value
 
 
 class Predictor:

@@ -204,3 +204,35 @@ def test_tree_and_zeror_classifiers_match_definitions():
             assert pz.classify(x) == tuning.classify_zeror(W)
     with pytest.raises(ls.StencilError):
         ls.Predictor("tree").classify([1.0])
+
+
+def test_algorithm2_regression_matches_definition():
+    scen = [ls.Stencil.from_workload(wl.config(i)) for i in range(5)]
+    feats = [s.features() for s in scen]
+    cands = tuning.enumerate_sizes("pow2", 2048)
+    rng = np.random.default_rng(17)
+    reg = ls.Regressor()
+    X, W, Y = [], [], []
+    for f in feats[:4]:
+        for w in cands:
+            if rng.random() < 0.8:
+                y = float(rng.uniform(0.1, 5.0))
+                reg.add(f, w, y)
+                X.append(f); W.append(w); Y.append(y)
+    big = ls.Stencil(4096, 4096, "f32", (30, 30, 30, 30), "clamp")      # many refused sizes (tile > local memory)
+    big.set_kernel("weighted_sum", np.zeros((61, 61), np.float32))
+    big.set_mapping("local", 4, 4)
+    for st in (scen[4], big):
+        f = st.features()
+        for w in cands[::7]:
+            a, b = reg.predict(f, w), tuning.regress_1nn(X, W, Y, f, w)
+            assert (math.isnan(a) and math.isnan(b)) or a == b
+        refused = [c for c in cands if c[0] * c[1] <= st.max_wg_size() and not st.is_legal(*c)]
+        for fitness, fn in (("reciprocal", lambda y: 1.0 / y), ("identity", lambda y: y)):
+            got, struck = st.predict_regression(reg, cands, fitness)
+            exp, exp_struck = tuning.predict_by_regression(lambda w: tuning.regress_1nn(X, W, Y, f, w), cands,
+                                                           st.max_wg_size(), refused, fn)
+            assert got == exp and struck == exp_struck and st.is_legal(*got)
+    assert len([c for c in cands if c[0] * c[1] <= 1024 and not big.is_legal(*c)]) > 5
+    with pytest.raises(ls.StencilError):
+        scen[0].predict_regression(ls.Regressor(), cands)

@@ -147,3 +147,23 @@ def test_decision_tree_by_hand():
     t3 = tuning.grow_tree(X3, W3)
     assert all(tuning.classify_tree(t3, x) == w for x, w in zip(X3, W3))
     assert tuning.classify_zeror([B, A, A, B, C]) == B and tuning.classify_zeror([C, A, A]) == A
+
+
+def test_algorithm2_regression_by_hand():
+    # two training scenarios (feature 10 and 20), runtimes per size
+    X = [(10.0,), (10.0,), (10.0,), (20.0,), (20.0,), (20.0,)]
+    W = [(4, 4), (8, 8), (64, 4)] * 2
+    Y = [4.0, 2.0, 1.0, 9.0, 3.0, 5.0]
+    assert tuning.regress_1nn(X, W, Y, (11.0,), (8, 8)) == 2.0
+    assert tuning.regress_1nn(X, W, Y, (19.0,), (8, 8)) == 3.0
+    assert math.isnan(tuning.regress_1nn(X, W, Y, (19.0,), (2, 2)))
+    cands = [(4, 4), (8, 8), (64, 4), (2, 2), (64, 32)]
+    near10 = lambda w: tuning.regress_1nn(X, W, Y, (11.0,), w)
+    recip = lambda y: 1.0 / y
+    # fastest predicted runtime wins; (2,2) has no tuple, (64,32) is above W_max
+    assert tuning.predict_by_regression(near10, cands, 1024, [], recip) == ((64, 4), 0)
+    # a refused parameter is struck and the next best taken
+    assert tuning.predict_by_regression(near10, cands, 1024, [(64, 4)], recip) == ((8, 8), 1)
+    assert tuning.predict_by_regression(near10, cands, 1024, [(64, 4), (8, 8), (4, 4)], recip) == (None, 3)
+    # speedups: identity fitness picks the largest
+    assert tuning.predict_by_regression(near10, cands, 1024, [], lambda y: y) == ((4, 4), 0)
