@@ -17,15 +17,6 @@
 
 namespace sk {
 
-// Cross-lane moves inside a wavefront: the value the lane one below / one above holds.
-// (Lane 0 has no lane below and lane 63 none above; they get 0 and must look elsewhere.)
-__device__ __forceinline__ uint32_t from_lane_below(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
-}
-__device__ __forceinline__ uint32_t from_lane_above(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xf, 0xf, false);
-}
-
 // Rows of an item handled by one work-item per pass through a time step: the window rolls down
 // over them, so R + 2 LDS rows are read for R rows written.
 constexpr int kTemporalRows = 2;

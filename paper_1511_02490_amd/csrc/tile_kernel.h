@@ -69,6 +69,15 @@ __device__ __forceinline__ void store_vec(E *dst, const E (&src)[CNT]) {
     for (int k = 0; k < NV; ++k) reinterpret_cast<uint4 *>(dst)[k] = tmp[k];
 }
 
+// Cross-lane moves inside a wavefront: the value the lane one below / one above holds.
+// (Lane 0 has no lane below and lane 63 none above; they get 0 and must look elsewhere.)
+__device__ __forceinline__ uint32_t from_lane_below(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint32_t from_lane_above(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xf, 0xf, false);
+}
+
 // Columns staged left / right of the tile: the border region's extent, widened to whole
 // 16-byte vectors when the work-items move vectors.
 template <int CC>
