@@ -119,10 +119,16 @@ def leave_one_out_prediction(ls, wl, torch, index, mapping_of, reps):
         st.set_option(ls.OPT_SWEEP_CUTOFF, 300)      # training sweeps: adaptive sampling
         a = torch.from_numpy(o.grid()).cuda()
         b = torch.empty_like(a)
-        res = st.sweep(a, b, o.wg_sizes(), iters=sweep_burst(o), fixed=(0, 0), reps=reps)
+        burst = sweep_burst(o)
+        res = st.sweep(a, b, o.wg_sizes(), iters=burst, fixed=(0, 0), reps=reps)
         if res.best:
             pred.add(st.features(), res.best)
-            table.append({"workload": o.name.split()[0], "oracle_wg": list(res.best)})
+            per_app_ms = res.best_ms / burst
+            table.append({"workload": o.name.split()[0], "oracle_wg": list(res.best),
+                          "mapping": mapping_name(mapping_of(o)), "ms_per_application": per_app_ms,
+                          "gcells_s": o.cells / per_app_ms / 1e6,
+                          "algorithmic_gbs": o.cells * o.bytes_per_cell_update / per_app_ms / 1e6,
+                          "frac_of_hbm_peak": o.cells * o.bytes_per_cell_update / per_app_ms / 1e6 / HBM_PEAK_GBS})
         st.close()
         del a, b
     return pred, table
@@ -219,7 +225,7 @@ def main():
         return
 
     st = ls.Stencil.from_workload(w)
-    sweeps, sweep_seconds, predictor = {}, 0.0, {}
+    sweeps, sweep_seconds, predictor, others = {}, 0.0, {}, {}
     if args.wg:
         wg = tuple(int(x) for x in args.wg.split(","))
         m = args.mapping.split(",") if args.mapping else ["local", "1", "1"]
@@ -260,7 +266,11 @@ def main():
                 if math.isnan(t_p) and st.is_legal(*p):
                     t_p = st.sweep(tin, tout, [p], iters=burst, fixed=(0, 0), reps=args.reps).mean_ms[0]
                 t4 = res.ms_of((4, 4))
-                predictor[tag] = {"mapping": mapping_name(mine), "trained_on": table, "predicted_wg": list(p),
+                if tag == "fast":
+                    others = {t["workload"]: {k: v for k, v in t.items() if k != "workload"} for t in table}
+                predictor[tag] = {"mapping": mapping_name(mine),
+                                  "trained_on": [{"workload": t["workload"], "oracle_wg": t["oracle_wg"]} for t in table],
+                                  "predicted_wg": list(p),
                                   "oracle_wg": list(res.best), "performance": res.best_ms / t_p,
                                   "speedup_over_4x4": (t4 / t_p) if not math.isnan(t4) else None}
             apply_mapping(st, blocking)
@@ -325,6 +335,7 @@ def main():
         "roofline_timed_kernel": roofline_timed,
         "sweep": {"seconds": sweep_seconds, "by_blocking": sweeps},
         "predictor": predictor,
+        "other_workloads": others,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, w, args.cpu_seconds)

@@ -95,7 +95,8 @@ void stencil_destroy(stencil_t *st);
 int stencil_set_kernel(stencil_t *st, int kernel_id, const float *weights, int n_weights,
                        const float *scalars, int n_scalars);
 
-/* Padding value for STENCIL_CONSTANT (Section 2); default 0.  For U8 it is truncated. */
+/* Padding value for STENCIL_CONSTANT (Section 2); default 0.  For a U8 matrix it must be an
+ * integer in [0, 255] (0 or 1 for LIFE). */
 int stencil_set_border_value(stencil_t *st, double value);
 
 /* How elements map to work-items and where the window is staged.

@@ -622,6 +622,9 @@ int stencil_set_kernel(stencil_t *s, int kernel_id, const float *weights, int n_
 
 int stencil_set_border_value(stencil_t *s, double value) {
     if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    if (std::isnan(value) && s->dtype == STENCIL_U8) return fail(STENCIL_E_INVALID, "padding value is NaN");
+    if (s->dtype == STENCIL_U8 && (value < 0 || value > 255 || value != std::floor(value)))
+        return fail(STENCIL_E_INVALID, "padding value of a U8 matrix must be an integer in [0, 255]");
     s->pad = value;
     return STENCIL_OK;
 }
@@ -718,7 +721,9 @@ int stencil_run(stencil_t *s, const void *in, void *out, int iters, int wg_rows,
     if (rc != STENCIL_OK) return rc;
     rc = ensure_device_state(s, v, iters > 1);
     if (rc != STENCIL_OK) return rc;
-    return run_checked(s, v, in, out, iters, wg_rows, wg_cols, (hipStream_t)stream);
+    rc = run_checked(s, v, in, out, iters, wg_rows, wg_cols, (hipStream_t)stream);
+    if (rc == STENCIL_OK) g_err[0] = '\0';
+    return rc;
 }
 
 int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const int *wg_rows_list,

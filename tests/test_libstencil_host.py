@@ -46,6 +46,10 @@ def test_create_validates_arguments():
     with pytest.raises(ls.StencilError):
         ls.Stencil(8, 8, border=7)
     st = ls.Stencil(8, 8, "u8")
+    for bad_pad in (-1.0, 256.0, 0.5):
+        with pytest.raises(ls.StencilError):
+            st.set_border_value(bad_pad)
+    st.set_border_value(1.0)
     with pytest.raises(ls.StencilError):
         st.set_kernel("heat", scalars=(0.2,))            # heat needs f32
     with pytest.raises(ls.StencilError):
