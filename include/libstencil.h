@@ -45,15 +45,18 @@ enum stencil_status {
     STENCIL_E_HIP = -4        /* HIP runtime error; text in stencil_last_error()           */
 };
 
-enum stencil_dtype { STENCIL_F32 = 0, STENCIL_U8 = 1 };
+/* Element types (Section 3.3: integers, single or double precision; U8 for cellular automata). */
+enum stencil_dtype { STENCIL_F32 = 0, STENCIL_U8 = 1, STENCIL_I32 = 2, STENCIL_F64 = 3 };
 
 /* Border substitution (Section 2): CLAMP = value of the nearest cell within the matrix,
  * CONSTANT = predefined padding value, WRAP = periodic (true modulo). */
 enum stencil_border { STENCIL_CLAMP = 0, STENCIL_WRAP = 1, STENCIL_CONSTANT = 2 };
 
 /* Customising functions (Table 2 names the paper's kernels; it does not print them).
- *   WEIGHTED_SUM (f32): sum of w * V over the region - "gaussian".  fp32 fma chain in
- *                 (dr, dc) row-major order.
+ *   WEIGHTED_SUM: sum of w * V over the region - "gaussian" - in (dr, dc) row-major order.
+ *                 F32: fp32 fma chain.  F64: fp64 fma chain (weights widened).  I32: 32-bit
+ *                 wrap-around arithmetic; the weights must be integers.  F64 / I32 run with
+ *                 the local-memory tile only, cells per work-item (1,1) or (2,2) / (2,4).
  *   LIFE (u8):    Conway B3/S23 on cells 0/1, region 1/1/1/1 - "gol".
  *   HEAT (f32):   u + alpha * (((n + s) + (e + w)) - 4u), region 1/1/1/1, every operation
  *                 rounded to fp32 in this order - "he".  scalars[0] = alpha.
@@ -91,7 +94,7 @@ void stencil_destroy(stencil_t *st);
 /* Selects the customising function (Section 2).  `weights` (host, copied) must hold
  * (north+south+1)*(east+west+1) floats for WEIGHTED_SUM / SINCOS and is ignored otherwise;
  * `scalars` (host, copied): HEAT takes alpha.  LIFE and HEAT require region 1/1/1/1;
- * LIFE requires dtype U8, the others F32. */
+ * LIFE requires dtype U8, HEAT and SINCOS F32, WEIGHTED_SUM F32, F64 or I32. */
 int stencil_set_kernel(stencil_t *st, int kernel_id, const float *weights, int n_weights,
                        const float *scalars, int n_scalars);
 

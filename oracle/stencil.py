@@ -45,10 +45,13 @@ def _load() -> ctypes.CDLL:
         p = ctypes.c_void_p
         lib.oracle_weighted_sum_f32.argtypes = [p, p, i64, i64, i32, i32, i32, i32, i32, f32, p, i32, i32]
         lib.oracle_sincos_f32.argtypes = [p, p, i64, i64, i32, i32, i32, i32, i32, f32, p, i32, i32]
+        lib.oracle_weighted_sum_f64.argtypes = [p, p, i64, i64, i32, i32, i32, i32, i32, f64, p, i32, i32]
+        lib.oracle_weighted_sum_i32.argtypes = [p, p, i64, i64, i32, i32, i32, i32, i32, i32, p, i32, i32]
         lib.oracle_life_u8.argtypes = [p, p, i64, i64, i32, i32, i32, i32, i32, ctypes.c_uint8, i32, i32]
         lib.oracle_heat_f32.argtypes = [p, p, i64, i64, i32, f32, f32, i32, i32]
         lib.oracle_heat_f64.argtypes = [p, p, i64, i64, i32, f64, f64, i32, i32]
-        for fn in (lib.oracle_weighted_sum_f32, lib.oracle_sincos_f32, lib.oracle_life_u8,
+        for fn in (lib.oracle_weighted_sum_f32, lib.oracle_sincos_f32, lib.oracle_weighted_sum_f64,
+                   lib.oracle_weighted_sum_i32, lib.oracle_life_u8,
                    lib.oracle_heat_f32, lib.oracle_heat_f64, lib.oracle_max_threads):
             fn.restype = i32
         _lib = lib
@@ -76,7 +79,7 @@ def apply(grid: np.ndarray, kernel: str, halo: Sequence[int], border: str, pad: 
           threads: int = 0, precision: str = "native") -> np.ndarray:
     """`iters` applications of the stencil (Section 2) to `grid`; returns the final grid.
 
-    kernel: "weighted_sum" (f32), "life" (u8, cells 0/1), "heat" (f32; scalars=(alpha,);
+    kernel: "weighted_sum" (f32; also f64 and i32, chosen by the grid's dtype), "life" (u8, cells 0/1), "heat" (f32; scalars=(alpha,);
     precision="f64" carries the state in float64 instead), "sincos" (f32).
     halo = (north, south, east, west).  threads=0 leaves OpenMP's default.
     """
@@ -86,7 +89,19 @@ def apply(grid: np.ndarray, kernel: str, halo: Sequence[int], border: str, pad: 
     rows, cols = grid.shape
     n, s, e, w = (int(h) for h in halo)
     b = _BORDER[border]
-    if kernel in ("weighted_sum", "sincos"):
+    if kernel == "weighted_sum" and grid.dtype in (np.float64, np.int32):
+        a = np.ascontiguousarray(grid)
+        wt = _check_weights(weights, (n, s, e, w))
+        out = np.empty_like(a)
+        if a.dtype == np.float64:
+            rc = lib.oracle_weighted_sum_f64(_ptr(a), _ptr(out), rows, cols, n, s, e, w, b, float(pad), _ptr(wt),
+                                             int(iters), int(threads))
+        else:
+            if np.any(wt != np.rint(wt)):
+                raise ValueError("an int32 matrix needs integer weights")
+            rc = lib.oracle_weighted_sum_i32(_ptr(a), _ptr(out), rows, cols, n, s, e, w, b, int(pad), _ptr(wt),
+                                             int(iters), int(threads))
+    elif kernel in ("weighted_sum", "sincos"):
         a = np.ascontiguousarray(grid, dtype=np.float32)
         wt = _check_weights(weights, (n, s, e, w))
         out = np.empty_like(a)

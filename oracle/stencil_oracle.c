@@ -81,6 +81,22 @@ static inline uint8_t V_u8(const uint8_t *a, int64_t rows, int64_t cols, int64_t
     return a[ri * cols + cj];
 }
 
+static inline double V_f64(const double *a, int64_t rows, int64_t cols, int64_t i, int64_t j,
+                           int border, double pad)
+{
+    int64_t ri = resolve(i, rows, border), cj = resolve(j, cols, border);
+    if (ri < 0 || cj < 0) return pad;
+    return a[ri * cols + cj];
+}
+
+static inline int32_t V_i32(const int32_t *a, int64_t rows, int64_t cols, int64_t i, int64_t j,
+                            int border, int32_t pad)
+{
+    int64_t ri = resolve(i, rows, border), cj = resolve(j, cols, border);
+    if (ri < 0 || cj < 0) return pad;
+    return a[ri * cols + cj];
+}
+
 /* ---- one application of each customising function --------------------------------- */
 
 /* Weighted sum (Gaussian blur and any linear stencil): fp64 accumulation over the fp32
@@ -98,6 +114,41 @@ static void step_weighted_sum(const float *in, float *out, int64_t rows, int64_t
                     acc += (double)w[(dr + N) * ww + (dc + W)] *
                            (double)V_f32(in, rows, cols, r + dr, c + dc, border, pad);
             out[r * cols + c] = (float)acc;
+        }
+}
+
+/* The weighted sum on the other element types of the paper's template (Section 3.3).
+ * double: accumulated in long double, rounded once.  int32: exact integer arithmetic reduced
+ * modulo 2^32 (the weights hold integers). */
+static void step_weighted_sum_f64(const double *in, double *out, int64_t rows, int64_t cols,
+                                  int N, int S, int E, int W, int border, double pad, const float *w)
+{
+    const int ww = E + W + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            long double acc = 0.0L;
+            for (int dr = -N; dr <= S; ++dr)
+                for (int dc = -W; dc <= E; ++dc)
+                    acc += (long double)w[(dr + N) * ww + (dc + W)] *
+                           (long double)V_f64(in, rows, cols, r + dr, c + dc, border, pad);
+            out[r * cols + c] = (double)acc;
+        }
+}
+
+static void step_weighted_sum_i32(const int32_t *in, int32_t *out, int64_t rows, int64_t cols,
+                                  int N, int S, int E, int W, int border, int32_t pad, const float *w)
+{
+    const int ww = E + W + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            uint64_t acc = 0;   /* two's complement, modulo 2^64 and in the end 2^32 */
+            for (int dr = -N; dr <= S; ++dr)
+                for (int dc = -W; dc <= E; ++dc)
+                    acc += (uint64_t)(int64_t)w[(dr + N) * ww + (dc + W)] *
+                           (uint64_t)(int64_t)V_i32(in, rows, cols, r + dr, c + dc, border, pad);
+            out[r * cols + c] = (int32_t)(uint32_t)acc;
         }
 }
 
@@ -203,6 +254,22 @@ int oracle_weighted_sum_f32(const float *in, float *out, int64_t rows, int64_t c
 {
     set_threads(threads);
     ITERATE(float, step_weighted_sum(src, dst, rows, cols, N, S, E, W, border, pad, w))
+}
+
+int oracle_weighted_sum_f64(const double *in, double *out, int64_t rows, int64_t cols,
+                            int N, int S, int E, int W, int border, double pad,
+                            const float *w, int iters, int threads)
+{
+    set_threads(threads);
+    ITERATE(double, step_weighted_sum_f64(src, dst, rows, cols, N, S, E, W, border, pad, w))
+}
+
+int oracle_weighted_sum_i32(const int32_t *in, int32_t *out, int64_t rows, int64_t cols,
+                            int N, int S, int E, int W, int border, int32_t pad,
+                            const float *w, int iters, int threads)
+{
+    set_threads(threads);
+    ITERATE(int32_t, step_weighted_sum_i32(src, dst, rows, cols, N, S, E, W, border, pad, w))
 }
 
 int oracle_life_u8(const uint8_t *in, uint8_t *out, int64_t rows, int64_t cols,

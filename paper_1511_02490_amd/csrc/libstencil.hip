@@ -71,11 +71,22 @@ struct stencil {
     float *d_weights = nullptr;
     bool weights_uploaded = false;
     std::vector<hipEvent_t> events;
-    size_t elem() const { return dtype == STENCIL_F32 ? 4 : 1; }
+    size_t elem() const { return dtype == STENCIL_U8 ? 1 : (dtype == STENCIL_F64 ? 8 : 4); }
     size_t bytes() const { return (size_t)rows * (size_t)cols * elem(); }
 };
 
+// Variant keys of WEIGHTED_SUM on the other element types (internal: the public kernel id is
+// STENCIL_WEIGHTED_SUM, the matrix dtype selects the variant).
+enum { STENCIL_WEIGHTED_SUM_F64 = 100, STENCIL_WEIGHTED_SUM_I32 = 101 };
+
 namespace {
+
+// the registry key of a scenario's kernel
+int variant_kernel(const stencil *s) {
+    if (s->kernel == STENCIL_WEIGHTED_SUM && s->dtype == STENCIL_F64) return STENCIL_WEIGHTED_SUM_F64;
+    if (s->kernel == STENCIL_WEIGHTED_SUM && s->dtype == STENCIL_I32) return STENCIL_WEIGHTED_SUM_I32;
+    return s->kernel;
+}
 
 struct TileGeom {
     int th, tw;        // elements covered by one workgroup
@@ -398,6 +409,11 @@ const std::vector<Variant> &registry() {
         reg_blockings<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloD, 4>(r);
         reg_blockings<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<1, 1, 1, 1>, 4>(r);
         reg_blockings<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<2, 2, 2, 2>, 4>(r);
+        // the other element types of the paper's template: run-time region, 1x1 and 2 x one vector
+        reg_borders<sk::OpWeightedSumF64, STENCIL_WEIGHTED_SUM_F64, sk::HaloD, 1, 1>(r);
+        reg_borders<sk::OpWeightedSumF64, STENCIL_WEIGHTED_SUM_F64, sk::HaloD, 2, 2>(r);
+        reg_borders<sk::OpWeightedSumI32, STENCIL_WEIGHTED_SUM_I32, sk::HaloD, 1, 1>(r);
+        reg_borders<sk::OpWeightedSumI32, STENCIL_WEIGHTED_SUM_I32, sk::HaloD, 2, 4>(r);
         reg_blockings<sk::OpSinCos, STENCIL_SINCOS, sk::HaloD, 4>(r);
         reg_blockings<sk::OpSinCos, STENCIL_SINCOS, sk::HaloC<1, 5, 3, 0>, 4>(r);
         reg_blockings<sk::OpHeat, STENCIL_HEAT, sk::HaloC<1, 1, 1, 1>, 4>(r);
@@ -430,7 +446,7 @@ const std::vector<Variant> &registry() {
 const Variant *find_variant(const stencil *s) {
     const Variant *dyn = nullptr;
     for (const Variant &v : registry()) {
-        if (v.kernel != s->kernel || v.border != s->border || v.cr != s->cr || v.cc != s->cc ||
+        if (v.kernel != variant_kernel(s) || v.border != s->border || v.cr != s->cr || v.cc != s->cc ||
             v.staging != s->staging)
             continue;
         if (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw) return &v;
@@ -441,7 +457,7 @@ const Variant *find_variant(const stencil *s) {
 
 bool mapping_supported(const stencil *s, int staging, int cr, int cc) {
     for (const Variant &v : registry())
-        if (v.kernel == s->kernel && v.border == s->border && v.staging == staging && v.cr == cr && v.cc == cc &&
+        if (v.kernel == variant_kernel(s) && v.border == s->border && v.staging == staging && v.cr == cr && v.cc == cc &&
             (v.hn < 0 || (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw)))
             return true;
     return false;
@@ -549,7 +565,7 @@ int stencil_create(stencil_t **out, int64_t rows, int64_t cols, int dtype, int h
                                           (long long)rows, (long long)cols);
     if (rows > INT32_MAX || cols > INT32_MAX || rows * cols > (int64_t)INT32_MAX)
         return fail(STENCIL_E_INVALID, "matrix too large: rows*cols must be < 2^31");
-    if (dtype != STENCIL_F32 && dtype != STENCIL_U8) return fail(STENCIL_E_INVALID, "unknown dtype %d", dtype);
+    if (dtype < STENCIL_F32 || dtype > STENCIL_F64) return fail(STENCIL_E_INVALID, "unknown dtype %d", dtype);
     const int h[4] = {halo_n, halo_s, halo_e, halo_w};
     for (int k = 0; k < 4; ++k)
         if (h[k] < 0 || h[k] > STENCIL_MAX_HALO)
@@ -563,7 +579,7 @@ int stencil_create(stencil_t **out, int64_t rows, int64_t cols, int dtype, int h
     s->dtype = dtype;
     s->hn = halo_n; s->hs = halo_s; s->he = halo_e; s->hw = halo_w;
     s->border = border_mode;
-    if (dtype == STENCIL_F32) {
+    if (dtype != STENCIL_U8) {
         s->kernel = STENCIL_WEIGHTED_SUM;
         s->weights.assign((size_t)(halo_n + halo_s + 1) * (halo_e + halo_w + 1), 0.0f);
     } else {
@@ -589,9 +605,14 @@ int stencil_set_kernel(stencil_t *s, int kernel_id, const float *weights, int n_
     switch (kernel_id) {
     case STENCIL_WEIGHTED_SUM:
     case STENCIL_SINCOS:
-        if (s->dtype != STENCIL_F32) return fail(STENCIL_E_INVALID, "this kernel needs an F32 matrix");
+        if (s->dtype == STENCIL_U8 || (kernel_id == STENCIL_SINCOS && s->dtype != STENCIL_F32))
+            return fail(STENCIL_E_INVALID, "this kernel is not available for the matrix's element type");
         if (!weights || n_weights != cells)
             return fail(STENCIL_E_INVALID, "weights must hold (N+S+1)*(E+W+1) = %d floats (got %d)", cells, n_weights);
+        if (s->dtype == STENCIL_I32)
+            for (int k = 0; k < cells; ++k)
+                if (weights[k] != std::rint(weights[k]) || std::fabs(weights[k]) > 16777216.0f)
+                    return fail(STENCIL_E_INVALID, "an I32 matrix needs integer weights (weights[%d] = %g)", k, weights[k]);
         s->weights.assign(weights, weights + cells);
         break;
     case STENCIL_LIFE:
@@ -622,7 +643,8 @@ int stencil_set_kernel(stencil_t *s, int kernel_id, const float *weights, int n_
 
 int stencil_set_border_value(stencil_t *s, double value) {
     if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
-    if (std::isnan(value) && s->dtype == STENCIL_U8) return fail(STENCIL_E_INVALID, "padding value is NaN");
+    if (s->dtype == STENCIL_I32 && !(value == std::floor(value) && std::fabs(value) <= 2147483647.0))
+        return fail(STENCIL_E_INVALID, "padding value of an I32 matrix must be an integer that fits");
     if (s->dtype == STENCIL_U8 && (value < 0 || value > 255 || value != std::floor(value)))
         return fail(STENCIL_E_INVALID, "padding value of a U8 matrix must be an integer in [0, 255]");
     s->pad = value;

@@ -72,6 +72,53 @@ struct OpWeightedSum {
     __device__ static __forceinline__ T finish(const State &s, float) { return s.acc; }
 };
 
+// ---- the same weighted sum on the paper's other element types (Section 3.3: integers, single
+// or double precision): double with an fp64 fma chain, int32 with wrap-around arithmetic
+// (the weight table must then hold integers).
+struct OpWeightedSumF64 {
+    static constexpr bool kRowFold = false;
+    using T = double;
+    using L = double;
+    using V = double;
+    static constexpr int kPlanes = 1;
+    static constexpr bool kWeights = true;
+    struct State { double acc; };
+    __device__ static __forceinline__ void stage(T v, L (&out)[1]) { out[0] = v; }
+    __device__ static __forceinline__ V combine(const L (&p)[1]) { return p[0]; }
+    template <int CC>
+    __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[1][CC]) {
+#pragma unroll
+        for (int k = 0; k < CC; ++k) out[0][k] = v[k];
+    }
+    __device__ static __forceinline__ void init(State &s) { s.acc = 0.0; }
+    __device__ static __forceinline__ void visit(State &s, int, int, float w, V v) {
+        s.acc = __fma_rn((double)w, v, s.acc);
+    }
+    __device__ static __forceinline__ T finish(const State &s, float) { return s.acc; }
+};
+
+struct OpWeightedSumI32 {
+    static constexpr bool kRowFold = false;
+    using T = int32_t;
+    using L = int32_t;
+    using V = int32_t;
+    static constexpr int kPlanes = 1;
+    static constexpr bool kWeights = true;
+    struct State { uint32_t acc; };
+    __device__ static __forceinline__ void stage(T v, L (&out)[1]) { out[0] = v; }
+    __device__ static __forceinline__ V combine(const L (&p)[1]) { return p[0]; }
+    template <int CC>
+    __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[1][CC]) {
+#pragma unroll
+        for (int k = 0; k < CC; ++k) out[0][k] = v[k];
+    }
+    __device__ static __forceinline__ void init(State &s) { s.acc = 0u; }
+    __device__ static __forceinline__ void visit(State &s, int, int, float w, V v) {
+        s.acc += (uint32_t)(int32_t)w * (uint32_t)v;      // modulo 2^32
+    }
+    __device__ static __forceinline__ T finish(const State &s, float) { return (T)s.acc; }
+};
+
 // ---- Conway's Game of Life, B3/S23 ("gol") -------------------------------------------------
 struct OpLife {
     static constexpr bool kRowFold = false;

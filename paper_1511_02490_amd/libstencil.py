@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "_lib", "libstencil.so")
 
 OK, E_INVALID, E_REFUSED, E_RESOURCES, E_HIP = 0, -1, -2, -3, -4
-F32, U8 = 0, 1
+F32, U8, I32, F64 = 0, 1, 2, 3
 CLAMP, WRAP, CONSTANT = 0, 1, 2
 WEIGHTED_SUM, LIFE, HEAT, SINCOS = 0, 1, 2, 3
 ENUM_POW2, ENUM_EVEN = 0, 1
@@ -24,7 +24,7 @@ OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF = 0, 1, 2
 _STAGINGS = {"local": STAGING_LOCAL, "direct": STAGING_DIRECT, "temporal": STAGING_TEMPORAL}
 N_FEATURES = 12
 
-_DTYPES = {"f32": F32, "u8": U8}
+_DTYPES = {"f32": F32, "u8": U8, "i32": I32, "f64": F64}
 _BORDERS = {"clamp": CLAMP, "wrap": WRAP, "constant": CONSTANT}
 _KERNELS = {"weighted_sum": WEIGHTED_SUM, "life": LIFE, "heat": HEAT, "sincos": SINCOS}
 
@@ -272,7 +272,8 @@ class Stencil:
 
     def _check_tensors(self, tin, tout):
         import torch
-        want = torch.float32 if self.dtype in ("f32", F32) else torch.uint8
+        want = {"f32": torch.float32, F32: torch.float32, "u8": torch.uint8, U8: torch.uint8,
+                "i32": torch.int32, I32: torch.int32, "f64": torch.float64, F64: torch.float64}[self.dtype]
         for t in (tin, tout):
             if not t.is_cuda or not t.is_contiguous() or t.dtype != want or t.numel() != self.rows * self.cols:
                 raise ValueError("tensors must be contiguous CUDA %s of %d x %d" % (want, self.rows, self.cols))

@@ -36,7 +36,7 @@ class Workload:
     name: str
     rows: int
     cols: int
-    dtype: str                      # "f32" or "u8"
+    dtype: str                      # "f32", "u8", "i32" or "f64"
     halo: Tuple[int, int, int, int]  # (north, south, east, west)
     border: str                     # "clamp" | "wrap" | "constant"
     pad: float                      # padding value for "constant"
@@ -55,7 +55,7 @@ class Workload:
     @property
     def bytes_per_cell_update(self) -> int:
         """One read and one write of a cell per application of the stencil."""
-        return 2 * (4 if self.dtype == "f32" else 1)
+        return 2 * {"f32": 4, "u8": 1, "i32": 4, "f64": 8}[self.dtype]
 
     def grid(self) -> np.ndarray:
         return make_grid(self)
@@ -119,6 +119,10 @@ def make_grid(w: "Workload") -> np.ndarray:
         return np.ascontiguousarray(u)
     if w.kernel == SINCOS:
         return np.ascontiguousarray(rng.random(shape, dtype=np.float32) * np.float32(2.0) - np.float32(1.0))
+    if w.dtype == "f64":
+        return np.ascontiguousarray(rng.random(shape, dtype=np.float64))
+    if w.dtype == "i32":
+        return np.ascontiguousarray(rng.integers(-1000, 1001, size=shape, dtype=np.int32))
     return np.ascontiguousarray(rng.random(shape, dtype=np.float32))
 
 

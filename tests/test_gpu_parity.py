@@ -50,7 +50,7 @@ def gpu_apply(ls, w, grid, wg, iters=None, blocking=(1, 1), offset=0):
     st = ls.Stencil.from_workload(w)
     set_mapping(st, blocking)
     n = grid.size
-    tdt = torch.float32 if w.dtype == "f32" else torch.uint8
+    tdt = {"f32": torch.float32, "u8": torch.uint8, "i32": torch.int32, "f64": torch.float64}[w.dtype]
     buf_in = torch.zeros(n + offset, dtype=tdt, device="cuda")
     buf_out = torch.full((n + offset,), 7, dtype=tdt, device="cuda")
     tin, tout = buf_in[offset:], buf_out[offset:]
@@ -68,8 +68,10 @@ def check(ls, w, wg, iters=None, blocking=(1, 1), offset=0, grid=None):
     it = w.iters if iters is None else iters
     ref = oracle.apply(g, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, it)
     got = gpu_apply(ls, w, g, wg, it, blocking, offset)
-    if w.dtype == "u8":
+    if w.dtype in ("u8", "i32"):
         np.testing.assert_array_equal(got, ref)
+    elif w.dtype == "f64":
+        assert rel_err(got, ref) <= 1e-13 * max(1, it)
     else:
         tol = REL_1 if it <= 1 else REL_N
         err = rel_err(got, ref)
@@ -180,6 +182,34 @@ def test_heat_conserves_total_and_long_run(ls):
     s0, s1 = g.astype(np.float64).sum(), got.astype(np.float64).sum()
     assert abs(s1 - s0) / s0 < 1e-6
     assert got.min() >= g.min() and got.max() <= g.max()
+
+
+# ---- the other element types of the paper's template (Section 3.3) ---------------------------
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_weighted_sum_on_double_and_int32_matrices(ls, border):
+    rng = np.random.default_rng(41)
+    for halo in [(1, 1, 1, 1), (2, 1, 2, 2), (0, 3, 4, 1)]:
+        n, s, e, w_ = halo
+        wf = rng.random((n + s + 1, e + w_ + 1), dtype=np.float32)
+        wd = wl.Workload("f64", 77, 90, "f64", halo, border, 0.5, wl.WEIGHTED_SUM, 2, 5, "pow2", weights=wf)
+        for blocking, wg in [((1, 1), (4, 16)), ((2, 2), (8, 32)), ((2, 2), (3, 5))]:
+            check(ls, wd, wg, blocking=blocking)
+        check(ls, wd, (4, 8), blocking=(2, 2), offset=1)
+        wi = rng.integers(-5, 6, size=wf.shape).astype(np.float32)
+        wi32 = wl.Workload("i32", 77, 90, "i32", halo, border, 3.0, wl.WEIGHTED_SUM, 3, 6, "pow2", weights=wi)
+        for blocking, wg in [((1, 1), (4, 16)), ((2, 4), (8, 32)), ((2, 4), (3, 5))]:
+            check(ls, wi32, wg, blocking=blocking)
+    # wrap-around arithmetic
+    big = np.full((40, 48), (1 << 20) + 1, np.int32)
+    wb = wl.Workload("i32", 40, 48, "i32", (1, 1, 1, 1), border, 0.0, wl.WEIGHTED_SUM, 1, 7, "pow2",
+                     weights=np.full((3, 3), float((1 << 20) + 1), np.float32))
+    check(ls, wb, (4, 16), blocking=(2, 4), grid=big)
+    st = ls.Stencil(8, 8, "i32")
+    with pytest.raises(ls.StencilError):
+        st.set_kernel("weighted_sum", np.full((3, 3), 0.5, np.float32))        # integer weights only
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(8, 8, "f64").set_kernel("sincos", np.zeros((3, 3), np.float32))
 
 
 # ---- temporal blocking: several applications per launch ------------------------------------

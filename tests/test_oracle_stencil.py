@@ -150,6 +150,42 @@ def test_weight_tables_of_the_workloads():
     assert abs(w5[0, 0] / w5[2, 2] - math.exp(-4.0)) < 1e-6
 
 
+def test_weighted_sum_on_double_and_int32_matrices():
+    """The other element types of the paper's template.  double: against torch's float64
+    correlation; int32: exact integers, reduced modulo 2^32 (checked with Python integers)."""
+    r = rng(31)
+    halo = (2, 1, 2, 2)
+    g = r.random((17, 21))
+    w = r.random((4, 5), dtype=np.float32)
+    for border in BORDERS:
+        out = oracle.apply(g, "weighted_sum", halo, border, 0.75, w)
+        assert out.dtype == np.float64
+        ref = _torch_correlate(g, w, halo, border, 0.75)
+        np.testing.assert_allclose(out, ref, rtol=1e-14, atol=1e-15)
+    # an impulse keeps all 53 bits: out = w * x exactly when w is a power of two
+    gi = np.zeros((5, 5)); gi[2, 2] = 1.0 / 3.0
+    oi = oracle.apply(gi, "weighted_sum", (1, 1, 1, 1), "constant", 0.0, np.full((3, 3), 0.25, np.float32))
+    assert oi[1, 1] == (1.0 / 3.0) * 0.25
+    gi32 = r.integers(-50, 51, size=(9, 11), dtype=np.int32)
+    wi = r.integers(-4, 5, size=(4, 5)).astype(np.float32)
+    for border in BORDERS:
+        out = oracle.apply(gi32, "weighted_sum", halo, border, 7, wi)
+        assert out.dtype == np.int32
+        ref = _torch_correlate(gi32.astype(np.float64), wi, halo, border, 7.0)
+        np.testing.assert_array_equal(out, np.rint(ref).astype(np.int32))
+    # wrap-around: 2^20 * 2^20 * 9 = 9 * 2^40 = 0 (mod 2^32); (2^20 + 1)^2 * 9 leaves 9 * (2^21 + 1)
+    big = np.full((3, 3), 1 << 20, np.int32)
+    wb = np.full((3, 3), float(1 << 20), np.float32)
+    assert oracle.apply(big, "weighted_sum", (1, 1, 1, 1), "wrap", 0, wb)[1, 1] == 0
+    big1 = np.full((3, 3), (1 << 20) + 1, np.int32)
+    wb1 = np.full((3, 3), float((1 << 20) + 1), np.float32)
+    want = (9 * ((1 << 20) + 1) ** 2) % (1 << 32)
+    want = want - (1 << 32) if want >= (1 << 31) else want
+    assert int(oracle.apply(big1, "weighted_sum", (1, 1, 1, 1), "wrap", 0, wb1)[1, 1]) == want
+    with pytest.raises(ValueError):
+        oracle.apply(gi32, "weighted_sum", halo, "clamp", 0, wi + 0.5)
+
+
 def test_iterations_compose():
     g = rng(9).random((12, 15), dtype=np.float32)
     w = wl.binomial3_weights()
