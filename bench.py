@@ -32,10 +32,12 @@ HBM_PEAK_GBS = 8000.0
 # (staging, cells_rows, cells_cols)
 # ... or ("temporal", cells_rows, 4, applications per launch) for the iterated heat workload
 MAPPINGS = {
-    "weighted_sum": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("direct", 1, 4), ("direct", 2, 4)],
+    "weighted_sum": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("direct", 1, 4), ("direct", 2, 4),
+                     ("direct", 4, 4)],
     "heat": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("direct", 1, 4), ("direct", 2, 4),
              ("temporal", 2, 4, 2), ("temporal", 4, 4, 2), ("temporal", 4, 4, 3), ("temporal", 2, 4, 4),
-             ("temporal", 4, 4, 4), ("temporal", 8, 4, 4)],
+             ("temporal", 4, 4, 4), ("temporal", 8, 4, 4),
+             ("stream", 16, 4, 4), ("stream", 32, 4, 4), ("stream", 64, 4, 4), ("stream", 32, 4, 2)],
     "sincos": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("local", 8, 4)],
     "life": [("local", 1, 1), ("local", 1, 16), ("local", 2, 16), ("direct", 1, 16), ("direct", 2, 16),
              ("temporal", 2, 16, 2), ("temporal", 4, 16, 2), ("temporal", 2, 16, 4), ("temporal", 4, 16, 4),
@@ -100,7 +102,7 @@ def sweep_burst(w):
 
 
 # the vectorised mapping each kernel is usually fastest with (predictor study)
-FAST_MAPPING = {"weighted_sum": ("direct", 2, 4), "heat": ("direct", 2, 4), "sincos": ("local", 2, 4),
+FAST_MAPPING = {"weighted_sum": ("local", 2, 4), "heat": ("direct", 2, 4), "sincos": ("local", 2, 4),
                 "life": ("direct", 2, 16)}
 
 
@@ -298,7 +300,7 @@ def main():
         kernel_ms = k_res.mean_ms[0] / launches
         achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
         label = "%s_kernel<%s> %dx%d cells/work-item, wg %dx%d" % (
-            {"local": "tile", "direct": "direct", "temporal": "temporal"}[mapping[0]], w.kernel, mapping[1],
+            {"local": "tile", "direct": "direct", "temporal": "temporal", "stream": "stream"}[mapping[0]], w.kernel, mapping[1],
             mapping[2], size[0], size[1]) + (", %d applications/launch" % depth if depth > 1 else "")
         return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(label),

@@ -121,9 +121,21 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            (w_c*cells_cols) elements.  (1,1) is the paper's one element per work-item.
  *            LOCAL: cells_rows in {1,2,4,8}, cells_cols in {1,4} (F32) or {1,16} (U8);
  *            DIRECT: cells_rows in {1,2,4}, cells_cols = 4 (F32) or 16 (U8).
+ *            STENCIL_STAGING_STREAM - temporal blocking in registers, no local memory: each
+ *            wavefront walks down a strip of 248 columns, cells_rows (16, 32, 64 or 128) rows
+ *            at a time, keeping the last three rows of every time level in registers and taking
+ *            row neighbours from adjacent lanes; STENCIL_OPT_TEMPORAL_DEPTH applications per
+ *            launch.  HEAT and WEIGHTED_SUM with region 1/1/1/1, WRAP and CONSTANT borders;
+ *            cells_cols = 4.  The workgroup only groups wavefronts: w_r*w_c must be a multiple
+ *            of 64 (other sizes are refused) and at most 256.
  * Output values never depend on the mapping.  Heavily blocked variants have a lower per-kernel
  * W_max (Section 3.1), see stencil_max_wg_size. */
-enum stencil_staging { STENCIL_STAGING_LOCAL = 0, STENCIL_STAGING_DIRECT = 1, STENCIL_STAGING_TEMPORAL = 2 };
+enum stencil_staging {
+    STENCIL_STAGING_LOCAL = 0,
+    STENCIL_STAGING_DIRECT = 1,
+    STENCIL_STAGING_TEMPORAL = 2,
+    STENCIL_STAGING_STREAM = 3
+};
 int stencil_set_mapping(stencil_t *st, int staging, int cells_rows, int cells_cols);
 int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int *cells_cols);
 

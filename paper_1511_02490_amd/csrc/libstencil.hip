@@ -15,6 +15,7 @@
 #include "../../include/libstencil.h"
 #include "host_tuning.h"
 #include "direct_kernel.h"
+#include "stream_kernel.h"
 #include "temporal_kernel.h"
 #include "tile_kernel.h"
 
@@ -42,7 +43,7 @@ int fail_hip(hipError_t e, const char *what) {
 using LaunchFn = hipError_t (*)(const stencil *, const void *, void *, int, int, int, hipStream_t);
 
 struct Variant {
-    int staging;          // STENCIL_STAGING_LOCAL, _DIRECT or _TEMPORAL
+    int staging;          // STENCIL_STAGING_LOCAL, _DIRECT, _TEMPORAL or _STREAM
     int kernel, border;
     int hn, hs, he, hw;   // -1: run-time border region
     int cr, cc;
@@ -108,6 +109,15 @@ TileGeom tile_geom(const stencil *s, const Variant &v, int wr, int wc) {
     if (v.staging == STENCIL_STAGING_DIRECT) {
         g.plane = 0;
         g.lds_bytes = 0;
+    } else if (v.staging == STENCIL_STAGING_STREAM) {
+        // one wavefront per tile: v.cr rows of a strip of 62 vectors; no local memory
+        g.th = v.cr;
+        g.tw = sk::kStreamCols;
+        g.pitch = 4;
+        g.plane = 0;
+        g.lds_bytes = 0;
+        g.tiles_r = (int)((s->rows + g.th - 1) / g.th);
+        g.tiles_c = (int)((s->cols + g.tw - 1) / g.tw);
     } else if (v.staging == STENCIL_STAGING_TEMPORAL) {
         // tile + `depth` rows above and below, one vector left and right; two buffers
         g.pitch = g.tw + 2 * v.cc;
@@ -196,6 +206,27 @@ hipError_t launch_temporal(const stencil *s, const void *in, void *out, int wr, 
                                      &raised_on);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((sk::temporal_kernel<Op, B, CR, MAXT>), dim3(blocks), dim3(wc, wr), lds, stream, a, depth);
+    return hipGetLastError();
+}
+
+template <class Op, int B, int CR>
+hipError_t launch_stream(const stencil *s, const void *in, void *out, int wr, int wc, int depth, hipStream_t stream) {
+    using Halo = sk::HaloC<1, 1, 1, 1>;
+    constexpr int kMaxT = 256;
+    unsigned blocks;
+    size_t lds;
+    auto a = make_args<Op, Halo, CR, 4>(s, STENCIL_STAGING_STREAM, in, out, wr, wc, &blocks, &lds);
+    a.xcd_chunk = 0;
+    const unsigned waves_per_block = (unsigned)(wr * wc) / 64u;
+    blocks = ((unsigned)a.n_tiles + waves_per_block - 1) / waves_per_block;
+    const dim3 grid(blocks), block(wc, wr);
+    switch (depth) {
+    case 1: hipLaunchKernelGGL((sk::stream_kernel<Op, B, 1, kMaxT>), grid, block, 0, stream, a, CR); break;
+    case 2: hipLaunchKernelGGL((sk::stream_kernel<Op, B, 2, kMaxT>), grid, block, 0, stream, a, CR); break;
+    case 3: hipLaunchKernelGGL((sk::stream_kernel<Op, B, 3, kMaxT>), grid, block, 0, stream, a, CR); break;
+    case 4: hipLaunchKernelGGL((sk::stream_kernel<Op, B, 4, kMaxT>), grid, block, 0, stream, a, CR); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
@@ -340,6 +371,33 @@ void reg_temporal(std::vector<Variant> &r) {
     reg_temporal_one<Op, KID, sk::kConstant, CR>(r);
 }
 
+template <class Op, int KID, int B, int CR>
+void reg_stream_one(std::vector<Variant> &r) {
+    Variant v;
+    v.staging = STENCIL_STAGING_STREAM;
+    v.kernel = KID;
+    v.border = B;
+    v.hn = v.hs = v.he = v.hw = 1;
+    v.cr = CR;
+    v.cc = 4;
+    v.max_threads = 256;
+    v.staged_bytes = 0;
+    v.launch = &launch_stream<Op, B, CR>;
+    r.push_back(v);
+}
+
+template <class Op, int KID>
+void reg_stream(std::vector<Variant> &r) {
+    reg_stream_one<Op, KID, sk::kWrap, 16>(r);
+    reg_stream_one<Op, KID, sk::kWrap, 32>(r);
+    reg_stream_one<Op, KID, sk::kWrap, 64>(r);
+    reg_stream_one<Op, KID, sk::kWrap, 128>(r);
+    reg_stream_one<Op, KID, sk::kConstant, 16>(r);
+    reg_stream_one<Op, KID, sk::kConstant, 32>(r);
+    reg_stream_one<Op, KID, sk::kConstant, 64>(r);
+    reg_stream_one<Op, KID, sk::kConstant, 128>(r);
+}
+
 template <int B, int CR>
 void reg_life_temporal_one(std::vector<Variant> &r) {
     Variant v;
@@ -429,6 +487,8 @@ const std::vector<Variant> &registry() {
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 2>(r);
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 4>(r);
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 8>(r);
+        reg_stream<sk::OpHeat, STENCIL_HEAT>(r);
+        reg_stream<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM>(r);
         reg_life_temporal<1>(r);
         reg_life_temporal<2>(r);
         reg_life_temporal<4>(r);
@@ -470,6 +530,9 @@ int check_legal(const stencil *s, const Variant *v, int wr, int wc) {
     if ((int64_t)wr * wc > v->max_threads)
         return fail(STENCIL_E_REFUSED, "workgroup size %dx%d exceeds W_max = %d work-items", wr, wc,
                     v->max_threads);
+    if (v->staging == STENCIL_STAGING_STREAM && (wr * wc) % 64 != 0)
+        return fail(STENCIL_E_REFUSED, "workgroup size %dx%d refused: this mapping gives each wavefront a strip, the "
+                                       "workgroup must be whole wavefronts of 64 work-items", wr, wc);
     const TileGeom g = tile_geom(s, *v, wr, wc);
     if (g.lds_bytes > STENCIL_LOCAL_MEM_BYTES)
         return fail(STENCIL_E_REFUSED, "workgroup size %dx%d refused: tile needs %lld bytes of local memory (limit %d)",
@@ -511,7 +574,9 @@ int run_checked(stencil *s, const Variant *v, const void *in, void *out, int ite
     }
     // `per` applications per launch; the launches alternate between `out` and the scratch
     // matrix so that the last one lands in `out`
-    const int per = v->staging == STENCIL_STAGING_TEMPORAL ? s->temporal_depth : 1;
+    const int per = (v->staging == STENCIL_STAGING_TEMPORAL || v->staging == STENCIL_STAGING_STREAM)
+                        ? s->temporal_depth
+                        : 1;
     const int launches = (iters + per - 1) / per;
     const void *src = in;
     void *dst = (launches % 2 == 1) ? out : s->scratch;

@@ -19,9 +19,10 @@ F32, U8, I32, F64 = 0, 1, 2, 3
 CLAMP, WRAP, CONSTANT = 0, 1, 2
 WEIGHTED_SUM, LIFE, HEAT, SINCOS = 0, 1, 2, 3
 ENUM_POW2, ENUM_EVEN = 0, 1
-STAGING_LOCAL, STAGING_DIRECT, STAGING_TEMPORAL = 0, 1, 2
+STAGING_LOCAL, STAGING_DIRECT, STAGING_TEMPORAL, STAGING_STREAM = 0, 1, 2, 3
 OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF = 0, 1, 2
-_STAGINGS = {"local": STAGING_LOCAL, "direct": STAGING_DIRECT, "temporal": STAGING_TEMPORAL}
+_STAGINGS = {"local": STAGING_LOCAL, "direct": STAGING_DIRECT, "temporal": STAGING_TEMPORAL,
+             "stream": STAGING_STREAM}
 N_FEATURES = 12
 
 _DTYPES = {"f32": F32, "u8": U8, "i32": I32, "f64": F64}

@@ -255,6 +255,30 @@ def test_temporal_blocking_life_bit_exact(ls, border):
         check(ls, wt, (2, 4), blocking=("temporal", 2, 16, 4))
 
 
+@pytest.mark.parametrize("border", ["wrap", "constant"])
+def test_register_streaming_temporal_kernel_bit_exact(ls, border):
+    """Time levels kept in registers, row neighbours from adjacent lanes; every wavefront owns a
+    strip of 248 columns: matrices wider than one strip, ragged ones, and ones smaller than a strip."""
+    for rows, cols, iters in [(70, 600, 9), (37, 250, 5), (130, 83, 6), (64, 256, 8), (5, 3, 7), (1, 1, 4)]:
+        w = wl.config(3, rows=rows, cols=cols, iters=iters)
+        w.border, w.pad = border, 50.0
+        for depth in (1, 2, 3, 4):
+            for h, wg in [(16, (1, 64)), (32, (2, 64)), (64, (4, 64)), (128, (8, 8)), (16, (2, 32))]:
+                check(ls, w, wg, blocking=("stream", h, 4, depth))
+    w = custom(wl.WEIGHTED_SUM, 90, 300, (1, 1, 1, 1), border, pad=0.4, seed=22, iters=7)
+    check(ls, w, (1, 64), blocking=("stream", 32, 4, 4))
+    check(ls, w, (2, 64), blocking=("stream", 16, 4, 3), offset=1)          # unaligned rows: element loads
+    st = ls.Stencil.from_workload(wl.config(3, rows=64, cols=64))
+    st.set_mapping("stream", 32, 4)
+    assert st.max_wg_size() == 256 and st.tile_bytes(1, 64) == 0
+    assert st.is_legal(1, 64) and st.is_legal(4, 64) and st.is_legal(16, 8)
+    assert not st.is_legal(4, 4) and not st.is_legal(1, 96) and not st.is_legal(8, 64)   # whole wavefronts, <= 256
+    clamp = wl.config(3, rows=64, cols=64)
+    clamp.border = "clamp"
+    with pytest.raises(ls.StencilError):
+        ls.Stencil.from_workload(clamp).set_mapping("stream", 32, 4)
+
+
 def test_temporal_blocking_not_offered_for_other_regions(ls):
     st = ls.Stencil.from_workload(wl.config(1))                    # 5x5 region
     with pytest.raises(ls.StencilError):
@@ -513,6 +537,8 @@ def test_c4_full_size(ls):
     got = gpu_apply(ls, w, g, (4, 64), iters=100, blocking=("temporal", 4, 4, 4))
     np.testing.assert_array_equal(got, ref)
     got = gpu_apply(ls, w, g, (16, 16), iters=100, blocking=("temporal", 2, 4, 4))
+    np.testing.assert_array_equal(got, ref)
+    got = gpu_apply(ls, w, g, (2, 64), iters=100, blocking=("stream", 32, 4, 4))
     np.testing.assert_array_equal(got, ref)
     c = gpu_apply(ls, w, g, (8, 32), iters=1000, blocking=("temporal", 2, 4, 3))
     a = gpu_apply(ls, w, g, (4, 64), iters=1000, blocking=("direct", 1, 4))
