@@ -38,7 +38,8 @@ MAPPINGS = {
              ("temporal", 2, 4, 2), ("temporal", 4, 4, 2), ("temporal", 4, 4, 3), ("temporal", 2, 4, 4),
              ("temporal", 4, 4, 4), ("temporal", 8, 4, 4),
              ("stream", 16, 4, 4), ("stream", 32, 4, 4), ("stream", 64, 4, 4), ("stream", 32, 4, 2)],
-    "sincos": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("local", 8, 4)],
+    "sincos": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("local", 8, 4),
+               ("stream", 64, 4), ("stream", 89, 4), ("stream", 134, 4)],
     "life": [("local", 1, 1), ("local", 1, 16), ("local", 2, 16), ("direct", 1, 16), ("direct", 2, 16),
              ("temporal", 2, 16, 2), ("temporal", 4, 16, 2), ("temporal", 2, 16, 4), ("temporal", 4, 16, 4),
              ("temporal", 8, 16, 4)],
@@ -299,9 +300,12 @@ def main():
         launches = -(-burst // depth)
         kernel_ms = k_res.mean_ms[0] / launches
         achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+        family = {"local": "tile", "direct": "direct", "temporal": "temporal", "stream": "stream"}[mapping[0]]
+        if mapping[0] == "stream" and len(mapping) == 3:
+            family = "march"            # register streaming, one application per launch
         label = "%s_kernel<%s> %dx%d cells/work-item, wg %dx%d" % (
-            {"local": "tile", "direct": "direct", "temporal": "temporal", "stream": "stream"}[mapping[0]], w.kernel, mapping[1],
-            mapping[2], size[0], size[1]) + (", %d applications/launch" % depth if depth > 1 else "")
+            family, w.kernel, mapping[1], mapping[2], size[0], size[1]) + (
+            ", %d applications/launch" % depth if depth > 1 else "")
         return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(label),
                 "kernel": label, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg_bytes,

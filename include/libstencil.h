@@ -121,13 +121,18 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            (w_c*cells_cols) elements.  (1,1) is the paper's one element per work-item.
  *            LOCAL: cells_rows in {1,2,4,8}, cells_cols in {1,4} (F32) or {1,16} (U8);
  *            DIRECT: cells_rows in {1,2,4}, cells_cols = 4 (F32) or 16 (U8).
- *            STENCIL_STAGING_STREAM - temporal blocking in registers, no local memory: each
- *            wavefront walks down a strip of 248 columns, cells_rows (16, 32, 64 or 128) rows
- *            at a time, keeping the last three rows of every time level in registers and taking
- *            row neighbours from adjacent lanes; STENCIL_OPT_TEMPORAL_DEPTH applications per
- *            launch.  HEAT and WEIGHTED_SUM with region 1/1/1/1, WRAP and CONSTANT borders;
- *            cells_cols = 4.  The workgroup only groups wavefronts: w_r*w_c must be a multiple
- *            of 64 (other sizes are refused) and at most 256.
+ *            STENCIL_STAGING_STREAM - register streaming, no local memory: each wavefront walks
+ *            down a strip of 62 to 64 four-cell vectors (one lane at each side that has a border
+ *            region only feeds its neighbours), cells_rows (1..4096) rows at a time, taking row
+ *            neighbours from adjacent lanes; cells_cols = 4.  Two kernels:
+ *            HEAT and WEIGHTED_SUM with region 1/1/1/1, WRAP and CONSTANT borders: temporal
+ *            blocking, the last three rows of every time level stay in registers,
+ *            STENCIL_OPT_TEMPORAL_DEPTH applications per launch;
+ *            SINCOS with region N1 S5 E3 W0 and WEIGHTED_SUM with region 2/2/2/2, any border
+ *            mode: one application per launch, each input row is loaded and pre-processed once
+ *            and folded into the N+S+1 output rows it belongs to.
+ *            The workgroup only groups wavefronts: w_r*w_c must be a multiple of 64 (other
+ *            sizes are refused) and at most 256.
  * Output values never depend on the mapping.  Heavily blocked variants have a lower per-kernel
  * W_max (Section 3.1), see stencil_max_wg_size. */
 enum stencil_staging {

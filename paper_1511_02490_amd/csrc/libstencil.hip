@@ -18,6 +18,7 @@
 #include "stream_kernel.h"
 #include "temporal_kernel.h"
 #include "tile_kernel.h"
+#include "march_kernel.h"
 
 namespace {
 
@@ -46,11 +47,14 @@ struct Variant {
     int staging;          // STENCIL_STAGING_LOCAL, _DIRECT, _TEMPORAL or _STREAM
     int kernel, border;
     int hn, hs, he, hw;   // -1: run-time border region
-    int cr, cc;
+    int cr, cc;           // cr = 0 (register-streaming kernels): any segment height up to kMaxSegmentRows
     int max_threads;      // per-kernel workgroup-size limit (Section 3.1)
     int staged_bytes;     // bytes per staged element in LDS
+    bool fuses = false;   // a launch makes `temporal_depth` applications instead of one
     LaunchFn launch;
 };
+constexpr int kMaxSegmentRows = 4096;
+inline bool rows_match(const Variant &v, int cr) { return v.cr == cr || (v.cr == 0 && cr >= 1 && cr <= kMaxSegmentRows); }
 
 struct stencil {
     int64_t rows = 0, cols = 0;
@@ -110,9 +114,9 @@ TileGeom tile_geom(const stencil *s, const Variant &v, int wr, int wc) {
         g.plane = 0;
         g.lds_bytes = 0;
     } else if (v.staging == STENCIL_STAGING_STREAM) {
-        // one wavefront per tile: v.cr rows of a strip of 62 vectors; no local memory
-        g.th = v.cr;
-        g.tw = sk::kStreamCols;
+        // one wavefront per tile: s->cr rows of a strip of 62..64 vectors; no local memory
+        g.th = s->cr;
+        g.tw = sk::march_vectors(s->hw, s->he) * 4;
         g.pitch = 4;
         g.plane = 0;
         g.lds_bytes = 0;
@@ -209,13 +213,15 @@ hipError_t launch_temporal(const stencil *s, const void *in, void *out, int wr, 
     return hipGetLastError();
 }
 
-template <class Op, int B, int CR>
+template <class Op, int B>
 hipError_t launch_stream(const stencil *s, const void *in, void *out, int wr, int wc, int depth, hipStream_t stream) {
     using Halo = sk::HaloC<1, 1, 1, 1>;
     constexpr int kMaxT = 256;
+    static_assert(sk::march_vectors(1, 1) * 4 == sk::kStreamCols, "strip width the geometry assumes");
+    const int CR = s->cr;   // rows per segment
     unsigned blocks;
     size_t lds;
-    auto a = make_args<Op, Halo, CR, 4>(s, STENCIL_STAGING_STREAM, in, out, wr, wc, &blocks, &lds);
+    auto a = make_args<Op, Halo, 0, 4>(s, STENCIL_STAGING_STREAM, in, out, wr, wc, &blocks, &lds);
     a.xcd_chunk = 0;
     const unsigned waves_per_block = (unsigned)(wr * wc) / 64u;
     blocks = ((unsigned)a.n_tiles + waves_per_block - 1) / waves_per_block;
@@ -227,6 +233,31 @@ hipError_t launch_stream(const stencil *s, const void *in, void *out, int wr, in
     case 4: hipLaunchKernelGGL((sk::stream_kernel<Op, B, 4, kMaxT>), grid, block, 0, stream, a, CR); break;
     default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+// One application, marched down the matrix in registers (march_kernel.h).
+template <class Op, int B, class Halo>
+hipError_t launch_march(const stencil *s, const void *in, void *out, int wr, int wc, int, hipStream_t stream) {
+    constexpr int kMaxT = 256;
+    unsigned blocks;
+    size_t lds;
+    auto a = make_args<Op, Halo, 0, 4>(s, STENCIL_STAGING_STREAM, in, out, wr, wc, &blocks, &lds);
+    // a tile is a wavefront's segment; workgroups only group wavefronts
+    const unsigned waves_per_block = (unsigned)(wr * wc) / 64u;
+    blocks = ((unsigned)a.n_tiles + waves_per_block - 1) / waves_per_block;
+    a.xcd_chunk = 0;
+    if (s->xcd_remap && blocks >= 64) {
+        a.xcd_chunk = (int)((blocks + 7) / 8);
+        blocks = (unsigned)a.xcd_chunk * 8u;
+    }
+    // whole aligned vectors per row, or the element-by-element body
+    if (a.vec_ok)
+        hipLaunchKernelGGL((sk::march_kernel<Op, B, Halo, true, kMaxT>), dim3(blocks), dim3(wc, wr), 0, stream, a,
+                           s->cr);
+    else
+        hipLaunchKernelGGL((sk::march_kernel<Op, B, Halo, false, kMaxT>), dim3(blocks), dim3(wc, wr), 0, stream, a,
+                           s->cr);
     return hipGetLastError();
 }
 
@@ -360,6 +391,7 @@ void reg_temporal_one(std::vector<Variant> &r) {
     v.cc = 4;
     v.max_threads = STENCIL_MAX_WG_SIZE;
     v.staged_bytes = 4;
+    v.fuses = true;
     v.launch = &launch_temporal<Op, B, CR, STENCIL_MAX_WG_SIZE>;
     r.push_back(v);
 }
@@ -371,31 +403,52 @@ void reg_temporal(std::vector<Variant> &r) {
     reg_temporal_one<Op, KID, sk::kConstant, CR>(r);
 }
 
-template <class Op, int KID, int B, int CR>
+template <class Op, int KID, int B>
 void reg_stream_one(std::vector<Variant> &r) {
     Variant v;
     v.staging = STENCIL_STAGING_STREAM;
     v.kernel = KID;
     v.border = B;
     v.hn = v.hs = v.he = v.hw = 1;
-    v.cr = CR;
+    v.cr = 0;
     v.cc = 4;
     v.max_threads = 256;
     v.staged_bytes = 0;
-    v.launch = &launch_stream<Op, B, CR>;
+    v.fuses = true;
+    v.launch = &launch_stream<Op, B>;
     r.push_back(v);
 }
 
 template <class Op, int KID>
 void reg_stream(std::vector<Variant> &r) {
-    reg_stream_one<Op, KID, sk::kWrap, 16>(r);
-    reg_stream_one<Op, KID, sk::kWrap, 32>(r);
-    reg_stream_one<Op, KID, sk::kWrap, 64>(r);
-    reg_stream_one<Op, KID, sk::kWrap, 128>(r);
-    reg_stream_one<Op, KID, sk::kConstant, 16>(r);
-    reg_stream_one<Op, KID, sk::kConstant, 32>(r);
-    reg_stream_one<Op, KID, sk::kConstant, 64>(r);
-    reg_stream_one<Op, KID, sk::kConstant, 128>(r);
+    reg_stream_one<Op, KID, sk::kWrap>(r);
+    reg_stream_one<Op, KID, sk::kConstant>(r);
+}
+
+template <class Op, int KID, int B, class Halo>
+void reg_march_one(std::vector<Variant> &r) {
+    Variant v;
+    v.staging = STENCIL_STAGING_STREAM;
+    v.kernel = KID;
+    v.border = B;
+    v.hn = Halo::N;
+    v.hs = Halo::S;
+    v.he = Halo::E;
+    v.hw = Halo::W;
+    v.cr = 0;
+    v.cc = 4;
+    v.max_threads = 256;
+    v.staged_bytes = 0;
+    v.fuses = false;
+    v.launch = &launch_march<Op, B, Halo>;
+    r.push_back(v);
+}
+
+template <class Op, int KID, class Halo>
+void reg_march(std::vector<Variant> &r) {
+    reg_march_one<Op, KID, sk::kClamp, Halo>(r);
+    reg_march_one<Op, KID, sk::kWrap, Halo>(r);
+    reg_march_one<Op, KID, sk::kConstant, Halo>(r);
 }
 
 template <int B, int CR>
@@ -409,6 +462,7 @@ void reg_life_temporal_one(std::vector<Variant> &r) {
     v.cc = 16;
     v.max_threads = STENCIL_MAX_WG_SIZE;
     v.staged_bytes = 1;
+    v.fuses = true;
     v.launch = &launch_life_temporal<B, CR, STENCIL_MAX_WG_SIZE>;
     r.push_back(v);
 }
@@ -489,6 +543,8 @@ const std::vector<Variant> &registry() {
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 8>(r);
         reg_stream<sk::OpHeat, STENCIL_HEAT>(r);
         reg_stream<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM>(r);
+        reg_march<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<2, 2, 2, 2>>(r);
+        reg_march<sk::OpSinCos, STENCIL_SINCOS, sk::HaloC<1, 5, 3, 0>>(r);
         reg_life_temporal<1>(r);
         reg_life_temporal<2>(r);
         reg_life_temporal<4>(r);
@@ -506,7 +562,7 @@ const std::vector<Variant> &registry() {
 const Variant *find_variant(const stencil *s) {
     const Variant *dyn = nullptr;
     for (const Variant &v : registry()) {
-        if (v.kernel != variant_kernel(s) || v.border != s->border || v.cr != s->cr || v.cc != s->cc ||
+        if (v.kernel != variant_kernel(s) || v.border != s->border || !rows_match(v, s->cr) || v.cc != s->cc ||
             v.staging != s->staging)
             continue;
         if (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw) return &v;
@@ -517,7 +573,7 @@ const Variant *find_variant(const stencil *s) {
 
 bool mapping_supported(const stencil *s, int staging, int cr, int cc) {
     for (const Variant &v : registry())
-        if (v.kernel == variant_kernel(s) && v.border == s->border && v.staging == staging && v.cr == cr && v.cc == cc &&
+        if (v.kernel == variant_kernel(s) && v.border == s->border && v.staging == staging && rows_match(v, cr) && v.cc == cc &&
             (v.hn < 0 || (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw)))
             return true;
     return false;
@@ -574,9 +630,7 @@ int run_checked(stencil *s, const Variant *v, const void *in, void *out, int ite
     }
     // `per` applications per launch; the launches alternate between `out` and the scratch
     // matrix so that the last one lands in `out`
-    const int per = (v->staging == STENCIL_STAGING_TEMPORAL || v->staging == STENCIL_STAGING_STREAM)
-                        ? s->temporal_depth
-                        : 1;
+    const int per = v->fuses ? s->temporal_depth : 1;
     const int launches = (iters + per - 1) / per;
     const void *src = in;
     void *dst = (launches % 2 == 1) ? out : s->scratch;

@@ -184,7 +184,7 @@ struct OpHeat {
 // summed pairwise from the west end ((c0 + c1) + (c2 + c3) + ...), so that neighbouring
 // cells of one work-item share their pair sums, and the row sums are added north to south.
 
-// sin and cos of x in fp32, absolute error below 2e-7 for |x| <= 2^16: x / (2 pi) is formed
+// sin and cos of x in fp32 for |x| <= 2^16, absolute error below 2e-7: x / (2 pi) is formed
 // as a two-term product (1 / (2 pi) split into an fp32 head and tail, fma for the exact
 // partial products), its integer part is dropped, and the hardware sine / cosine (which take
 // their argument in turns) finish the job.
@@ -196,6 +196,14 @@ __device__ __forceinline__ void sincos_small_f32(float x, float &sn_out, float &
     sn_out = __builtin_amdgcn_sinf(turns);
     cs_out = __builtin_amdgcn_cosf(turns);
 }
+// ... and for |x| <= 2, where one rounded product is already that accurate (the angle is off by
+// at most |x| * 1e-7) and less than half a turn, so nothing has to be dropped.
+__device__ __forceinline__ void sincos_tiny_f32(float x, float &sn_out, float &cs_out) {
+    const float turns = __fmul_rn(x, 0.15915493667125702f);
+    sn_out = __builtin_amdgcn_sinf(turns);
+    cs_out = __builtin_amdgcn_cosf(turns);
+}
+constexpr float kSinCosTinyLimit = 2.0f;
 constexpr float kSinCosSmallLimit = 65536.0f;   // beyond this (or NaN) the library routine is used
 
 struct OpSinCos {
@@ -206,25 +214,43 @@ struct OpSinCos {
     static constexpr bool kWeights = true;
     static constexpr bool kRowFold = true;
     struct State { float s, c; };
+    // which routine serves an element depends on that element alone, so every mapping computes
+    // the same bits for it
     __device__ static __forceinline__ void stage(T v, L (&out)[2]) {
-        if (__builtin_expect(fabsf(v) <= kSinCosSmallLimit, 1))
+        const float m = fabsf(v);
+        if (__builtin_expect(m <= kSinCosTinyLimit, 1))
+            sincos_tiny_f32(v, out[0], out[1]);
+        else if (m <= kSinCosSmallLimit)
             sincos_small_f32(v, out[0], out[1]);
         else
             sincosf(v, &out[0], &out[1]);
     }
-    // CC cells at once: one range test for all of them
+    // CC cells at once: one test of the largest magnitude serves all of them.  (A NaN does not
+    // raise the maximum; the short routine turns it into NaN like the others would.  Inf does.)
     template <int CC>
     __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[2][CC]) {
-        // sum of magnitudes <= limit implies each is; NaN or Inf anywhere makes the test fail
         float mag = fabsf(v[0]);
 #pragma unroll
-        for (int k = 1; k < CC; ++k) mag = __fadd_rn(mag, fabsf(v[k]));
-        if (__builtin_expect(mag <= kSinCosSmallLimit, 1)) {
+        for (int k = 1; k < CC; ++k) mag = fmaxf(mag, fabsf(v[k]));
+        if (__builtin_expect(mag <= kSinCosTinyLimit, 1)) {
 #pragma unroll
-            for (int k = 0; k < CC; ++k) sincos_small_f32(v[k], out[0][k], out[1][k]);
+            for (int k = 0; k < CC; ++k) sincos_tiny_f32(v[k], out[0][k], out[1][k]);
         } else {
-#pragma unroll
-            for (int k = 0; k < CC; ++k) sincosf(v[k], &out[0][k], &out[1][k]);
+            // rare: one element per trip of a rolled loop, so that the long routines appear once;
+            // inputs and results rotate through scalars (no indexed array, nothing leaves registers)
+            static_assert(CC == 4, "four-cell vectors");
+            T x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3];
+            L s0 = 0, s1 = 0, s2 = 0, s3 = 0, c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll 1
+            for (int k = 0; k < CC; ++k) {
+                L one[2];
+                stage(x0, one);
+                x0 = x1, x1 = x2, x2 = x3;
+                s0 = s1, s1 = s2, s2 = s3, s3 = one[0];
+                c0 = c1, c1 = c2, c2 = c3, c3 = one[1];
+            }
+            out[0][0] = s0, out[0][1] = s1, out[0][2] = s2, out[0][3] = s3;
+            out[1][0] = c0, out[1][1] = c1, out[1][2] = c2, out[1][3] = c3;
         }
     }
     __device__ static __forceinline__ V combine(const L (&p)[2]) { return make_float2(p[0], p[1]); }

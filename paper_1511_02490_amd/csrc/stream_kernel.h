@@ -35,8 +35,9 @@ __global__ __launch_bounds__(MAXT) void stream_kernel(const TileArgs<Op, HaloC<1
     const int tid = (int)threadIdx.y * (int)blockDim.x + (int)threadIdx.x;
     const int lane = tid & 63;
     const int waves_per_block = ((int)blockDim.x * (int)blockDim.y) >> 6;
-    const int wave = (int)blockIdx.x * waves_per_block + (tid >> 6);
-    if (wave >= a.n_tiles) return;                  // whole wavefronts leave together
+    // a wavefront's index is the same in all its lanes: keep it, and all that follows from it, scalar
+    const int wave = __builtin_amdgcn_readfirstlane((int)blockIdx.x * waves_per_block + (tid >> 6));
+    if (wave >= a.n_tiles) return;
     const int seg = wave / a.tiles_c, strip = wave - seg * a.tiles_c;
     const int rows = a.rows, cols = a.cols;
     const int r0 = seg * H;

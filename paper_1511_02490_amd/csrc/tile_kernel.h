@@ -70,12 +70,13 @@ __device__ __forceinline__ void store_vec(E *dst, const E (&src)[CNT]) {
 }
 
 // Cross-lane moves inside a wavefront: the value the lane one below / one above holds.
-// (Lane 0 has no lane below and lane 63 none above; they get 0 and must look elsewhere.)
+// (Lane 0 has no lane below and lane 63 none above; they get 0 - the move's bound control -
+// and must look elsewhere.)
 __device__ __forceinline__ uint32_t from_lane_below(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xf, 0xf, true);
 }
 __device__ __forceinline__ uint32_t from_lane_above(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xf, 0xf, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x130 /* wave_shl:1 */, 0xf, 0xf, true);
 }
 
 // Columns staged left / right of the tile: the border region's extent, widened to whole

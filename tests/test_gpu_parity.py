@@ -279,6 +279,42 @@ def test_register_streaming_temporal_kernel_bit_exact(ls, border):
         ls.Stencil.from_workload(clamp).set_mapping("stream", 32, 4)
 
 
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_register_marching_single_application_kernels(ls, border):
+    """One application marched down the matrix in registers (sin/cos stencil N1 S5 E3 W0 and the
+    5x5 weighted sum): matrices wider than one strip (252 / 248 columns), ragged ones, ones smaller
+    than a strip or than the region, unaligned rows, segment heights that do and do not divide
+    the rows, and the output bits of the local-memory mapping."""
+    shapes = [(70, 600), (37, 252), (41, 256), (130, 83), (64, 1024), (5, 3), (1, 1), (9, 508)]
+    for kernel, halo in [(wl.SINCOS, (1, 5, 3, 0)), (wl.WEIGHTED_SUM, (2, 2, 2, 2))]:
+        for rows, cols in shapes:
+            w = custom(kernel, rows, cols, halo, border, pad=0.3, seed=rows + cols)
+            ref = None
+            for h, wg in [(64, (1, 64)), (8, (2, 64)), (1, (4, 64)), (29, (8, 8)), (4096, (2, 32))]:
+                got = check(ls, w, wg, blocking=("stream", h, 4))
+                if ref is None:
+                    ref = gpu_apply(ls, w, w.grid(), (8, 8), blocking=(2, 4))
+                np.testing.assert_array_equal(got, ref)
+        w = custom(kernel, 50, 300, halo, border, pad=0.3, seed=77)
+        check(ls, w, (1, 64), blocking=("stream", 16, 4), offset=1)            # unaligned rows: element loads
+        big = w.grid() * np.float32(300.0)                                       # beyond the small-argument range
+        big[3, 5], big[20, 299] = 1.0e6, -3.0e7
+        # sums of sines and cosines of large arguments pass near zero: absolute error here
+        ref = oracle.apply(big, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1)
+        got = gpu_apply(ls, w, big, (2, 64), blocking=("stream", 16, 4))
+        scale = 1.0 if kernel == wl.SINCOS else float(np.abs(big).max())
+        assert np.max(np.abs(got.astype(np.float64) - ref)) <= 2e-5 * scale
+        np.testing.assert_array_equal(got, gpu_apply(ls, w, big, (8, 8), blocking=(2, 4)))
+    st = ls.Stencil.from_workload(wl.config(4, rows=64, cols=64))
+    st.set_mapping("stream", 64, 4)
+    assert st.max_wg_size() == 256 and st.tile_bytes(1, 64) == 0
+    assert st.is_legal(1, 64) and st.is_legal(16, 16) and not st.is_legal(4, 4) and not st.is_legal(8, 64)
+    with pytest.raises(ls.StencilError):
+        st.set_mapping("stream", 5000, 4)                                        # segment height limit
+    with pytest.raises(ls.StencilError):
+        ls.Stencil.from_workload(custom(wl.SINCOS, 32, 32, (2, 0, 1, 3), border)).set_mapping("stream", 16, 4)
+
+
 def test_temporal_blocking_not_offered_for_other_regions(ls):
     st = ls.Stencil.from_workload(wl.config(1))                    # 5x5 region
     with pytest.raises(ls.StencilError):
