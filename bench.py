@@ -37,7 +37,8 @@ MAPPINGS = {
     "heat": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("direct", 1, 4), ("direct", 2, 4),
              ("temporal", 2, 4, 2), ("temporal", 4, 4, 2), ("temporal", 4, 4, 3), ("temporal", 2, 4, 4),
              ("temporal", 4, 4, 4), ("temporal", 8, 4, 4),
-             ("stream", 16, 4, 4), ("stream", 32, 4, 4), ("stream", 64, 4, 4), ("stream", 32, 4, 2)],
+             ("stream", 16, 4, 4), ("stream", 36, 4, 4), ("stream", 40, 4, 6), ("stream", 38, 4, 8),
+             ("stream", 74, 4, 8)],
     "sincos": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("local", 8, 4),
                ("stream", 64, 4), ("stream", 89, 4), ("stream", 134, 4)],
     "life": [("local", 1, 1), ("local", 1, 16), ("local", 2, 16), ("direct", 1, 16), ("direct", 2, 16),
@@ -99,7 +100,7 @@ def sweep_burst(w):
     that negligible; at least 10 for the iterated workloads."""
     est_us = w.rows * w.cols * w.bytes_per_cell_update / 4e12 * 1e6
     burst = int(min(20, max(1, math.ceil(100.0 / max(est_us, 1e-3)))))
-    return max(burst, 12) if w.iters > 1 else burst      # 12: a multiple of every temporal depth
+    return max(burst, 24) if w.iters > 1 else burst      # 24: a multiple of every temporal depth swept
 
 
 # the vectorised mapping each kernel is usually fastest with (predictor study)

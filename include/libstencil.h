@@ -122,12 +122,13 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            LOCAL: cells_rows in {1,2,4,8}, cells_cols in {1,4} (F32) or {1,16} (U8);
  *            DIRECT: cells_rows in {1,2,4}, cells_cols = 4 (F32) or 16 (U8).
  *            STENCIL_STAGING_STREAM - register streaming, no local memory: each wavefront walks
- *            down a strip of 62 to 64 four-cell vectors (one lane at each side that has a border
- *            region only feeds its neighbours), cells_rows (1..4096) rows at a time, taking row
- *            neighbours from adjacent lanes; cells_cols = 4.  Two kernels:
+ *            down a strip of 60 to 64 four-cell vectors (the outermost lanes at a side that has
+ *            a border region only feed their neighbours), cells_rows (1..4096) rows at a time,
+ *            taking row neighbours from adjacent lanes; cells_cols = 4.  Two kernels:
  *            HEAT and WEIGHTED_SUM with region 1/1/1/1, WRAP and CONSTANT borders: temporal
  *            blocking, the last three rows of every time level stay in registers,
- *            STENCIL_OPT_TEMPORAL_DEPTH applications per launch;
+ *            STENCIL_OPT_TEMPORAL_DEPTH applications per launch (up to
+ *            STENCIL_MAX_STREAM_DEPTH; one rim lane per side up to 4, two beyond);
  *            SINCOS with region N1 S5 E3 W0 and WEIGHTED_SUM with region 2/2/2/2, any border
  *            mode: one application per launch, each input row is loaded and pre-processed once
  *            and folded into the N+S+1 output rows it belongs to.
@@ -146,14 +147,16 @@ int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int 
 
 /* Launch options.  STENCIL_OPT_XCD_REMAP (default 1): workgroups are numbered so that each of
  * the eight XCDs (each with its own L2) works on one contiguous band of tiles.
- * STENCIL_OPT_TEMPORAL_DEPTH (default 2, 1..STENCIL_MAX_TEMPORAL_DEPTH): applications fused
- * into one launch under STENCIL_STAGING_TEMPORAL.
+ * STENCIL_OPT_TEMPORAL_DEPTH (default 2): applications fused into one launch, 1..
+ * STENCIL_MAX_TEMPORAL_DEPTH under STENCIL_STAGING_TEMPORAL, 1..STENCIL_MAX_STREAM_DEPTH under
+ * STENCIL_STAGING_STREAM (a depth above 4 makes every size illegal under the former).
  * STENCIL_OPT_SWEEP_CUTOFF (default 0 = off; otherwise a percentage >= 100): adaptive sampling
  * for stencil_sweep_wg, after the paper's closing remarks on minimising the observations needed
  * to tell bad sizes from good ones: every size first gets one warm-up and two samples; only the
  * sizes whose two-sample mean is within cutoff/100 times the best one are then sampled in full
  * (3 warm-ups + `reps` samples); the others keep their two-sample statistics. */
-#define STENCIL_MAX_TEMPORAL_DEPTH 4
+#define STENCIL_MAX_TEMPORAL_DEPTH 4   /* STENCIL_STAGING_TEMPORAL */
+#define STENCIL_MAX_STREAM_DEPTH 8     /* STENCIL_STAGING_STREAM */
 enum stencil_option { STENCIL_OPT_XCD_REMAP = 0, STENCIL_OPT_TEMPORAL_DEPTH = 1, STENCIL_OPT_SWEEP_CUTOFF = 2 };
 int stencil_set_option(stencil_t *st, int option, int value);
 

@@ -116,7 +116,7 @@ TileGeom tile_geom(const stencil *s, const Variant &v, int wr, int wc) {
     } else if (v.staging == STENCIL_STAGING_STREAM) {
         // one wavefront per tile: s->cr rows of a strip of 62..64 vectors; no local memory
         g.th = s->cr;
-        g.tw = sk::march_vectors(s->hw, s->he) * 4;
+        g.tw = v.fuses ? sk::stream_cols(s->temporal_depth) : sk::march_vectors(s->hw, s->he) * 4;
         g.pitch = 4;
         g.plane = 0;
         g.lds_bytes = 0;
@@ -217,22 +217,38 @@ template <class Op, int B>
 hipError_t launch_stream(const stencil *s, const void *in, void *out, int wr, int wc, int depth, hipStream_t stream) {
     using Halo = sk::HaloC<1, 1, 1, 1>;
     constexpr int kMaxT = 256;
-    static_assert(sk::march_vectors(1, 1) * 4 == sk::kStreamCols, "strip width the geometry assumes");
+    if (depth < 1 || depth > sk::kStreamMaxDepth) return hipErrorInvalidValue;
     const int CR = s->cr;   // rows per segment
     unsigned blocks;
     size_t lds;
     auto a = make_args<Op, Halo, 0, 4>(s, STENCIL_STAGING_STREAM, in, out, wr, wc, &blocks, &lds);
+    // a tile is one wavefront's segment: CR rows of a strip whose width follows from the number of
+    // applications this launch fuses (the last launch of a run may fuse fewer)
+    const int strip_cols = sk::stream_cols(depth);
+    a.tiles_c = (int)((s->cols + strip_cols - 1) / strip_cols);
+    a.n_tiles = (int)((s->rows + CR - 1) / CR) * a.tiles_c;
     a.xcd_chunk = 0;
     const unsigned waves_per_block = (unsigned)(wr * wc) / 64u;
     blocks = ((unsigned)a.n_tiles + waves_per_block - 1) / waves_per_block;
     const dim3 grid(blocks), block(wc, wr);
+#define STREAM_LAUNCH(D)                                                                                       \
+    if (a.vec_ok)                                                                                              \
+        hipLaunchKernelGGL((sk::stream_kernel<Op, B, D, true, kMaxT>), grid, block, 0, stream, a, CR);         \
+    else                                                                                                       \
+        hipLaunchKernelGGL((sk::stream_kernel<Op, B, D, false, kMaxT>), grid, block, 0, stream, a, CR);        \
+    break
     switch (depth) {
-    case 1: hipLaunchKernelGGL((sk::stream_kernel<Op, B, 1, kMaxT>), grid, block, 0, stream, a, CR); break;
-    case 2: hipLaunchKernelGGL((sk::stream_kernel<Op, B, 2, kMaxT>), grid, block, 0, stream, a, CR); break;
-    case 3: hipLaunchKernelGGL((sk::stream_kernel<Op, B, 3, kMaxT>), grid, block, 0, stream, a, CR); break;
-    case 4: hipLaunchKernelGGL((sk::stream_kernel<Op, B, 4, kMaxT>), grid, block, 0, stream, a, CR); break;
+    case 1: STREAM_LAUNCH(1);
+    case 2: STREAM_LAUNCH(2);
+    case 3: STREAM_LAUNCH(3);
+    case 4: STREAM_LAUNCH(4);
+    case 5: STREAM_LAUNCH(5);
+    case 6: STREAM_LAUNCH(6);
+    case 7: STREAM_LAUNCH(7);
+    case 8: STREAM_LAUNCH(8);
     default: return hipErrorInvalidValue;
     }
+#undef STREAM_LAUNCH
     return hipGetLastError();
 }
 
@@ -586,6 +602,9 @@ int check_legal(const stencil *s, const Variant *v, int wr, int wc) {
     if ((int64_t)wr * wc > v->max_threads)
         return fail(STENCIL_E_REFUSED, "workgroup size %dx%d exceeds W_max = %d work-items", wr, wc,
                     v->max_threads);
+    if (v->staging == STENCIL_STAGING_TEMPORAL && s->temporal_depth > STENCIL_MAX_TEMPORAL_DEPTH)
+        return fail(STENCIL_E_INVALID, "the local-memory temporal kernels fuse at most %d applications (depth is %d)",
+                    STENCIL_MAX_TEMPORAL_DEPTH, s->temporal_depth);
     if (v->staging == STENCIL_STAGING_STREAM && (wr * wc) % 64 != 0)
         return fail(STENCIL_E_REFUSED, "workgroup size %dx%d refused: this mapping gives each wavefront a strip, the "
                                        "workgroup must be whole wavefronts of 64 work-items", wr, wc);
@@ -803,8 +822,11 @@ int stencil_set_option(stencil_t *s, int option, int value) {
         s->sweep_cutoff_pct = value;
         return STENCIL_OK;
     case STENCIL_OPT_TEMPORAL_DEPTH:
-        if (value < 1 || value > STENCIL_MAX_TEMPORAL_DEPTH)
-            return fail(STENCIL_E_INVALID, "temporal depth must be in [1, %d]", STENCIL_MAX_TEMPORAL_DEPTH);
+        if (value < 1 || value > STENCIL_MAX_STREAM_DEPTH)
+            return fail(STENCIL_E_INVALID, "temporal depth must be in [1, %d]", STENCIL_MAX_STREAM_DEPTH);
+        if (value > STENCIL_MAX_TEMPORAL_DEPTH && s->staging == STENCIL_STAGING_TEMPORAL)
+            return fail(STENCIL_E_INVALID, "the local-memory temporal kernels fuse at most %d applications",
+                        STENCIL_MAX_TEMPORAL_DEPTH);
         s->temporal_depth = value;
         s->best_rows = s->best_cols = 0;
         return STENCIL_OK;

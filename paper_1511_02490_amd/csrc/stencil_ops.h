@@ -173,7 +173,9 @@ struct OpHeat {
         float ns = __fadd_rn(s.n, s.s);
         float ew = __fadd_rn(s.e, s.w);
         float sum = __fadd_rn(ns, ew);
-        float t = __fsub_rn(sum, __fmul_rn(4.0f, s.u));
+        // 4u is exact (a power-of-two multiple), so one fma rounds exactly where the separate
+        // multiply and subtract would (they differ only where 4u overflows)
+        float t = __fmaf_rn(-4.0f, s.u, sum);
         return __fadd_rn(s.u, __fmul_rn(alpha, t));
     }
 };

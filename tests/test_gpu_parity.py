@@ -259,11 +259,12 @@ def test_temporal_blocking_life_bit_exact(ls, border):
 def test_register_streaming_temporal_kernel_bit_exact(ls, border):
     """Time levels kept in registers, row neighbours from adjacent lanes; every wavefront owns a
     strip of 248 columns: matrices wider than one strip, ragged ones, and ones smaller than a strip."""
-    for rows, cols, iters in [(70, 600, 9), (37, 250, 5), (130, 83, 6), (64, 256, 8), (5, 3, 7), (1, 1, 4)]:
+    for rows, cols, iters in [(70, 600, 9), (37, 250, 5), (130, 83, 6), (64, 256, 8), (5, 3, 7), (1, 1, 4),
+                              (40, 244, 17), (33, 484, 11)]:
         w = wl.config(3, rows=rows, cols=cols, iters=iters)
         w.border, w.pad = border, 50.0
-        for depth in (1, 2, 3, 4):
-            for h, wg in [(16, (1, 64)), (32, (2, 64)), (64, (4, 64)), (128, (8, 8)), (16, (2, 32))]:
+        for depth in (1, 2, 3, 4, 5, 6, 7, 8):
+            for h, wg in [(16, (1, 64)), (32, (2, 64)), (64, (4, 64)), (128, (8, 8)), (16, (2, 32)), (23, (1, 64))]:
                 check(ls, w, wg, blocking=("stream", h, 4, depth))
     w = custom(wl.WEIGHTED_SUM, 90, 300, (1, 1, 1, 1), border, pad=0.4, seed=22, iters=7)
     check(ls, w, (1, 64), blocking=("stream", 32, 4, 4))
@@ -273,6 +274,13 @@ def test_register_streaming_temporal_kernel_bit_exact(ls, border):
     assert st.max_wg_size() == 256 and st.tile_bytes(1, 64) == 0
     assert st.is_legal(1, 64) and st.is_legal(4, 64) and st.is_legal(16, 8)
     assert not st.is_legal(4, 4) and not st.is_legal(1, 96) and not st.is_legal(8, 64)   # whole wavefronts, <= 256
+    st.set_option(1, 8)
+    with pytest.raises(ls.StencilError):
+        st.set_option(1, 9)                                        # two rim lanes cover eight applications
+    st.set_mapping("temporal", 2, 4)
+    assert not st.is_legal(4, 16)                                  # the local-memory kernels stop at four
+    st.set_option(1, 4)
+    assert st.is_legal(4, 16)
     clamp = wl.config(3, rows=64, cols=64)
     clamp.border = "clamp"
     with pytest.raises(ls.StencilError):
