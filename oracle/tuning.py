@@ -299,6 +299,75 @@ def regress_1nn(train_x: Sequence[Sequence[float]], train_w: Sequence[WG], train
     return best_y
 
 
+# Regression trees and their bagged ensemble (Section 5: "a Random Forest with regression trees";
+# the trees are CART regression trees, the forest averages trees grown on bootstrap samples, each
+# with a random subset of the inputs).  The random draws are arguments: `bootstrap[t]` lists the
+# tuple indices tree t is grown on (with repetition), `masks[t][j]` says whether input j is open
+# to tree t.
+
+def grow_regression_tree(xs: Sequence[Sequence[float]], ys: Sequence[float], mask: Sequence[bool],
+                         min_leaf: int = 1, max_depth: int = 64):
+    """CART: a node splits on the (input, threshold) pair that minimises the summed squared error
+    of the two sides' means, thresholds midway between consecutive distinct values, each side
+    keeping at least `min_leaf` tuples; x <= threshold goes left.  Among equal scores the first
+    input, then the lowest threshold, is kept.  A node is a leaf when its targets are all equal, no split is admissible
+    or `max_depth` is reached; it predicts the mean of its targets."""
+    nf = len(xs[0])
+
+    def build(idx, depth):
+        ysub = [ys[i] for i in idx]
+        mean = sum(ysub) / len(ysub)
+        if depth >= max_depth or len(idx) < 2 * min_leaf or min(ysub) == max(ysub):
+            return ("leaf", mean)
+        best = None            # (score, input, threshold)
+        for j in range(nf):
+            if not mask[j]:
+                continue
+            order = sorted(idx, key=lambda i: xs[i][j])        # stable: ties keep index order
+            total = sum(ys[i] for i in order)
+            left_sum = 0.0
+            for pos in range(len(order) - 1):
+                left_sum += ys[order[pos]]
+                a, b = xs[order[pos]][j], xs[order[pos + 1]][j]
+                n_l, n_r = pos + 1, len(order) - pos - 1
+                if a == b or n_l < min_leaf or n_r < min_leaf:
+                    continue
+                right_sum = total - left_sum
+                # minimising SSE = maximising sum_l^2 / n_l + sum_r^2 / n_r
+                score = left_sum * left_sum / n_l + right_sum * right_sum / n_r
+                if best is None or score > best[0]:
+                    best = (score, j, (a + b) / 2.0)
+        if best is None:
+            return ("leaf", mean)
+        _, j, thr = best
+        left = [i for i in idx if xs[i][j] <= thr]
+        right = [i for i in idx if xs[i][j] > thr]
+        return ("node", j, thr, build(left, depth + 1), build(right, depth + 1))
+
+    return build(list(range(len(xs))), 0)
+
+
+def predict_regression_tree(tree, x: Sequence[float]) -> float:
+    while tree[0] == "node":
+        _, j, thr, left, right = tree
+        tree = left if x[j] <= thr else right
+    return tree[1]
+
+
+def grow_forest(xs: Sequence[Sequence[float]], ys: Sequence[float], bootstrap: Sequence[Sequence[int]],
+                masks: Sequence[Sequence[bool]], min_leaf: int = 1, max_depth: int = 64):
+    """One CART tree per bootstrap sample, each restricted to its own subset of the inputs."""
+    forest = []
+    for rows, mask in zip(bootstrap, masks):
+        forest.append(grow_regression_tree([xs[i] for i in rows], [ys[i] for i in rows], mask, min_leaf, max_depth))
+    return forest
+
+
+def predict_forest(forest, x: Sequence[float]) -> float:
+    """The mean of the trees' predictions."""
+    return sum(predict_regression_tree(t, x) for t in forest) / len(forest)
+
+
 def predict_by_regression(predict, candidates: Sequence[WG], w_max: int, refused: Iterable[WG],
                           fitness) -> Tuple[Optional[WG], int]:
     """Algorithm 2.  `predict(w)` is R(f(s), w) for the scenario at hand, `fitness` the function

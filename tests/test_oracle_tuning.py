@@ -167,3 +167,89 @@ def test_algorithm2_regression_by_hand():
     assert tuning.predict_by_regression(near10, cands, 1024, [(64, 4), (8, 8), (4, 4)], recip) == (None, 3)
     # speedups: identity fitness picks the largest
     assert tuning.predict_by_regression(near10, cands, 1024, [], lambda y: y) == ((4, 4), 0)
+
+
+def test_regression_tree_by_hand_and_by_brute_force():
+    # a step in input 0, input 1 is noise: one split, midway between the two points next to the step
+    X = [(0.1, 5.0), (0.2, 1.0), (0.4, 3.0), (0.7, 2.0), (0.8, 4.0), (0.9, 0.0)]
+    Y = [1.0, 1.0, 1.0, 3.0, 3.0, 3.0]
+    tree = tuning.grow_regression_tree(X, Y, [True, True])
+    assert tree == ("node", 0, (0.4 + 0.7) / 2.0, ("leaf", 1.0), ("leaf", 3.0))
+    assert tuning.predict_regression_tree(tree, (0.55, 9.0)) == 1.0
+    assert tuning.predict_regression_tree(tree, (0.5500001, -9.0)) == 3.0
+    # input 0 closed to the tree: it has to make do with the noise input
+    blind = tuning.grow_regression_tree(X, Y, [False, True])
+    assert blind[0] == "node" and blind[1] == 1
+    # equal targets, too few tuples for two leaves, depth 0: a leaf with the mean
+    assert tuning.grow_regression_tree(X, [2.0] * 6, [True, True]) == ("leaf", 2.0)
+    assert tuning.grow_regression_tree(X, Y, [True, True], min_leaf=4) == ("leaf", 2.0)
+    assert tuning.grow_regression_tree(X, Y, [True, True], max_depth=0) == ("leaf", 2.0)
+    # brute force: the root split minimises the summed squared error over every (input, cut)
+    import random
+    rnd = random.Random(11)
+    for trial in range(20):
+        n = rnd.randrange(4, 9)
+        Xr = [(rnd.random(), float(rnd.randrange(3)), rnd.random()) for _ in range(n)]
+        Yr = [rnd.random() * 10 for _ in range(n)]
+        min_leaf = rnd.choice([1, 2])
+        root = tuning.grow_regression_tree(Xr, Yr, [True] * 3, min_leaf=min_leaf, max_depth=1)
+        sse = lambda ys: sum((y - sum(ys) / len(ys)) ** 2 for y in ys) if ys else 0.0
+        cuts = {}
+        for j in range(3):
+            vals = sorted(set(x[j] for x in Xr))
+            for a, b in zip(vals, vals[1:]):
+                thr = (a + b) / 2.0
+                left = [y for x, y in zip(Xr, Yr) if x[j] <= thr]
+                right = [y for x, y in zip(Xr, Yr) if x[j] > thr]
+                if len(left) >= min_leaf and len(right) >= min_leaf:
+                    cuts[(j, thr)] = sse(left) + sse(right)
+        if not cuts:
+            assert root[0] == "leaf"
+        else:
+            # (two cuts that part the tuples the same way tie: either is the minimum)
+            assert root[0] == "node" and cuts[(root[1], root[2])] <= min(cuts.values()) * (1 + 1e-12)
+            assert root[3][0] == "leaf" and root[4][0] == "leaf"
+            side = [y for x, y in zip(Xr, Yr) if x[root[1]] <= root[2]]
+            assert abs(root[3][1] - sum(side) / len(side)) < 1e-12
+
+
+def test_regression_tree_and_forest_against_a_library_cart():
+    """scikit-learn's DecisionTreeRegressor is an independent implementation of CART with the same
+    conventions (squared error, midpoint thresholds, x <= threshold goes left; it holds the inputs
+    in float32, so the data here is float32-exact).  Where no two cuts tie it must predict what the
+    oracle's trees predict: continuous random data, and leaves of three or more tuples or shallow
+    trees (two inputs order a handful of tuples the same way too often, and CART does not say which
+    of two equally good cuts to take).  The forest is checked as the mean of library trees grown on
+    the same bootstrap rows and columns."""
+    np = pytest.importorskip("numpy")
+    sk = pytest.importorskip("sklearn.tree")
+    rng = np.random.default_rng(17)
+    X = rng.random((70, 4)).astype(np.float32).astype(np.float64)
+    y = np.sin(3 * X[:, 0]) + X[:, 1] ** 2 + 0.1 * rng.random(70)
+    Q = rng.random((200, 4)).astype(np.float32).astype(np.float64)
+    for min_leaf, max_depth, tie_free in [(3, 64, True), (1, 3, True), (2, 3, True), (4, 6, True), (5, 64, True),
+                                          (8, 2, True), (1, 64, False), (2, 5, False)]:
+        mine = tuning.grow_regression_tree(X.tolist(), y.tolist(), [True] * 4, min_leaf, max_depth)
+        ref = sk.DecisionTreeRegressor(min_samples_leaf=min_leaf, max_depth=min(max_depth, 60)).fit(X, y)
+        # the training tuples are parted the same way whichever of two tied cuts is taken
+        got = np.array([tuning.predict_regression_tree(mine, q) for q in X.tolist()])
+        assert np.max(np.abs(got - ref.predict(X))) < 1e-12
+        if tie_free:
+            got = np.array([tuning.predict_regression_tree(mine, q) for q in Q.tolist()])
+            assert np.max(np.abs(got - ref.predict(Q))) < 1e-12
+    n_trees = 7
+    bootstrap = rng.integers(0, 70, size=(n_trees, 70))
+    masks = np.array([[True, True, False, True], [True, False, True, True], [False, True, True, True],
+                      [True, True, True, False], [True, True, True, True], [True, False, False, True],
+                      [False, True, True, False]])
+    forest = tuning.grow_forest(X.tolist(), y.tolist(), bootstrap.tolist(), masks.tolist(), 5, 4)
+    expect = np.zeros(len(Q))
+    for rows, mask in zip(bootstrap, masks):
+        t = sk.DecisionTreeRegressor(min_samples_leaf=5, max_depth=4).fit(X[rows][:, mask], y[rows])
+        expect += t.predict(Q[:, mask])
+    got = np.array([tuning.predict_forest(forest, q) for q in Q.tolist()])
+    assert np.max(np.abs(got - expect / n_trees)) < 1e-12
+    # a forest of identical full samples with every input open is the single tree
+    same = tuning.grow_forest(X.tolist(), y.tolist(), [list(range(70))] * 3, [[True] * 4] * 3)
+    one = tuning.grow_regression_tree(X.tolist(), y.tolist(), [True] * 4)
+    assert all(abs(tuning.predict_forest(same, q) - tuning.predict_regression_tree(one, q)) < 1e-15 for q in Q.tolist())
