@@ -211,16 +211,9 @@ def main():
     warmup = args.warmup if args.warmup >= 0 else max(1, steps // 10)
 
     def copy_reference(n=20):
-        """GB/s of the plain copy kernel on this matrix (read + write), by events on the stream."""
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for _ in range(3):
-            ls.device_copy(tin, tout)
-        e0.record()
-        for _ in range(n):
-            ls.device_copy(tin, tout)
-        e1.record()
-        e1.synchronize()
-        return 2.0 * tin.numel() * tin.element_size() / (e0.elapsed_time(e1) / n * 1e-3) / 1e9
+        """GB/s of the plain copy kernel on this matrix (read + write), timed like a sweep sample."""
+        mean_ms, _ = ls.time_copy(tin, tout, burst=max(burst, 2), reps=n)
+        return 2.0 * tin.numel() * tin.element_size() / (mean_ms * 1e-3) / 1e9
 
     if args.copy_only:
         gbs = copy_reference(max(steps, 20))

@@ -215,6 +215,12 @@ int stencil_sweep_wg(stencil_t *st, const void *in, void *out, int iters,
  * traffic counters against a kernel of known size. */
 int stencil_device_copy(const void *in, void *out, int64_t bytes, void *stream);
 
+/* The same copy timed by the sweep's protocol (Section 5: warm-up, then `reps` samples by
+ * events on `stream`, a sample being `burst` launches back to back): mean_ms and, if not NULL,
+ * min_ms (host pointers) receive milliseconds per launch.  Synchronous.  burst, reps >= 1. */
+int stencil_time_copy(const void *in, void *out, int64_t bytes, int burst, int reps, double *mean_ms,
+                      double *min_ms, void *stream);
+
 /* The reductions of a sweep on their own (Eq. 3; Section 7's performance and speedup), on
  * host arrays: best_index as above; performance[i] = mean_ms[best] / mean_ms[i] (NaN where
  * status[i] != STENCIL_OK; may be NULL); speedup = fixed_ms / mean_ms[best]. */
@@ -282,6 +288,19 @@ int stencil_regressor_add(stencil_regressor_t *r, const double *features, int n_
                           int wg_rows, int wg_cols, double value);
 int stencil_regressor_predict(const stencil_regressor_t *r, const double *features, int n_features,
                               int wg_rows, int wg_cols, double *value);
+
+/* Section 5's regressor: a random forest of regression trees over the tuples added so far.
+ * Inputs of the trees: the features, then w_r, then w_c (n_features + 2 of them).  Tree t is a
+ * CART regression tree (cuts minimise the summed squared error of the two sides' means, thresholds
+ * midway between consecutive distinct values, at least min_leaf tuples a side, at most max_depth
+ * levels) grown on the tuples bootstrap[t*n_rows .. (t+1)*n_rows) (indices into the order of
+ * stencil_regressor_add, repetition allowed; NULL: all tuples once) using only the inputs j with
+ * masks[t*(n_features+2) + j] != 0 (NULL: all).  The random draws are thus the caller's (host
+ * arrays, not kept).  Afterwards stencil_regressor_predict returns the mean of the trees'
+ * predictions; adding a tuple discards the forest.  STENCIL_E_INVALID on an index out of range, a
+ * tree with no open input, or no tuples. */
+int stencil_regressor_fit_forest(stencil_regressor_t *r, int n_trees, int n_rows, const int *bootstrap,
+                                 const unsigned char *masks, int min_leaf, int max_depth);
 
 /* Algorithm 2: among the candidates within W_max(s) that the regressor can price, take the one
  * with the highest fitness of the prediction - STENCIL_FITNESS_RECIPROCAL (1/x, for predicted

@@ -1,7 +1,7 @@
 """The paper's experiment in miniature, on one MI355X: sweep the workgroup-size space of a set
 of synthetic and real stencil scenarios (Section 5), then evaluate workgroup-size prediction
 (Algorithm 1: nearest-neighbour and decision-tree classifiers over f(s) with the NearestNeighbour
-fallback; Algorithm 2: nearest-neighbour regressors on runtimes and on speedups) against
+fallback; Algorithm 2: nearest-neighbour and random-forest regressors on runtimes and on speedups) against
 the sweep's oracle sizes with the metrics of Section 7.
 
     python -m paper_1511_02490_amd.autotune_study [--synthetic 32] [--reps 5] [--mapping local,1,1]
@@ -97,12 +97,15 @@ def main():
                          "speedup_over_32x4": times[i][idx[(32, 4)]] / t if status[i][idx[(32, 4)]] == 0 else nan})
         return rows
 
-    def evaluate_regression(train, test, target):
-        """Algorithm 2 with the nearest-neighbour regressor trained on runtimes (target = "runtime",
-        fitness 1/x) or on speedups over the baseline size (target = "speedup", fitness x)."""
+    def evaluate_regression(train, test, target, model="nearest"):
+        """Algorithm 2 with a regressor trained on runtimes (target = "runtime", fitness 1/x) or on
+        speedups over the baseline size (target = "speedup", fitness x); model = "nearest"
+        (nearest-neighbour regression) or "forest" (Section 5's random forest of regression trees:
+        30 trees, seeded bootstrap samples and input subsets, leaves of two tuples or more)."""
         rows = []
         for i in test:
             reg = ls.Regressor()
+            n_tuples = 0
             for k in train:
                 if k == i:
                     continue
@@ -110,6 +113,10 @@ def main():
                     if status[k][j] == 0:
                         y = times[k][j] if target == "runtime" else times[k][base] / times[k][j]
                         reg.add(feats[k], w, y)
+                        n_tuples += 1
+            if model == "forest":
+                bootstrap, masks = wl.forest_draws(30, n_tuples, len(feats[i]) + 2, seed=wl.BASE_SEED + 200 + i)
+                reg.fit_forest(bootstrap, masks, min_leaf=2, max_depth=32)
             st = ls.Stencil.from_workload(scen[i])
             try:
                 st.set_mapping(*mapping)
@@ -147,6 +154,9 @@ def main():
              "leave-one-out, regressor on runtimes (Algorithm 2)": evaluate_regression(all_i, all_i, "runtime"),
              "leave-one-out, regressor on speedups (Algorithm 2)": evaluate_regression(all_i, all_i, "speedup"),
              "synthetic -> real, regressor on speedups (Algorithm 2)": evaluate_regression(syn, real, "speedup"),
+             "leave-one-out, random forest on runtimes (Algorithm 2)": evaluate_regression(all_i, all_i, "runtime", "forest"),
+             "leave-one-out, random forest on speedups (Algorithm 2)": evaluate_regression(all_i, all_i, "speedup", "forest"),
+             "synthetic -> real, random forest on speedups (Algorithm 2)": evaluate_regression(syn, real, "speedup", "forest"),
              "ZeroR (always the baseline size)": evaluate(all_i, all_i, "zeror")}
 
     worst_over_best = [max(t for t, s in zip(times[i], status[i]) if s == 0) / times[i][oracle[i]] for i in all_i]

@@ -265,6 +265,10 @@ private:
 // R(f(s), w) of Algorithm 2 as a nearest-neighbour regressor over (f(s), w, y) tuples: the y of
 // the tuple with the same w whose scenario is nearest to f (features scaled by their range over
 // all tuples, Euclidean distance, first nearest wins ties); NaN if no tuple has this w.
+// R(f(s), w) of Algorithm 2.  Without a fitted forest: the value of the nearest training scenario
+// that was measured with the same w.  With one (Section 5: a random forest of regression trees):
+// the mean of CART trees over the inputs (f(s), w_r, w_c), each grown on its own bootstrap sample
+// with its own subset of the inputs; the random draws are the caller's.
 class Regressor {
 public:
     bool add(const double *f, int nf, int wr, int wc, double y) {
@@ -274,10 +278,58 @@ public:
         wr_.push_back(wr);
         wc_.push_back(wc);
         y_.push_back(y);
+        trees_.clear();     // a forest describes the tuples it was grown on
         return true;
     }
     int n_features() const { return nf_; }
+    size_t n_tuples() const { return y_.size(); }
+    int n_inputs() const { return nf_ + 2; }
+    bool has_forest() const { return !trees_.empty(); }
+
+    // bootstrap: n_trees x n_rows tuple indices (NULL: every tree sees every tuple once);
+    // masks: n_trees x n_inputs() flags (NULL: every input open).  False on a bad index or a tree
+    // with no open input.
+    bool fit_forest(int n_trees, int n_rows, const int *bootstrap, const unsigned char *masks, int min_leaf,
+                    int max_depth) {
+        const int n = (int)y_.size(), ni = n_inputs();
+        if (n_trees < 1 || n < 1 || min_leaf < 1 || max_depth < 0) return false;
+        if (bootstrap && n_rows < 1) return false;
+        std::vector<Tree> trees((size_t)n_trees);
+        for (int t = 0; t < n_trees; ++t) {
+            std::vector<int> rows;
+            if (bootstrap) {
+                rows.assign(bootstrap + (size_t)t * n_rows, bootstrap + (size_t)(t + 1) * n_rows);
+                for (int r : rows)
+                    if (r < 0 || r >= n) return false;
+            } else {
+                rows.resize((size_t)n);
+                for (int i = 0; i < n; ++i) rows[(size_t)i] = i;
+            }
+            std::vector<unsigned char> open((size_t)ni, 1);
+            if (masks) open.assign(masks + (size_t)t * ni, masks + (size_t)(t + 1) * ni);
+            bool any = false;
+            for (unsigned char o : open) any = any || o;
+            if (!any) return false;
+            grow(trees[(size_t)t], rows, open, min_leaf, max_depth, 0);
+        }
+        trees_.swap(trees);
+        return true;
+    }
+
     double predict(const double *f, int wr, int wc) const {
+        if (!trees_.empty()) {
+            double sum = 0.0;
+            for (const Tree &t : trees_) {
+                int k = 0;
+                while (t[(size_t)k].input >= 0) {
+                    const Node &nd = t[(size_t)k];
+                    const double v = nd.input < nf_ ? f[nd.input] : (nd.input == nf_ ? (double)wr : (double)wc);
+                    k = v <= nd.threshold ? nd.left : nd.right;
+                }
+                sum += t[(size_t)k].value;
+            }
+            return sum / (double)trees_.size();
+        }
         const size_t n = y_.size();
         std::vector<double> lo(nf_), hi(nf_);
         for (int j = 0; j < nf_; ++j) {
@@ -308,9 +360,75 @@ public:
     }
 
 private:
+    struct Node {
+        int input = -1;         // -1: leaf
+        double threshold = 0.0;
+        int left = -1, right = -1;
+        double value = 0.0;     // leaf: mean of the targets
+    };
+    using Tree = std::vector<Node>;
+
+    double input(int tuple, int j) const {
+        return j < nf_ ? x_[(size_t)tuple * nf_ + j] : (j == nf_ ? (double)wr_[(size_t)tuple] : (double)wc_[(size_t)tuple]);
+    }
+
+    // CART: the cut that minimises the two sides' summed squared error (= maximises
+    // sum_l^2 / n_l + sum_r^2 / n_r), thresholds midway between consecutive distinct values,
+    // at least min_leaf tuples a side, x <= threshold to the left; first best cut kept.
+    int grow(Tree &tree, const std::vector<int> &rows, const std::vector<unsigned char> &open, int min_leaf,
+             int max_depth, int depth) const {
+        const int me = (int)tree.size();
+        tree.push_back(Node());
+        double sum = 0.0, lo = y_[(size_t)rows[0]], hi = lo;
+        for (int r : rows) {
+            sum += y_[(size_t)r];
+            lo = std::min(lo, y_[(size_t)r]);
+            hi = std::max(hi, y_[(size_t)r]);
+        }
+        tree[(size_t)me].value = sum / (double)rows.size();
+        if (depth >= max_depth || (int)rows.size() < 2 * min_leaf || lo == hi) return me;
+        bool found = false;
+        double best_score = 0.0, best_thr = 0.0;
+        int best_input = -1;
+        std::vector<int> order;
+        for (int j = 0; j < n_inputs(); ++j) {
+            if (!open[(size_t)j]) continue;
+            order = rows;
+            std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return input(a, j) < input(b, j); });
+            double total = 0.0;
+            for (int r : order) total += y_[(size_t)r];
+            double left_sum = 0.0;
+            for (size_t pos = 0; pos + 1 < order.size(); ++pos) {
+                left_sum += y_[(size_t)order[pos]];
+                const double a = input(order[pos], j), b = input(order[pos + 1], j);
+                const double n_l = (double)(pos + 1), n_r = (double)(order.size() - pos - 1);
+                if (a == b || (int)(pos + 1) < min_leaf || (int)(order.size() - pos - 1) < min_leaf) continue;
+                const double right_sum = total - left_sum;
+                const double score = left_sum * left_sum / n_l + right_sum * right_sum / n_r;
+                if (!found || score > best_score) {
+                    found = true;
+                    best_score = score;
+                    best_input = j;
+                    best_thr = (a + b) / 2.0;
+                }
+            }
+        }
+        if (!found) return me;
+        std::vector<int> left, right;
+        for (int r : rows) (input(r, best_input) <= best_thr ? left : right).push_back(r);
+        tree[(size_t)me].input = best_input;
+        tree[(size_t)me].threshold = best_thr;
+        const int l = grow(tree, left, open, min_leaf, max_depth, depth + 1);
+        const int r = grow(tree, right, open, min_leaf, max_depth, depth + 1);
+        tree[(size_t)me].left = l;
+        tree[(size_t)me].right = r;
+        return me;
+    }
+
     int nf_ = 0;
     std::vector<double> x_, y_;
     std::vector<int> wr_, wc_;
+    std::vector<Tree> trees_;
 };
 
 }  // namespace host_tuning

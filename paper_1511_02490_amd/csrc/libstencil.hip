@@ -689,6 +689,8 @@ void default_wg(const stencil *s, const Variant *v, int *wr, int *wc) {
 
 }  // namespace
 
+constexpr int kWarmup = 3;   // untimed launches before the samples of a size (Section 5)
+
 // ---- C ABI -----------------------------------------------------------------------------------
 
 extern "C" {
@@ -911,7 +913,6 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
         s->events.push_back(e);
     }
     const double nan = std::numeric_limits<double>::quiet_NaN();
-    const int kWarmup = 3;
     std::vector<double> samples((size_t)reps);
 
     std::vector<double> means((size_t)n + 1, nan);
@@ -1035,6 +1036,41 @@ int stencil_device_copy(const void *in, void *out, int64_t bytes, void *stream) 
                        static_cast<const uint4 *>(in), static_cast<uint4 *>(out), n_vec, (size_t)bytes);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? STENCIL_OK : fail_hip(e, "copy kernel launch");
+}
+
+int stencil_time_copy(const void *in, void *out, int64_t bytes, int burst, int reps, double *mean_ms,
+                      double *min_ms, void *stream_) {
+    if (burst < 1 || reps < 1 || !mean_ms) return fail(STENCIL_E_INVALID, "bad arguments to stencil_time_copy");
+    hipStream_t stream = (hipStream_t)stream_;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return fail_hip(e, "hipEventCreate");
+    }
+    int rc = STENCIL_OK;
+    double sum = 0.0, lo = 0.0;
+    // the sweep's protocol: warm-up launches, then `reps` samples, a sample being a burst of launches
+    for (int i = -kWarmup; i < reps && rc == STENCIL_OK; ++i) {
+        if ((e = hipEventRecord(e0, stream)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
+        for (int b = 0; b < burst && rc == STENCIL_OK; ++b) rc = stencil_device_copy(in, out, bytes, stream_);
+        if (rc != STENCIL_OK) break;
+        if ((e = hipEventRecord(e1, stream)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
+        if ((e = hipEventSynchronize(e1)) != hipSuccess) { rc = fail_hip(e, "hipEventSynchronize"); break; }
+        float ms = 0.0f;
+        if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) { rc = fail_hip(e, "hipEventElapsedTime"); break; }
+        if (i < 0) continue;
+        const double per = (double)ms / burst;
+        sum += per;
+        lo = (i == 0 || per < lo) ? per : lo;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != STENCIL_OK) return rc;
+    *mean_ms = sum / reps;
+    if (min_ms) *min_ms = lo;
+    return STENCIL_OK;
 }
 
 int stencil_sweep_reduce(const int *wg_rows_list, const int *wg_cols_list, int n, const double *mean_ms,
@@ -1175,6 +1211,16 @@ int stencil_regressor_predict(const stencil_regressor_t *r, const double *featur
     auto *reg = reinterpret_cast<const host_tuning::Regressor *>(r);
     if (reg->n_features() != n_features) return fail(STENCIL_E_INVALID, "regressor is empty, or feature count differs");
     *value = reg->predict(features, wg_rows, wg_cols);
+    return STENCIL_OK;
+}
+
+int stencil_regressor_fit_forest(stencil_regressor_t *r, int n_trees, int n_rows, const int *bootstrap,
+                                 const unsigned char *masks, int min_leaf, int max_depth) {
+    if (!r) return fail(STENCIL_E_INVALID, "NULL argument");
+    auto *reg = reinterpret_cast<host_tuning::Regressor *>(r);
+    if (reg->n_tuples() == 0) return fail(STENCIL_E_INVALID, "the regressor holds no tuples");
+    if (!reg->fit_forest(n_trees, n_rows, bootstrap, masks, min_leaf, max_depth))
+        return fail(STENCIL_E_INVALID, "bad forest description (tree count, bootstrap index, input mask or limits)");
     return STENCIL_OK;
 }
 

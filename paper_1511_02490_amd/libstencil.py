@@ -64,6 +64,7 @@ def _load() -> ctypes.CDLL:
         "stencil_sweep_wg": (c_int, [vp, vp, vp, c_int, ip, ip, c_int, c_int, c_int, c_int,
                                      dp, dp, dp, dp, ip, ip, dp, vp]),
         "stencil_device_copy": (c_int, [vp, vp, c_i64, vp]),
+        "stencil_time_copy": (c_int, [vp, vp, c_i64, c_int, c_int, dp, dp, vp]),
         "stencil_sweep_reduce": (c_int, [ip, ip, c_int, dp, ip, c_dbl, ip, dp, dp]),
         "stencil_baseline_wg": (c_int, [dp, c_int, c_int, ip]),
         "stencil_features": (c_int, [vp, dp]),
@@ -76,6 +77,7 @@ def _load() -> ctypes.CDLL:
         "stencil_regressor_destroy": (None, [vp]),
         "stencil_regressor_add": (c_int, [vp, dp, c_int, c_int, c_int, c_dbl]),
         "stencil_regressor_predict": (c_int, [vp, dp, c_int, c_int, c_int, dp]),
+        "stencil_regressor_fit_forest": (c_int, [vp, c_int, c_int, ip, ctypes.POINTER(ctypes.c_ubyte), c_int, c_int]),
         "stencil_predict_wg_regression": (c_int, [vp, vp, ip, ip, c_int, c_int, ip, ip, ip]),
         "stencil_last_error": (ctypes.c_char_p, []),
     }
@@ -89,10 +91,11 @@ _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
            "stencil_set_mapping", "stencil_get_mapping", "stencil_set_option", "stencil_max_wg_size", "stencil_tile_bytes",
            "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg",
-           "stencil_device_copy", "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
+           "stencil_device_copy", "stencil_time_copy", "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
            "stencil_predict_wg", "stencil_regressor_create", "stencil_regressor_destroy",
-           "stencil_regressor_add", "stencil_regressor_predict", "stencil_predict_wg_regression",
+           "stencil_regressor_add", "stencil_regressor_predict", "stencil_regressor_fit_forest",
+           "stencil_predict_wg_regression",
            "stencil_last_error")
 
 
@@ -129,6 +132,18 @@ def device_copy(tin, tout, stream=None):
     _check(_lib.stencil_device_copy(ctypes.c_void_p(tin.data_ptr()), ctypes.c_void_p(tout.data_ptr()),
                                     nbytes, Stencil._stream_ptr(stream)))
     return tout
+
+
+def time_copy(tin, tout, burst: int = 10, reps: int = 30, stream=None) -> Tuple[float, float]:
+    """(mean, min) milliseconds per launch of the plain copy kernel, timed like a sweep sample:
+    3 warm-ups, then `reps` event-timed bursts of `burst` launches."""
+    nbytes = tin.numel() * tin.element_size()
+    assert tout.numel() * tout.element_size() == nbytes and tin.is_cuda and tout.is_cuda
+    mean, lo = ctypes.c_double(), ctypes.c_double()
+    _check(_lib.stencil_time_copy(ctypes.c_void_p(tin.data_ptr()), ctypes.c_void_p(tout.data_ptr()), nbytes,
+                                  int(burst), int(reps), ctypes.byref(mean), ctypes.byref(lo),
+                                  Stencil._stream_ptr(stream)))
+    return mean.value, lo.value
 
 
 def sweep_reduce(sizes: Sequence[Tuple[int, int]], mean_ms: Sequence[float], status: Sequence[int],
@@ -323,7 +338,8 @@ class Stencil:
 
 
 class Regressor:
-    """Nearest-neighbour regressor over (f(s), w, y) tuples (Sections 4.2 / 4.3)."""
+    """Regressor over (f(s), w, y) tuples (Sections 4.2 / 4.3): nearest neighbour, or, after
+    `fit_forest`, a random forest of regression trees (Section 5)."""
 
     def __init__(self):
         self._h = ctypes.c_void_p()
@@ -338,6 +354,27 @@ class Regressor:
 
     def add(self, features: Sequence[float], wg: Tuple[int, int], value: float):
         _check(_lib.stencil_regressor_add(self._h, _dbls(features), len(features), int(wg[0]), int(wg[1]), float(value)))
+
+    def fit_forest(self, bootstrap=None, masks=None, n_trees: Optional[int] = None, min_leaf: int = 1,
+                   max_depth: int = 64):
+        """bootstrap: n_trees rows of tuple indices (None: every tuple once per tree); masks: n_trees
+        rows of n_features + 2 flags (None: every input open).  The draws are the caller's."""
+        if n_trees is None:
+            n_trees = len(bootstrap) if bootstrap is not None else len(masks) if masks is not None else 1
+        b_arr, n_rows = None, 0
+        if bootstrap is not None:
+            assert len(bootstrap) == n_trees
+            n_rows = len(bootstrap[0])
+            flat = [int(i) for row in bootstrap for i in row]
+            assert len(flat) == n_trees * n_rows
+            b_arr = (ctypes.c_int * len(flat))(*flat)
+        m_arr = None
+        if masks is not None:
+            assert len(masks) == n_trees
+            flat = [1 if m else 0 for row in masks for m in row]
+            m_arr = (ctypes.c_ubyte * len(flat))(*flat)
+        _check(_lib.stencil_regressor_fit_forest(self._h, int(n_trees), int(n_rows), b_arr, m_arr, int(min_leaf),
+                                                 int(max_depth)))
 
     def predict(self, features: Sequence[float], wg: Tuple[int, int]) -> float:
         y = ctypes.c_double()

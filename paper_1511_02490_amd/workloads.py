@@ -199,6 +199,19 @@ def synthetic_scenarios(n: int, seed: int = BASE_SEED + 100) -> List[Workload]:
     return out
 
 
+def forest_draws(n_trees: int, n_tuples: int, n_inputs: int, seed: int = BASE_SEED + 200,
+                 open_fraction: float = 0.7) -> Tuple[List[List[int]], List[List[bool]]]:
+    """The random draws of a random forest (Section 5's regressor), made here so that whoever grows
+    the forest is handed them as data: per tree a bootstrap sample of the tuple indices (n_tuples
+    draws with repetition) and the subset of the inputs open to it (each with probability
+    `open_fraction`; the last two inputs, the workgroup size, always)."""
+    rng = np.random.default_rng(seed)
+    bootstrap = rng.integers(0, n_tuples, size=(n_trees, n_tuples)).tolist()
+    masks = rng.random((n_trees, n_inputs)) < open_fraction
+    masks[:, n_inputs - 2:] = True
+    return bootstrap, masks.tolist()
+
+
 def real_scenarios() -> List[Workload]:
     """The reference applications of Section 5 that this build defines (Gaussian blur, Game of
     Life, heat equation) on the paper's four matrix sizes."""

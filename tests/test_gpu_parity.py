@@ -429,6 +429,12 @@ def test_device_copy_and_workgroup_numbering_option(ls):
     x = torch.zeros(64, device="cuda")
     with pytest.raises(ls.StencilError):
         ls.device_copy(x[:32], x[16:48])                             # overlap
+    a = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda")
+    b = torch.zeros_like(a)
+    mean_ms, min_ms = ls.time_copy(a, b, burst=4, reps=5)
+    assert 0.0 < min_ms <= mean_ms < 10.0 and torch.equal(a, b)
+    with pytest.raises(ls.StencilError):
+        ls.time_copy(a, b, burst=0, reps=5)
     # the XCD-aware numbering of workgroups changes the schedule, never the values
     w = wl.config(4, rows=200, cols=312)
     g = w.grid()

@@ -240,3 +240,45 @@ def test_algorithm2_regression_matches_definition():
     assert len([c for c in cands if c[0] * c[1] <= 1024 and not big.is_legal(*c)]) > 5
     with pytest.raises(ls.StencilError):
         scen[0].predict_regression(ls.Regressor(), cands)
+
+
+def test_random_forest_regressor_matches_definition():
+    """The library's forest against the oracle's, given the same bootstrap rows and input masks:
+    the same cuts, so the same predictions to the last bit, on training tuples and elsewhere."""
+    rng = np.random.default_rng(23)
+    nf = 5
+    scen_f = rng.random((9, nf)) * np.array([4096.0, 4096.0, 8.0, 30.0, 1.0])
+    sizes = tuning.enumerate_sizes("pow2", 256)
+    reg = ls.Regressor()
+    xs, ys, fs, ws = [], [], [], []
+    for f in scen_f.tolist():
+        for w in sizes:
+            if rng.random() < 0.7:
+                y = float(math.log(f[0] * f[1]) / (w[0] * w[1]) ** 0.5 + 0.3 * abs(math.log2(w[1]) - 5) + 0.05 * rng.random())
+                reg.add(f, w, y)
+                xs.append(list(f) + [float(w[0]), float(w[1])]); ys.append(y); fs.append(f); ws.append(w)
+    n, ni = len(ys), nf + 2
+    probes = [(f, w) for f in (rng.random((6, nf)) * np.array([4096.0, 4096.0, 8.0, 30.0, 1.0])).tolist() for w in sizes[::3]]
+    probes += list(zip(fs, ws))[::5]
+    for n_trees, n_rows, min_leaf, max_depth in [(1, 0, 1, 64), (5, n, 2, 6), (8, n // 2, 1, 64), (3, n, 7, 2)]:
+        bootstrap = rng.integers(0, n, size=(n_trees, n_rows)).tolist() if n_rows else None
+        masks = (rng.random((n_trees, ni)) < 0.6)
+        masks[:, ni - 1] = True                                  # never a tree without an open input
+        masks = masks.tolist() if n_rows else None
+        reg.fit_forest(bootstrap, masks, n_trees=n_trees, min_leaf=min_leaf, max_depth=max_depth)
+        forest = tuning.grow_forest(xs, ys, bootstrap if bootstrap else [list(range(n))] * n_trees,
+                                    masks if masks else [[True] * ni] * n_trees, min_leaf, max_depth)
+        for f, w in probes:
+            assert reg.predict(f, w) == tuning.predict_forest(forest, list(f) + [float(w[0]), float(w[1])])
+    # a fully grown single tree on all tuples reproduces its training targets (the tuples are distinct)
+    reg.fit_forest(None, None, n_trees=1)
+    assert all(abs(reg.predict(f, w) - y) < 1e-12 for f, w, y in zip(fs, ws, ys))
+    # adding a tuple discards the forest: back to the nearest-neighbour rule
+    reg.add(fs[0], (3, 3), 42.0)
+    assert reg.predict(fs[0], (3, 3)) == 42.0 and math.isnan(reg.predict(fs[0], (5, 5)))
+    with pytest.raises(ls.StencilError):
+        reg.fit_forest([[0, n + 5]], None)                       # bootstrap index out of range
+    with pytest.raises(ls.StencilError):
+        reg.fit_forest(None, [[False] * ni])                     # a tree with no input
+    with pytest.raises(ls.StencilError):
+        ls.Regressor().fit_forest(None, None, n_trees=2)         # nothing to grow on
