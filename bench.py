@@ -43,7 +43,8 @@ MAPPINGS = {
                ("stream", 64, 4), ("stream", 89, 4), ("stream", 134, 4)],
     "life": [("local", 1, 1), ("local", 1, 16), ("local", 2, 16), ("direct", 1, 16), ("direct", 2, 16),
              ("temporal", 2, 16, 2), ("temporal", 4, 16, 2), ("temporal", 2, 16, 4), ("temporal", 4, 16, 4),
-             ("temporal", 8, 16, 4)],
+             ("temporal", 8, 16, 4), ("stream", 16, 4, 4), ("stream", 40, 4, 6), ("stream", 40, 4, 8),
+             ("stream", 20, 8, 8)],
 }
 
 

@@ -19,6 +19,7 @@
 #include "temporal_kernel.h"
 #include "tile_kernel.h"
 #include "march_kernel.h"
+#include "life_stream_kernel.h"
 
 namespace {
 
@@ -116,7 +117,9 @@ TileGeom tile_geom(const stencil *s, const Variant &v, int wr, int wc) {
     } else if (v.staging == STENCIL_STAGING_STREAM) {
         // one wavefront per tile: s->cr rows of a strip of 62..64 vectors; no local memory
         g.th = s->cr;
-        g.tw = v.fuses ? sk::stream_cols(s->temporal_depth) : sk::march_vectors(s->hw, s->he) * 4;
+        g.tw = !v.fuses ? sk::march_vectors(s->hw, s->he) * 4
+               : s->kernel == STENCIL_LIFE ? sk::life_stream_cols(s->temporal_depth, v.cc / 4)
+                                           : sk::stream_cols(s->temporal_depth);
         g.pitch = 4;
         g.plane = 0;
         g.lds_bytes = 0;
@@ -154,7 +157,8 @@ sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, 
     a.pitch = g.pitch;
     a.plane = g.plane;
     {
-        const unsigned items = (unsigned)(g.pitch / CC);   // vectors (elements when CC = 1) per staged row
+        // vectors (elements when CC = 1) per staged row; kernels that stage nothing have none
+        const unsigned items = std::max(1u, (unsigned)(g.pitch / CC));
         a.stage_magic = (unsigned)((0x100000000ull + items - 1) / items);
     }
     const size_t row_bytes = (size_t)s->cols * sizeof(T);
@@ -249,6 +253,45 @@ hipError_t launch_stream(const stencil *s, const void *in, void *out, int wr, in
     default: return hipErrorInvalidValue;
     }
 #undef STREAM_LAUNCH
+    return hipGetLastError();
+}
+
+// Game of Life, `depth` generations per launch in registers (life_stream_kernel.h).
+template <int B, int WORDS>
+hipError_t launch_life_stream(const stencil *s, const void *in, void *out, int wr, int wc, int depth,
+                              hipStream_t stream) {
+    using Halo = sk::HaloC<1, 1, 1, 1>;
+    constexpr int kMaxT = 256;
+    if (depth < 1 || depth > sk::kLifeStreamMaxDepth) return hipErrorInvalidValue;
+    const int CR = s->cr;   // rows per segment
+    unsigned blocks;
+    size_t lds;
+    auto a = make_args<sk::OpLife, Halo, 0, 16>(s, STENCIL_STAGING_STREAM, in, out, wr, wc, &blocks, &lds);
+    const int strip_cols = sk::life_stream_cols(depth, WORDS);
+    a.tiles_c = (int)((s->cols + strip_cols - 1) / strip_cols);
+    a.n_tiles = (int)((s->rows + CR - 1) / CR) * a.tiles_c;
+    a.xcd_chunk = 0;
+    const unsigned waves_per_block = (unsigned)(wr * wc) / 64u;
+    blocks = ((unsigned)a.n_tiles + waves_per_block - 1) / waves_per_block;
+    const dim3 grid(blocks), block(wc, wr);
+#define LIFE_STREAM_LAUNCH(D)                                                                                  \
+    if (a.vec_ok)                                                                                              \
+        hipLaunchKernelGGL((sk::life_stream_kernel<B, D, WORDS, true, kMaxT>), grid, block, 0, stream, a, CR); \
+    else                                                                                                       \
+        hipLaunchKernelGGL((sk::life_stream_kernel<B, D, WORDS, false, kMaxT>), grid, block, 0, stream, a, CR);\
+    break
+    switch (depth) {
+    case 1: LIFE_STREAM_LAUNCH(1);
+    case 2: LIFE_STREAM_LAUNCH(2);
+    case 3: LIFE_STREAM_LAUNCH(3);
+    case 4: LIFE_STREAM_LAUNCH(4);
+    case 5: LIFE_STREAM_LAUNCH(5);
+    case 6: LIFE_STREAM_LAUNCH(6);
+    case 7: LIFE_STREAM_LAUNCH(7);
+    case 8: LIFE_STREAM_LAUNCH(8);
+    default: return hipErrorInvalidValue;
+    }
+#undef LIFE_STREAM_LAUNCH
     return hipGetLastError();
 }
 
@@ -441,6 +484,28 @@ void reg_stream(std::vector<Variant> &r) {
     reg_stream_one<Op, KID, sk::kConstant>(r);
 }
 
+template <int B, int WORDS>
+void reg_life_stream_one(std::vector<Variant> &r) {
+    Variant v;
+    v.staging = STENCIL_STAGING_STREAM;
+    v.kernel = STENCIL_LIFE;
+    v.border = B;
+    v.hn = v.hs = v.he = v.hw = 1;
+    v.cr = 0;
+    v.cc = 4 * WORDS;
+    v.max_threads = 256;
+    v.staged_bytes = 0;
+    v.fuses = true;
+    v.launch = &launch_life_stream<B, WORDS>;
+    r.push_back(v);
+}
+
+template <int WORDS>
+void reg_life_stream(std::vector<Variant> &r) {
+    reg_life_stream_one<sk::kWrap, WORDS>(r);
+    reg_life_stream_one<sk::kConstant, WORDS>(r);
+}
+
 template <class Op, int KID, int B, class Halo>
 void reg_march_one(std::vector<Variant> &r) {
     Variant v;
@@ -561,6 +626,9 @@ const std::vector<Variant> &registry() {
         reg_stream<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM>(r);
         reg_march<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<2, 2, 2, 2>>(r);
         reg_march<sk::OpSinCos, STENCIL_SINCOS, sk::HaloC<1, 5, 3, 0>>(r);
+        reg_life_stream<1>(r);
+        reg_life_stream<2>(r);
+        reg_life_stream<4>(r);
         reg_life_temporal<1>(r);
         reg_life_temporal<2>(r);
         reg_life_temporal<4>(r);

@@ -323,6 +323,35 @@ def test_register_marching_single_application_kernels(ls, border):
         ls.Stencil.from_workload(custom(wl.SINCOS, 32, 32, (2, 0, 1, 3), border)).set_mapping("stream", 16, 4)
 
 
+@pytest.mark.parametrize("border", ["wrap", "constant"])
+def test_register_streaming_life_bit_exact(ls, border):
+    """Generations kept in registers, 4 / 8 / 16 cells per lane: matrices wider than one strip, ragged
+    ones (cell-by-cell loads), ones smaller than a strip, live padding, unaligned rows."""
+    for rows, cols, iters in [(70, 1200, 9), (37, 256, 5), (130, 83, 6), (64, 512, 8), (5, 3, 7), (1, 1, 4),
+                              (40, 976, 17), (33, 2064, 11)]:
+        w = wl.config(2, rows=rows, cols=cols, iters=iters)
+        w.border = border
+        for cells in (4, 8, 16):
+            for depth, h, wg in [(1, 16, (1, 64)), (2, 32, (2, 64)), (3, 7, (4, 64)), (4, 64, (8, 8)), (5, 16, (2, 32)),
+                                 (6, 23, (1, 64)), (7, 128, (1, 128)), (8, 38, (1, 64))]:
+                check(ls, w, wg, blocking=("stream", h, cells, depth))
+    w1 = wl.config(2, rows=80, cols=96, iters=6)
+    w1.border, w1.pad = "constant", 1.0                            # live padding
+    check(ls, w1, (1, 64), blocking=("stream", 16, 4, 4))
+    check(ls, w1, (1, 64), blocking=("stream", 16, 16, 8))
+    check(ls, w1, (1, 64), blocking=("stream", 16, 8, 3), offset=5)
+    st = ls.Stencil.from_workload(wl.config(2, rows=64, cols=64))
+    st.set_mapping("stream", 32, 8)
+    assert st.max_wg_size() == 256 and st.tile_bytes(1, 64) == 0
+    assert st.is_legal(1, 64) and not st.is_legal(4, 4) and not st.is_legal(8, 64)
+    with pytest.raises(ls.StencilError):
+        st.set_mapping("stream", 32, 2)                            # 4, 8 or 16 cells per lane
+    clamp = wl.config(2, rows=64, cols=64)
+    clamp.border = "clamp"
+    with pytest.raises(ls.StencilError):
+        ls.Stencil.from_workload(clamp).set_mapping("stream", 32, 16)
+
+
 def test_temporal_blocking_not_offered_for_other_regions(ls):
     st = ls.Stencil.from_workload(wl.config(1))                    # 5x5 region
     with pytest.raises(ls.StencilError):
