@@ -171,12 +171,22 @@ def cpu_baseline(wl_mod, w, target_seconds):
         if dt >= target_seconds / 3 or iters >= w.iters:
             break
         iters = int(min(w.iters, max(2 * iters, iters * 0.8 * target_seconds / max(dt, 1e-3))))
+    # the same oracle on one thread, on a sample a tenth the size (context for the threaded figure)
+    it1 = max(1, iters // 10)
+    rows1 = rows if iters >= 10 else max(64, rows // 10)
+    g1 = g[:rows1]
+    t0 = time.perf_counter()
+    oracle.apply(g1, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, it1, threads=1)
+    dt1 = time.perf_counter() - t0
+    oracle.apply(g[:8], w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1, threads=threads)   # thread count back
     return {
         "value": rows * w.cols * iters / dt / 1e9,
         "unit": "Gcells/s",
         "cores": threads,
         "kind": "oracle",
         "sample": "whole %d x %d matrix, %d of %d iterations, %.1f s" % (w.rows, w.cols, iters, w.iters, dt),
+        "single_thread": {"value": rows1 * w.cols * it1 / dt1 / 1e9, "unit": "Gcells/s", "cores": 1,
+                          "sample": "first %d rows, %d iterations, %.1f s" % (rows1, it1, dt1)},
     }
 
 
