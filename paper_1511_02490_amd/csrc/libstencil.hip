@@ -1090,6 +1090,53 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
     return STENCIL_OK;
 }
 
+int stencil_sweep_configs(stencil_t *s, const void *in, void *out, int iters, const stencil_config_t *configs, int n,
+                          int reps, double *mean_ms, int *status, int *best_index, void *stream) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    if (n < 0 || (n > 0 && !configs) || !mean_ms || !status) return fail(STENCIL_E_INVALID, "bad configuration list");
+    if (iters < 1) return fail(STENCIL_E_INVALID, "a sweep needs iters >= 1");
+    int rc = validate_buffers(s, in, out);
+    if (rc != STENCIL_OK) return rc;
+    const double nan = std::numeric_limits<double>::quiet_NaN();
+    const int staging0 = s->staging, cr0 = s->cr, cc0 = s->cc, depth0 = s->temporal_depth;
+    int best = -1;
+    for (int k = 0; k < n; ++k) {
+        const stencil_config_t &c = configs[k];
+        mean_ms[k] = nan;
+        status[k] = STENCIL_E_INVALID;
+        // a mapping the scenario does not have, or a depth the mapping does not have: skipped
+        s->temporal_depth = depth0;       // "as is" means as it was when the sweep began
+        if (stencil_set_mapping(s, c.staging, c.cells_rows, c.cells_cols) != STENCIL_OK) continue;
+        if (c.depth != 0 && stencil_set_option(s, STENCIL_OPT_TEMPORAL_DEPTH, c.depth) != STENCIL_OK) continue;
+        const Variant *v = find_variant(s);
+        if (v && check_legal(s, v, c.wg_rows, c.wg_cols) == STENCIL_E_INVALID) continue;
+        int st = STENCIL_E_REFUSED, b = -1;
+        rc = stencil_sweep_wg(s, in, out, iters, &c.wg_rows, &c.wg_cols, 1, 0, 0, reps, &mean_ms[k], nullptr, nullptr,
+                              nullptr, &st, &b, nullptr, stream);
+        if (rc != STENCIL_OK) break;      // a runtime error ends the sweep
+        status[k] = st;
+        if (st == STENCIL_OK && (best < 0 || mean_ms[k] < mean_ms[best])) best = k;
+    }
+    if (rc == STENCIL_OK && best >= 0) {
+        // leave the scenario on the fastest configuration, remembered for stencil_run(0, 0)
+        const stencil_config_t &c = configs[best];
+        s->temporal_depth = depth0;
+        (void)stencil_set_mapping(s, c.staging, c.cells_rows, c.cells_cols);
+        if (c.depth != 0) (void)stencil_set_option(s, STENCIL_OPT_TEMPORAL_DEPTH, c.depth);
+        s->best_rows = c.wg_rows;
+        s->best_cols = c.wg_cols;
+    } else {
+        s->staging = staging0;
+        s->cr = cr0;
+        s->cc = cc0;
+        s->temporal_depth = depth0;
+        s->best_rows = s->best_cols = 0;
+    }
+    if (best_index) *best_index = best;
+    if (rc == STENCIL_OK) g_err[0] = '\0';
+    return rc;
+}
+
 int stencil_device_copy(const void *in, void *out, int64_t bytes, void *stream) {
     if (!in || !out || bytes < 0) return fail(STENCIL_E_INVALID, "bad arguments to stencil_device_copy");
     if ((uintptr_t)in % 16 || (uintptr_t)out % 16) return fail(STENCIL_E_INVALID, "buffers must be 16-byte aligned");

@@ -63,6 +63,7 @@ def _load() -> ctypes.CDLL:
         "stencil_run": (c_int, [vp, vp, vp, c_int, c_int, c_int, vp]),
         "stencil_sweep_wg": (c_int, [vp, vp, vp, c_int, ip, ip, c_int, c_int, c_int, c_int,
                                      dp, dp, dp, dp, ip, ip, dp, vp]),
+        "stencil_sweep_configs": (c_int, [vp, vp, vp, c_int, vp, c_int, c_int, dp, ip, ip, vp]),
         "stencil_device_copy": (c_int, [vp, vp, c_i64, vp]),
         "stencil_time_copy": (c_int, [vp, vp, c_i64, c_int, c_int, dp, dp, vp]),
         "stencil_sweep_reduce": (c_int, [ip, ip, c_int, dp, ip, c_dbl, ip, dp, dp]),
@@ -90,7 +91,7 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
            "stencil_set_mapping", "stencil_get_mapping", "stencil_set_option", "stencil_max_wg_size", "stencil_tile_bytes",
-           "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg",
+           "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg", "stencil_sweep_configs",
            "stencil_device_copy", "stencil_time_copy", "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
            "stencil_predict_wg", "stencil_regressor_create", "stencil_regressor_destroy",
@@ -165,6 +166,11 @@ def baseline_wg(performance: Sequence[Sequence[float]]) -> int:
     best = ctypes.c_int(-1)
     _check(_lib.stencil_baseline_wg(_dbls(flat), n_s, n_w, ctypes.byref(best)))
     return best.value
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [("staging", ctypes.c_int), ("cells_rows", ctypes.c_int), ("cells_cols", ctypes.c_int),
+                ("depth", ctypes.c_int), ("wg_rows", ctypes.c_int), ("wg_cols", ctypes.c_int)]
 
 
 class SweepResult:
@@ -314,6 +320,24 @@ class Stencil:
                                      ctypes.byref(best), ctypes.byref(sp), self._stream_ptr(stream)))
         return SweepResult([tuple(s) for s in sizes], list(mean)[:n], list(mn)[:n], list(med)[:n],
                            list(sd)[:n], list(status)[:n], best.value, sp.value)
+
+    def sweep_configs(self, tin, tout, configs, iters: int = 1, reps: int = 30, stream=None):
+        """Sweep whole configurations: each is (staging, cells_rows, cells_cols, depth, (wg_rows,
+        wg_cols)) with depth 0 = leave as is.  Returns (mean_ms list, status list, best index); the
+        scenario is left on the fastest configuration."""
+        self._check_tensors(tin, tout)
+        n = len(configs)
+        arr = (_Config * max(n, 1))()
+        for k, (staging, cr, cc, depth, wg) in enumerate(configs):
+            sg = _STAGINGS[staging] if isinstance(staging, str) else int(staging)
+            arr[k] = _Config(sg, int(cr), int(cc), int(depth), int(wg[0]), int(wg[1]))
+        mean = (ctypes.c_double * max(n, 1))()
+        status = (ctypes.c_int * max(n, 1))()
+        best = ctypes.c_int(-1)
+        _check(_lib.stencil_sweep_configs(self._h, ctypes.c_void_p(tin.data_ptr()), ctypes.c_void_p(tout.data_ptr()),
+                                          int(iters), ctypes.cast(arr, ctypes.c_void_p), n, int(reps), mean, status,
+                                          ctypes.byref(best), self._stream_ptr(stream)))
+        return list(mean)[:n], list(status)[:n], best.value
 
     def predict_regression(self, regressor: "Regressor", candidates: Sequence[Tuple[int, int]],
                            fitness: str = "reciprocal") -> Tuple[Tuple[int, int], int]:

@@ -448,6 +448,35 @@ def test_error_paths_do_not_launch(ls):
     assert rel_err(tout.cpu().numpy(), ref) <= REL_1
 
 
+def test_sweep_over_whole_configurations(ls):
+    """Mapping, fused applications and workgroup size swept together; the scenario is left on the
+    fastest configuration and still computes the oracle's result with it."""
+    w = wl.config(3, rows=512, cols=768, iters=8)
+    g = w.grid()
+    st = ls.Stencil.from_workload(w)
+    tin = torch.from_numpy(g).cuda()
+    tout = torch.empty_like(tin)
+    configs = [("local", 1, 1, 0, (4, 4)), ("direct", 2, 4, 0, (4, 16)), ("temporal", 2, 4, 4, (16, 16)),
+               ("stream", 23, 4, 8, (1, 64)), ("stream", 23, 4, 8, (4, 4)),      # not whole wavefronts: refused
+               ("temporal", 2, 4, 8, (16, 16)),                                   # depth the mapping lacks
+               ("direct", 3, 4, 0, (4, 16)),                                      # no such mapping
+               ("local", 2, 4, 0, (64, 32))]                                      # above W_max: refused
+    mean, status, best = st.sweep_configs(tin, tout, configs, iters=8, reps=5)
+    assert status == [ls.OK, ls.OK, ls.OK, ls.OK, ls.E_REFUSED, ls.E_INVALID, ls.E_INVALID, ls.E_REFUSED]
+    assert all((m > 0) == (s == ls.OK) for m, s in zip(mean, status)) and all(np.isnan(m) for m, s in zip(mean, status) if s != ls.OK)
+    assert best == int(np.nanargmin(mean)) and status[best] == ls.OK
+    sg, cr, cc = st.get_mapping()
+    assert (sg, cr, cc) == ({"local": 0, "direct": 1, "temporal": 2, "stream": 3}[configs[best][0]],) + tuple(configs[best][1:3])
+    st.run(tin, tout, w.iters, (0, 0))                               # the remembered size of that configuration
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(tout.cpu().numpy(), oracle.apply_workload(w, g))
+    # nothing usable: the scenario keeps the configuration it had
+    before = st.get_mapping()
+    mean, status, best = st.sweep_configs(tin, tout, [("direct", 3, 4, 0, (4, 16))], iters=1, reps=3)
+    assert best == -1 and status == [ls.E_INVALID] and st.get_mapping() == before
+    st.close()
+
+
 def test_device_copy_and_workgroup_numbering_option(ls):
     for n in (1, 15, 16, 17, 4096, 1000003):
         a = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
