@@ -27,6 +27,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+FP32_VECTOR_PEAK_TFLOPS = 157.3      # published: packed fp32 fma on 256 CUs x 4 SIMDs x 16 lanes at 2.4 GHz
+
+
+def flops_per_cell_update(w):
+    """fp32 operations the customising function states per cell and application (None: integer)."""
+    n, s_, e, w_ = w.halo
+    taps = (n + s_ + 1) * (e + w_ + 1)
+    if w.kernel == "heat":
+        return 7                     # three adds, 4u, the subtraction, alpha * t, the final add
+    if w.kernel == "weighted_sum":
+        return 2 * taps - 1 if w.dtype == "f32" else None
+    if w.kernel == "sincos":
+        return 3 * taps + 1          # per cell of the region: w * sin + cos and the running sum; sin and cos once
+    return None
 
 # mappings swept besides the paper's one element per work-item with a local-memory tile:
 # (staging, cells_rows, cells_cols)
@@ -107,6 +121,44 @@ def sweep_burst(w):
 # the vectorised mapping each kernel is usually fastest with (predictor study)
 FAST_MAPPING = {"weighted_sum": ("local", 2, 4), "heat": ("direct", 2, 4), "sincos": ("local", 2, 4),
                 "life": ("direct", 2, 16)}
+
+
+# strong configurations of each kernel, swept together (stencil_sweep_configs) for the per-workload
+# figures of the workloads that are not the one being benchmarked:
+# (staging, cells_rows, cells_cols, applications per launch or 0, workgroup size)
+STRONG_CONFIGS = {
+    "weighted_sum": [("local", 2, 4, 0, (16, 8)), ("local", 2, 4, 0, (8, 8)), ("direct", 2, 4, 0, (8, 16)),
+                     ("direct", 4, 4, 0, (4, 128)), ("local", 4, 4, 0, (16, 8))],
+    "life": [("direct", 2, 16, 0, (2, 128)), ("temporal", 2, 16, 4, (64, 8)), ("stream", 40, 4, 8, (1, 64)),
+             ("stream", 40, 4, 8, (4, 64)), ("stream", 40, 4, 6, (1, 64))],
+    "heat": [("direct", 2, 4, 0, (4, 16)), ("temporal", 2, 4, 4, (32, 32)), ("stream", 38, 4, 8, (1, 64)),
+             ("stream", 38, 4, 8, (2, 64)), ("stream", 40, 4, 6, (1, 64))],
+    "sincos": [("local", 4, 4, 0, (8, 32)), ("local", 2, 4, 0, (18, 14)), ("stream", 89, 4, 0, (4, 64)),
+               ("stream", 134, 4, 0, (32, 8)), ("stream", 134, 4, 0, (1, 64))],
+}
+
+
+def best_known_configuration(ls, torch, o, reps):
+    """The fastest of the kernel's strong configurations on workload `o`, per application."""
+    st = ls.Stencil.from_workload(o)
+    a = torch.from_numpy(o.grid()).cuda()
+    b = torch.empty_like(a)
+    burst = sweep_burst(o)
+    configs = STRONG_CONFIGS[o.kernel]
+    mean, status, best = st.sweep_configs(a, b, configs, iters=burst, reps=reps)
+    st.close()
+    del a, b
+    if best < 0:
+        return None
+    c = configs[best]
+    per_app_ms = mean[best] / burst
+    fused = max(1, c[3])
+    # a launch moves the matrix once whatever it fuses: bytes per launch over the launch's time
+    gbs = o.cells * o.bytes_per_cell_update / (per_app_ms * fused) / 1e6
+    return {"mapping": mapping_name((c[0], c[1], c[2]) + ((c[3],) if c[3] else ())), "wg": list(c[4]),
+            "applications_per_launch": fused, "ms_per_application": per_app_ms,
+            "gcells_s": o.cells / per_app_ms / 1e6, "algorithmic_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
+            "configurations_swept": len(configs)}
 
 
 def leave_one_out_prediction(ls, wl, torch, index, mapping_of, reps):
@@ -282,6 +334,12 @@ def main():
                                   "oracle_wg": list(res.best), "performance": res.best_ms / t_p,
                                   "speedup_over_4x4": (t4 / t_p) if not math.isnan(t4) else None}
             apply_mapping(st, blocking)
+            # the other workloads with the fastest kernels known for them (any mapping)
+            for i in range(5):
+                if i != index:
+                    o = wl.config(i)
+                    others.setdefault(o.name.split()[0], {})["best_known"] = best_known_configuration(
+                        ls, torch, o, max(5, args.reps // 3))
 
     for _ in range(warmup):
         st.run(tin, tout, w.iters, wg)
@@ -311,11 +369,19 @@ def main():
         label = "%s_kernel<%s> %dx%d cells/work-item, wg %dx%d" % (
             family, w.kernel, mapping[1], mapping[2], size[0], size[1]) + (
             ", %d applications/launch" % depth if depth > 1 else "")
-        return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(label),
-                "kernel": label, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg_bytes,
-                "applications_per_launch": depth,
-                "gcells_s": cells * depth / (kernel_ms * 1e-3) / 1e9}
+        out = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+               "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(label),
+               "kernel": label, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg_bytes,
+               "applications_per_launch": depth,
+               "gcells_s": cells * depth / (kernel_ms * 1e-3) / 1e9}
+        # kernels that vector arithmetic bounds rather than memory (the sin/cos stencil; fused
+        # applications): algorithmic fp32 operations against the published vector peak
+        flops = flops_per_cell_update(w)
+        if flops and (w.kernel == "sincos" or depth > 1):
+            tflops = flops * cells * depth / (kernel_ms * 1e-3) / 1e12
+            out["alu"] = {"bound": "alu", "achieved": tflops, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "frac": tflops / FP32_VECTOR_PEAK_TFLOPS, "flops_per_cell_update": flops}
+        return out
 
     # `roofline` prices the best kernel that makes ONE application per launch: that is the
     # kernel whose bytes are all compulsory.  A temporally blocked kernel moves the matrix once
