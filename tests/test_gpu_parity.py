@@ -613,7 +613,8 @@ def test_c2_full_size(ls):
     w = wl.config(1)
     g = w.grid()
     ref = oracle.apply_workload(w, g)
-    for wg, blocking in [((16, 16), (1, 1)), ((4, 64), (4, 4)), ((4, 64), ("direct", 1, 4))]:
+    for wg, blocking in [((16, 16), (1, 1)), ((4, 64), (4, 4)), ((4, 64), ("direct", 1, 4)), ((16, 8), (2, 4)),
+                         ((1, 64), ("stream", 16, 4))]:
         got = gpu_apply(ls, w, g, wg, blocking=blocking)
         assert rel_err(got, ref) <= REL_1
 
@@ -627,6 +628,10 @@ def test_c3_full_size_100_generations(ls):
     got = gpu_apply(ls, w, g, (4, 64), blocking=("direct", 1, 16))
     np.testing.assert_array_equal(got, ref)
     got = gpu_apply(ls, w, g, (8, 16), blocking=("temporal", 4, 16, 4))
+    np.testing.assert_array_equal(got, ref)
+    got = gpu_apply(ls, w, g, (1, 64), blocking=("stream", 40, 4, 8))         # 100 = 12 launches of 8 + one of 4
+    np.testing.assert_array_equal(got, ref)
+    got = gpu_apply(ls, w, g, (4, 64), blocking=("stream", 20, 8, 6))
     np.testing.assert_array_equal(got, ref)
     assert 0.02 < got.mean() < 0.2
 
@@ -648,7 +653,13 @@ def test_c4_full_size(ls):
     np.testing.assert_array_equal(got, ref)
     got = gpu_apply(ls, w, g, (2, 64), iters=100, blocking=("stream", 32, 4, 4))
     np.testing.assert_array_equal(got, ref)
+    got = gpu_apply(ls, w, g, (2, 64), iters=100, blocking=("stream", 38, 4, 8))
+    np.testing.assert_array_equal(got, ref)
+    got = gpu_apply(ls, w, g, (1, 64), iters=100, blocking=("stream", 40, 4, 6))
+    np.testing.assert_array_equal(got, ref)
+    d = gpu_apply(ls, w, g, (2, 64), iters=1000, blocking=("stream", 38, 4, 8))
     c = gpu_apply(ls, w, g, (8, 32), iters=1000, blocking=("temporal", 2, 4, 3))
+    np.testing.assert_array_equal(d, c)
     a = gpu_apply(ls, w, g, (4, 64), iters=1000, blocking=("direct", 1, 4))
     np.testing.assert_array_equal(a, c)
     b = gpu_apply(ls, w, g, (16, 16), iters=1000, blocking=(1, 1))
@@ -668,6 +679,8 @@ def test_c5_full_size_sampled_windows(ls):
     got = gpu_apply(ls, w, g, (2, 64), blocking=(4, 4))
     got1 = gpu_apply(ls, w, g, (16, 16), blocking=(1, 1))
     np.testing.assert_array_equal(got, got1)
+    for h, wg in [(134, (32, 8)), (89, (4, 64)), (64, (1, 64))]:      # the marching kernel, as bench.py launches it
+        np.testing.assert_array_equal(got, gpu_apply(ls, w, g, wg, blocking=("stream", h, 4)))
     N, S, E, W = w.halo
     R, C = w.rows, w.cols
     rng = np.random.default_rng(99)
