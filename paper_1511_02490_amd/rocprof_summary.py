@@ -115,6 +115,12 @@ def main():
                "plain copy kernel on the same matrix: %.0f GB/s."
                % (roof["kernel_ms"] * 1e6, roof["achieved"], roof["algorithmic_bytes_per_launch"], roof["frac"],
                   roof["peak"], roof["copy_kernel_gbs"]))
+    if float(stats[k]["AverageNs"]) < 15000.0:
+        out.append("")
+        out.append("(A kernel this short finishes faster than the host can issue the next launch while the profiler "
+                   "intercepts every call, so in a profiled run the event-timed figure includes idle gaps between "
+                   "launches; the trace's average is the kernel's own duration and agrees with bench.py's clock in "
+                   "an unprofiled run.)")
     out.append("")
     out.append("## HBM traffic counters (--pmc, one counter per run)")
     out.append("")
