@@ -50,9 +50,13 @@ def _load() -> ctypes.CDLL:
         lib.oracle_life_u8.argtypes = [p, p, i64, i64, i32, i32, i32, i32, i32, ctypes.c_uint8, i32, i32]
         lib.oracle_heat_f32.argtypes = [p, p, i64, i64, i32, f32, f32, i32, i32]
         lib.oracle_heat_f64.argtypes = [p, p, i64, i64, i32, f64, f64, i32, i32]
+        lib.oracle_sobel_f32.argtypes = [p, p, i64, i64, i32, f32, i32, i32]
+        lib.oracle_nms_f32.argtypes = [p, p, i64, i64, i32, f32, i32, i32]
+        lib.oracle_threshold_f32_u8.argtypes = [p, p, i64, i64, f32, i32]
         for fn in (lib.oracle_weighted_sum_f32, lib.oracle_sincos_f32, lib.oracle_weighted_sum_f64,
                    lib.oracle_weighted_sum_i32, lib.oracle_life_u8,
-                   lib.oracle_heat_f32, lib.oracle_heat_f64, lib.oracle_max_threads):
+                   lib.oracle_heat_f32, lib.oracle_heat_f64, lib.oracle_sobel_f32, lib.oracle_nms_f32,
+                   lib.oracle_threshold_f32_u8, lib.oracle_max_threads):
             fn.restype = i32
         _lib = lib
     return _lib
@@ -80,7 +84,8 @@ def apply(grid: np.ndarray, kernel: str, halo: Sequence[int], border: str, pad: 
     """`iters` applications of the stencil (Section 2) to `grid`; returns the final grid.
 
     kernel: "weighted_sum" (f32; also f64 and i32, chosen by the grid's dtype), "life" (u8, cells 0/1), "heat" (f32; scalars=(alpha,);
-    precision="f64" carries the state in float64 instead), "sincos" (f32).
+    precision="f64" carries the state in float64 instead), "sincos" (f32), and the Canny detector's
+    "sobel", "nms" (f32) and "threshold" (f32 in, u8 out; scalars=(level,)).
     halo = (north, south, east, west).  threads=0 leaves OpenMP's default.
     """
     lib = _load()
@@ -125,6 +130,19 @@ def apply(grid: np.ndarray, kernel: str, halo: Sequence[int], border: str, pad: 
             a = np.ascontiguousarray(grid, dtype=np.float32)
             out = np.empty_like(a)
             rc = lib.oracle_heat_f32(_ptr(a), _ptr(out), rows, cols, b, float(pad), alpha, int(iters), int(threads))
+    elif kernel in ("sobel", "nms"):
+        if (n, s, e, w) != (1, 1, 1, 1):
+            raise ValueError("%s has border region 1/1/1/1" % kernel)
+        a = np.ascontiguousarray(grid, dtype=np.float32)
+        out = np.empty_like(a)
+        fn = lib.oracle_sobel_f32 if kernel == "sobel" else lib.oracle_nms_f32
+        rc = fn(_ptr(a), _ptr(out), rows, cols, b, float(pad), int(iters), int(threads))
+    elif kernel == "threshold":
+        if (n, s, e, w) != (0, 0, 0, 0) or int(iters) != 1:
+            raise ValueError("threshold has no border region and is applied once (float in, bytes out)")
+        a = np.ascontiguousarray(grid, dtype=np.float32)
+        out = np.empty(a.shape, dtype=np.uint8)
+        rc = lib.oracle_threshold_f32_u8(_ptr(a), _ptr(out), rows, cols, float(scalars[0]), int(threads))
     else:
         raise ValueError("unknown kernel %r" % kernel)
     if rc != 0:

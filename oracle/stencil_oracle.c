@@ -192,6 +192,67 @@ static void step_heat_f32(const float *in, float *out, int64_t rows, int64_t col
         }
 }
 
+/* The three stencils of the Canny edge detector that Table 2 lists (sobel, nms, threshold).
+ * The paper names them and gives their border regions (1/1/1/1, 1/1/1/1, none) but not their
+ * formulas; these are this build's, each operation rounded to fp32 in the order written.
+ *
+ * sobel: gradient magnitude of the 3x3 Sobel operator,
+ *   gx = ((ne - nw) + 2 (e - w)) + (se - sw),  gy = ((sw - nw) + 2 (s - n)) + (se - ne),
+ *   out = sqrt(gx gx + gy gy). */
+static void step_sobel_f32(const float *in, float *out, int64_t rows, int64_t cols, int border, float pad)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            float nw = V_f32(in, rows, cols, r - 1, c - 1, border, pad);
+            float n = V_f32(in, rows, cols, r - 1, c, border, pad);
+            float ne = V_f32(in, rows, cols, r - 1, c + 1, border, pad);
+            float w = V_f32(in, rows, cols, r, c - 1, border, pad);
+            float e = V_f32(in, rows, cols, r, c + 1, border, pad);
+            float sw = V_f32(in, rows, cols, r + 1, c - 1, border, pad);
+            float s = V_f32(in, rows, cols, r + 1, c, border, pad);
+            float se = V_f32(in, rows, cols, r + 1, c + 1, border, pad);
+            float a = ne - nw, b = e - w, d = se - sw;
+            float two_b = 2.0f * b;
+            float ab = a + two_b;
+            float gx = ab + d;
+            float f = sw - nw, g = s - n, h = se - ne;
+            float two_g = 2.0f * g;
+            float fg = f + two_g;
+            float gy = fg + h;
+            float xx = gx * gx, yy = gy * gy;
+            float sum = xx + yy;
+            out[r * cols + c] = sqrtf(sum);
+        }
+}
+
+/* nms: non-maximum suppression along the two axes - a cell keeps its value if it is no smaller
+ * than both its west and east neighbours, or no smaller than both its north and south neighbours;
+ * otherwise it becomes 0. */
+static void step_nms_f32(const float *in, float *out, int64_t rows, int64_t cols, int border, float pad)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            float u = in[r * cols + c];
+            float n = V_f32(in, rows, cols, r - 1, c, border, pad);
+            float s = V_f32(in, rows, cols, r + 1, c, border, pad);
+            float e = V_f32(in, rows, cols, r, c + 1, border, pad);
+            float w = V_f32(in, rows, cols, r, c - 1, border, pad);
+            int keep = (u >= w && u >= e) || (u >= n && u >= s);
+            out[r * cols + c] = keep ? u : 0.0f;
+        }
+}
+
+/* threshold: no border region; a float matrix in, a byte matrix out: 1 where the value reaches
+ * the threshold, else 0 (a NaN reaches nothing). */
+static void step_threshold_f32_u8(const float *in, uint8_t *out, int64_t rows, int64_t cols, float level)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) out[r * cols + c] = in[r * cols + c] >= level ? 1 : 0;
+}
+
 /* The same step carried in fp64 (state included): used to attribute rounding error and
  * to check conservation, never as the parity reference. */
 static void step_heat_f64(const double *in, double *out, int64_t rows, int64_t cols,
@@ -299,4 +360,26 @@ int oracle_sincos_f32(const float *in, float *out, int64_t rows, int64_t cols,
 {
     set_threads(threads);
     ITERATE(float, step_sincos(src, dst, rows, cols, N, S, E, W, border, pad, w))
+}
+
+int oracle_sobel_f32(const float *in, float *out, int64_t rows, int64_t cols, int border, float pad,
+                     int iters, int threads)
+{
+    set_threads(threads);
+    ITERATE(float, step_sobel_f32(src, dst, rows, cols, border, pad))
+}
+
+int oracle_nms_f32(const float *in, float *out, int64_t rows, int64_t cols, int border, float pad,
+                   int iters, int threads)
+{
+    set_threads(threads);
+    ITERATE(float, step_nms_f32(src, dst, rows, cols, border, pad))
+}
+
+/* one application only: the output is of another type than the input */
+int oracle_threshold_f32_u8(const float *in, uint8_t *out, int64_t rows, int64_t cols, float level, int threads)
+{
+    set_threads(threads);
+    step_threshold_f32_u8(in, out, rows, cols, level);
+    return 0;
 }

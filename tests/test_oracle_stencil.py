@@ -480,3 +480,73 @@ def test_workload_recipes():
     g5 = wl.config(4, rows=256, cols=256).grid()
     assert -1.0 <= g5.min() and g5.max() < 1.0 and abs(g5.mean()) < 0.02
     assert wl.config(4).weights.shape == (7, 4)
+
+
+# ---- the Canny detector's stencils (Table 2: sobel, nms, threshold) ---------------------------
+
+_NP_MODE = {"clamp": "edge", "wrap": "wrap", "constant": "constant"}
+_NDI_MODE = {"clamp": "nearest", "wrap": "wrap", "constant": "constant"}
+
+
+def test_sobel_closed_forms():
+    """The Sobel operator answers a ramp a*c + b*r with (8a, 8b), so the magnitude is
+    8*sqrt(a^2 + b^2) in the interior; a constant field has no gradient anywhere under clamp."""
+    r, c = np.meshgrid(np.arange(9), np.arange(11), indexing="ij")
+    for a, b in [(1.0, 0.0), (0.0, 1.0), (3.0, 4.0), (-2.0, 0.5)]:
+        g = (a * c + b * r).astype(np.float32)
+        out = oracle.apply(g, "sobel", (1, 1, 1, 1), "clamp")
+        np.testing.assert_allclose(out[1:-1, 1:-1], 8.0 * math.hypot(a, b), rtol=1e-6)
+    assert np.all(oracle.apply(np.full((5, 6), 7.5, np.float32), "sobel", (1, 1, 1, 1), "clamp") == 0.0)
+    # orientation by hand: one bright cell; its west neighbour sees it to the east (gx = 2), the
+    # cell north-west of it sees it to the south-east (gx = gy = 1)
+    g = np.zeros((5, 5), np.float32)
+    g[2, 2] = 1.0
+    out = oracle.apply(g, "sobel", (1, 1, 1, 1), "constant")
+    assert out[2, 1] == 2.0 and out[2, 3] == 2.0 and out[1, 2] == 2.0 and out[2, 2] == 0.0
+    assert out[1, 1] == np.float32(math.sqrt(2.0)) and out[0, 0] == 0.0
+
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_sobel_matches_library_operator(border):
+    g = wl.config(0, rows=23, cols=31).grid() * np.float32(10.0)
+    out = oracle.apply(g, "sobel", (1, 1, 1, 1), border, pad=2.5)
+    g64 = g.astype(np.float64)
+    kx = np.array([[-1.0, 0.0, 1.0], [-2.0, 0.0, 2.0], [-1.0, 0.0, 1.0]])
+    gx = ndi.correlate(g64, kx, mode=_NDI_MODE[border], cval=2.5)
+    gy = ndi.correlate(g64, kx.T, mode=_NDI_MODE[border], cval=2.5)
+    np.testing.assert_allclose(out, np.hypot(gx, gy), rtol=2e-6, atol=2e-5)
+    if border != "constant":      # the library's own (separable) Sobel filter pads its passes one by one
+        np.testing.assert_allclose(np.hypot(ndi.sobel(g64, axis=1, mode=_NDI_MODE[border]),
+                                            ndi.sobel(g64, axis=0, mode=_NDI_MODE[border])), np.hypot(gx, gy), rtol=1e-12)
+
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_nms_by_hand_and_by_shifted_arrays(border):
+    # by hand: a ridge along a row survives (maximal north-south), its flanks do not
+    g = np.array([[1, 1, 1, 1], [5, 6, 5, 6], [2, 4, 2, 3], [0, 3, 0, 0]], np.float32)
+    out = oracle.apply(g, "nms", (1, 1, 1, 1), "constant")            # padding 0 around the matrix
+    np.testing.assert_array_equal(out[0], g[0])                       # a row of equals: none smaller than west / east
+    np.testing.assert_array_equal(out[1], g[1])                       # every ridge cell tops its column neighbours
+    np.testing.assert_array_equal(out[2], [0, 4, 0, 3])               # below the ridge only west-east maxima survive
+    np.testing.assert_array_equal(out[3], [0, 3, 0, 0])
+    # whole arrays at once: neighbours as padded, shifted copies
+    x = wl.config(0, rows=17, cols=29).grid()
+    p = np.pad(x, 1, mode=_NP_MODE[border], **({"constant_values": 0.25} if border == "constant" else {}))
+    u, n, s, w, e = p[1:-1, 1:-1], p[:-2, 1:-1], p[2:, 1:-1], p[1:-1, :-2], p[1:-1, 2:]
+    expect = np.where(((u >= w) & (u >= e)) | ((u >= n) & (u >= s)), u, np.float32(0.0))
+    np.testing.assert_array_equal(oracle.apply(x, "nms", (1, 1, 1, 1), border, pad=0.25), expect)
+    # a strict minimum of its four neighbours never survives; survivors keep their value
+    out = oracle.apply(x, "nms", (1, 1, 1, 1), "wrap")
+    assert set(np.unique(out[out != x])) <= {0.0}
+
+
+def test_threshold_bytes_out():
+    x = np.array([[0.1, 0.5, 0.49999997], [np.nan, np.inf, -1.0]], np.float32)
+    out = oracle.apply(x, "threshold", (0, 0, 0, 0), "clamp", scalars=(0.5,))
+    assert out.dtype == np.uint8
+    np.testing.assert_array_equal(out, [[0, 1, 0], [0, 1, 0]])
+    g = wl.config(0, rows=40, cols=33).grid()
+    np.testing.assert_array_equal(oracle.apply(g, "threshold", (0, 0, 0, 0), "wrap", scalars=(0.3,)),
+                                  (g >= np.float32(0.3)).astype(np.uint8))
+    with pytest.raises(ValueError):
+        oracle.apply(g, "threshold", (0, 0, 0, 0), "wrap", scalars=(0.3,), iters=2)
