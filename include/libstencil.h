@@ -62,12 +62,24 @@ enum stencil_border { STENCIL_CLAMP = 0, STENCIL_WRAP = 1, STENCIL_CONSTANT = 2 
  *                 rounded to fp32 in this order - "he".  scalars[0] = alpha.
  *   SINCOS (f32): sum over the region of w * sin(V) + cos(V) - a compute-intensive
  *                 synthetic stencil (Section 3.3).  sin/cos are evaluated in fp32.
+ * The three stencils of the Canny edge detector (Section 5, Table 2: "sobel", "nms", "threshold";
+ * the formulas are this library's, every operation rounded to fp32 in the order written):
+ *   SOBEL (f32):  region 1/1/1/1; gx = ((ne - nw) + 2 (e - w)) + (se - sw),
+ *                 gy = ((sw - nw) + 2 (s - n)) + (se - ne), out = sqrt(gx gx + gy gy).
+ *   NMS (f32):    region 1/1/1/1; a cell keeps its value if it is no smaller than both its west
+ *                 and east neighbours, or than both its north and south neighbours; else 0.
+ *   THRESHOLD:    no border region (0/0/0/0); F32 matrix in, U8 matrix out (the kernel whose
+ *                 output type differs from its input type, Section 3.3): 1 where the value is
+ *                 >= scalars[0], else 0.  Exactly one application per stencil_run / sweep sample.
  */
 enum stencil_kernel {
     STENCIL_WEIGHTED_SUM = 0,
     STENCIL_LIFE = 1,
     STENCIL_HEAT = 2,
-    STENCIL_SINCOS = 3
+    STENCIL_SINCOS = 3,
+    STENCIL_SOBEL = 4,
+    STENCIL_NMS = 5,
+    STENCIL_THRESHOLD = 6
 };
 
 enum stencil_enum_mode {
@@ -108,7 +120,7 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            its window from there.  Available for every scenario; the default.
  *            STENCIL_STAGING_DIRECT - nothing is staged: work-items read their windows from
  *            global memory as 16-byte vectors and rely on the L1/L2 caches for the overlap.
- *            Available for WEIGHTED_SUM with regions 1/1/1/1 and 2/2/2/2, HEAT and LIFE;
+ *            Available for WEIGHTED_SUM with regions 1/1/1/1 and 2/2/2/2, HEAT, SOBEL, NMS and LIFE;
  *            needs no local memory, so no size is refused for its tile.
  *            STENCIL_STAGING_TEMPORAL - temporal blocking for iterated runs: one launch stages
  *            the tile plus a border region STENCIL_OPT_TEMPORAL_DEPTH cells deep in local
@@ -119,7 +131,8 @@ int stencil_set_border_value(stencil_t *st, double value);
  *   cells_rows x cells_cols: block of adjacent cells one work-item computes (register
  *            blocking); a workgroup of w_r x w_c work-items covers (w_r*cells_rows) x
  *            (w_c*cells_cols) elements.  (1,1) is the paper's one element per work-item.
- *            LOCAL: cells_rows in {1,2,4,8}, cells_cols in {1,4} (F32) or {1,16} (U8);
+ *            LOCAL: cells_rows in {1,2,4,8}, cells_cols in {1,4} (F32) or {1,16} (U8); THRESHOLD:
+ *            (1,1), (2,1), (1,4), (2,4), (4,4), and nothing is staged for want of a border region;
  *            DIRECT: cells_rows in {1,2,4}, cells_cols = 4 (F32) or 16 (U8).
  *            STENCIL_STAGING_STREAM - register streaming, no local memory: each wavefront walks
  *            down a strip of 60 to 64 four-cell vectors (the outermost lanes at a side that has
@@ -143,6 +156,10 @@ enum stencil_staging {
     STENCIL_STAGING_STREAM = 3
 };
 int stencil_set_mapping(stencil_t *st, int staging, int cells_rows, int cells_cols);
+
+/* Element type (enum stencil_dtype) of the matrix `out` must be: the scenario's own, except
+ * STENCIL_U8 once STENCIL_THRESHOLD is selected.  `out` always holds rows*cols elements of it. */
+int stencil_output_dtype(const stencil_t *st);
 int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int *cells_cols);
 
 /* Launch options.  STENCIL_OPT_XCD_REMAP (default 1): workgroups are numbered so that each of
@@ -255,11 +272,12 @@ int stencil_baseline_wg(const double *performance, int n_scenarios, int n_sizes,
 
 /* ---- prediction (Section 3.2, Section 4.1, Algorithm 1) ---------------------------------- */
 
-#define STENCIL_N_FEATURES 12
+#define STENCIL_N_FEATURES 13
 
 /* f(s): dataset, kernel and device features of the scenario, STENCIL_N_FEATURES doubles:
- * rows, cols, element bytes, north, south, east, west, region cells, compute-intensive
- * flag, compute units, local memory bytes, max workgroup size. */
+ * rows, cols, input element bytes, north, south, east, west, region cells, compute-intensive
+ * flag, compute units, local memory bytes, max workgroup size, output element bytes
+ * (Section 3.2: "the input and output data types"). */
 int stencil_features(const stencil_t *st, double *features);
 
 /* A classifier over (f(s), Omega(s)) pairs (Section 4.1's D_training):

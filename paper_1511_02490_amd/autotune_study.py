@@ -46,7 +46,7 @@ def main():
         except ls.StencilError:
             st.set_mapping("local", 1, 1)
         tin = torch.from_numpy(w.grid()).cuda()
-        tout = torch.empty_like(tin)
+        tout = torch.empty(tin.shape, dtype=torch.uint8 if w.out_dtype == "u8" else tin.dtype, device="cuda")
         res = st.sweep(tin, tout, sizes, iters=max(1, min(w.iters, 10)), fixed=(0, 0), reps=a.reps)
         feats.append(st.features())
         times.append(res.mean_ms)

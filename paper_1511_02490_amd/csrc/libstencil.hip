@@ -20,6 +20,7 @@
 #include "tile_kernel.h"
 #include "march_kernel.h"
 #include "life_stream_kernel.h"
+#include "pointwise_kernel.h"
 
 namespace {
 
@@ -79,6 +80,10 @@ struct stencil {
     std::vector<hipEvent_t> events;
     size_t elem() const { return dtype == STENCIL_U8 ? 1 : (dtype == STENCIL_F64 ? 8 : 4); }
     size_t bytes() const { return (size_t)rows * (size_t)cols * elem(); }
+    // the output matrix: the input's element type, except for the threshold stencil (bytes)
+    int out_dtype() const { return kernel == STENCIL_THRESHOLD ? STENCIL_U8 : dtype; }
+    size_t out_elem() const { return out_dtype() == STENCIL_U8 ? 1 : (out_dtype() == STENCIL_F64 ? 8 : 4); }
+    size_t out_bytes() const { return (size_t)rows * (size_t)cols * out_elem(); }
 };
 
 // Variant keys of WEIGHTED_SUM on the other element types (internal: the public kernel id is
@@ -295,6 +300,29 @@ hipError_t launch_life_stream(const stencil *s, const void *in, void *out, int w
     return hipGetLastError();
 }
 
+// The threshold stencil: float in, bytes out, no border region (pointwise_kernel.h).
+template <int CR, int CC>
+hipError_t launch_threshold(const stencil *s, const void *in, void *out, int wr, int wc, int, hipStream_t stream) {
+    sk::ThresholdArgs a;
+    a.in = static_cast<const float *>(in);
+    a.out = static_cast<uint8_t *>(out);
+    a.rows = (int)s->rows;
+    a.cols = (int)s->cols;
+    const int th = wr * CR, tw = wc * CC;
+    a.tiles_c = (a.cols + tw - 1) / tw;
+    a.n_tiles = ((a.rows + th - 1) / th) * a.tiles_c;
+    a.vec_ok = (CC == 4 && s->cols % 4 == 0 && (uintptr_t)in % 16 == 0 && (uintptr_t)out % 4 == 0) ? 1 : 0;
+    a.level = s->scalar0;
+    unsigned blocks = (unsigned)a.n_tiles;
+    a.xcd_chunk = 0;
+    if (s->xcd_remap && a.n_tiles >= 64) {
+        a.xcd_chunk = (a.n_tiles + 7) / 8;
+        blocks = (unsigned)a.xcd_chunk * 8u;
+    }
+    hipLaunchKernelGGL((sk::threshold_kernel<CR, CC, STENCIL_MAX_WG_SIZE>), dim3(blocks), dim3(wc, wr), 0, stream, a);
+    return hipGetLastError();
+}
+
 // One application, marched down the matrix in registers (march_kernel.h).
 template <class Op, int B, class Halo>
 hipError_t launch_march(const stencil *s, const void *in, void *out, int wr, int wc, int, hipStream_t stream) {
@@ -506,6 +534,28 @@ void reg_life_stream(std::vector<Variant> &r) {
     reg_life_stream_one<sk::kConstant, WORDS>(r);
 }
 
+template <int B, int CR, int CC>
+void reg_threshold_one(std::vector<Variant> &r) {
+    Variant v;
+    v.staging = STENCIL_STAGING_LOCAL;     // the paper's mapping; with no border region there is no tile to stage
+    v.kernel = STENCIL_THRESHOLD;
+    v.border = B;
+    v.hn = v.hs = v.he = v.hw = 0;
+    v.cr = CR;
+    v.cc = CC;
+    v.max_threads = STENCIL_MAX_WG_SIZE;
+    v.staged_bytes = 0;
+    v.launch = &launch_threshold<CR, CC>;
+    r.push_back(v);
+}
+
+template <int CR, int CC>
+void reg_threshold(std::vector<Variant> &r) {
+    reg_threshold_one<sk::kClamp, CR, CC>(r);
+    reg_threshold_one<sk::kWrap, CR, CC>(r);
+    reg_threshold_one<sk::kConstant, CR, CC>(r);
+}
+
 template <class Op, int KID, int B, class Halo>
 void reg_march_one(std::vector<Variant> &r) {
     Variant v;
@@ -622,6 +672,16 @@ const std::vector<Variant> &registry() {
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 2>(r);
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 4>(r);
         reg_temporal<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, 8>(r);
+        // the Canny detector's stencils (Table 2)
+        reg_blockings<sk::OpSobel, STENCIL_SOBEL, sk::HaloC<1, 1, 1, 1>, 4>(r);
+        reg_blockings<sk::OpNms, STENCIL_NMS, sk::HaloC<1, 1, 1, 1>, 4>(r);
+        reg_direct<sk::OpSobel, STENCIL_SOBEL, sk::HaloC<1, 1, 1, 1>, 4>(r);
+        reg_direct<sk::OpNms, STENCIL_NMS, sk::HaloC<1, 1, 1, 1>, 4>(r);
+        reg_threshold<1, 1>(r);
+        reg_threshold<2, 1>(r);
+        reg_threshold<1, 4>(r);
+        reg_threshold<2, 4>(r);
+        reg_threshold<4, 4>(r);
         reg_stream<sk::OpHeat, STENCIL_HEAT>(r);
         reg_stream<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM>(r);
         reg_march<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<2, 2, 2, 2>>(r);
@@ -711,6 +771,8 @@ int ensure_device_state(stencil *s, const Variant *v, bool need_scratch) {
 // `iters` out-of-place applications ending in `out`, never writing `in`.
 int run_checked(stencil *s, const Variant *v, const void *in, void *out, int iters, int wr, int wc,
                 hipStream_t stream) {
+    if (s->out_dtype() != s->dtype && iters != 1)
+        return fail(STENCIL_E_INVALID, "the output is of another element type than the input: exactly one application");
     if (iters == 0) {
         hipError_t e = hipMemcpyAsync(out, in, s->bytes(), hipMemcpyDeviceToDevice, stream);
         return e == hipSuccess ? STENCIL_OK : fail_hip(e, "hipMemcpyAsync");
@@ -734,9 +796,9 @@ int run_checked(stencil *s, const Variant *v, const void *in, void *out, int ite
 
 int validate_buffers(const stencil *s, const void *in, const void *out) {
     if (!in || !out) return fail(STENCIL_E_INVALID, "in/out must not be NULL");
-    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out, n = s->bytes();
-    if (a < b + n && b < a + n) return fail(STENCIL_E_INVALID, "in and out overlap");
-    if (a % s->elem() || b % s->elem()) return fail(STENCIL_E_INVALID, "in/out are not element-aligned");
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out, n = s->bytes(), m = s->out_bytes();
+    if (a < b + m && b < a + n) return fail(STENCIL_E_INVALID, "in and out overlap");
+    if (a % s->elem() || b % s->out_elem()) return fail(STENCIL_E_INVALID, "in/out are not element-aligned");
     return STENCIL_OK;
 }
 
@@ -835,6 +897,19 @@ int stencil_set_kernel(stencil_t *s, int kernel_id, const float *weights, int n_
         s->scalar0 = scalars[0];
         s->weights.clear();
         break;
+    case STENCIL_SOBEL:
+    case STENCIL_NMS:
+        if (s->dtype != STENCIL_F32) return fail(STENCIL_E_INVALID, "SOBEL and NMS need an F32 matrix");
+        if (!unit_region) return fail(STENCIL_E_INVALID, "SOBEL and NMS need border region 1/1/1/1");
+        s->weights.clear();
+        break;
+    case STENCIL_THRESHOLD:
+        if (s->dtype != STENCIL_F32) return fail(STENCIL_E_INVALID, "THRESHOLD needs an F32 matrix");
+        if (s->hn || s->hs || s->he || s->hw) return fail(STENCIL_E_INVALID, "THRESHOLD has no border region (0/0/0/0)");
+        if (!scalars || n_scalars < 1) return fail(STENCIL_E_INVALID, "THRESHOLD needs scalars[0] = level");
+        s->scalar0 = scalars[0];
+        s->weights.clear();
+        break;
     default:
         return fail(STENCIL_E_INVALID, "unknown kernel id %d", kernel_id);
     }
@@ -870,6 +945,11 @@ int stencil_set_mapping(stencil_t *s, int staging, int cells_rows, int cells_col
     s->cc = cells_cols;
     s->best_rows = s->best_cols = 0;
     return STENCIL_OK;
+}
+
+int stencil_output_dtype(const stencil_t *s) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    return s->out_dtype();
 }
 
 int stencil_get_mapping(const stencil_t *s, int *staging, int *cells_rows, int *cells_cols) {
@@ -1219,6 +1299,7 @@ int stencil_features(const stencil_t *s, double *f) {
     f[9] = 256.0;                              // compute units of an MI355X
     f[10] = (double)STENCIL_LOCAL_MEM_BYTES;
     f[11] = (double)STENCIL_MAX_WG_SIZE;
+    f[12] = (double)s->out_elem();
     return STENCIL_OK;
 }
 

@@ -180,6 +180,72 @@ struct OpHeat {
     }
 };
 
+// ---- the Canny detector's stencils (Table 2: sobel, nms, threshold) --------------------------
+// The paper names them and gives their border regions; the formulas are this library's, every
+// operation rounded to fp32 in the order written.
+//
+// sobel: gx = ((ne - nw) + 2 (e - w)) + (se - sw), gy = ((sw - nw) + 2 (s - n)) + (se - ne),
+// out = sqrt(gx gx + gy gy).  (a + 2 b is one fma: 2 b is exact, so nothing is rounded differently.)
+struct OpSobel {
+    static constexpr bool kRowFold = false;
+    using T = float;
+    using L = float;
+    using V = float;
+    static constexpr int kPlanes = 1;
+    static constexpr bool kWeights = false;
+    struct State { float nw, n, ne, w, e, sw, s, se; };
+    __device__ static __forceinline__ void stage(T v, L (&out)[1]) { out[0] = v; }
+    __device__ static __forceinline__ V combine(const L (&p)[1]) { return p[0]; }
+    template <int CC>
+    __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[1][CC]) {
+#pragma unroll
+        for (int k = 0; k < CC; ++k) out[0][k] = v[k];
+    }
+    __device__ static __forceinline__ void init(State &s) { s.nw = s.n = s.ne = s.w = s.e = s.sw = s.s = s.se = 0.0f; }
+    __device__ static __forceinline__ void visit(State &s, int dr, int dc, float, V v) {
+        if (dr == -1) { if (dc == -1) s.nw = v; else if (dc == 0) s.n = v; else s.ne = v; }
+        else if (dr == 0) { if (dc == -1) s.w = v; else if (dc == 1) s.e = v; }
+        else { if (dc == -1) s.sw = v; else if (dc == 0) s.s = v; else s.se = v; }
+    }
+    __device__ static __forceinline__ T finish(const State &s, float) {
+        const float gx = __fadd_rn(__fmaf_rn(2.0f, __fsub_rn(s.e, s.w), __fsub_rn(s.ne, s.nw)), __fsub_rn(s.se, s.sw));
+        const float gy = __fadd_rn(__fmaf_rn(2.0f, __fsub_rn(s.s, s.n), __fsub_rn(s.sw, s.nw)), __fsub_rn(s.se, s.ne));
+        // sqrtf is the correctly rounded root (the shorter intrinsic is not)
+        return sqrtf(__fadd_rn(__fmul_rn(gx, gx), __fmul_rn(gy, gy)));
+    }
+};
+
+// nms: a cell keeps its value if it is no smaller than both its west and east neighbours, or no
+// smaller than both its north and south neighbours; otherwise it becomes 0.
+struct OpNms {
+    static constexpr bool kRowFold = false;
+    using T = float;
+    using L = float;
+    using V = float;
+    static constexpr int kPlanes = 1;
+    static constexpr bool kWeights = false;
+    struct State { float n, w, u, e, s; };
+    __device__ static __forceinline__ void stage(T v, L (&out)[1]) { out[0] = v; }
+    __device__ static __forceinline__ V combine(const L (&p)[1]) { return p[0]; }
+    template <int CC>
+    __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[1][CC]) {
+#pragma unroll
+        for (int k = 0; k < CC; ++k) out[0][k] = v[k];
+    }
+    __device__ static __forceinline__ void init(State &s) { s.n = s.w = s.u = s.e = s.s = 0.0f; }
+    __device__ static __forceinline__ void visit(State &s, int dr, int dc, float, V v) {
+        if (dr == -1 && dc == 0) s.n = v;
+        else if (dr == 0 && dc == -1) s.w = v;
+        else if (dr == 0 && dc == 0) s.u = v;
+        else if (dr == 0 && dc == 1) s.e = v;
+        else if (dr == 1 && dc == 0) s.s = v;
+    }
+    __device__ static __forceinline__ T finish(const State &s, float) {
+        const bool keep = (s.u >= s.w && s.u >= s.e) || (s.u >= s.n && s.u >= s.s);
+        return keep ? s.u : 0.0f;
+    }
+};
+
 // ---- compute-intensive synthetic stencil: sum of w * sin(x) + cos(x) over the region ------
 // sin and cos are evaluated once per staged cell (fp32) and kept side by side in local
 // memory (one plane each).  The fold keeps one fma chain for the sines; the cosines of one region row are

@@ -23,11 +23,13 @@ STAGING_LOCAL, STAGING_DIRECT, STAGING_TEMPORAL, STAGING_STREAM = 0, 1, 2, 3
 OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF = 0, 1, 2
 _STAGINGS = {"local": STAGING_LOCAL, "direct": STAGING_DIRECT, "temporal": STAGING_TEMPORAL,
              "stream": STAGING_STREAM}
-N_FEATURES = 12
+N_FEATURES = 13
 
 _DTYPES = {"f32": F32, "u8": U8, "i32": I32, "f64": F64}
 _BORDERS = {"clamp": CLAMP, "wrap": WRAP, "constant": CONSTANT}
-_KERNELS = {"weighted_sum": WEIGHTED_SUM, "life": LIFE, "heat": HEAT, "sincos": SINCOS}
+SOBEL, NMS, THRESHOLD = 4, 5, 6
+_KERNELS = {"weighted_sum": WEIGHTED_SUM, "life": LIFE, "heat": HEAT, "sincos": SINCOS, "sobel": SOBEL, "nms": NMS,
+            "threshold": THRESHOLD}
 
 
 class StencilError(RuntimeError):
@@ -55,6 +57,7 @@ def _load() -> ctypes.CDLL:
         "stencil_set_border_value": (c_int, [vp, c_dbl]),
         "stencil_set_mapping": (c_int, [vp, c_int, c_int, c_int]),
         "stencil_get_mapping": (c_int, [vp, ip, ip, ip]),
+        "stencil_output_dtype": (c_int, [vp]),
         "stencil_set_option": (c_int, [vp, c_int, c_int]),
         "stencil_max_wg_size": (c_int, [vp]),
         "stencil_tile_bytes": (c_i64, [vp, c_int, c_int]),
@@ -90,7 +93,7 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
-           "stencil_set_mapping", "stencil_get_mapping", "stencil_set_option", "stencil_max_wg_size", "stencil_tile_bytes",
+           "stencil_set_mapping", "stencil_get_mapping", "stencil_output_dtype", "stencil_set_option", "stencil_max_wg_size", "stencil_tile_bytes",
            "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg", "stencil_sweep_configs",
            "stencil_device_copy", "stencil_time_copy", "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
@@ -294,11 +297,15 @@ class Stencil:
 
     def _check_tensors(self, tin, tout):
         import torch
-        want = {"f32": torch.float32, F32: torch.float32, "u8": torch.uint8, U8: torch.uint8,
-                "i32": torch.int32, I32: torch.int32, "f64": torch.float64, F64: torch.float64}[self.dtype]
-        for t in (tin, tout):
+        types = {"f32": torch.float32, F32: torch.float32, "u8": torch.uint8, U8: torch.uint8,
+                 "i32": torch.int32, I32: torch.int32, "f64": torch.float64, F64: torch.float64}
+        for t, want in ((tin, types[self.dtype]), (tout, types[self.output_dtype()])):
             if not t.is_cuda or not t.is_contiguous() or t.dtype != want or t.numel() != self.rows * self.cols:
                 raise ValueError("tensors must be contiguous CUDA %s of %d x %d" % (want, self.rows, self.cols))
+
+    def output_dtype(self) -> int:
+        """Element type of the output matrix (the input's, except bytes for the threshold stencil)."""
+        return _check(_lib.stencil_output_dtype(self._h))
 
     def run(self, tin, tout, iters: int = 1, wg: Tuple[int, int] = (0, 0), stream=None):
         self._check_tensors(tin, tout)

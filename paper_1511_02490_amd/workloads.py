@@ -27,6 +27,9 @@ WEIGHTED_SUM = "weighted_sum"
 LIFE = "life"
 HEAT = "heat"
 SINCOS = "sincos"
+SOBEL = "sobel"
+NMS = "nms"
+THRESHOLD = "threshold"
 
 
 @dataclass
@@ -53,9 +56,15 @@ class Workload:
         return self.rows * self.cols
 
     @property
+    def out_dtype(self) -> str:
+        """Element type of the output matrix: the input's, except bytes for the threshold stencil."""
+        return "u8" if self.kernel == THRESHOLD else self.dtype
+
+    @property
     def bytes_per_cell_update(self) -> int:
         """One read and one write of a cell per application of the stencil."""
-        return 2 * {"f32": 4, "u8": 1, "i32": 4, "f64": 8}[self.dtype]
+        size = {"f32": 4, "u8": 1, "i32": 4, "f64": 8}
+        return size[self.dtype] + size[self.out_dtype]
 
     def grid(self) -> np.ndarray:
         return make_grid(self)
@@ -212,9 +221,18 @@ def forest_draws(n_trees: int, n_tuples: int, n_inputs: int, seed: int = BASE_SE
     return bootstrap, masks.tolist()
 
 
+def canny_stage(kernel: str, rows: int, cols: int, border: str = "clamp", level: float = 0.5) -> Workload:
+    """One stencil of the Canny edge detector (Table 2: sobel and nms with border region 1/1/1/1,
+    threshold with none) on a seeded U[0,1) image."""
+    halo = (0, 0, 0, 0) if kernel == THRESHOLD else (1, 1, 1, 1)
+    seed = BASE_SEED + 300 + {SOBEL: 0, NMS: 1, THRESHOLD: 2}[kernel]
+    return Workload("%s %dx%d" % (kernel, rows, cols), rows, cols, "f32", halo, border, 0.0, kernel, 1, seed, "pow2",
+                    scalars=(level,) if kernel == THRESHOLD else ())
+
+
 def real_scenarios() -> List[Workload]:
-    """The reference applications of Section 5 that this build defines (Gaussian blur, Game of
-    Life, heat equation) on the paper's four matrix sizes."""
+    """The reference applications of Section 5 (Gaussian blur, Game of Life, heat equation, and
+    the sobel / nms / threshold stencils of the Canny detector) on the paper's four matrix sizes."""
     out = []
     for side in (512, 1024, 2048, 4096):
         for radius in (1, 2):
@@ -228,4 +246,6 @@ def real_scenarios() -> List[Workload]:
         h = config(3, rows=side, cols=side, iters=10)
         h.name = "he %dx%d" % (side, side)
         out.append(h)
+        for kernel in (SOBEL, NMS, THRESHOLD):
+            out.append(canny_stage(kernel, side, side))
     return out

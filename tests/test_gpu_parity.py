@@ -50,14 +50,15 @@ def gpu_apply(ls, w, grid, wg, iters=None, blocking=(1, 1), offset=0):
     st = ls.Stencil.from_workload(w)
     set_mapping(st, blocking)
     n = grid.size
-    tdt = {"f32": torch.float32, "u8": torch.uint8, "i32": torch.int32, "f64": torch.float64}[w.dtype]
+    types = {"f32": torch.float32, "u8": torch.uint8, "i32": torch.int32, "f64": torch.float64}
+    tdt = types[w.dtype]
     buf_in = torch.zeros(n + offset, dtype=tdt, device="cuda")
-    buf_out = torch.full((n + offset,), 7, dtype=tdt, device="cuda")
+    buf_out = torch.full((n + offset,), 7, dtype=types[getattr(w, "out_dtype", w.dtype)], device="cuda")
     tin, tout = buf_in[offset:], buf_out[offset:]
     tin.copy_(torch.from_numpy(grid.reshape(-1)))
     st.run(tin, tout, w.iters if iters is None else iters, wg)
     torch.cuda.synchronize()
-    assert np.array_equal(tin.cpu().numpy().reshape(grid.shape), grid), "input was modified"
+    assert np.array_equal(tin.cpu().numpy().reshape(grid.shape), grid, equal_nan=grid.dtype.kind == "f"), "input was modified"
     out = tout.cpu().numpy().reshape(grid.shape)
     st.close()
     return out
@@ -68,8 +69,8 @@ def check(ls, w, wg, iters=None, blocking=(1, 1), offset=0, grid=None):
     it = w.iters if iters is None else iters
     ref = oracle.apply(g, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, it)
     got = gpu_apply(ls, w, g, wg, it, blocking, offset)
-    if w.dtype in ("u8", "i32"):
-        np.testing.assert_array_equal(got, ref)
+    if w.dtype in ("u8", "i32") or w.kernel in (wl.SOBEL, wl.NMS, wl.THRESHOLD):
+        np.testing.assert_array_equal(got, ref)        # integer work, or fp32 operations in a fixed order
     elif w.dtype == "f64":
         assert rel_err(got, ref) <= 1e-13 * max(1, it)
     else:
@@ -210,6 +211,75 @@ def test_weighted_sum_on_double_and_int32_matrices(ls, border):
         st.set_kernel("weighted_sum", np.full((3, 3), 0.5, np.float32))        # integer weights only
     with pytest.raises(ls.StencilError):
         ls.Stencil(8, 8, "f64").set_kernel("sincos", np.zeros((3, 3), np.float32))
+
+
+# ---- the Canny detector's stencils (Table 2) ---------------------------------------------------
+
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_sobel_and_nms_bit_exact(ls, border):
+    for kernel in (wl.SOBEL, wl.NMS):
+        for rows, cols in [(131, 157), (96, 128), (1, 1), (3, 50)]:
+            w = wl.canny_stage(kernel, rows, cols, border)
+            w.pad = 0.7
+            g = w.grid() * np.float32(50.0)
+            for blocking in BLOCKINGS_F32 + DIRECT_F32:
+                for wg in [(4, 4), (16, 16), (3, 21), (2, 64)]:
+                    check(ls, w, wg, blocking=blocking, grid=g)
+        w = wl.canny_stage(kernel, 64, 96, border)
+        check(ls, w, (8, 16), blocking=(4, 4), offset=1)                  # unaligned rows
+        check(ls, w, (8, 16), blocking=("direct", 2, 4), offset=3)
+        check(ls, w, (8, 16), blocking=("direct", 2, 4), iters=3)         # iterated: ping-pong
+        with pytest.raises(ls.StencilError):
+            ls.Stencil.from_workload(w).set_mapping("stream", 16, 4)
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(8, 8, "f32", (1, 1, 1, 0), border).set_kernel("sobel")   # region must be 1/1/1/1
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(8, 8, "u8", (1, 1, 1, 1), border).set_kernel("nms")
+
+
+def test_threshold_float_in_bytes_out(ls):
+    for rows, cols in [(131, 157), (96, 128), (1, 1), (5, 1030)]:
+        w = wl.canny_stage(wl.THRESHOLD, rows, cols, level=0.37)
+        g = w.grid()
+        g[0, 0] = np.nan
+        g[rows // 2, cols // 2] = np.float32(0.37)                           # exactly the level: reached
+        for blocking in [(1, 1), (2, 1), (1, 4), (2, 4), (4, 4)]:
+            for wg in [(4, 4), (16, 16), (3, 21), (2, 64), (1, 1024)]:
+                got = check(ls, w, wg, blocking=blocking, grid=g)
+                assert got.dtype == np.uint8 and got[rows // 2, cols // 2] == 1 and (got[0, 0] == 0 or rows == 1)
+        check(ls, w, (8, 16), blocking=(2, 4), offset=1, grid=g)             # unaligned rows
+    st = ls.Stencil.from_workload(wl.canny_stage(wl.THRESHOLD, 32, 32))
+    assert st.output_dtype() == ls.U8 and st.tile_bytes(8, 8) == 0 and st.features()[12] == 1.0 and st.features()[2] == 4.0
+    a = torch.zeros(32 * 32, device="cuda")
+    with pytest.raises(ValueError):
+        st.run(a, torch.zeros(32 * 32, device="cuda"), 1, (8, 8))            # the output is a byte matrix
+    out = torch.zeros(32 * 32, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ls.StencilError):
+        st.run(a, out, 2, (8, 8))                                            # another type out than in: one application
+    with pytest.raises(ls.StencilError):
+        st.set_mapping("direct", 1, 4)
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(8, 8, "f32", (1, 1, 1, 1), "clamp").set_kernel("threshold", scalars=(0.5,))   # has no border region
+    res = st.sweep(a, out, [(8, 8), (4, 64), (64, 32)], iters=1, reps=3)
+    assert res.status == [ls.OK, ls.OK, ls.E_REFUSED] and res.best in [(8, 8), (4, 64)]
+    st.close()
+
+
+def test_canny_chain_stage_by_stage(ls):
+    """Gaussian blur -> sobel -> nms -> threshold, the detector the paper takes three of its kernels
+    from: every stage is checked against the oracle on the input the previous stage produced."""
+    rows, cols = 300, 420
+    blur = wl.config(1, rows=rows, cols=cols)
+    g = blur.grid()
+    yy, xx = np.mgrid[0:rows, 0:cols]
+    g = (g * np.float32(0.2) + ((xx // 60 + yy // 50) % 2).astype(np.float32)).astype(np.float32)   # a noisy chequerboard
+    x = check(ls, blur, (16, 8), blocking=(2, 4), grid=g)
+    for stage in (wl.canny_stage(wl.SOBEL, rows, cols), wl.canny_stage(wl.NMS, rows, cols),
+                  wl.canny_stage(wl.THRESHOLD, rows, cols, level=1.0)):
+        x = check(ls, stage, (4, 16), blocking=("direct", 2, 4) if stage.kernel != wl.THRESHOLD else (2, 4), grid=x)
+    assert x.dtype == np.uint8 and 0.005 < x.mean() < 0.3                      # edges are thin lines
+    # an edge runs along column 60: cells next to it are marked, cells well inside a square are not
+    assert x[25, 58:62].max() == 1 and x[25, 20:40].max() == 0
 
 
 # ---- temporal blocking: several applications per launch ------------------------------------
