@@ -328,7 +328,8 @@ def test_temporal_blocking_life_bit_exact(ls, border):
 @pytest.mark.parametrize("border", ["wrap", "constant"])
 def test_register_streaming_temporal_kernel_bit_exact(ls, border):
     """Time levels kept in registers, row neighbours from adjacent lanes; every wavefront owns a
-    strip of 248 columns: matrices wider than one strip, ragged ones, and ones smaller than a strip."""
+    strip of 248 (240 beyond depth 4) columns: matrices wider than one strip, ragged ones, and ones
+    smaller than a strip."""
     for rows, cols, iters in [(70, 600, 9), (37, 250, 5), (130, 83, 6), (64, 256, 8), (5, 3, 7), (1, 1, 4),
                               (40, 244, 17), (33, 484, 11)]:
         w = wl.config(3, rows=rows, cols=cols, iters=iters)
