@@ -85,6 +85,7 @@ def main():
     k = pick(stats, a.kernel)
     kc = pick(stats, "copy_kernel")
     roof = bench["roofline"]
+    hbm = roof.get("hbm") or roof       # the memory view (kernels that arithmetic bounds carry it beside)
     copy_kib = bench["config"]["rows"] * bench["config"]["cols"] * (4 if bench["dtype"] == "f32" else 1) / 1024.0
     f_scale = copy_kib / fetch[pick(fetch, "copy_kernel")][0]
     w_scale = copy_kib / write[pick(write, "copy_kernel")][0]
@@ -113,8 +114,13 @@ def main():
     out.append("bench.py's own clock in the same run (HIP events on the launch stream): kernel %.0f ns per launch, "
                "%.0f GB/s of algorithmic bytes (%d bytes per launch) = %.3f of the %.0f GB/s HBM peak; "
                "plain copy kernel on the same matrix: %.0f GB/s."
-               % (roof["kernel_ms"] * 1e6, roof["achieved"], roof["algorithmic_bytes_per_launch"], roof["frac"],
-                  roof["peak"], roof["copy_kernel_gbs"]))
+               % (roof["kernel_ms"] * 1e6, hbm["achieved"], roof["algorithmic_bytes_per_launch"], hbm["frac"],
+                  hbm["peak"], roof["copy_kernel_gbs"]))
+    if "hbm" in roof:
+        out.append("")
+        out.append("bench.py reports this kernel as bound by vector arithmetic: %.1f TFLOP/s of algorithmic fp32 "
+                   "operations (%d per cell) = %.3f of the published %.1f TFLOP/s vector peak."
+                   % (roof["achieved"], roof["flops_per_cell_update"], roof["frac"], roof["peak"]))
     if float(stats[k]["AverageNs"]) < 15000.0:
         out.append("")
         out.append("(A kernel this short finishes faster than the host can issue the next launch while the profiler "
