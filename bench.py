@@ -195,11 +195,18 @@ def recorded_traffic(kernel_label):
     """HBM bytes per launch from the committed rocprofv3 counter summary, or None when there is
     none for this kernel or the kernel sources have changed since the counters were taken."""
     from paper_1511_02490_amd import rocprof_summary as rs
+    import re
     try:
         with open(rs.TRAFFIC_JSON) as fh:
-            rec = json.load(fh).get(kernel_label)
+            table = json.load(fh)
     except (OSError, ValueError):
         return None
+    rec = table.get(kernel_label)
+    if rec is None and kernel_label.startswith(("stream_kernel", "march_kernel")):
+        # in the streaming kernels a wavefront's accesses do not depend on how wavefronts are grouped
+        # into workgroups: a record taken with another workgroup size of the same mapping serves
+        strip = lambda k: re.sub(r", wg \d+x\d+", "", k)
+        rec = next((v for k, v in sorted(table.items()) if strip(k) == strip(kernel_label)), None)
     if not rec or rec.get("source_hash") != rs.kernel_source_hash():
         return None
     return rec["traffic_bytes_per_launch"]
