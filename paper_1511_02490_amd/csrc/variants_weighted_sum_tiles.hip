@@ -1,0 +1,12 @@
+// Variants: weighted sums under the local-memory tile (fp32 with run-time and compile-time regions, fp64, int32).
+#include "variants.h"
+
+void register_weighted_sum_tiles(std::vector<Variant> &r) {
+    reg_blockings<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloD, 4>(r);
+    reg_blockings<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<1, 1, 1, 1>, 4>(r);
+    reg_blockings<sk::OpWeightedSum, STENCIL_WEIGHTED_SUM, sk::HaloC<2, 2, 2, 2>, 4>(r);
+    reg_borders<sk::OpWeightedSumF64, STENCIL_WEIGHTED_SUM_F64, sk::HaloD, 1, 1>(r);
+    reg_borders<sk::OpWeightedSumF64, STENCIL_WEIGHTED_SUM_F64, sk::HaloD, 2, 2>(r);
+    reg_borders<sk::OpWeightedSumI32, STENCIL_WEIGHTED_SUM_I32, sk::HaloD, 1, 1>(r);
+    reg_borders<sk::OpWeightedSumI32, STENCIL_WEIGHTED_SUM_I32, sk::HaloD, 2, 4>(r);
+}
