@@ -768,3 +768,90 @@ def test_c5_full_size_sampled_windows(ls):
         err = rel_err(got[r0 + lo_r:r0 + hi_r, c0 + lo_c:c0 + hi_c], ref[lo_r:hi_r, lo_c:hi_c])
         worst = max(worst, err)
     assert worst <= REL_1, worst
+
+
+# ---- a matrix whose byte offsets pass 2^32 ------------------------------------------------------
+
+def _window(t, rows, cols, r0, c0, h, w_, margin):
+    """Rows r0-margin .. r0+h+margin and columns c0-margin .. c0+w_+margin of the device matrix `t`,
+    taken periodically (the workloads here use the wrap border), as a host array."""
+    ri = (torch.arange(r0 - margin, r0 + h + margin, device=t.device) % rows)
+    ci = (torch.arange(c0 - margin, c0 + w_ + margin, device=t.device) % cols)
+    return t.view(rows, cols).index_select(0, ri).index_select(1, ci).cpu().numpy()
+
+
+def test_matrix_beyond_four_gibibytes(ls):
+    """20000 x 60000 fp32 (4.8 GB per matrix): element offsets need more than 32 bits in bytes.  The
+    input is drawn on the device from a seeded generator; the oracle recomputes windows at the
+    corners, across the periodic edges, around the 2^32-byte line and in the interior, each cut with
+    a margin as wide as the applications reach."""
+    rows, cols = 20000, 60000
+    free, _ = torch.cuda.mem_get_info()
+    if free < 3 * rows * cols * 4 + (1 << 30):
+        pytest.skip("not enough device memory")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.BASE_SEED + 400)
+    tin = torch.rand(rows * cols, generator=gen, device="cuda", dtype=torch.float32) * 100.0
+    tout = torch.empty_like(tin)
+    line = (1 << 32) // (cols * 4)                                   # the row in which byte offset 2^32 falls
+    spots = [(0, 0), (0, cols - 40), (rows - 40, 0), (rows - 40, cols - 40), (line - 20, 30000), (line - 20, cols - 40),
+             (9000, 12345), (rows - 40, 29990), (15000, 0)]
+    heat = wl.config(3, rows=rows, cols=cols, iters=2)
+    runs = [(heat, ("direct", 2, 4), None, (4, 16), 1), (heat, ("stream", 38, 4), 2, (1, 64), 2),
+            (heat, ("local", 2, 4), None, (8, 8), 1), (heat, ("temporal", 2, 4), 2, (16, 16), 2)]
+    sc = wl.config(4, rows=rows, cols=cols)
+    sc.border = "wrap"
+    runs.append((sc, ("stream", 134, 4), None, (4, 64), 1))
+    for w, mapping, depth, wg, iters in runs:
+        st = ls.Stencil.from_workload(w)
+        st.set_mapping(*mapping)
+        if depth:
+            st.set_option(ls.OPT_TEMPORAL_DEPTH, depth)
+        tout.fill_(-1.0)
+        st.run(tin, tout, iters, wg)
+        torch.cuda.synchronize()
+        st.close()
+        reach = max(w.halo) * iters
+        for r0, c0 in spots:
+            sub = _window(tin, rows, cols, r0, c0, 40, 40, reach)
+            ref = oracle.apply(sub, w.kernel, w.halo, "wrap", w.pad, w.weights, w.scalars, iters)[reach:-reach, reach:-reach]
+            got = tout.view(rows, cols)[r0:r0 + 40, c0:c0 + 40].cpu().numpy()
+            if w.kernel == wl.HEAT:
+                np.testing.assert_array_equal(got, ref, err_msg="%s %s at (%d, %d)" % (w.kernel, mapping, r0, c0))
+            else:       # sines and cosines of arguments up to 100 sum to anything, zero included: absolute error
+                assert np.max(np.abs(got.astype(np.float64) - ref)) <= 2e-5, (mapping, r0, c0)
+
+
+def test_largest_matrix_the_library_accepts(ls):
+    """rows*cols just under 2^31 (the limit stencil_create states): 32776 x 65520 cells of Life, 2 GiB
+    per matrix; windows at the corners, across the periodic edges and in the interior against the
+    oracle, for one generation per launch and for fused generations."""
+    rows, cols = 32776, 65520
+    assert rows * cols < 2 ** 31 <= (rows + 1) * cols                     # 128 cells short of 2^31
+    with pytest.raises(ls.StencilError):
+        ls.Stencil(rows + 1, cols, "u8", (1, 1, 1, 1), "wrap")            # one row beyond
+    free, _ = torch.cuda.mem_get_info()
+    if free < 3 * rows * cols + (1 << 30):
+        pytest.skip("not enough device memory")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.BASE_SEED + 401)
+    tin = (torch.rand(rows * cols, generator=gen, device="cuda", dtype=torch.float32) < 0.3).to(torch.uint8)
+    tout = torch.empty_like(tin)
+    w = wl.config(2, rows=rows, cols=cols, iters=3)
+    spots = [(0, 0), (0, cols - 48), (rows - 48, 0), (rows - 48, cols - 48), (rows - 48, 32000), (16384, 65000), (20000, 100)]
+    for mapping, depth, wg in [(("direct", 2, 16), None, (2, 128)), (("stream", 40, 4), 3, (1, 64)),
+                               (("stream", 20, 16), 2, (4, 64)), (("temporal", 2, 16), 3, (64, 8)), (("local", 1, 16), None, (16, 4))]:
+        st = ls.Stencil.from_workload(w)
+        st.set_mapping(*mapping)
+        if depth:
+            st.set_option(ls.OPT_TEMPORAL_DEPTH, depth)
+        tout.fill_(9)
+        st.run(tin, tout, w.iters, wg)
+        torch.cuda.synchronize()
+        st.close()
+        for r0, c0 in spots:
+            sub = _window(tin, rows, cols, r0, c0, 48, 48, w.iters)
+            ref = oracle.apply(sub, w.kernel, w.halo, "wrap", 0.0, None, (), w.iters)[w.iters:-w.iters, w.iters:-w.iters]
+            got = tout.view(rows, cols)[r0:r0 + 48, c0:c0 + 48].cpu().numpy()
+            np.testing.assert_array_equal(got, ref, err_msg="%s at (%d, %d)" % (mapping, r0, c0))
+
