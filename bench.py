@@ -161,6 +161,41 @@ def best_known_configuration(ls, torch, o, reps):
             "configurations_swept": len(configs)}
 
 
+# one application of the heat step on matrices that no cache holds (256 MiB and 1 GiB each way): the
+# workgroup sizes that win there are not those of the 4096^2 matrix, and the workgroup numbering
+# matters the other way round - the reason to sweep per dataset
+LARGE_HEAT_CONFIGS = [(m, cr, 4, 0, wg, remap)
+                      for m, cr in (("direct", 2), ("direct", 4), ("local", 2), ("local", 4))
+                      for wg in ((4, 16), (4, 64), (2, 256), (8, 64), (1, 512))
+                      for remap in (1, 0)]
+
+
+def larger_matrices(ls, wl, torch, reps):
+    out = {}
+    for n in (8192, 16384):
+        o = wl.config(3, rows=n, cols=n, iters=1)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(o.seed)
+        a = torch.rand(n * n, generator=gen, device="cuda", dtype=torch.float32) * 100.0
+        b = torch.empty_like(a)
+        st = ls.Stencil.from_workload(o)
+        burst = 4
+        mean, status, best = st.sweep_configs(a, b, LARGE_HEAT_CONFIGS, iters=burst, reps=reps)
+        copy_ms, _ = ls.time_copy(a, b, burst=burst, reps=reps)
+        fixed = LARGE_HEAT_CONFIGS.index(("direct", 2, 4, 0, (4, 16), 1))      # the 4096^2 matrix's best
+        st.close()
+        del a, b
+        c = LARGE_HEAT_CONFIGS[best]
+        gbs = lambda ms: n * n * 8 / (ms / burst) / 1e6
+        out["heat %dx%d" % (n, n)] = {
+            "best": {"mapping": mapping_name(c[:3]), "wg": list(c[4]), "xcd_remap": c[5]},
+            "ms_per_application": mean[best] / burst, "algorithmic_gbs": gbs(mean[best]),
+            "frac_of_hbm_peak": gbs(mean[best]) / HBM_PEAK_GBS,
+            "with_the_4096_best": {"algorithmic_gbs": gbs(mean[fixed]), "frac_of_hbm_peak": gbs(mean[fixed]) / HBM_PEAK_GBS},
+            "copy_kernel_gbs": 2.0 * n * n * 4 / copy_ms / 1e6, "configurations_swept": len(LARGE_HEAT_CONFIGS)}
+    return out
+
+
 def leave_one_out_prediction(ls, wl, torch, index, mapping_of, reps):
     """Section 7's leave-one-out evaluation in miniature: sweep the other four workloads, train
     the classifier on their (f(s), Omega(s)) pairs, predict for workload `index` with the
@@ -416,6 +451,8 @@ def main():
     roofline["copy_kernel_gbs"] = copy_reference()
     apply_mapping(st, blocking)
 
+    larger = larger_matrices(ls, wl, torch, max(5, args.reps // 3)) if (index == 3 and not args.wg and not args.quick) else {}
+
     out = {
         "metric": "Gcells/s at best swept workgroup size (achieved HBM GB/s in roofline)",
         "value": value, "unit": "Gcells/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -431,6 +468,7 @@ def main():
         "sweep": {"seconds": sweep_seconds, "by_blocking": sweeps},
         "predictor": predictor,
         "other_workloads": others,
+        "larger_matrices": larger,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, w, args.cpu_seconds)

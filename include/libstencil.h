@@ -228,16 +228,18 @@ int stencil_sweep_wg(stencil_t *st, const void *in, void *out, int iters,
 /* The sweep over more than the workgroup size (the paper's closing section names further
  * optimisation parameters as the next step): each configuration fixes the mapping
  * (stencil_set_mapping's three arguments), the number of applications fused per launch (depth; 0
- * keeps the current STENCIL_OPT_TEMPORAL_DEPTH) and a workgroup size, and is timed by
+ * keeps the current STENCIL_OPT_TEMPORAL_DEPTH), the numbering of workgroups (xcd_remap; -1 keeps
+ * the current STENCIL_OPT_XCD_REMAP) and a workgroup size, and is timed by
  * stencil_sweep_wg's protocol.  mean_ms[k] = mean milliseconds per sample (`iters` applications),
  * NaN unless status[k] == STENCIL_OK; status[k] = STENCIL_E_INVALID for a mapping or depth the
  * scenario does not offer, STENCIL_E_REFUSED for an illegal workgroup size; best_index (may be
  * NULL) = fastest configuration or -1.  Afterwards the scenario is left on the fastest
- * configuration (mapping, depth, and its size for stencil_run(0, 0)); on error, or if none ran, on
+ * configuration (mapping, depth, numbering, and its size for stencil_run(0, 0)); on error, or if none ran, on
  * the one it had.  configs, mean_ms, status: host arrays of n.  Synchronous. */
 typedef struct stencil_config {
     int staging, cells_rows, cells_cols;   /* as for stencil_set_mapping */
     int depth;                             /* applications per launch, 0 = leave as is */
+    int xcd_remap;                         /* STENCIL_OPT_XCD_REMAP: 0 or 1, -1 = leave as is */
     int wg_rows, wg_cols;
 } stencil_config_t;
 int stencil_sweep_configs(stencil_t *st, const void *in, void *out, int iters,

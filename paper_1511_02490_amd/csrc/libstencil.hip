@@ -539,7 +539,7 @@ int stencil_sweep_configs(stencil_t *s, const void *in, void *out, int iters, co
     int rc = validate_buffers(s, in, out);
     if (rc != STENCIL_OK) return rc;
     const double nan = std::numeric_limits<double>::quiet_NaN();
-    const int staging0 = s->staging, cr0 = s->cr, cc0 = s->cc, depth0 = s->temporal_depth;
+    const int staging0 = s->staging, cr0 = s->cr, cc0 = s->cc, depth0 = s->temporal_depth, remap0 = s->xcd_remap;
     int best = -1;
     for (int k = 0; k < n; ++k) {
         const stencil_config_t &c = configs[k];
@@ -547,6 +547,7 @@ int stencil_sweep_configs(stencil_t *s, const void *in, void *out, int iters, co
         status[k] = STENCIL_E_INVALID;
         // a mapping the scenario does not have, or a depth the mapping does not have: skipped
         s->temporal_depth = depth0;       // "as is" means as it was when the sweep began
+        s->xcd_remap = c.xcd_remap < 0 ? remap0 : (c.xcd_remap ? 1 : 0);
         if (stencil_set_mapping(s, c.staging, c.cells_rows, c.cells_cols) != STENCIL_OK) continue;
         if (c.depth != 0 && stencil_set_option(s, STENCIL_OPT_TEMPORAL_DEPTH, c.depth) != STENCIL_OK) continue;
         const Variant *v = find_variant(s);
@@ -562,6 +563,7 @@ int stencil_sweep_configs(stencil_t *s, const void *in, void *out, int iters, co
         // leave the scenario on the fastest configuration, remembered for stencil_run(0, 0)
         const stencil_config_t &c = configs[best];
         s->temporal_depth = depth0;
+        s->xcd_remap = c.xcd_remap < 0 ? remap0 : (c.xcd_remap ? 1 : 0);
         (void)stencil_set_mapping(s, c.staging, c.cells_rows, c.cells_cols);
         if (c.depth != 0) (void)stencil_set_option(s, STENCIL_OPT_TEMPORAL_DEPTH, c.depth);
         s->best_rows = c.wg_rows;
@@ -571,6 +573,7 @@ int stencil_sweep_configs(stencil_t *s, const void *in, void *out, int iters, co
         s->cr = cr0;
         s->cc = cc0;
         s->temporal_depth = depth0;
+        s->xcd_remap = remap0;
         s->best_rows = s->best_cols = 0;
     }
     if (best_index) *best_index = best;

@@ -173,7 +173,7 @@ def baseline_wg(performance: Sequence[Sequence[float]]) -> int:
 
 class _Config(ctypes.Structure):
     _fields_ = [("staging", ctypes.c_int), ("cells_rows", ctypes.c_int), ("cells_cols", ctypes.c_int),
-                ("depth", ctypes.c_int), ("wg_rows", ctypes.c_int), ("wg_cols", ctypes.c_int)]
+                ("depth", ctypes.c_int), ("xcd_remap", ctypes.c_int), ("wg_rows", ctypes.c_int), ("wg_cols", ctypes.c_int)]
 
 
 class SweepResult:
@@ -330,14 +330,17 @@ class Stencil:
 
     def sweep_configs(self, tin, tout, configs, iters: int = 1, reps: int = 30, stream=None):
         """Sweep whole configurations: each is (staging, cells_rows, cells_cols, depth, (wg_rows,
-        wg_cols)) with depth 0 = leave as is.  Returns (mean_ms list, status list, best index); the
-        scenario is left on the fastest configuration."""
+        wg_cols)) with depth 0 = leave as is, optionally followed by the workgroup numbering (0 / 1;
+        left as is when absent).  Returns (mean_ms list, status list, best index); the scenario is
+        left on the fastest configuration."""
         self._check_tensors(tin, tout)
         n = len(configs)
         arr = (_Config * max(n, 1))()
-        for k, (staging, cr, cc, depth, wg) in enumerate(configs):
+        for k, cfg in enumerate(configs):
+            staging, cr, cc, depth, wg = cfg[:5]
+            remap = int(cfg[5]) if len(cfg) > 5 else -1
             sg = _STAGINGS[staging] if isinstance(staging, str) else int(staging)
-            arr[k] = _Config(sg, int(cr), int(cc), int(depth), int(wg[0]), int(wg[1]))
+            arr[k] = _Config(sg, int(cr), int(cc), int(depth), remap, int(wg[0]), int(wg[1]))
         mean = (ctypes.c_double * max(n, 1))()
         status = (ctypes.c_int * max(n, 1))()
         best = ctypes.c_int(-1)

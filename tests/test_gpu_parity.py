@@ -531,9 +531,10 @@ def test_sweep_over_whole_configurations(ls):
                ("stream", 23, 4, 8, (1, 64)), ("stream", 23, 4, 8, (4, 4)),      # not whole wavefronts: refused
                ("temporal", 2, 4, 8, (16, 16)),                                   # depth the mapping lacks
                ("direct", 3, 4, 0, (4, 16)),                                      # no such mapping
-               ("local", 2, 4, 0, (64, 32))]                                      # above W_max: refused
+               ("local", 2, 4, 0, (64, 32)),                                      # above W_max: refused
+               ("direct", 2, 4, 0, (4, 16), 0)]                                   # plain workgroup numbering
     mean, status, best = st.sweep_configs(tin, tout, configs, iters=8, reps=5)
-    assert status == [ls.OK, ls.OK, ls.OK, ls.OK, ls.E_REFUSED, ls.E_INVALID, ls.E_INVALID, ls.E_REFUSED]
+    assert status == [ls.OK, ls.OK, ls.OK, ls.OK, ls.E_REFUSED, ls.E_INVALID, ls.E_INVALID, ls.E_REFUSED, ls.OK]
     assert all((m > 0) == (s == ls.OK) for m, s in zip(mean, status)) and all(np.isnan(m) for m, s in zip(mean, status) if s != ls.OK)
     assert best == int(np.nanargmin(mean)) and status[best] == ls.OK
     sg, cr, cc = st.get_mapping()
