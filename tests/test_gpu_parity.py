@@ -603,7 +603,7 @@ def test_iterated_run_inside_a_hip_graph(ls):
     w = wl.config(3, rows=192, cols=256, iters=9)
     g = w.grid()
     ref = oracle.apply_workload(w, g)
-    for blocking in [("direct", 2, 4), ("temporal", 2, 4, 4)]:
+    for blocking in [("direct", 2, 4), ("temporal", 2, 4, 4), ("stream", 23, 4, 8)]:
         st = ls.Stencil.from_workload(w)
         set_mapping(st, blocking)
         tin = torch.from_numpy(g).cuda()
