@@ -340,6 +340,23 @@ struct OpSinCos {
         if (dc <= E) h = __fadd_rn(h, v(dc).y);
         s.c = __fadd_rn(s.c, h);
     }
+    // The same row fold, one value at a time (k = 0, 1, ... counts the row's cells from its west
+    // end): the operations, and so the bits, of visit_row.
+    struct RowState { float pending, h; };
+    __device__ static __forceinline__ void row_visit(State &s, RowState &rs, int k, float w, V v) {
+        s.s = __fmaf_rn(w, v.x, s.s);
+        if (k & 1) {
+            const float pair = __fadd_rn(rs.pending, v.y);
+            rs.h = k == 1 ? pair : __fadd_rn(rs.h, pair);
+        } else {
+            rs.pending = v.y;
+        }
+    }
+    __device__ static __forceinline__ void row_end(State &s, const RowState &rs, int count) {
+        float h = rs.h;
+        if (count & 1) h = count == 1 ? rs.pending : __fadd_rn(rs.h, rs.pending);
+        s.c = __fadd_rn(s.c, h);
+    }
     __device__ static __forceinline__ T finish(const State &s, float) { return __fadd_rn(s.s, s.c); }
 };
 

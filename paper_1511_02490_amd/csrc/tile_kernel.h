@@ -69,6 +69,13 @@ __device__ __forceinline__ void store_vec(E *dst, const E (&src)[CNT]) {
     for (int k = 0; k < NV; ++k) reinterpret_cast<uint4 *>(dst)[k] = tmp[k];
 }
 
+// What a cell keeps while one row of its region goes by (operators that fold a row at a time).
+struct NoRowState {};
+template <class Op, bool = Op::kRowFold>
+struct row_state_of { using type = NoRowState; };
+template <class Op>
+struct row_state_of<Op, true> { using type = typename Op::RowState; };
+
 // Cross-lane moves inside a wavefront: the value the lane one below / one above holds.
 // (Lane 0 has no lane below and lane 63 none above; they get 0 - the move's bound control -
 // and must look elsewhere.)
@@ -221,22 +228,94 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
             }
         }
     } else {
-        const int wcols = he + hw + 1;
+        // Run-time region: the cells of a work-item walk through the region together, so that a
+        // tap's weight (a uniform, scalar load) is fetched once for all of them; every cell still
+        // sees its taps in row-major order.
+        const int wcols = he + hw + 1, wrows = hn + hs + 1;
+        constexpr bool kVec = CC > 1 && (sizeof(L) * CC) % 16 == 0;
+        if constexpr (kVec) {
+            // Columns are counted from the staged tile's aligned west edge (column kk of the window
+            // of cell (cr, 0) is dc = kk - hwa) and taken CC at a time: the cells of a row need
+            // window columns kk .. kk + CC - 1 for tap kk, i.e. two aligned vectors per chunk, of
+            // which one is the previous chunk's.  Taps outside [k_lo, k_hi] are not in the region.
+            const int k_lo = hwa - hw, k_hi = hwa + he;
+            const L *west[CR];
 #pragma unroll
-        for (int cr = 0; cr < CR; ++cr) {
-            if (r0 + lr0 + cr >= rows) break;
+            for (int cr = 0; cr < CR; ++cr) west[cr] = tile + (lr0 + cr) * pitch + lc0;
+            for (int i = 0; i < wrows; ++i) {
+                const int dr = i - hn;
+                [[maybe_unused]] typename row_state_of<Op>::type rs[CR][CC] = {};
+                L va[CR][NP][CC], vb[CR][NP][CC];
+                auto load_chunk = [&](L (&v)[CR][NP][CC], int j) {
 #pragma unroll
-            for (int cc = 0; cc < CC; ++cc) {
-                const L *ctr = tile + (lr0 + cr + hn) * pitch + hwa + lc0 + cc;
-                for (int dr = -hn; dr <= hs; ++dr)
-                    fold_row<Op>(
-                        st[cr][cc], dr, hw, he, [&](int dc) { return a.w[(dr + hn) * wcols + dc + hw]; },
-                        [&](int dc) {
+                    for (int cr = 0; cr < CR; ++cr)
+#pragma unroll
+                        for (int p = 0; p < NP; ++p) load_vec(v[cr][p], west[cr] + p * a.plane + i * pitch + CC * j);
+                };
+                // taps CC * j .. CC * j + CC - 1: `lo` holds window columns CC * j .., `hi` the next CC
+                auto chunk = [&](const L (&lo)[CR][NP][CC], L (&hi)[CR][NP][CC], int j) {
+                    if (CC * j + 1 <= k_hi) load_chunk(hi, j + 1);
+#pragma unroll
+                    for (int t = 0; t < CC; ++t) {
+                        const int kk = CC * j + t;
+                        if (kk < k_lo || kk > k_hi) continue;
+                        const auto w = a.w[i * wcols + kk - k_lo];
+#pragma unroll
+                        for (int cr = 0; cr < CR; ++cr)
+#pragma unroll
+                            for (int cc = 0; cc < CC; ++cc) {
+                                L parts[NP];
+#pragma unroll
+                                for (int p = 0; p < NP; ++p)
+                                    parts[p] = t + cc < CC ? lo[cr][p][(t + cc) % CC] : hi[cr][p][(t + cc) % CC];
+                                if constexpr (Op::kRowFold)
+                                    Op::row_visit(st[cr][cc], rs[cr][cc], kk - k_lo, w, Op::combine(parts));
+                                else
+                                    Op::visit(st[cr][cc], dr, kk - hwa, w, Op::combine(parts));
+                            }
+                    }
+                };
+                int j = k_lo / CC;
+                load_chunk(va, j);
+                for (; CC * j <= k_hi; j += 2) {
+                    chunk(va, vb, j);
+                    if (CC * (j + 1) <= k_hi) chunk(vb, va, j + 1);
+                }
+                if constexpr (Op::kRowFold) {
+#pragma unroll
+                    for (int cr = 0; cr < CR; ++cr)
+#pragma unroll
+                        for (int cc = 0; cc < CC; ++cc) Op::row_end(st[cr][cc], rs[cr][cc], wcols);
+                }
+            }
+        } else {
+            const L *nw[CR];      // the north-west corner of the region of cell (cr, 0)
+#pragma unroll
+            for (int cr = 0; cr < CR; ++cr) nw[cr] = tile + (lr0 + cr) * pitch + (hwa - hw) + lc0;
+            for (int i = 0; i < wrows; ++i) {
+                const int dr = i - hn;
+                [[maybe_unused]] typename row_state_of<Op>::type rs[CR][CC] = {};
+                for (int k = 0; k < wcols; ++k) {
+                    const auto w = a.w[i * wcols + k];
+#pragma unroll
+                    for (int cr = 0; cr < CR; ++cr)
+#pragma unroll
+                        for (int cc = 0; cc < CC; ++cc) {
                             L parts[NP];
 #pragma unroll
-                            for (int p = 0; p < NP; ++p) parts[p] = ctr[p * a.plane + dr * pitch + dc];
-                            return Op::combine(parts);
-                        });
+                            for (int p = 0; p < NP; ++p) parts[p] = nw[cr][p * a.plane + i * pitch + k + cc];
+                            if constexpr (Op::kRowFold)
+                                Op::row_visit(st[cr][cc], rs[cr][cc], k, w, Op::combine(parts));
+                            else
+                                Op::visit(st[cr][cc], dr, k - hw, w, Op::combine(parts));
+                        }
+                }
+                if constexpr (Op::kRowFold) {
+#pragma unroll
+                    for (int cr = 0; cr < CR; ++cr)
+#pragma unroll
+                        for (int cc = 0; cc < CC; ++cc) Op::row_end(st[cr][cc], rs[cr][cc], wcols);
+                }
             }
         }
     }

@@ -230,7 +230,9 @@ class Stencil:
             _lib.stencil_destroy(self._h)
             self._h = ctypes.c_void_p()
 
-    __del__ = close
+    def __del__(self):
+        if _lib is not None:          # at interpreter exit the module's globals may be gone already
+            self.close()
 
     def __enter__(self):
         return self
@@ -384,7 +386,9 @@ class Regressor:
             _lib.stencil_regressor_destroy(self._h)
             self._h = ctypes.c_void_p()
 
-    __del__ = close
+    def __del__(self):
+        if _lib is not None:
+            self.close()
 
     def add(self, features: Sequence[float], wg: Tuple[int, int], value: float):
         _check(_lib.stencil_regressor_add(self._h, _dbls(features), len(features), int(wg[0]), int(wg[1]), float(value)))
@@ -430,7 +434,9 @@ class Predictor:
             _lib.stencil_predictor_destroy(self._h)
             self._h = ctypes.c_void_p()
 
-    __del__ = close
+    def __del__(self):
+        if _lib is not None:
+            self.close()
 
     def add(self, features: Sequence[float], wg: Tuple[int, int]):
         _check(_lib.stencil_predictor_add(self._h, _dbls(features), len(features), int(wg[0]), int(wg[1])))

@@ -146,6 +146,24 @@ def test_sincos_borders(ls, border):
                 check(ls, w, wg, blocking=blocking)
 
 
+def test_region_alignments_of_the_vector_walk(ls):
+    """Run-time regions are walked four window columns at a time from the staged tile's aligned
+    west edge: every residue of the west and east extents, against the oracle, and bit for bit
+    against the one-cell-per-work-item mapping, which walks tap by tap."""
+    for kernel in (wl.WEIGHTED_SUM, wl.SINCOS):
+        for west in range(0, 6):
+            for east in (0, 1, 2, 3, 4, 7):
+                w = custom(kernel, 37, 83, (1, 2, east, west), "wrap", pad=0.3, seed=10 * west + east)
+                one = check(ls, w, (4, 16), blocking=(1, 1))
+                for blocking in [(1, 4), (2, 4)]:
+                    np.testing.assert_array_equal(check(ls, w, (4, 16), blocking=blocking), one)
+    for west, east in [(0, 0), (1, 3), (2, 1), (3, 2)]:
+        n, s = 2, 1
+        wf = np.random.default_rng(west).random((n + s + 1, east + west + 1), dtype=np.float32)
+        wd = wl.Workload("f64", 41, 66, "f64", (n, s, east, west), "clamp", 0.5, wl.WEIGHTED_SUM, 1, 5, "pow2", weights=wf)
+        np.testing.assert_array_equal(check(ls, wd, (4, 16), blocking=(2, 2)), check(ls, wd, (4, 16), blocking=(1, 1)))
+
+
 @pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
 def test_life_bit_exact(ls, border):
     for rows, cols in [(150, 203), (64, 256)]:
