@@ -201,8 +201,11 @@ int stencil_enumerate_wg(int mode, int max_threads, int *rows, int *cols, int ca
  * output of step k) with workgroups of wg_rows x wg_cols work-items.  `in` and `out` are
  * device buffers of rows*cols elements, contiguous row-major, non-overlapping; `in` is
  * never written; the final matrix is always in `out`; iters = 0 copies.  A scratch matrix
- * for the intermediate steps is allocated on first use and kept until destroy.
- * Asynchronous on `stream` (a hipStream_t; NULL = default stream), no host synchronisation.
+ * for the intermediate steps is allocated by the first run that takes more than one launch
+ * and kept until destroy.  Asynchronous on `stream` (a hipStream_t; NULL = default stream),
+ * no host synchronisation - except in the first run after stencil_set_kernel replaced a
+ * weight table that was already on the device, which waits for the device to go idle
+ * before it uploads the new table.
  * wg_rows = wg_cols = 0 lets the library choose (Section 2: selecting the size is the
  * implementation's responsibility): the best size of the handle's last sweep, else a
  * built-in default.  Illegal sizes return STENCIL_E_REFUSED without launching. */

@@ -1,6 +1,7 @@
 // Host-side arithmetic around the workgroup-size sweep: the enumeration of Section 5, the
-// oracle size of Eq. 3, the performance / speedup metrics of Section 7, sample statistics,
-// and the nearest-neighbour classifier used for classify(f(s)) in Algorithm 1.
+// oracle size of Eq. 3, the performance / speedup metrics of Section 7, sample statistics, the
+// classifiers behind classify(f(s)) in Algorithm 1 (nearest neighbour, decision tree, ZeroR) and
+// the regressors behind R(f(s), w) in Algorithm 2 (nearest neighbour, random forest).
 #pragma once
 #include <algorithm>
 #include <cmath>
@@ -262,11 +263,9 @@ private:
     mutable bool built_ = false;
 };
 
-// R(f(s), w) of Algorithm 2 as a nearest-neighbour regressor over (f(s), w, y) tuples: the y of
-// the tuple with the same w whose scenario is nearest to f (features scaled by their range over
-// all tuples, Euclidean distance, first nearest wins ties); NaN if no tuple has this w.
-// R(f(s), w) of Algorithm 2.  Without a fitted forest: the value of the nearest training scenario
-// that was measured with the same w.  With one (Section 5: a random forest of regression trees):
+// R(f(s), w) of Algorithm 2 over (f(s), w, y) tuples.  Without a fitted forest: the y of the
+// tuple with the same w whose scenario is nearest to f (features scaled by their range over all
+// tuples, Euclidean distance, first nearest wins ties); NaN if no tuple has this w.  With one (Section 5: a random forest of regression trees):
 // the mean of CART trees over the inputs (f(s), w_r, w_c), each grown on its own bootstrap sample
 // with its own subset of the inputs; the random draws are the caller's.
 class Regressor {

@@ -110,6 +110,10 @@ int ensure_device_state(stencil *s, const Variant *v, bool need_scratch) {
         if (!s->d_weights) {
             hipError_t e = hipMalloc((void **)&s->d_weights, n * sizeof(float));
             if (e != hipSuccess) return fail(STENCIL_E_RESOURCES, "hipMalloc(weights): %s", hipGetErrorString(e));
+        } else {
+            // launches still in flight (on any stream) may be reading the table about to be replaced
+            hipError_t e = hipDeviceSynchronize();
+            if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
         }
         if (!s->weights.empty()) {
             hipError_t e = hipMemcpy(s->d_weights, s->weights.data(), s->weights.size() * sizeof(float),
@@ -129,6 +133,12 @@ int ensure_device_state(stencil *s, const Variant *v, bool need_scratch) {
     return STENCIL_OK;
 }
 
+// Launches a run of `iters` applications takes: the fusing kernels make `temporal_depth` per launch.
+int launches_of(const stencil *s, const Variant *v, int iters) {
+    const int per = v->fuses ? s->temporal_depth : 1;
+    return (iters + per - 1) / per;
+}
+
 // `iters` out-of-place applications ending in `out`, never writing `in`.
 int run_checked(stencil *s, const Variant *v, const void *in, void *out, int iters, int wr, int wc,
                 hipStream_t stream) {
@@ -141,7 +151,7 @@ int run_checked(stencil *s, const Variant *v, const void *in, void *out, int ite
     // `per` applications per launch; the launches alternate between `out` and the scratch
     // matrix so that the last one lands in `out`
     const int per = v->fuses ? s->temporal_depth : 1;
-    const int launches = (iters + per - 1) / per;
+    const int launches = launches_of(s, v, iters);
     const void *src = in;
     void *dst = (launches % 2 == 1) ? out : s->scratch;
     for (int done = 0; done < iters;) {
@@ -393,7 +403,7 @@ int stencil_run(stencil_t *s, const void *in, void *out, int iters, int wg_rows,
     if (wg_rows == 0 && wg_cols == 0) default_wg(s, v, &wg_rows, &wg_cols);
     rc = check_legal(s, v, wg_rows, wg_cols);
     if (rc != STENCIL_OK) return rc;
-    rc = ensure_device_state(s, v, iters > 1);
+    rc = ensure_device_state(s, v, launches_of(s, v, iters) > 1);
     if (rc != STENCIL_OK) return rc;
     rc = run_checked(s, v, in, out, iters, wg_rows, wg_cols, (hipStream_t)stream);
     if (rc == STENCIL_OK) g_err[0] = '\0';
@@ -413,7 +423,7 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
     if (!v) return fail(STENCIL_E_INVALID, "no kernel selected for this scenario");
     if (reps <= 0) reps = 30;
     hipStream_t stream = (hipStream_t)stream_;
-    rc = ensure_device_state(s, v, iters > 1);
+    rc = ensure_device_state(s, v, launches_of(s, v, iters) > 1);
     if (rc != STENCIL_OK) return rc;
     while ((int)s->events.size() < 2 * reps) {
         hipEvent_t e;

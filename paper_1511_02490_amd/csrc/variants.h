@@ -108,8 +108,6 @@ TileGeom tile_geom(const stencil *s, const Variant &v, int wr, int wc) {
         g.pitch = 4;
         g.plane = 0;
         g.lds_bytes = 0;
-        g.tiles_r = (int)((s->rows + g.th - 1) / g.th);
-        g.tiles_c = (int)((s->cols + g.tw - 1) / g.tw);
     } else if (v.staging == STENCIL_STAGING_TEMPORAL) {
         // tile + `depth` rows above and below, one vector left and right; two buffers
         g.pitch = g.tw + 2 * v.cc;

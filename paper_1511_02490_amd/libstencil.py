@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "_lib", "libstencil.so")
 OK, E_INVALID, E_REFUSED, E_RESOURCES, E_HIP = 0, -1, -2, -3, -4
 F32, U8, I32, F64 = 0, 1, 2, 3
 CLAMP, WRAP, CONSTANT = 0, 1, 2
-WEIGHTED_SUM, LIFE, HEAT, SINCOS = 0, 1, 2, 3
+WEIGHTED_SUM, LIFE, HEAT, SINCOS, SOBEL, NMS, THRESHOLD = 0, 1, 2, 3, 4, 5, 6
 ENUM_POW2, ENUM_EVEN = 0, 1
 STAGING_LOCAL, STAGING_DIRECT, STAGING_TEMPORAL, STAGING_STREAM = 0, 1, 2, 3
 OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF = 0, 1, 2
@@ -27,7 +27,6 @@ N_FEATURES = 13
 
 _DTYPES = {"f32": F32, "u8": U8, "i32": I32, "f64": F64}
 _BORDERS = {"clamp": CLAMP, "wrap": WRAP, "constant": CONSTANT}
-SOBEL, NMS, THRESHOLD = 4, 5, 6
 _KERNELS = {"weighted_sum": WEIGHTED_SUM, "life": LIFE, "heat": HEAT, "sincos": SINCOS, "sobel": SOBEL, "nms": NMS,
             "threshold": THRESHOLD}
 
@@ -93,9 +92,10 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
-           "stencil_set_mapping", "stencil_get_mapping", "stencil_output_dtype", "stencil_set_option", "stencil_max_wg_size", "stencil_tile_bytes",
-           "stencil_is_legal", "stencil_enumerate_wg", "stencil_run", "stencil_sweep_wg", "stencil_sweep_configs",
-           "stencil_device_copy", "stencil_time_copy", "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
+           "stencil_set_mapping", "stencil_get_mapping", "stencil_output_dtype", "stencil_set_option",
+           "stencil_max_wg_size", "stencil_tile_bytes", "stencil_is_legal", "stencil_enumerate_wg", "stencil_run",
+           "stencil_sweep_wg", "stencil_sweep_configs", "stencil_device_copy", "stencil_time_copy",
+           "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
            "stencil_predict_wg", "stencil_regressor_create", "stencil_regressor_destroy",
            "stencil_regressor_add", "stencil_regressor_predict", "stencil_regressor_fit_forest",

@@ -513,6 +513,39 @@ def test_iters_zero_copies_and_even_odd_iteration_counts(ls):
         check(ls, w, (8, 8), iters=it)
 
 
+def test_one_handle_serves_successive_weight_tables_and_kernels(ls):
+    """A handle whose weight table (kept on the device for run-time regions) is replaced, and whose
+    kernel is switched, between runs on a side stream: every run uses what was set last."""
+    halo = (2, 1, 3, 0)
+    w = custom(wl.WEIGHTED_SUM, 90, 117, halo, "wrap", seed=8)
+    g = w.grid()
+    st = ls.Stencil.from_workload(w)
+    st.set_mapping("local", 2, 4)
+    tin = torch.from_numpy(g).cuda()
+    tout = torch.empty_like(tin)
+    side = torch.cuda.Stream()
+    rng = np.random.default_rng(12)
+    tables, results = [], []
+    for k in range(3):
+        table = rng.random((halo[0] + halo[1] + 1, halo[2] + halo[3] + 1), dtype=np.float32)
+        tables.append(table)
+        st.set_kernel("weighted_sum", table)
+        with torch.cuda.stream(side):
+            for _ in range(4):                          # still in flight when the next table arrives
+                st.run(tin, tout, 3, (8, 16), stream=side)
+            results.append(tout.clone())
+    side.synchronize()
+    for table, res in zip(tables, results):
+        ref = oracle.apply(g, wl.WEIGHTED_SUM, halo, "wrap", 0.0, table, (), 3)
+        assert rel_err(res.cpu().numpy(), ref) <= REL_N
+    st.set_kernel("sincos", table)
+    st.run(tin, tout, 1, (8, 16))
+    torch.cuda.synchronize()
+    ref = oracle.apply(g, wl.SINCOS, halo, "wrap", 0.0, table, (), 1)
+    assert np.max(np.abs(tout.cpu().numpy() - ref)) <= 1e-4
+    st.close()
+
+
 def test_error_paths_do_not_launch(ls):
     w = wl.config(1, rows=64, cols=64)
     st = ls.Stencil.from_workload(w)
