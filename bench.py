@@ -162,12 +162,12 @@ def best_known_configuration(ls, torch, o, reps):
 
 
 # one application of the heat step on matrices that no cache holds (256 MiB and 1 GiB each way): the
-# workgroup sizes that win there are not those of the 4096^2 matrix, and the workgroup numbering
-# matters the other way round - the reason to sweep per dataset
-LARGE_HEAT_CONFIGS = [(m, cr, 4, 0, wg, remap)
+# workgroup sizes that win there are not those of the 4096^2 matrix, and the workgroup numbering and
+# non-temporal output stores matter the other way round - the reason to sweep per dataset
+LARGE_HEAT_CONFIGS = [(m, cr, 4, 0, wg, remap, nt)
                       for m, cr in (("direct", 2), ("direct", 4), ("local", 2), ("local", 4))
                       for wg in ((4, 16), (4, 64), (2, 256), (8, 64), (1, 512))
-                      for remap in (1, 0)]
+                      for remap in (1, 0) for nt in (0, 1)]
 
 
 def larger_matrices(ls, wl, torch, reps):
@@ -182,13 +182,13 @@ def larger_matrices(ls, wl, torch, reps):
         burst = 4
         mean, status, best = st.sweep_configs(a, b, LARGE_HEAT_CONFIGS, iters=burst, reps=reps)
         copy_ms, _ = ls.time_copy(a, b, burst=burst, reps=reps)
-        fixed = LARGE_HEAT_CONFIGS.index(("direct", 2, 4, 0, (4, 16), 1))      # the 4096^2 matrix's best
+        fixed = LARGE_HEAT_CONFIGS.index(("direct", 2, 4, 0, (4, 16), 1, 0))   # the 4096^2 matrix's best
         st.close()
         del a, b
         c = LARGE_HEAT_CONFIGS[best]
         gbs = lambda ms: n * n * 8 / (ms / burst) / 1e6
         out["heat %dx%d" % (n, n)] = {
-            "best": {"mapping": mapping_name(c[:3]), "wg": list(c[4]), "xcd_remap": c[5]},
+            "best": {"mapping": mapping_name(c[:3]), "wg": list(c[4]), "xcd_remap": c[5], "nt_store": c[6]},
             "ms_per_application": mean[best] / burst, "algorithmic_gbs": gbs(mean[best]),
             "frac_of_hbm_peak": gbs(mean[best]) / HBM_PEAK_GBS,
             "with_the_4096_best": {"algorithmic_gbs": gbs(mean[fixed]), "frac_of_hbm_peak": gbs(mean[fixed]) / HBM_PEAK_GBS},

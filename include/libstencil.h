@@ -171,10 +171,16 @@ int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int 
  * for stencil_sweep_wg, after the paper's closing remarks on minimising the observations needed
  * to tell bad sizes from good ones: every size first gets one warm-up and two samples; only the
  * sizes whose two-sample mean is within cutoff/100 times the best one are then sampled in full
- * (3 warm-ups + `reps` samples); the others keep their two-sample statistics. */
+ * (3 warm-ups + `reps` samples); the others keep their two-sample statistics.
+ * STENCIL_OPT_NT_STORE (default 0): the kernels' 16-byte stores of output cells are issued as
+ * non-temporal stores (the output is not read again by the launch that writes it); narrower
+ * stores (unaligned rows, one cell per work-item, the threshold stencil) stay plain.  Same
+ * results, different cache behaviour: it pays on matrices beyond the caches and costs where
+ * the next application would have found its input in a cache. */
 #define STENCIL_MAX_TEMPORAL_DEPTH 4   /* STENCIL_STAGING_TEMPORAL */
 #define STENCIL_MAX_STREAM_DEPTH 8     /* STENCIL_STAGING_STREAM */
-enum stencil_option { STENCIL_OPT_XCD_REMAP = 0, STENCIL_OPT_TEMPORAL_DEPTH = 1, STENCIL_OPT_SWEEP_CUTOFF = 2 };
+enum stencil_option { STENCIL_OPT_XCD_REMAP = 0, STENCIL_OPT_TEMPORAL_DEPTH = 1, STENCIL_OPT_SWEEP_CUTOFF = 2,
+                      STENCIL_OPT_NT_STORE = 3 };
 int stencil_set_option(stencil_t *st, int option, int value);
 
 /* ---- legality (Section 3.1) ---------------------------------------------------------- */
@@ -232,17 +238,19 @@ int stencil_sweep_wg(stencil_t *st, const void *in, void *out, int iters,
  * optimisation parameters as the next step): each configuration fixes the mapping
  * (stencil_set_mapping's three arguments), the number of applications fused per launch (depth; 0
  * keeps the current STENCIL_OPT_TEMPORAL_DEPTH), the numbering of workgroups (xcd_remap; -1 keeps
- * the current STENCIL_OPT_XCD_REMAP) and a workgroup size, and is timed by
+ * the current STENCIL_OPT_XCD_REMAP), the kind of output stores (nt_store; -1 keeps the current
+ * STENCIL_OPT_NT_STORE) and a workgroup size, and is timed by
  * stencil_sweep_wg's protocol.  mean_ms[k] = mean milliseconds per sample (`iters` applications),
  * NaN unless status[k] == STENCIL_OK; status[k] = STENCIL_E_INVALID for a mapping or depth the
  * scenario does not offer, STENCIL_E_REFUSED for an illegal workgroup size; best_index (may be
  * NULL) = fastest configuration or -1.  Afterwards the scenario is left on the fastest
- * configuration (mapping, depth, numbering, and its size for stencil_run(0, 0)); on error, or if none ran, on
+ * configuration (mapping, depth, numbering, stores, and its size for stencil_run(0, 0)); on error, or if none ran, on
  * the one it had.  configs, mean_ms, status: host arrays of n.  Synchronous. */
 typedef struct stencil_config {
     int staging, cells_rows, cells_cols;   /* as for stencil_set_mapping */
     int depth;                             /* applications per launch, 0 = leave as is */
     int xcd_remap;                         /* STENCIL_OPT_XCD_REMAP: 0 or 1, -1 = leave as is */
+    int nt_store;                          /* STENCIL_OPT_NT_STORE: 0 or 1, -1 = leave as is */
     int wg_rows, wg_cols;
 } stencil_config_t;
 int stencil_sweep_configs(stencil_t *st, const void *in, void *out, int iters,

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(MAXT) void direct_kernel(const TileArgs<Op, Halo> a
         for (int cc = 0; cc < CC; ++cc) res[cc] = Op::finish(st[cr][cc], a.scalar0);
         T *dst = a.out + (size_t)r * cols + c0;
         if (a.vec_ok && c0 + CC <= cols) {
-            store_vec(dst, res);
+            store_out_vec(dst, res, a.nt_store != 0);
         } else {
 #pragma unroll
             for (int cc = 0; cc < CC; ++cc)
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(MAXT) void life_direct_kernel(const TileArgs<OpLife
         life_rule(o, above, cur, below);
         uint8_t *dst = a.out + (size_t)r * cols + c0;
         if (a.vec_ok && c0 + CC <= cols) {
-            *reinterpret_cast<uint4 *>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
+            store_word4(dst, make_uint4(o[0], o[1], o[2], o[3]), a.nt_store != 0);
         } else {
 #pragma unroll
             for (int k = 0; k < CC; ++k)

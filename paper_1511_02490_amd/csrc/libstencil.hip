@@ -337,6 +337,9 @@ int stencil_set_option(stencil_t *s, int option, int value) {
     case STENCIL_OPT_XCD_REMAP:
         s->xcd_remap = value ? 1 : 0;
         return STENCIL_OK;
+    case STENCIL_OPT_NT_STORE:
+        s->nt_store = value ? 1 : 0;
+        return STENCIL_OK;
     case STENCIL_OPT_SWEEP_CUTOFF:
         if (value < 0 || (value > 0 && value < 100))
             return fail(STENCIL_E_INVALID, "sweep cutoff is a percentage >= 100, or 0 to sample every size fully");
@@ -550,6 +553,7 @@ int stencil_sweep_configs(stencil_t *s, const void *in, void *out, int iters, co
     if (rc != STENCIL_OK) return rc;
     const double nan = std::numeric_limits<double>::quiet_NaN();
     const int staging0 = s->staging, cr0 = s->cr, cc0 = s->cc, depth0 = s->temporal_depth, remap0 = s->xcd_remap;
+    const int nt0 = s->nt_store;
     int best = -1;
     for (int k = 0; k < n; ++k) {
         const stencil_config_t &c = configs[k];
@@ -558,6 +562,7 @@ int stencil_sweep_configs(stencil_t *s, const void *in, void *out, int iters, co
         // a mapping the scenario does not have, or a depth the mapping does not have: skipped
         s->temporal_depth = depth0;       // "as is" means as it was when the sweep began
         s->xcd_remap = c.xcd_remap < 0 ? remap0 : (c.xcd_remap ? 1 : 0);
+        s->nt_store = c.nt_store < 0 ? nt0 : (c.nt_store ? 1 : 0);
         if (stencil_set_mapping(s, c.staging, c.cells_rows, c.cells_cols) != STENCIL_OK) continue;
         if (c.depth != 0 && stencil_set_option(s, STENCIL_OPT_TEMPORAL_DEPTH, c.depth) != STENCIL_OK) continue;
         const Variant *v = find_variant(s);
@@ -574,6 +579,7 @@ int stencil_sweep_configs(stencil_t *s, const void *in, void *out, int iters, co
         const stencil_config_t &c = configs[best];
         s->temporal_depth = depth0;
         s->xcd_remap = c.xcd_remap < 0 ? remap0 : (c.xcd_remap ? 1 : 0);
+        s->nt_store = c.nt_store < 0 ? nt0 : (c.nt_store ? 1 : 0);
         (void)stencil_set_mapping(s, c.staging, c.cells_rows, c.cells_cols);
         if (c.depth != 0) (void)stencil_set_option(s, STENCIL_OPT_TEMPORAL_DEPTH, c.depth);
         s->best_rows = c.wg_rows;
@@ -584,6 +590,7 @@ int stencil_sweep_configs(stencil_t *s, const void *in, void *out, int iters, co
         s->cc = cc0;
         s->temporal_depth = depth0;
         s->xcd_remap = remap0;
+        s->nt_store = nt0;
         s->best_rows = s->best_cols = 0;
     }
     if (best_index) *best_index = best;

@@ -32,14 +32,15 @@ __device__ __forceinline__ void load_words(uint32_t (&v)[WORDS], const void *src
         v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
     }
 }
+// (the 16-byte stores can be non-temporal, as in the other kernels; the narrower ones are plain)
 template <int WORDS>
-__device__ __forceinline__ void store_words(void *dst, const uint32_t (&v)[WORDS]) {
+__device__ __forceinline__ void store_words(void *dst, const uint32_t (&v)[WORDS], bool nt) {
     if constexpr (WORDS == 1) {
         *reinterpret_cast<uint32_t *>(dst) = v[0];
     } else if constexpr (WORDS == 2) {
         *reinterpret_cast<uint2 *>(dst) = make_uint2(v[0], v[1]);
     } else {
-        *reinterpret_cast<uint4 *>(dst) = make_uint4(v[0], v[1], v[2], v[3]);
+        store_word4(dst, make_uint4(v[0], v[1], v[2], v[3]), nt);
     }
 }
 
@@ -177,7 +178,7 @@ __device__ __forceinline__ void life_stream_body(const TileArgs<OpLife, HaloC<1,
                 } else if (t >= 2 * DEPTH && t < kSteps && gr < rows && writes) {
                     uint8_t *dst = a.out + (size_t)gr * cols + (unsigned)gc0;
                     if (FAST) {
-                        store_words<WORDS>(dst, res);
+                        store_words<WORDS>(dst, res, a.nt_store != 0);
                     } else {
 #pragma unroll
                         for (int c = 0; c < CC; ++c)

@@ -171,7 +171,7 @@ __device__ __forceinline__ void march_body(const TileArgs<Op, Halo> &a, const in
                             for (int cc = 0; cc < CC; ++cc) res[cc] = Op::finish(st[slot][cc], a.scalar0);
                             if (FAST) {
                                 char *rowp = reinterpret_cast<char *>(a.out + (size_t)gr * cols);
-                                store_vec(reinterpret_cast<T *>(rowp + out_off), res);
+                                store_out_vec(reinterpret_cast<T *>(rowp + out_off), res, a.nt_store != 0);
                             } else {
                                 T *out = a.out + (size_t)gr * cols + gc0;
 #pragma unroll

@@ -156,7 +156,7 @@ __device__ __forceinline__ void stream_body(const TileArgs<Op, HaloC<1, 1, 1, 1>
                     // gr = r0 + t - 2*DEPTH runs over this segment's rows
                     if (FAST) {
                         char *rowp = reinterpret_cast<char *>(a.out + (size_t)gr * cols);
-                        store_vec(reinterpret_cast<T *>(rowp + out_off), res);
+                        store_out_vec(reinterpret_cast<T *>(rowp + out_off), res, a.nt_store != 0);
                     } else {
                         T *out = a.out + (size_t)gr * cols + gc0;
 #pragma unroll

@@ -177,7 +177,7 @@ __global__ __launch_bounds__(MAXT) void temporal_kernel(const TileArgs<Op, HaloC
             temporal_quad<Op>(res, up, mid, dn, a.w, a.scalar0);
             T *out = a.out + (size_t)r * cols + c;
             if (a.vec_ok && c + CC <= cols) {
-                store_vec(out, res);
+                store_out_vec(out, res, a.nt_store != 0);
             } else {
 #pragma unroll
                 for (int cc = 0; cc < CC; ++cc)
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(MAXT) void life_temporal_kernel(const TileArgs<OpLi
             life_rule(o, up, mid, dn);
             uint8_t *out = a.out + (size_t)r * cols + c;
             if (a.vec_ok && c + CC <= cols) {
-                *reinterpret_cast<uint4 *>(out) = make_uint4(o[0], o[1], o[2], o[3]);
+                store_word4(out, make_uint4(o[0], o[1], o[2], o[3]), a.nt_store != 0);
             } else {
 #pragma unroll
                 for (int b = 0; b < CC; ++b)

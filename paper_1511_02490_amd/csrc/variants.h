@@ -50,6 +50,7 @@ struct stencil {
     int staging = STENCIL_STAGING_LOCAL;
     int cr = 1, cc = 1;
     int xcd_remap = 1;
+    int nt_store = 0;         // output vectors are written with non-temporal stores
     int temporal_depth = 2;   // applications per launch under STENCIL_STAGING_TEMPORAL
     int sweep_cutoff_pct = 0; // > 0: sizes slower than this percentage of the best so far are cut short
     int best_rows = 0, best_cols = 0;
@@ -146,6 +147,7 @@ sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, 
     }
     const size_t row_bytes = (size_t)s->cols * sizeof(T);
     a.vec_ok = (CC > 1 && row_bytes % 16 == 0 && (uintptr_t)in % 16 == 0 && (uintptr_t)out % 16 == 0) ? 1 : 0;
+    a.nt_store = s->nt_store;
     a.pad = (T)s->pad;
     a.scalar0 = s->scalar0;
     if constexpr (Halo::kStatic) {

@@ -20,7 +20,7 @@ CLAMP, WRAP, CONSTANT = 0, 1, 2
 WEIGHTED_SUM, LIFE, HEAT, SINCOS, SOBEL, NMS, THRESHOLD = 0, 1, 2, 3, 4, 5, 6
 ENUM_POW2, ENUM_EVEN = 0, 1
 STAGING_LOCAL, STAGING_DIRECT, STAGING_TEMPORAL, STAGING_STREAM = 0, 1, 2, 3
-OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF = 0, 1, 2
+OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF, OPT_NT_STORE = 0, 1, 2, 3
 _STAGINGS = {"local": STAGING_LOCAL, "direct": STAGING_DIRECT, "temporal": STAGING_TEMPORAL,
              "stream": STAGING_STREAM}
 N_FEATURES = 13
@@ -173,7 +173,8 @@ def baseline_wg(performance: Sequence[Sequence[float]]) -> int:
 
 class _Config(ctypes.Structure):
     _fields_ = [("staging", ctypes.c_int), ("cells_rows", ctypes.c_int), ("cells_cols", ctypes.c_int),
-                ("depth", ctypes.c_int), ("xcd_remap", ctypes.c_int), ("wg_rows", ctypes.c_int), ("wg_cols", ctypes.c_int)]
+                ("depth", ctypes.c_int), ("xcd_remap", ctypes.c_int), ("nt_store", ctypes.c_int),
+                ("wg_rows", ctypes.c_int), ("wg_cols", ctypes.c_int)]
 
 
 class SweepResult:
@@ -332,8 +333,8 @@ class Stencil:
 
     def sweep_configs(self, tin, tout, configs, iters: int = 1, reps: int = 30, stream=None):
         """Sweep whole configurations: each is (staging, cells_rows, cells_cols, depth, (wg_rows,
-        wg_cols)) with depth 0 = leave as is, optionally followed by the workgroup numbering (0 / 1;
-        left as is when absent).  Returns (mean_ms list, status list, best index); the scenario is
+        wg_cols)) with depth 0 = leave as is, optionally followed by the workgroup numbering and then
+        the non-temporal-store switch (0 / 1 each; left as is when absent).  Returns (mean_ms list, status list, best index); the scenario is
         left on the fastest configuration."""
         self._check_tensors(tin, tout)
         n = len(configs)
@@ -341,8 +342,9 @@ class Stencil:
         for k, cfg in enumerate(configs):
             staging, cr, cc, depth, wg = cfg[:5]
             remap = int(cfg[5]) if len(cfg) > 5 else -1
+            nt = int(cfg[6]) if len(cfg) > 6 else -1
             sg = _STAGINGS[staging] if isinstance(staging, str) else int(staging)
-            arr[k] = _Config(sg, int(cr), int(cc), int(depth), remap, int(wg[0]), int(wg[1]))
+            arr[k] = _Config(sg, int(cr), int(cc), int(depth), remap, nt, int(wg[0]), int(wg[1]))
         mean = (ctypes.c_double * max(n, 1))()
         status = (ctypes.c_int * max(n, 1))()
         best = ctypes.c_int(-1)

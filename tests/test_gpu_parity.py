@@ -634,6 +634,45 @@ def test_device_copy_and_workgroup_numbering_option(ls):
     assert rel_err(outs[0], oracle.apply_workload(w, g)) <= REL_1
 
 
+def test_non_temporal_stores_change_no_value(ls):
+    """STENCIL_OPT_NT_STORE only changes how output vectors are written: every kernel family gives
+    the same matrix with it as without it, and the one the oracle gives."""
+    heat = wl.config(3, rows=150, cols=256, iters=8)
+    heat.border = "constant"
+    life = wl.config(2, rows=150, cols=256, iters=8)
+    cases = [(heat, ("local", 2, 4)), (heat, ("direct", 2, 4)), (heat, ("temporal", 2, 4, 4)), (heat, ("stream", 20, 4, 8)),
+             (life, ("local", 2, 16)), (life, ("direct", 2, 16)), (life, ("temporal", 2, 16, 2)), (life, ("stream", 20, 16, 8)),
+             (custom(wl.SINCOS, 90, 256, (1, 5, 3, 0), "clamp", seed=4), ("stream", 16, 4)),
+             (custom(wl.WEIGHTED_SUM, 90, 256, (3, 0, 2, 1), "wrap", seed=4), ("local", 2, 4))]
+    for w, blocking in cases:
+        g = w.grid()
+        ref = oracle.apply_workload(w, g)
+        tin = torch.from_numpy(g).cuda()
+        outs = []
+        for nt in (0, 1):
+            st = ls.Stencil.from_workload(w)
+            set_mapping(st, blocking)
+            st.set_option(ls.OPT_NT_STORE, nt)
+            tout = torch.zeros_like(tin)
+            st.run(tin, tout, w.iters, (2, 64))
+            torch.cuda.synchronize()
+            outs.append(tout.cpu().numpy())
+            st.close()
+        np.testing.assert_array_equal(outs[0], outs[1])
+        if w.dtype == "u8" or w.kernel == wl.HEAT:
+            np.testing.assert_array_equal(outs[1], ref)
+        else:
+            assert rel_err(outs[1], ref) <= REL_1
+    # the switch is one of the things stencil_sweep_configs sweeps
+    w = wl.config(3, rows=512, cols=512, iters=1)
+    st = ls.Stencil.from_workload(w)
+    tin = torch.from_numpy(w.grid()).cuda()
+    tout = torch.empty_like(tin)
+    mean, status, best = st.sweep_configs(tin, tout, [("direct", 2, 4, 0, (4, 16), 1, nt) for nt in (0, 1)], iters=2, reps=3)
+    assert status == [ls.OK, ls.OK] and best in (0, 1)
+    st.close()
+
+
 def test_runs_on_a_side_stream(ls):
     w = wl.config(0)
     g = w.grid()
