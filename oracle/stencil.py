@@ -53,10 +53,11 @@ def _load() -> ctypes.CDLL:
         lib.oracle_sobel_f32.argtypes = [p, p, i64, i64, i32, f32, i32, i32]
         lib.oracle_nms_f32.argtypes = [p, p, i64, i64, i32, f32, i32, i32]
         lib.oracle_threshold_f32_u8.argtypes = [p, p, i64, i64, f32, i32]
+        lib.oracle_weighted_sum_u8_f32.argtypes = [p, p, i64, i64, i32, i32, i32, i32, i32, ctypes.c_uint8, p, i32]
         for fn in (lib.oracle_weighted_sum_f32, lib.oracle_sincos_f32, lib.oracle_weighted_sum_f64,
                    lib.oracle_weighted_sum_i32, lib.oracle_life_u8,
                    lib.oracle_heat_f32, lib.oracle_heat_f64, lib.oracle_sobel_f32, lib.oracle_nms_f32,
-                   lib.oracle_threshold_f32_u8, lib.oracle_max_threads):
+                   lib.oracle_threshold_f32_u8, lib.oracle_weighted_sum_u8_f32, lib.oracle_max_threads):
             fn.restype = i32
         _lib = lib
     return _lib
@@ -83,7 +84,7 @@ def apply(grid: np.ndarray, kernel: str, halo: Sequence[int], border: str, pad: 
           threads: int = 0, precision: str = "native") -> np.ndarray:
     """`iters` applications of the stencil (Section 2) to `grid`; returns the final grid.
 
-    kernel: "weighted_sum" (f32; also f64 and i32, chosen by the grid's dtype), "life" (u8, cells 0/1), "heat" (f32; scalars=(alpha,);
+    kernel: "weighted_sum" (f32; also f64 and i32, and u8 in / f32 out, chosen by the grid's dtype), "life" (u8, cells 0/1), "heat" (f32; scalars=(alpha,);
     precision="f64" carries the state in float64 instead), "sincos" (f32), and the Canny detector's
     "sobel", "nms" (f32) and "threshold" (f32 in, u8 out; scalars=(level,)).
     halo = (north, south, east, west).  threads=0 leaves OpenMP's default.
@@ -94,7 +95,15 @@ def apply(grid: np.ndarray, kernel: str, halo: Sequence[int], border: str, pad: 
     rows, cols = grid.shape
     n, s, e, w = (int(h) for h in halo)
     b = _BORDER[border]
-    if kernel == "weighted_sum" and grid.dtype in (np.float64, np.int32):
+    if kernel == "weighted_sum" and grid.dtype == np.uint8:
+        if int(iters) != 1:
+            raise ValueError("a weighted sum of a byte matrix is applied once (bytes in, floats out)")
+        a = np.ascontiguousarray(grid)
+        wt = _check_weights(weights, (n, s, e, w))
+        out = np.empty(a.shape, dtype=np.float32)
+        rc = lib.oracle_weighted_sum_u8_f32(_ptr(a), _ptr(out), rows, cols, n, s, e, w, b, int(pad), _ptr(wt),
+                                            int(threads))
+    elif kernel == "weighted_sum" and grid.dtype in (np.float64, np.int32):
         a = np.ascontiguousarray(grid)
         wt = _check_weights(weights, (n, s, e, w))
         out = np.empty_like(a)

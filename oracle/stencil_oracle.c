@@ -117,6 +117,26 @@ static void step_weighted_sum(const float *in, float *out, int64_t rows, int64_t
         }
 }
 
+/* The weighted sum with different input and output element types (Section 3.3 lists both among
+ * a kernel's features): a byte matrix in, a float matrix out - an 8-bit image blurred into floats,
+ * the first stage of the Canny detector.  The padding value is a byte like any other cell; fp64
+ * accumulation in (dr, dc) row-major order, rounded once to fp32. */
+static void step_weighted_sum_u8_f32(const uint8_t *in, float *out, int64_t rows, int64_t cols,
+                                     int N, int S, int E, int W, int border, uint8_t pad, const float *w)
+{
+    const int ww = E + W + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            double acc = 0.0;
+            for (int dr = -N; dr <= S; ++dr)
+                for (int dc = -W; dc <= E; ++dc)
+                    acc += (double)w[(dr + N) * ww + (dc + W)] *
+                           (double)V_u8(in, rows, cols, r + dr, c + dc, border, pad);
+            out[r * cols + c] = (float)acc;
+        }
+}
+
 /* The weighted sum on the other element types of the paper's template (Section 3.3).
  * double: accumulated in long double, rounded once.  int32: exact integer arithmetic reduced
  * modulo 2^32 (the weights hold integers). */
@@ -374,6 +394,16 @@ int oracle_nms_f32(const float *in, float *out, int64_t rows, int64_t cols, int 
 {
     set_threads(threads);
     ITERATE(float, step_nms_f32(src, dst, rows, cols, border, pad))
+}
+
+/* one application only: the output is of another type than the input */
+int oracle_weighted_sum_u8_f32(const uint8_t *in, float *out, int64_t rows, int64_t cols,
+                               int N, int S, int E, int W, int border, uint8_t pad,
+                               const float *w, int threads)
+{
+    set_threads(threads);
+    step_weighted_sum_u8_f32(in, out, rows, cols, N, S, E, W, border, pad, w);
+    return 0;
 }
 
 /* one application only: the output is of another type than the input */

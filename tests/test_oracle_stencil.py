@@ -186,6 +186,41 @@ def test_weighted_sum_on_double_and_int32_matrices():
         oracle.apply(gi32, "weighted_sum", halo, "clamp", 0, wi + 0.5)
 
 
+def test_weighted_sum_of_a_byte_matrix_into_floats():
+    """Bytes in, floats out (the kernel whose input and output types differ): torch's float64
+    correlation of the same integers for every border mode; an impulse of 255 under distinct
+    weights by hand (orientation, and no wrap-around at the top of the byte range); a byte padding
+    value; integer weights give exact integers; one application only."""
+    r = rng(77)
+    halo = (2, 1, 2, 2)
+    g = r.integers(0, 256, size=(17, 21), dtype=np.uint8)
+    w = r.random((4, 5), dtype=np.float32)
+    for border in BORDERS:
+        out = oracle.apply(g, "weighted_sum", halo, border, 200, w)
+        assert out.dtype == np.float32 and out.shape == g.shape
+        ref = _torch_correlate(g.astype(np.float64), w, halo, border, 200.0)
+        np.testing.assert_array_equal(out, ref.astype(np.float32))     # fp64 sums of <= 20 products, rounded once
+    N, S, E, W = halo
+    wd = np.arange(1, 21, dtype=np.float32).reshape(4, 5)
+    gi = np.zeros((9, 9), np.uint8)
+    gi[4, 4] = 255
+    oi = oracle.apply(gi, "weighted_sum", halo, "constant", 0, wd)
+    expect = np.zeros((9, 9), np.float32)
+    for dr in range(-N, S + 1):
+        for dc in range(-W, E + 1):
+            expect[4 - dr, 4 - dc] = 255.0 * wd[dr + N, dc + W]
+    np.testing.assert_array_equal(oi, expect)
+    # all-255 image, weights 1: every cell 20 * 255 (a byte sum would have wrapped)
+    full = np.full((6, 7), 255, np.uint8)
+    np.testing.assert_array_equal(oracle.apply(full, "weighted_sum", halo, "clamp", 0, np.ones((4, 5), np.float32)),
+                                  np.full((6, 7), 5100.0, np.float32))
+    # the padding value is a byte: a 1x1 matrix of 10 with pad 3 under a 3x3 box sums to 10 + 8 * 3
+    one = np.array([[10]], np.uint8)
+    assert oracle.apply(one, "weighted_sum", (1, 1, 1, 1), "constant", 3, np.ones((3, 3), np.float32))[0, 0] == 34.0
+    with pytest.raises(ValueError):
+        oracle.apply(g, "weighted_sum", halo, "clamp", 0, w, iters=2)
+
+
 def test_iterations_compose():
     g = rng(9).random((12, 15), dtype=np.float32)
     w = wl.binomial3_weights()
