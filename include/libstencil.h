@@ -57,6 +57,11 @@ enum stencil_border { STENCIL_CLAMP = 0, STENCIL_WRAP = 1, STENCIL_CONSTANT = 2 
  *                 F32: fp32 fma chain.  F64: fp64 fma chain (weights widened).  I32: 32-bit
  *                 wrap-around arithmetic; the weights must be integers.  F64 / I32 run with
  *                 the local-memory tile only, cells per work-item (1,1) or (2,2) / (2,4).
+ *                 U8: a byte matrix in, an F32 matrix out (input and output types differ,
+ *                 Section 3.3) - an 8-bit image blurred into floats; cells are converted
+ *                 exactly, then the fp32 fma chain; the padding value is a byte.  Exactly one
+ *                 application per stencil_run / sweep sample; local-memory tile only, cells
+ *                 per work-item (1,1), (4,1), (1,4), (2,4), (4,4), (1,16) or (2,16).
  *   LIFE (u8):    Conway B3/S23 on cells 0/1, region 1/1/1/1 - "gol".
  *   HEAT (f32):   u + alpha * (((n + s) + (e + w)) - 4u), region 1/1/1/1, every operation
  *                 rounded to fp32 in this order - "he".  scalars[0] = alpha.
@@ -158,7 +163,8 @@ enum stencil_staging {
 int stencil_set_mapping(stencil_t *st, int staging, int cells_rows, int cells_cols);
 
 /* Element type (enum stencil_dtype) of the matrix `out` must be: the scenario's own, except
- * STENCIL_U8 once STENCIL_THRESHOLD is selected.  `out` always holds rows*cols elements of it. */
+ * STENCIL_U8 once STENCIL_THRESHOLD is selected and STENCIL_F32 for STENCIL_WEIGHTED_SUM on a
+ * U8 matrix.  `out` always holds rows*cols elements of it. */
 int stencil_output_dtype(const stencil_t *st);
 int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int *cells_cols);
 

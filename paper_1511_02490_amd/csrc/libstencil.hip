@@ -246,7 +246,7 @@ int stencil_set_kernel(stencil_t *s, int kernel_id, const float *weights, int n_
     switch (kernel_id) {
     case STENCIL_WEIGHTED_SUM:
     case STENCIL_SINCOS:
-        if (s->dtype == STENCIL_U8 || (kernel_id == STENCIL_SINCOS && s->dtype != STENCIL_F32))
+        if (kernel_id == STENCIL_SINCOS && s->dtype != STENCIL_F32)
             return fail(STENCIL_E_INVALID, "this kernel is not available for the matrix's element type");
         if (!weights || n_weights != cells)
             return fail(STENCIL_E_INVALID, "weights must hold (N+S+1)*(E+W+1) = %d floats (got %d)", cells, n_weights);

@@ -119,6 +119,40 @@ struct OpWeightedSumI32 {
     __device__ static __forceinline__ T finish(const State &s, float) { return (T)s.acc; }
 };
 
+// The weighted sum of a byte matrix, written as floats: a kernel whose input and output element
+// types differ (Section 3.3 lists both among a kernel's features) - an 8-bit image blurred into
+// floats, the first stage of the Canny detector.  Cells become floats when they are staged
+// (exact); from there on it is the fp32 fma chain above.  O names the output element type where
+// it is not T.
+struct OpWeightedSumU8 {
+    static constexpr bool kRowFold = false;
+    using T = uint8_t;
+    using O = float;
+    using L = float;
+    using V = float;
+    static constexpr int kPlanes = 1;
+    static constexpr bool kWeights = true;
+    struct State { float acc; };
+    __device__ static __forceinline__ void stage(T v, L (&out)[1]) { out[0] = (float)v; }
+    __device__ static __forceinline__ V combine(const L (&p)[1]) { return p[0]; }
+    template <int CC>
+    __device__ static __forceinline__ void stage_vec(const T (&v)[CC], L (&out)[1][CC]) {
+#pragma unroll
+        for (int k = 0; k < CC; ++k) out[0][k] = (float)v[k];
+    }
+    __device__ static __forceinline__ void init(State &s) { s.acc = 0.0f; }
+    __device__ static __forceinline__ void visit(State &s, int, int, float w, V v) {
+        s.acc = __fmaf_rn(w, v, s.acc);
+    }
+    __device__ static __forceinline__ O finish(const State &s, float) { return s.acc; }
+};
+
+// The output element type of a customising function: Op::O where it names one, else Op::T.
+template <class Op, class = void>
+struct out_type_of { using type = typename Op::T; };
+template <class Op>
+struct out_type_of<Op, decltype(void(sizeof(typename Op::O)))> { using type = typename Op::O; };
+
 // ---- Conway's Game of Life, B3/S23 ("gol") -------------------------------------------------
 struct OpLife {
     static constexpr bool kRowFold = false;

@@ -31,7 +31,7 @@ struct WeightStore<Op, Halo, false> {
 template <class Op, class Halo>
 struct TileArgs {
     const typename Op::T *in;
-    typename Op::T *out;
+    typename out_type_of<Op>::type *out;
     int rows, cols;
     int tiles_c;     // tiles per row of tiles
     int n_tiles;
@@ -39,7 +39,7 @@ struct TileArgs {
     int pitch;       // LDS tile pitch, in staged elements
     int plane;       // elements per LDS plane (tile rows x pitch)
     unsigned stage_magic;   // ceil(2^32 / items per staged row): tid / items by one multiply
-    int vec_ok;      // rows of `in` / `out` start 16-byte aligned and cols % CC == 0
+    int vec_ok;      // rows of `in` / `out` start at multiples of a work-item's load / store width and cols % CC == 0
     int nt_store;    // vector stores of output cells are non-temporal
     typename Op::T pad;
     float scalar0;
@@ -50,15 +50,21 @@ struct TileArgs {
 __host__ __device__ constexpr int round_up(int x, int m) { return (x + m - 1) / m * m; }
 __host__ __device__ constexpr int round_down(int x, int m) { return x / m * m; }
 
-// 16-byte moves between global memory / LDS and register arrays.
+// 16-byte moves between global memory / LDS and register arrays (a load may also be one 4-byte
+// word: four byte cells that are widened to floats afterwards).
 template <class E, int CNT>
 __device__ __forceinline__ void load_vec(E (&dst)[CNT], const E *src) {
-    static_assert(sizeof(E) * CNT % 16 == 0, "vector moves are whole 16-byte words");
-    constexpr int NV = sizeof(E) * CNT / 16;
-    uint4 tmp[NV];
+    if constexpr (sizeof(E) * CNT == 4) {
+        const uint32_t tmp = *reinterpret_cast<const uint32_t *>(src);
+        __builtin_memcpy(dst, &tmp, 4);
+    } else {
+        static_assert(sizeof(E) * CNT % 16 == 0, "vector moves are whole 16-byte words");
+        constexpr int NV = sizeof(E) * CNT / 16;
+        uint4 tmp[NV];
 #pragma unroll
-    for (int k = 0; k < NV; ++k) tmp[k] = reinterpret_cast<const uint4 *>(src)[k];
-    __builtin_memcpy(dst, tmp, sizeof(tmp));
+        for (int k = 0; k < NV; ++k) tmp[k] = reinterpret_cast<const uint4 *>(src)[k];
+        __builtin_memcpy(dst, tmp, sizeof(tmp));
+    }
 }
 template <class E, int CNT>
 __device__ __forceinline__ void store_vec(E *dst, const E (&src)[CNT]) {
@@ -172,7 +178,7 @@ __device__ __forceinline__ void stage_tile(typename Op::L *tile, int plane, int 
 
 template <class Op, int B, class Halo, int CR, int CC, int MAXT>
 __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) {
-    using T = typename Op::T;
+    using O = typename out_type_of<Op>::type;
     using L = typename Op::L;
     constexpr int NP = Op::kPlanes;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -348,10 +354,10 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
     for (int cr = 0; cr < CR; ++cr) {
         const int r = r0 + lr0 + cr;
         if (r >= rows) break;
-        T res[CC];
+        O res[CC];
 #pragma unroll
         for (int cc = 0; cc < CC; ++cc) res[cc] = Op::finish(st[cr][cc], a.scalar0);
-        T *dst = a.out + (size_t)r * cols + c0 + lc0;
+        O *dst = a.out + (size_t)r * cols + c0 + lc0;
         if constexpr (CC > 1) {
             if (a.vec_ok && c0 + lc0 + CC <= cols) {
                 store_out_vec(dst, res, a.nt_store != 0);

@@ -61,15 +61,20 @@ struct stencil {
     std::vector<hipEvent_t> events;
     size_t elem() const { return dtype == STENCIL_U8 ? 1 : (dtype == STENCIL_F64 ? 8 : 4); }
     size_t bytes() const { return (size_t)rows * (size_t)cols * elem(); }
-    // the output matrix: the input's element type, except for the threshold stencil (bytes)
-    int out_dtype() const { return kernel == STENCIL_THRESHOLD ? STENCIL_U8 : dtype; }
+    // the output matrix: the input's element type, except for the threshold stencil (floats in,
+    // bytes out) and the weighted sum of a byte matrix (bytes in, floats out)
+    int out_dtype() const {
+        if (kernel == STENCIL_THRESHOLD) return STENCIL_U8;
+        if (kernel == STENCIL_WEIGHTED_SUM && dtype == STENCIL_U8) return STENCIL_F32;
+        return dtype;
+    }
     size_t out_elem() const { return out_dtype() == STENCIL_U8 ? 1 : (out_dtype() == STENCIL_F64 ? 8 : 4); }
     size_t out_bytes() const { return (size_t)rows * (size_t)cols * out_elem(); }
 };
 
 // Variant keys of WEIGHTED_SUM on the other element types (internal: the public kernel id is
 // STENCIL_WEIGHTED_SUM, the matrix dtype selects the variant).
-enum { STENCIL_WEIGHTED_SUM_F64 = 100, STENCIL_WEIGHTED_SUM_I32 = 101 };
+enum { STENCIL_WEIGHTED_SUM_F64 = 100, STENCIL_WEIGHTED_SUM_I32 = 101, STENCIL_WEIGHTED_SUM_U8 = 102 };
 
 namespace {
 
@@ -77,6 +82,7 @@ namespace {
 int variant_kernel(const stencil *s) {
     if (s->kernel == STENCIL_WEIGHTED_SUM && s->dtype == STENCIL_F64) return STENCIL_WEIGHTED_SUM_F64;
     if (s->kernel == STENCIL_WEIGHTED_SUM && s->dtype == STENCIL_I32) return STENCIL_WEIGHTED_SUM_I32;
+    if (s->kernel == STENCIL_WEIGHTED_SUM && s->dtype == STENCIL_U8) return STENCIL_WEIGHTED_SUM_U8;
     return s->kernel;
 }
 
@@ -133,7 +139,7 @@ sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, 
     const TileGeom g = tile_geom(s, v, wr, wc);
     sk::TileArgs<Op, Halo> a;
     a.in = static_cast<const T *>(in);
-    a.out = static_cast<T *>(out);
+    a.out = static_cast<typename sk::out_type_of<Op>::type *>(out);
     a.rows = (int)s->rows;
     a.cols = (int)s->cols;
     a.tiles_c = g.tiles_c;
@@ -145,8 +151,12 @@ sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, 
         const unsigned items = std::max(1u, (unsigned)(g.pitch / CC));
         a.stage_magic = (unsigned)((0x100000000ull + items - 1) / items);
     }
-    const size_t row_bytes = (size_t)s->cols * sizeof(T);
-    a.vec_ok = (CC > 1 && row_bytes % 16 == 0 && (uintptr_t)in % 16 == 0 && (uintptr_t)out % 16 == 0) ? 1 : 0;
+    // a work-item moves CC cells at a time: rows of both matrices must start at multiples of that
+    // (16 bytes, except 4 where four byte cells are loaded)
+    using O = typename sk::out_type_of<Op>::type;
+    constexpr size_t in_vec = CC * sizeof(T), out_vec = CC * sizeof(O);
+    a.vec_ok = (CC > 1 && ((size_t)s->cols * sizeof(T)) % in_vec == 0 && (uintptr_t)in % in_vec == 0 &&
+                ((size_t)s->cols * sizeof(O)) % out_vec == 0 && (uintptr_t)out % out_vec == 0) ? 1 : 0;
     a.nt_store = s->nt_store;
     a.pad = (T)s->pad;
     a.scalar0 = s->scalar0;
@@ -383,6 +393,7 @@ template <class Op, int CR, int CC>
 constexpr int variant_max_threads() {
     if (std::is_same<Op, sk::OpSinCos>::value && CR * CC >= 32) return 256;
     if (std::is_same<Op, sk::OpLife>::value && CR * CC >= 64) return 256;
+    if (std::is_same<Op, sk::OpWeightedSumU8>::value && CR * CC >= 32) return 256;
     return STENCIL_MAX_WG_SIZE;
 }
 

@@ -57,8 +57,13 @@ class Workload:
 
     @property
     def out_dtype(self) -> str:
-        """Element type of the output matrix: the input's, except bytes for the threshold stencil."""
-        return "u8" if self.kernel == THRESHOLD else self.dtype
+        """Element type of the output matrix: the input's, except bytes for the threshold stencil
+        and floats for the weighted sum of a byte image."""
+        if self.kernel == THRESHOLD:
+            return "u8"
+        if self.kernel == WEIGHTED_SUM and self.dtype == "u8":
+            return "f32"
+        return self.dtype
 
     @property
     def bytes_per_cell_update(self) -> int:
@@ -128,6 +133,8 @@ def make_grid(w: "Workload") -> np.ndarray:
         return np.ascontiguousarray(u)
     if w.kernel == SINCOS:
         return np.ascontiguousarray(rng.random(shape, dtype=np.float32) * np.float32(2.0) - np.float32(1.0))
+    if w.dtype == "u8":
+        return np.ascontiguousarray(rng.integers(0, 256, size=shape, dtype=np.uint8))     # an 8-bit image
     if w.dtype == "f64":
         return np.ascontiguousarray(rng.random(shape, dtype=np.float64))
     if w.dtype == "i32":
@@ -228,6 +235,13 @@ def canny_stage(kernel: str, rows: int, cols: int, border: str = "clamp", level:
     seed = BASE_SEED + 300 + {SOBEL: 0, NMS: 1, THRESHOLD: 2}[kernel]
     return Workload("%s %dx%d" % (kernel, rows, cols), rows, cols, "f32", halo, border, 0.0, kernel, 1, seed, "pow2",
                     scalars=(level,) if kernel == THRESHOLD else ())
+
+
+def image_blur(rows: int, cols: int, radius: int = 2, border: str = "clamp") -> Workload:
+    """The Canny detector's first stage on an 8-bit image: Gaussian blur, bytes in, floats out."""
+    side = 2 * radius + 1
+    return Workload("gaussian%dx%d u8->f32 %dx%d" % (side, side, rows, cols), rows, cols, "u8", (radius,) * 4, border,
+                    0.0, WEIGHTED_SUM, 1, BASE_SEED + 310 + radius, "pow2", weights=gaussian_weights(radius, 1.0))
 
 
 def real_scenarios() -> List[Workload]:

@@ -69,7 +69,7 @@ def check(ls, w, wg, iters=None, blocking=(1, 1), offset=0, grid=None):
     it = w.iters if iters is None else iters
     ref = oracle.apply(g, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, it)
     got = gpu_apply(ls, w, g, wg, it, blocking, offset)
-    if w.dtype in ("u8", "i32") or w.kernel in (wl.SOBEL, wl.NMS, wl.THRESHOLD):
+    if w.dtype == "i32" or w.kernel in (wl.LIFE, wl.SOBEL, wl.NMS, wl.THRESHOLD):
         np.testing.assert_array_equal(got, ref)        # integer work, or fp32 operations in a fixed order
     elif w.dtype == "f64":
         assert rel_err(got, ref) <= 1e-13 * max(1, it)
@@ -283,6 +283,42 @@ def test_threshold_float_in_bytes_out(ls):
     st.close()
 
 
+@pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
+def test_weighted_sum_of_a_byte_image_into_floats(ls, border):
+    """Bytes in, floats out (Section 3.3: input and output types differ): every blocking the kernel
+    has, regions of several alignments, ragged and aligned matrices, misaligned rows, a byte padding
+    value; bit-identical across blockings."""
+    for halo, shape in [((1, 1, 1, 1), (131, 157)), ((2, 2, 2, 2), (96, 128)), ((3, 0, 5, 2), (77, 200)), ((0, 0, 0, 0), (40, 64))]:
+        n, s, e, w_ = halo
+        wt = np.random.default_rng(sum(halo)).random((n + s + 1, e + w_ + 1), dtype=np.float32)
+        w = wl.Workload("u8 image", shape[0], shape[1], "u8", halo, border, 200.0, wl.WEIGHTED_SUM, 1, 17, "pow2", weights=wt)
+        assert w.out_dtype == "f32"
+        first = None
+        for blocking, wg in [((1, 1), (8, 8)), ((1, 1), (3, 21)), ((4, 1), (4, 16)), ((1, 4), (4, 16)), ((2, 4), (16, 16)),
+                             ((4, 4), (3, 7)), ((1, 16), (4, 4)), ((1, 16), (16, 8)), ((2, 16), (2, 8)), ((2, 16), (5, 3))]:
+            got = check(ls, w, wg, blocking=blocking)
+            assert got.dtype == np.float32
+            first = got if first is None else first
+            np.testing.assert_array_equal(got, first)
+        check(ls, w, (4, 8), blocking=(1, 16), offset=3)
+        check(ls, w, (4, 8), blocking=(2, 4), offset=3)
+        check(ls, w, (4, 8), blocking=(2, 4), offset=4)               # byte rows 4-aligned, float rows 16-aligned
+    st = ls.Stencil(64, 64, "u8", (1, 1, 1, 1), border)
+    st.set_kernel("weighted_sum", np.ones((3, 3), np.float32))
+    assert st.output_dtype() == ls.F32 and st.features()[2] == 1.0 and st.features()[12] == 4.0
+    tin = torch.zeros(64 * 64, dtype=torch.uint8, device="cuda")
+    tout = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
+    with pytest.raises(ls.StencilError):
+        st.run(tin, tout, 2, (8, 8))                                   # one application only
+    with pytest.raises(ValueError):
+        st.run(tin, tin.clone(), 1, (8, 8))                            # the output must be float
+    with pytest.raises(ls.StencilError):
+        st.set_mapping("direct", 1, 16)                                # local-memory tile only
+    with pytest.raises(ls.StencilError):
+        st.set_border_value(256)
+    st.close()
+
+
 def test_canny_chain_stage_by_stage(ls):
     """Gaussian blur -> sobel -> nms -> threshold, the detector the paper takes three of its kernels
     from: every stage is checked against the oracle on the input the previous stage produced."""
@@ -292,6 +328,10 @@ def test_canny_chain_stage_by_stage(ls):
     yy, xx = np.mgrid[0:rows, 0:cols]
     g = (g * np.float32(0.2) + ((xx // 60 + yy // 50) % 2).astype(np.float32)).astype(np.float32)   # a noisy chequerboard
     x = check(ls, blur, (16, 8), blocking=(2, 4), grid=g)
+    # the same chain from an 8-bit image: the blur takes bytes and hands floats to the sobel stage
+    g8 = np.clip(np.rint(g * 200.0), 0, 255).astype(np.uint8)
+    x8 = check(ls, wl.image_blur(rows, cols), (8, 8), blocking=(1, 16), grid=g8)
+    assert x8.dtype == np.float32 and abs(float(x8.mean()) - 200.0 * float(x.mean())) < 1.0
     for stage in (wl.canny_stage(wl.SOBEL, rows, cols), wl.canny_stage(wl.NMS, rows, cols),
                   wl.canny_stage(wl.THRESHOLD, rows, cols, level=1.0)):
         x = check(ls, stage, (4, 16), blocking=("direct", 2, 4) if stage.kernel != wl.THRESHOLD else (2, 4), grid=x)

@@ -105,6 +105,27 @@ def test_blocking_changes_tile_and_per_kernel_limit():
     assert heat.tile_bytes(128, 8) == (1024 + 2) * (32 + 8) * 4 and not heat.is_legal(128, 8)   # > 160 KiB
 
 
+def test_kernels_whose_output_type_differs_from_the_input():
+    """Section 3.3 lists input and output element types among a kernel's features."""
+    blur = ls.Stencil.from_workload(wl.image_blur(512, 512))        # bytes in, floats out
+    assert blur.output_dtype() == ls.F32
+    f = blur.features()
+    assert f[2] == 1.0 and f[12] == 4.0
+    assert blur.tile_bytes(16, 16) == (16 + 4) * (16 + 4) * 4           # the tile holds the cells as floats
+    blur.set_blocking(1, 16)
+    assert blur.tile_bytes(4, 16) == (4 + 4) * (256 + 32) * 4           # extents widened to whole 16-cell vectors
+    blur.set_blocking(2, 16)
+    assert blur.max_wg_size() == 256
+    with pytest.raises(ls.StencilError):
+        blur.set_mapping("direct", 1, 16)
+    edges = ls.Stencil.from_workload(wl.canny_stage(wl.THRESHOLD, 512, 512))   # floats in, bytes out
+    assert edges.output_dtype() == ls.U8
+    f = edges.features()
+    assert f[2] == 4.0 and f[12] == 1.0
+    heat = ls.Stencil.from_workload(wl.config(3))
+    assert heat.output_dtype() == ls.F32
+
+
 def test_sweep_reduce_matches_definitions():
     rng = np.random.default_rng(0)
     for trial in range(20):
