@@ -75,6 +75,8 @@ def parse_args():
     ap.add_argument("--quick", action="store_true", help="sweep a thinned size list (development only)")
     ap.add_argument("--wg", default="", help="R,C: skip the sweep and time this workgroup size (profiling runs)")
     ap.add_argument("--mapping", default="", help="staging,cells_rows,cells_cols to go with --wg, e.g. direct,2,4")
+    ap.add_argument("--nt-store", default=None, choices=["0", "1"],
+                    help="force plain (0) or non-temporal (1) output stores instead of timing both")
     ap.add_argument("--copy-only", action="store_true",
                     help="launch only the plain copy kernel on the workload's matrix (counter calibration)")
     return ap.parse_args()
@@ -128,13 +130,17 @@ FAST_MAPPING = {"weighted_sum": ("local", 2, 4), "heat": ("direct", 2, 4), "sinc
 # (staging, cells_rows, cells_cols, applications per launch or 0, workgroup size)
 STRONG_CONFIGS = {
     "weighted_sum": [("local", 2, 4, 0, (16, 8)), ("local", 2, 4, 0, (8, 8)), ("direct", 2, 4, 0, (8, 16)),
-                     ("direct", 4, 4, 0, (4, 128)), ("local", 4, 4, 0, (16, 8)), ("stream", 10, 4, 0, (1, 64))],
+                     ("direct", 4, 4, 0, (4, 128)), ("local", 4, 4, 0, (16, 8)), ("stream", 10, 4, 0, (1, 64)),
+                     # the same with non-temporal output stores (numbering as is)
+                     ("local", 2, 4, 0, (16, 8), -1, 1), ("direct", 2, 4, 0, (8, 16), -1, 1),
+                     ("stream", 10, 4, 0, (1, 64), -1, 1)],
     "life": [("direct", 2, 16, 0, (2, 128)), ("temporal", 2, 16, 4, (64, 8)), ("stream", 40, 4, 8, (1, 64)),
              ("stream", 40, 4, 8, (4, 64)), ("stream", 40, 4, 6, (1, 64))],
     "heat": [("direct", 2, 4, 0, (4, 16)), ("temporal", 2, 4, 4, (32, 32)), ("stream", 38, 4, 8, (1, 64)),
              ("stream", 38, 4, 8, (2, 64)), ("stream", 40, 4, 6, (1, 64))],
     "sincos": [("local", 4, 4, 0, (8, 32)), ("local", 2, 4, 0, (18, 14)), ("stream", 89, 4, 0, (4, 64)),
-               ("stream", 134, 4, 0, (32, 8)), ("stream", 134, 4, 0, (1, 64))],
+               ("stream", 134, 4, 0, (32, 8)), ("stream", 134, 4, 0, (1, 64)),
+               ("stream", 134, 4, 0, (32, 8), -1, 1), ("stream", 89, 4, 0, (4, 64), -1, 1)],
 }
 
 
@@ -156,7 +162,7 @@ def best_known_configuration(ls, torch, o, reps):
     # a launch moves the matrix once whatever it fuses: bytes per launch over the launch's time
     gbs = o.cells * o.bytes_per_cell_update / (per_app_ms * fused) / 1e6
     return {"mapping": mapping_name((c[0], c[1], c[2]) + ((c[3],) if c[3] else ())), "wg": list(c[4]),
-            "applications_per_launch": fused, "ms_per_application": per_app_ms,
+            "nt_store": c[6] if len(c) > 6 else 0, "applications_per_launch": fused, "ms_per_application": per_app_ms,
             "gcells_s": o.cells / per_app_ms / 1e6, "algorithmic_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
             "configurations_swept": len(configs)}
 
@@ -386,6 +392,24 @@ def main():
                     others.setdefault(o.name.split()[0], {})["best_known"] = best_known_configuration(
                         ls, torch, o, max(5, args.reps // 3))
 
+    def choose_stores(mapping, size):
+        """Plain or non-temporal output stores for this configuration, whichever the sweep's clock
+        prefers (forced by --nt-store); leaves the handle on that choice."""
+        if args.nt_store is not None:
+            nt = int(args.nt_store)
+        elif args.wg:
+            nt = 0
+        else:
+            depth = mapping[3] if len(mapping) > 3 else 0
+            pair = [(mapping[0], mapping[1], mapping[2], depth, size, -1, flag) for flag in (0, 1)]
+            mean, status, pick = st.sweep_configs(tin, tout, pair, iters=burst, reps=args.reps)
+            # plain stores unless the others win by more than the run-to-run noise
+            nt = 1 if (status[0] == ls.OK and status[1] == ls.OK and mean[1] < 0.98 * mean[0]) else 0
+        apply_mapping(st, mapping)
+        st.set_option(ls.OPT_NT_STORE, nt)
+        return nt
+
+    nt_store = choose_stores(blocking, wg)
     for _ in range(warmup):
         st.run(tin, tout, w.iters, wg)
     torch.cuda.synchronize()
@@ -402,7 +426,7 @@ def main():
     alg_bytes = cells * w.bytes_per_cell_update
 
     def kernel_roofline(mapping, size):
-        apply_mapping(st, mapping)
+        nt = choose_stores(mapping, size)
         depth = mapping[3] if len(mapping) > 3 else 1
         k_res = st.sweep(tin, tout, [size], iters=burst, fixed=(0, 0), reps=max(args.reps, 30))
         launches = -(-burst // depth)
@@ -413,11 +437,11 @@ def main():
             family = "march"            # register streaming, one application per launch
         label = "%s_kernel<%s> %dx%d cells/work-item, wg %dx%d" % (
             family, w.kernel, mapping[1], mapping[2], size[0], size[1]) + (
-            ", %d applications/launch" % depth if depth > 1 else "")
+            ", %d applications/launch" % depth if depth > 1 else "") + (", non-temporal stores" if nt else "")
         out = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(label),
                "kernel": label, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg_bytes,
-               "applications_per_launch": depth,
+               "applications_per_launch": depth, "nt_store": nt,
                "gcells_s": cells * depth / (kernel_ms * 1e-3) / 1e9}
         # kernels that vector arithmetic bounds rather than memory (the sin/cos stencil; fused
         # applications): algorithmic fp32 operations against the published vector peak
@@ -450,6 +474,7 @@ def main():
         roofline = kernel_roofline(blocking, wg)
     roofline["copy_kernel_gbs"] = copy_reference()
     apply_mapping(st, blocking)
+    st.set_option(ls.OPT_NT_STORE, nt_store)
 
     larger = larger_matrices(ls, wl, torch, max(5, args.reps // 3)) if (index == 3 and not args.wg and not args.quick) else {}
 
@@ -462,7 +487,7 @@ def main():
                    "halo_nsew": list(w.halo), "border": w.border, "best_wg": list(wg),
                    "staging": blocking[0], "cells_per_work_item": list(blocking[1:3]),
                    "applications_per_launch": blocking[3] if len(blocking) > 3 else 1,
-                   "sweep_burst": burst, "sweep_reps": args.reps},
+                   "nt_store": nt_store, "sweep_burst": burst, "sweep_reps": args.reps},
         "roofline": roofline,
         "roofline_timed_kernel": roofline_timed,
         "sweep": {"seconds": sweep_seconds, "by_blocking": sweeps},
