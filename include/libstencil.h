@@ -21,6 +21,13 @@
  * never abort or throw; `stencil_last_error()` gives the text of the calling thread's last
  * failure.  Functions that take no `in`/`out` make no GPU call and work on a machine
  * without a GPU.
+ *
+ * Ownership and concurrency: a handle (stencil_t, predictor, regressor) belongs to its
+ * creator until the matching destroy call; different handles may be used from different
+ * threads at once, one handle from one thread at a time.  A stencil_t owns device memory on
+ * the device that was current when it first ran (a scratch matrix for iterated runs, the
+ * weight table of a run-time region): use it with that device current, and do not overlap
+ * iterated runs of one handle on different streams - they share the scratch matrix.
  */
 #ifndef LIBSTENCIL_H
 #define LIBSTENCIL_H
