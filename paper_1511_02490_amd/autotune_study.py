@@ -6,6 +6,10 @@ the sweep's oracle sizes with the metrics of Section 7.
 
     python -m paper_1511_02490_amd.autotune_study [--synthetic 32] [--reps 5] [--mapping local,1,1]
 
+A large study can be split: `--json FILE --sweep-only` on the GPU records the sweeps, `--from-json
+FILE` (same --synthetic and --mapping) evaluates them anywhere - legality, features and the
+predictors make no GPU call.
+
 Everything measured goes through the C ABI (sweeps, legality, features, predictor, baseline);
 this script only builds the scenario list and the tables.  Prints a markdown report.
 """
@@ -24,10 +28,11 @@ def main():
     ap.add_argument("--synthetic", type=int, default=32)
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--mapping", default="local,1,1")
-    ap.add_argument("--json", default="", help="also write the raw tables here")
+    ap.add_argument("--json", default="", help="also write the raw sweep tables here")
+    ap.add_argument("--sweep-only", action="store_true", help="stop after the sweeps (with --json)")
+    ap.add_argument("--from-json", default="", help="evaluate sweeps recorded with --json instead of sweeping")
     a = ap.parse_args()
 
-    import torch
     from paper_1511_02490_amd import libstencil as ls
     from paper_1511_02490_amd import workloads as wl
 
@@ -39,7 +44,18 @@ def main():
 
     feats, times, status = [], [], []
     t0 = time.perf_counter()
-    for w in scen:
+    recorded = None
+    if a.from_json:
+        with open(a.from_json) as fh:
+            recorded = json.load(fh)
+        if recorded["scenarios"] != [w.name for w in scen] or [tuple(x) for x in recorded["sizes"]] != sizes \
+                or recorded.get("mapping", a.mapping) != a.mapping:
+            raise SystemExit("%s was recorded for another scenario list, size list or mapping" % a.from_json)
+        times, status, feats = recorded["times_ms"], recorded["status"], recorded["features"]
+        a.reps = recorded.get("reps", a.reps)
+    else:
+        import torch
+    for w in ([] if recorded else scen):
         st = ls.Stencil.from_workload(w)
         try:
             st.set_mapping(*mapping)
@@ -56,7 +72,13 @@ def main():
         print("swept %-44s best %-10s %.4f ms  refused %d" % (w.name, res.best, res.best_ms,
                                                              sum(1 for s in res.status if s != 0)),
               file=sys.stderr, flush=True)
-    sweep_s = time.perf_counter() - t0
+    sweep_s = recorded["sweep_seconds"] if recorded else time.perf_counter() - t0
+    if a.json and not recorded:
+        with open(a.json, "w") as fh:
+            json.dump({"sizes": sizes, "scenarios": [w.name for w in scen], "times_ms": times, "status": status,
+                       "features": feats, "mapping": a.mapping, "reps": a.reps, "sweep_seconds": sweep_s}, fh)
+    if a.sweep_only:
+        return
 
     n_s, n_w = len(scen), len(sizes)
     nan = float("nan")
@@ -68,9 +90,14 @@ def main():
     base = ls.baseline_wg(perf)                      # best fixed size that is legal everywhere
     idx = {s: j for j, s in enumerate(sizes)}
 
+    def progress(what, done, of):
+        if done == of or done % 10 == 0:
+            print("evaluated %s: %d of %d" % (what, done, of), file=sys.stderr, flush=True)
+
     def evaluate(train, test, predictor_kind):
         rows = []
-        for i in test:
+        for n_done, i in enumerate(test):
+            progress(predictor_kind, n_done, len(test))
             tr = [k for k in train if k != i]
             if predictor_kind == "zeror":
                 j = base
@@ -103,7 +130,8 @@ def main():
         (nearest-neighbour regression) or "forest" (Section 5's random forest of regression trees:
         30 trees, seeded bootstrap samples and input subsets, leaves of two tuples or more)."""
         rows = []
-        for i in test:
+        for n_done, i in enumerate(test):
+            progress("%s regressor on %s" % (model, target), n_done, len(test))
             reg = ls.Regressor()
             n_tuples = 0
             for k in train:
@@ -191,10 +219,6 @@ def main():
         print("| %s | %dx%d | %.4f | %dx%d | %.2f |" % (r["scenario"], r["oracle"][0], r["oracle"][1],
                                                        times[i][oracle[i]], r["predicted"][0], r["predicted"][1],
                                                        r["performance"]))
-    if a.json:
-        with open(a.json, "w") as fh:
-            json.dump({"sizes": sizes, "scenarios": [w.name for w in scen], "times_ms": times, "status": status,
-                       "features": feats}, fh)
 
 
 if __name__ == "__main__":

@@ -46,6 +46,12 @@ def _load() -> ctypes.CDLL:
         raise ImportError(
             "libstencil.so is not built (%s missing): run `python -c 'import __graft_entry__ as g; "
             "g.build()'` or `python paper_1511_02490_amd/build.py` first" % LIB_PATH)
+    # PyTorch ships its own copy of the HIP runtime; it has to be the one already in the process
+    # when the library is loaded, or the library would bring in a second runtime that finds no device
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass          # host-side functions (enumeration, legality, predictors) still work
     lib = ctypes.CDLL(LIB_PATH)
     c_int, c_i64, c_dbl, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
     ip, dp, fp = ctypes.POINTER(c_int), ctypes.POINTER(c_dbl), ctypes.POINTER(ctypes.c_float)
