@@ -379,7 +379,17 @@ def main():
                 t4 = res.ms_of((4, 4))
                 if tag == "fast":
                     others = {t["workload"]: {k: v for k, v in t.items() if k != "workload"} for t in table}
-                predictor[tag] = {"mapping": mapping_name(mine),
+                pretrained = None
+                if mine == ("local", 1, 1):
+                    # the classifier shipped with the library (trained offline on the 128-scenario study,
+                    # which contains this kernel on other matrix sizes and, for C4, on this one)
+                    shipped = ls.pretrained_predictor("local,1,1")
+                    q = st.predict(shipped, sizes)
+                    shipped.close()
+                    t_q = res.ms_of(q)
+                    pretrained = {"predicted_wg": list(q),
+                                  "performance": (res.best_ms / t_q) if not math.isnan(t_q) else None}
+                predictor[tag] = {"mapping": mapping_name(mine), "pretrained": pretrained,
                                   "trained_on": [{"workload": t["workload"], "oracle_wg": t["oracle_wg"]} for t in table],
                                   "predicted_wg": list(p),
                                   "oracle_wg": list(res.best), "performance": res.best_ms / t_p,
@@ -397,7 +407,7 @@ def main():
         prefers (forced by --nt-store); leaves the handle on that choice."""
         if args.nt_store is not None:
             nt = int(args.nt_store)
-        elif args.wg:
+        elif args.wg or mapping[2] == 1:      # one cell per work-item: no 16-byte stores to switch
             nt = 0
         else:
             depth = mapping[3] if len(mapping) > 3 else 0
@@ -409,7 +419,34 @@ def main():
         st.set_option(ls.OPT_NT_STORE, nt)
         return nt
 
-    nt_store = choose_stores(blocking, wg)
+    def choose_stores_for_steps():
+        """The same choice for the timed steps, made on whole steps (all iterations of the workload):
+        a short burst does not show what the stores do to a long chain of dependent launches."""
+        if args.nt_store is not None or args.wg or blocking[2] == 1:
+            return choose_stores(blocking, wg)
+        apply_mapping(st, blocking)
+        took = []
+        per_trial = 1
+        for flag in (0, 1):
+            st.set_option(ls.OPT_NT_STORE, flag)
+            t_a = time.perf_counter()
+            st.run(tin, tout, w.iters, wg)
+            torch.cuda.synchronize()
+            if flag == 0:     # a trial lasts a few milliseconds, so that the host's part does not decide
+                per_trial = max(1, min(500, int(0.004 / max(time.perf_counter() - t_a, 1e-6))))
+            trials = []
+            for _ in range(3):
+                t_a = time.perf_counter()
+                for _ in range(per_trial):
+                    st.run(tin, tout, w.iters, wg)
+                torch.cuda.synchronize()
+                trials.append(time.perf_counter() - t_a)
+            took.append(min(trials))
+        nt = 1 if took[1] < 0.98 * took[0] else 0
+        st.set_option(ls.OPT_NT_STORE, nt)
+        return nt
+
+    nt_store = choose_stores_for_steps()
     for _ in range(warmup):
         st.run(tin, tout, w.iters, wg)
     torch.cuda.synchronize()

@@ -8,7 +8,8 @@ the sweep's oracle sizes with the metrics of Section 7.
 
 A large study can be split: `--json FILE --sweep-only` on the GPU records the sweeps, `--from-json
 FILE` (same --synthetic and --mapping) evaluates them anywhere - legality, features and the
-predictors make no GPU call.
+predictors make no GPU call.  `--export-training FILE` writes the (f(s), oracle size) pairs of the
+sweeps: the files under tuning_data/ that `libstencil.pretrained_predictor` loads were made so.
 
 Everything measured goes through the C ABI (sweeps, legality, features, predictor, baseline);
 this script only builds the scenario list and the tables.  Prints a markdown report.
@@ -31,6 +32,8 @@ def main():
     ap.add_argument("--json", default="", help="also write the raw sweep tables here")
     ap.add_argument("--sweep-only", action="store_true", help="stop after the sweeps (with --json)")
     ap.add_argument("--from-json", default="", help="evaluate sweeps recorded with --json instead of sweeping")
+    ap.add_argument("--export-training", default="",
+                    help="write the (f(s), oracle size) pairs here (the data libstencil.pretrained_predictor loads) and stop")
     a = ap.parse_args()
 
     from paper_1511_02490_amd import libstencil as ls
@@ -87,6 +90,13 @@ def main():
         b, p, _ = ls.sweep_reduce(sizes, times[i], status[i], nan)
         oracle.append(b)
         perf.append(p)
+    if a.export_training:
+        with open(a.export_training, "w") as fh:
+            pairs = [json.dumps({"scenario": scen[i].name, "features": feats[i], "wg": list(sizes[oracle[i]])})
+                     for i in range(n_s) if oracle[i] >= 0]
+            fh.write('{"device": "MI355X", "mapping": "%s", "samples_per_size": %d, "pairs": [\n%s\n]}\n'
+                     % (a.mapping, a.reps, ",\n".join(pairs)))
+        return
     base = ls.baseline_wg(perf)                      # best fixed size that is legal everywhere
     idx = {s: j for j, s in enumerate(sizes)}
 

@@ -429,6 +429,23 @@ class Regressor:
         return y.value
 
 
+def pretrained_predictor(mapping: str = "local,1,1", classifier: str = "tree") -> "Predictor":
+    """A classifier already trained on this device (Section 4.1: training data is collected
+    offline, prediction happens at run time): the (f(s), oracle size) pairs of the 128-scenario
+    sweeps that autotune_study recorded on an MI355X under the mapping "local,1,1" (the paper's)
+    or "local,2,4".  Use with Stencil.predict(predictor, candidate sizes)."""
+    import json
+    path = os.path.join(_HERE, "tuning_data", "mi355x_%s.json" % mapping.replace(",", "_"))
+    if not os.path.exists(path):
+        raise ValueError("no training data for mapping %r (have: local,1,1 and local,2,4)" % mapping)
+    with open(path) as fh:
+        data = json.load(fh)
+    pred = Predictor(classifier)
+    for pair in data["pairs"]:
+        pred.add(pair["features"], tuple(pair["wg"]))
+    return pred
+
+
 class Predictor:
     """Classifier over (f(s), Omega(s)) pairs (Section 4.1): "nearest", "tree" or "zeror"."""
 

@@ -786,6 +786,27 @@ def test_sweep_reports_times_best_and_refusals(ls):
     assert rel_err(tout.cpu().numpy(), oracle.apply_workload(w)) <= REL_1
 
 
+def test_pretrained_predictor_picks_a_good_size(ls):
+    """The shipped classifier's size for the 4096^2 heat step runs within reach of the sweep's best
+    (Section 7's "performance"), far above the paper's 4x4 baseline."""
+    w = wl.config(3, iters=4)
+    sizes = w.wg_sizes()
+    tin = torch.from_numpy(w.grid()).cuda()
+    tout = torch.empty_like(tin)
+    for mapping in ("local,1,1", "local,2,4"):
+        st = ls.Stencil.from_workload(w)
+        m = mapping.split(",")
+        st.set_mapping(m[0], int(m[1]), int(m[2]))
+        res = st.sweep(tin, tout, sizes, iters=4, fixed=(4, 4), reps=5)
+        pred = ls.pretrained_predictor(mapping)
+        wg = st.predict(pred, sizes)
+        performance = res.best_ms / res.ms_of(wg)
+        assert performance >= 0.75, (mapping, wg, performance)
+        assert res.ms_of((4, 4)) / res.ms_of(wg) >= 1.3, (mapping, wg)
+        pred.close()
+        st.close()
+
+
 def test_sweep_with_adaptive_sampling_finds_the_same_best(ls):
     import time
     w = wl.config(3, rows=1024, cols=1024)

@@ -188,6 +188,31 @@ def test_features_and_prediction_algorithm1():
         ls.Predictor().classify(feats[0])
 
 
+def test_pretrained_predictor_ships_with_the_library():
+    """The (f(s), oracle size) pairs recorded on the device are loaded into a classifier; what it
+    predicts, repaired by Algorithm 1's fallback, is a legal size for every benchmark workload."""
+    sizes = ls.enumerate_wg("pow2", 1024)
+    for mapping in ("local,1,1", "local,2,4"):
+        for kind in ("tree", "nearest", "zeror"):
+            pred = ls.pretrained_predictor(mapping, kind)
+            for i in range(5):
+                st = ls.Stencil.from_workload(wl.config(i))
+                m = mapping.split(",")
+                try:
+                    st.set_mapping(m[0], int(m[1]), int(m[2]))
+                except ls.StencilError:
+                    continue                                  # Life has no 2x4 blocking
+                wr, wc = st.predict(pred, sizes)
+                assert (wr, wc) in sizes and st.is_legal(wr, wc)
+                st.close()
+            pred.close()
+    # the study's most common oracle size under the paper's mapping is what ZeroR answers
+    st = ls.Stencil.from_workload(wl.config(3))
+    assert st.predict(ls.pretrained_predictor("local,1,1", "zeror"), sizes) == (16, 32)
+    with pytest.raises(ValueError):
+        ls.pretrained_predictor("direct,2,4")
+
+
 def test_baseline_handler_matches_definition():
     sizes = [(4, 4), (8, 8), (64, 4)]
     nan = float("nan")
