@@ -525,6 +525,39 @@ def test_every_swept_size_matches_baseline_output(ls, index):
         st.close()
 
 
+@pytest.mark.parametrize("index", [1, 2, 3, 4])
+def test_gold_standard_at_full_size(ls, index):
+    """The same check on the full-size workloads, for every size of the workload's own list (66
+    powers of two; all 590 even sizes for C5) under the paper's mapping, the fast mappings and the
+    register-streaming ones: outputs are compared on the device with the 4x4 baseline's, which
+    the full-size tests below tie to the oracle."""
+    w = wl.config(index, iters=2 if index in (2, 3) else None)
+    tin = torch.from_numpy(w.grid()).cuda()
+    base = torch.empty_like(tin)
+    st = ls.Stencil.from_workload(w)
+    st.run(tin, base, w.iters, (4, 4))
+    st.close()
+    vec = 16 if w.dtype == "u8" else 4
+    mappings = {1: [(1, 1), (2, vec), ("direct", 2, vec), ("stream", 10, vec)],
+                2: [(1, 1), (2, vec), ("direct", 2, vec), ("temporal", 2, vec, 2), ("stream", 40, 4, 2)],
+                3: [(1, 1), (2, vec), ("direct", 2, vec), ("temporal", 2, vec, 2), ("stream", 38, vec, 2)],
+                4: [(1, 1), (4, vec), ("stream", 134, vec)]}[index]
+    tout = torch.empty_like(tin)
+    for blocking in mappings:
+        st = ls.Stencil.from_workload(w)
+        set_mapping(st, blocking)
+        n_run = 0
+        for wg in w.wg_sizes():
+            if not st.is_legal(*wg):
+                continue
+            tout.fill_(9)
+            st.run(tin, tout, w.iters, wg)
+            assert torch.equal(tout, base), "wg %s blocking %s" % (wg, blocking)
+            n_run += 1
+        assert n_run >= (4 if blocking[0] == "stream" else len(w.wg_sizes()) // 2), (blocking, n_run)
+        st.close()
+
+
 # ---- degenerate shapes and the error paths ----------------------------------------------------
 
 @pytest.mark.parametrize("shape", [(1, 1), (1, 37), (41, 1), (2, 3), (5, 4)])
