@@ -81,13 +81,26 @@ __global__ __launch_bounds__(MAXT) void direct_kernel(const TileArgs<Op, Halo> a
 #pragma unroll
         for (int cc = 0; cc < CC; ++cc) Op::init(st[cr][cc]);
 
+    // A small window is fetched whole before its first row is used (rows below the matrix resolve
+    // like any other out-of-matrix row): no branch separates the loads, so all of them are in
+    // flight together instead of one memory round trip per row.  A large window would cost
+    // registers, and with them resident wavefronts: its rows are fetched as they are needed.
+    constexpr bool kWhole = (CR + N + S) * (W + CC + E) <= 32;
+    V win[kWhole ? CR + N + S : 1][W + CC + E];
+    if constexpr (kWhole) {
+#pragma unroll
+        for (int wi = 0; wi < CR + N + S; ++wi)
+            fetch_row<Op, B, CC, W, E>(win[wi], a.in, r0 - N + wi, c0, rows, cols, fast_cols, a.pad);
+    }
 #pragma unroll
     for (int wi = 0; wi < CR + N + S; ++wi) {
-        // the first cell-row this window row feeds; stop once that lies below the matrix
-        const int first_cr = wi - N - S > 0 ? wi - N - S : 0;
-        if (r0 + first_cr >= rows) break;
-        V row[W + CC + E];
-        fetch_row<Op, B, CC, W, E>(row, a.in, r0 - N + wi, c0, rows, cols, fast_cols, a.pad);
+        if constexpr (!kWhole) {
+            // the first cell-row this window row feeds; stop once that lies below the matrix
+            const int first_cr = wi - N - S > 0 ? wi - N - S : 0;
+            if (r0 + first_cr >= rows) break;
+            fetch_row<Op, B, CC, W, E>(win[0], a.in, r0 - N + wi, c0, rows, cols, fast_cols, a.pad);
+        }
+        const V(&row)[W + CC + E] = win[kWhole ? wi : 0];
 #pragma unroll
         for (int cr = 0; cr < CR; ++cr) {
             const int dr = wi - N - cr;
@@ -147,17 +160,17 @@ __device__ __forceinline__ void life_rule(uint32_t (&o)[4], const LifeRow &above
     }
 }
 
-// Loads one row of 16 cells.  The cells just west and east of them are the neighbouring lanes'
-// last and first cells: `lane_w` / `lane_e` say whether that lane belongs to the same wavefront
-// and the same matrix row and is executing this call too (then a cross-lane move fetches the
-// byte); otherwise the cell is read from memory with the border rule.
+// Loads one row of 16 cells and the two cells just west and east of them (columns gcw / gce after
+// border resolution, -1 for padding).  All three loads are unconditional and independent of each
+// other, so the loads of every row a work-item needs can be in flight together.
 template <int B>
 __device__ __forceinline__ LifeRow life_fetch(const uint8_t *in, int gr_raw, int c0, int rows, int cols,
-                                              bool fast_cols, uint8_t pad, bool lane_w, bool lane_e) {
+                                              bool fast_cols, uint8_t pad, int gcw, int gce) {
     LifeRow x;
     const int gr = resolve<B>(gr_raw, rows);
+    const uint8_t *row = in + (size_t)(gr < 0 ? 0 : gr) * cols;
     if (gr >= 0 && fast_cols) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(in + (size_t)gr * cols + c0);
+        const uint4 v = *reinterpret_cast<const uint4 *>(row + c0);
         x.w[0] = v.x; x.w[1] = v.y; x.w[2] = v.z; x.w[3] = v.w;
     } else {
 #pragma unroll
@@ -166,23 +179,15 @@ __device__ __forceinline__ LifeRow life_fetch(const uint8_t *in, int gr_raw, int
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int gc = resolve<B>(c0 + 4 * k + b, cols);
-                const uint32_t cell = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
+                const uint32_t cell = (gr < 0 || gc < 0) ? pad : row[gc];
                 word |= cell << (8 * b);
             }
             x.w[k] = word;
         }
     }
-    // every lane that is here takes part in both moves
-    x.l = (uint32_t)__shfl_up((int)x.w[3], 1) >> 24;
-    x.r = (uint32_t)__shfl_down((int)x.w[0], 1) & 0xffu;
-    if (!lane_w) {
-        const int gc = resolve<B>(c0 - 1, cols);
-        x.l = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
-    }
-    if (!lane_e) {
-        const int gc = resolve<B>(c0 + 16, cols);
-        x.r = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
-    }
+    const uint32_t west = row[gcw < 0 ? 0 : gcw], east = row[gce < 0 ? 0 : gce];
+    x.l = (gr < 0 || gcw < 0) ? pad : west;
+    x.r = (gr < 0 || gce < 0) ? pad : east;
     return x;
 }
 
@@ -198,19 +203,16 @@ __global__ __launch_bounds__(MAXT) void life_direct_kernel(const TileArgs<OpLife
     const int c0 = (tile_c * (int)blockDim.x + (int)threadIdx.x) * CC;
     if (r0 >= rows || c0 >= cols) return;
     const bool fast_cols = a.vec_ok && c0 + CC <= cols;
-    // the lanes one below / above hold the cells just west / east when they are work-items of
-    // the same workgroup row inside the same wavefront (and, to the east, inside the matrix)
-    const int lane = ((int)threadIdx.y * (int)blockDim.x + (int)threadIdx.x) & 63;
-    const bool lane_w = threadIdx.x > 0 && lane > 0;
-    const bool lane_e = threadIdx.x + 1 < blockDim.x && lane < 63 && c0 + CC < cols;
+    // the columns just west and east of this work-item's cells, the same for every row
+    const int gcw = resolve<B>(c0 - 1, cols), gce = resolve<B>(c0 + CC, cols);
 
-    LifeRow above = life_fetch<B>(a.in, r0 - 1, c0, rows, cols, fast_cols, a.pad, lane_w, lane_e);
-    LifeRow cur = life_fetch<B>(a.in, r0, c0, rows, cols, fast_cols, a.pad, lane_w, lane_e);
+    LifeRow above = life_fetch<B>(a.in, r0 - 1, c0, rows, cols, fast_cols, a.pad, gcw, gce);
+    LifeRow cur = life_fetch<B>(a.in, r0, c0, rows, cols, fast_cols, a.pad, gcw, gce);
 #pragma unroll
     for (int cr = 0; cr < CR; ++cr) {
         const int r = r0 + cr;
         if (r >= rows) break;
-        const LifeRow below = life_fetch<B>(a.in, r + 1, c0, rows, cols, fast_cols, a.pad, lane_w, lane_e);
+        const LifeRow below = life_fetch<B>(a.in, r + 1, c0, rows, cols, fast_cols, a.pad, gcw, gce);
         uint32_t o[4];
         life_rule(o, above, cur, below);
         uint8_t *dst = a.out + (size_t)r * cols + c0;

@@ -22,6 +22,9 @@ __device__ __forceinline__ int resolve(int i, int n) {
     if ((unsigned)i < (unsigned)n) return i;
     if (B == kClamp) return i < 0 ? 0 : n - 1;
     if (B == kWrap) {
+        // one period away in all but tiny matrices: an add; the division only beyond that
+        const int once = i < 0 ? i + n : i - n;
+        if (__builtin_expect((unsigned)once < (unsigned)n, 1)) return once;
         int m = i % n;
         return m < 0 ? m + n : m;
     }

@@ -139,39 +139,61 @@ __device__ __forceinline__ void stage_tile(typename Op::L *tile, int plane, int 
     int i = (int)__umulhi((unsigned)tid, magic);
     int q = tid - i * n_items;
     const int di = (int)__umulhi((unsigned)nthreads, magic), dq = nthreads - di * n_items;
+    // Vectors are taken kBatch at a time: the loads of a batch are all issued before the first of
+    // them is waited for and written to LDS, so a work-item with several items pays one memory
+    // round trip per batch, not one per item.  (Single elements gain nothing from it.)
+    constexpr int kBatch = CC == 1 ? 1 : 4;
     while (i < n_rows) {
-        const int gr = resolve<B>(row_first + i, rows);
-        if constexpr (CC == 1) {
-            const int gc = resolve<B>(col_first + q, cols);
-            const T v = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
-            L sv[NP];
-            Op::stage(v, sv);
+        T v[kBatch][CC];
+        int at_i[kBatch], at_q[kBatch];
+        bool have[kBatch];
 #pragma unroll
-            for (int p = 0; p < NP; ++p) tile[p * plane + i * pitch + q] = sv[p];
-        } else {
-            const int gc0 = col_first + q * CC;
-            if (gc0 < col_end) {
-                T v[CC];
-                if (gr >= 0 && vec_ok && gc0 >= 0 && gc0 + CC <= cols) {
-                    load_vec(v, in + (size_t)gr * cols + gc0);
+        for (int b = 0; b < kBatch; ++b) {
+            at_i[b] = i;
+            at_q[b] = q;
+            have[b] = i < n_rows;
+            if (have[b]) {
+                const int gr = resolve<B>(row_first + i, rows);
+                if constexpr (CC == 1) {
+                    const int gc = resolve<B>(col_first + q, cols);
+                    v[b][0] = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
                 } else {
+                    const int gc0 = col_first + q * CC;
+                    have[b] = gc0 < col_end;
+                    if (have[b]) {
+                        if (gr >= 0 && vec_ok && gc0 >= 0 && gc0 + CC <= cols) {
+                            load_vec(v[b], in + (size_t)gr * cols + gc0);
+                        } else {
 #pragma unroll
-                    for (int k = 0; k < CC; ++k) {
-                        const int gc = resolve<B>(gc0 + k, cols);
-                        v[k] = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
+                            for (int k = 0; k < CC; ++k) {
+                                const int gc = resolve<B>(gc0 + k, cols);
+                                v[b][k] = (gr < 0 || gc < 0) ? pad : in[(size_t)gr * cols + gc];
+                            }
+                        }
                     }
                 }
-                L sv[NP][CC];
-                Op::template stage_vec<CC>(v, sv);
-#pragma unroll
-                for (int p = 0; p < NP; ++p) store_vec(tile + p * plane + i * pitch + q * CC, sv[p]);
+            }
+            i += di;
+            q += dq;
+            if (q >= n_items) {
+                q -= n_items;
+                ++i;
             }
         }
-        i += di;
-        q += dq;
-        if (q >= n_items) {
-            q -= n_items;
-            ++i;
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            if (!have[b]) continue;
+            if constexpr (CC == 1) {
+                L sv[NP];
+                Op::stage(v[b][0], sv);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) tile[p * plane + at_i[b] * pitch + at_q[b]] = sv[p];
+            } else {
+                L sv[NP][CC];
+                Op::template stage_vec<CC>(v[b], sv);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) store_vec(tile + p * plane + at_i[b] * pitch + at_q[b] * CC, sv[p]);
+            }
         }
     }
 }
