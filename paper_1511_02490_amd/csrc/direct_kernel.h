@@ -206,15 +206,18 @@ __global__ __launch_bounds__(MAXT) void life_direct_kernel(const TileArgs<OpLife
     // the columns just west and east of this work-item's cells, the same for every row
     const int gcw = resolve<B>(c0 - 1, cols), gce = resolve<B>(c0 + CC, cols);
 
-    LifeRow above = life_fetch<B>(a.in, r0 - 1, c0, rows, cols, fast_cols, a.pad, gcw, gce);
-    LifeRow cur = life_fetch<B>(a.in, r0, c0, rows, cols, fast_cols, a.pad, gcw, gce);
+    // all CR + 2 rows before the first is used (rows below the matrix resolve like any other
+    // out-of-matrix row): every load of the work-item is in flight at once
+    LifeRow win[CR + 2];
+#pragma unroll
+    for (int k = 0; k < CR + 2; ++k)
+        win[k] = life_fetch<B>(a.in, r0 - 1 + k, c0, rows, cols, fast_cols, a.pad, gcw, gce);
 #pragma unroll
     for (int cr = 0; cr < CR; ++cr) {
         const int r = r0 + cr;
         if (r >= rows) break;
-        const LifeRow below = life_fetch<B>(a.in, r + 1, c0, rows, cols, fast_cols, a.pad, gcw, gce);
         uint32_t o[4];
-        life_rule(o, above, cur, below);
+        life_rule(o, win[cr], win[cr + 1], win[cr + 2]);
         uint8_t *dst = a.out + (size_t)r * cols + c0;
         if (a.vec_ok && c0 + CC <= cols) {
             store_word4(dst, make_uint4(o[0], o[1], o[2], o[3]), a.nt_store != 0);
@@ -223,8 +226,6 @@ __global__ __launch_bounds__(MAXT) void life_direct_kernel(const TileArgs<OpLife
             for (int k = 0; k < CC; ++k)
                 if (c0 + k < cols) dst[k] = (uint8_t)(o[k >> 2] >> (8 * (k & 3)));
         }
-        above = cur;
-        cur = below;
     }
 }
 
