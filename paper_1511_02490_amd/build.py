@@ -57,5 +57,20 @@ def build(verbose: bool = False, extra_flags=(), jobs: int = 0) -> str:
     return LIB_PATH
 
 
+EXAMPLE_SRC = os.path.join(os.path.dirname(_HERE), "examples", "heat_sweep.cpp")
+EXAMPLE_BIN = os.path.join(os.path.dirname(_HERE), "examples", "_build", "heat_sweep")
+
+
+def build_example(verbose: bool = False) -> str:
+    """Compiles examples/heat_sweep.cpp (plain C++ against include/libstencil.h) and links it with
+    the library just built; the binary finds the library relative to itself."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(os.path.dirname(EXAMPLE_BIN), exist_ok=True)
+    _run([hipcc, "-O2", "-std=c++17", EXAMPLE_SRC, "-I" + os.path.join(os.path.dirname(_HERE), "include"),
+          "-L" + os.path.dirname(LIB_PATH), "-lstencil", "-Wl,-rpath,$ORIGIN/../../paper_1511_02490_amd/_lib",
+          "-o", EXAMPLE_BIN], verbose)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     print(build(verbose=True, extra_flags=sys.argv[1:]))

@@ -4,6 +4,8 @@ Bar: bit-exact for the integer (Life) kernel; max relative error <= 1e-5 per app
 <= 1e-4 after iterated runs for fp32.  The heat kernel is specified as a fixed sequence of
 fp32 operations, so for it the GPU is additionally required to match the fp32 oracle exactly.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -744,6 +746,17 @@ def test_non_temporal_stores_change_no_value(ls):
     mean, status, best = st.sweep_configs(tin, tout, [("direct", 2, 4, 0, (4, 16), 1, nt) for nt in (0, 1)], iters=2, reps=3)
     assert status == [ls.OK, ls.OK] and best in (0, 1)
     st.close()
+
+
+def test_plain_cpp_example_runs(ls):
+    """The C ABI from a program that is neither Python nor PyTorch: the example built by
+    build() sweeps, runs 1000 heat steps at the best size and checks conservation itself."""
+    import subprocess
+    from paper_1511_02490_amd import build
+    assert os.path.exists(build.EXAMPLE_BIN), "examples/_build/heat_sweep is missing: run __graft_entry__.build() first"
+    proc = subprocess.run([build.EXAMPLE_BIN], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert proc.returncode == 0, proc.stdout
+    assert "sizes swept; best" in proc.stdout and "after 1000 steps" in proc.stdout
 
 
 def test_runs_on_a_side_stream(ls):

@@ -26,6 +26,14 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
+def test_plain_cpp_example_builds_against_the_header():
+    """examples/heat_sweep.cpp uses nothing but include/libstencil.h and the HIP runtime: it
+    compiles as C++ and links with the library (running it needs a GPU: test_gpu_parity)."""
+    from paper_1511_02490_amd import build
+    path = build.build_example()
+    assert os.path.exists(path) and os.access(path, os.X_OK)
+
+
 @pytest.mark.parametrize("mode,count", [("pow2", 66), ("even", 590)])
 def test_enumeration_matches_definition(mode, count):
     got = ls.enumerate_wg(mode, 1024)
