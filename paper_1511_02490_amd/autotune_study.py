@@ -187,15 +187,17 @@ def main():
     real = [i for i in all_i if kind[i] == "real"]
     parts = {"leave-one-out, 1-NN + NearestNeighbour": evaluate(all_i, all_i, "nearest"),
              "leave-one-out, decision tree + NearestNeighbour": evaluate(all_i, all_i, "tree"),
-             "synthetic -> real, 1-NN + NearestNeighbour": evaluate(syn, real, "nearest"),
-             "synthetic -> real, decision tree + NearestNeighbour": evaluate(syn, real, "tree"),
              "leave-one-out, regressor on runtimes (Algorithm 2)": evaluate_regression(all_i, all_i, "runtime"),
              "leave-one-out, regressor on speedups (Algorithm 2)": evaluate_regression(all_i, all_i, "speedup"),
-             "synthetic -> real, regressor on speedups (Algorithm 2)": evaluate_regression(syn, real, "speedup"),
              "leave-one-out, random forest on runtimes (Algorithm 2)": evaluate_regression(all_i, all_i, "runtime", "forest"),
              "leave-one-out, random forest on speedups (Algorithm 2)": evaluate_regression(all_i, all_i, "speedup", "forest"),
-             "synthetic -> real, random forest on speedups (Algorithm 2)": evaluate_regression(syn, real, "speedup", "forest"),
              "ZeroR (always the baseline size)": evaluate(all_i, all_i, "zeror")}
+    if syn and real:       # the paper's cross-validation: train on the synthetic scenarios, test on the real ones
+        parts.update({
+            "synthetic -> real, 1-NN + NearestNeighbour": evaluate(syn, real, "nearest"),
+            "synthetic -> real, decision tree + NearestNeighbour": evaluate(syn, real, "tree"),
+            "synthetic -> real, regressor on speedups (Algorithm 2)": evaluate_regression(syn, real, "speedup"),
+            "synthetic -> real, random forest on speedups (Algorithm 2)": evaluate_regression(syn, real, "speedup", "forest")})
 
     worst_over_best = [max(t for t, s in zip(times[i], status[i]) if s == 0) / times[i][oracle[i]] for i in all_i]
     distinct = len({oracle[i] for i in all_i})

@@ -336,3 +336,38 @@ def test_random_forest_regressor_matches_definition():
         reg.fit_forest(None, [[False] * ni])                     # a tree with no input
     with pytest.raises(ls.StencilError):
         ls.Regressor().fit_forest(None, None, n_trees=2)         # nothing to grow on
+
+
+def test_study_evaluates_a_fabricated_landscape(tmp_path, capsys, monkeypatch):
+    """The autotuning study's evaluation stage (Section 7's metrics over Algorithms 1 and 2, all
+    through the C ABI) on sweeps made up so that prediction matters: the best size is 4x64 on
+    matrices up to 1024^2 and 8x64 above.  A decision tree and a forest on speedups learn that
+    from the other scenarios; the best fixed size is right for half of them."""
+    import json
+    import sys
+    from paper_1511_02490_amd import autotune_study
+    sizes = ls.enumerate_wg("pow2", 1024)
+    scen = wl.real_scenarios()
+    times, status, feats = [], [], []
+    for w in scen:
+        st = ls.Stencil.from_workload(w)
+        feats.append(st.features())
+        legal = [st.is_legal(r, c) for r, c in sizes]
+        tall = 4 if w.rows <= 1024 else 8
+        times.append([(abs(r - tall) + 1) * (abs(c - 64) + 32) * w.rows * 1e-6 if ok else float("nan")
+                      for (r, c), ok in zip(sizes, legal)])
+        status.append([0 if ok else ls.E_REFUSED for ok in legal])
+        st.close()
+    path = tmp_path / "sweeps.json"
+    path.write_text(json.dumps({"sizes": sizes, "scenarios": [w.name for w in scen], "times_ms": times, "status": status,
+                                "features": feats, "mapping": "local,1,1", "reps": 3, "sweep_seconds": 1.0}))
+    monkeypatch.setattr(sys, "argv", ["autotune_study", "--synthetic", "0", "--mapping", "local,1,1", "--from-json", str(path)])
+    autotune_study.main()
+    report = capsys.readouterr().out
+    rows = {line.split("|")[1].strip(): [c.strip() for c in line.split("|")[2:-1]]
+            for line in report.splitlines() if line.startswith("| leave-one-out") or line.startswith("| ZeroR")}
+    assert rows["leave-one-out, decision tree + NearestNeighbour"][1] == "100 %"        # accuracy
+    assert rows["leave-one-out, decision tree + NearestNeighbour"][3] == "100 %"        # performance
+    assert int(rows["leave-one-out, random forest on speedups (Algorithm 2)"][1].split()[0]) >= 90
+    assert rows["ZeroR (always the baseline size)"][1] == "50 %"
+    assert all(r[2] == "100 %" for r in rows.values())                                  # every first answer legal
