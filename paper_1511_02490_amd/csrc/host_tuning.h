@@ -309,7 +309,14 @@ public:
             bool any = false;
             for (unsigned char o : open) any = any || o;
             if (!any) return false;
-            grow(trees[(size_t)t], rows, open, min_leaf, max_depth, 0);
+            std::vector<std::vector<int>> sorted((size_t)ni);
+            for (int j = 0; j < ni; ++j) {
+                if (!open[(size_t)j]) continue;
+                sorted[(size_t)j] = rows;
+                std::stable_sort(sorted[(size_t)j].begin(), sorted[(size_t)j].end(),
+                                 [&](int a, int b) { return input(a, j) < input(b, j); });
+            }
+            grow(trees[(size_t)t], rows, sorted, open, min_leaf, max_depth, 0);
         }
         trees_.swap(trees);
         return true;
@@ -374,8 +381,11 @@ private:
     // CART: the cut that minimises the two sides' summed squared error (= maximises
     // sum_l^2 / n_l + sum_r^2 / n_r), thresholds midway between consecutive distinct values,
     // at least min_leaf tuples a side, x <= threshold to the left; first best cut kept.
-    int grow(Tree &tree, const std::vector<int> &rows, const std::vector<unsigned char> &open, int min_leaf,
-             int max_depth, int depth) const {
+    // `rows` are the node's tuples in the order they were drawn; `sorted[j]` holds the same tuples
+    // ordered by input j (equal values in drawing order) for every open input - sorted once per
+    // tree and split stably from node to node, which is what sorting each node afresh would give.
+    int grow(Tree &tree, const std::vector<int> &rows, const std::vector<std::vector<int>> &sorted,
+             const std::vector<unsigned char> &open, int min_leaf, int max_depth, int depth) const {
         const int me = (int)tree.size();
         tree.push_back(Node());
         double sum = 0.0, lo = y_[(size_t)rows[0]], hi = lo;
@@ -389,11 +399,9 @@ private:
         bool found = false;
         double best_score = 0.0, best_thr = 0.0;
         int best_input = -1;
-        std::vector<int> order;
         for (int j = 0; j < n_inputs(); ++j) {
             if (!open[(size_t)j]) continue;
-            order = rows;
-            std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return input(a, j) < input(b, j); });
+            const std::vector<int> &order = sorted[(size_t)j];
             double total = 0.0;
             for (int r : order) total += y_[(size_t)r];
             double left_sum = 0.0;
@@ -413,12 +421,16 @@ private:
             }
         }
         if (!found) return me;
+        auto goes_left = [&](int r) { return input(r, best_input) <= best_thr; };
         std::vector<int> left, right;
-        for (int r : rows) (input(r, best_input) <= best_thr ? left : right).push_back(r);
+        for (int r : rows) (goes_left(r) ? left : right).push_back(r);
+        std::vector<std::vector<int>> sorted_l(sorted.size()), sorted_r(sorted.size());
+        for (size_t j = 0; j < sorted.size(); ++j)
+            for (int r : sorted[j]) (goes_left(r) ? sorted_l[j] : sorted_r[j]).push_back(r);
         tree[(size_t)me].input = best_input;
         tree[(size_t)me].threshold = best_thr;
-        const int l = grow(tree, left, open, min_leaf, max_depth, depth + 1);
-        const int r = grow(tree, right, open, min_leaf, max_depth, depth + 1);
+        const int l = grow(tree, left, sorted_l, open, min_leaf, max_depth, depth + 1);
+        const int r = grow(tree, right, sorted_r, open, min_leaf, max_depth, depth + 1);
         tree[(size_t)me].left = l;
         tree[(size_t)me].right = r;
         return me;

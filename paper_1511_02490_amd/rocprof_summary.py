@@ -26,8 +26,12 @@ TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 
 
 def kernel_source_hash() -> str:
+    """Hash of everything that shapes the device code and its launches (host_tuning.h is arithmetic
+    on the host around the sweep: the predictors, the statistics)."""
     h = hashlib.sha256()
     for f in sorted(glob.glob(os.path.join(HERE, "csrc", "*"))):
+        if os.path.basename(f) == "host_tuning.h":
+            continue
         with open(f, "rb") as fh:
             h.update(os.path.basename(f).encode() + b"\0" + fh.read())
     return h.hexdigest()[:16]
