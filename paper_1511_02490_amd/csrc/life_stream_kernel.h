@@ -148,6 +148,8 @@ __device__ __forceinline__ void life_stream_body(const TileArgs<OpLife, HaloC<1,
             load_row(t + PF, pf[p]);
 #pragma unroll
             for (int k = 1; k <= DEPTH; ++k) {
+                // generation k's first row that anything depends on is due at step 2k
+                if (t < 2 * k) continue;
                 // generation k's row r0 - DEPTH + t - k from generation k-1's three newest rows
                 const uint32_t(&up)[WORDS] = lv[k - 1][(u + 1) % R];
                 const uint32_t(&mid)[WORDS] = lv[k - 1][(u + 2) % R];

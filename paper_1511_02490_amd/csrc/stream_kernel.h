@@ -126,6 +126,9 @@ __device__ __forceinline__ void stream_body(const TileArgs<Op, HaloC<1, 1, 1, 1>
             load_row(t + PF, pf[v]);
 #pragma unroll
             for (int k = 1; k <= DEPTH; ++k) {
+                // level k's first row that anything depends on is r0 - DEPTH + k, due at step 2k:
+                // before that the level has nothing to do (a wavefront-uniform test)
+                if (t < 2 * k) continue;
                 // level k's row r0 - DEPTH + t - k from level k-1's three newest rows
                 const T(&up)[CC] = lv[k - 1][(u + 1) % R];
                 const T(&mid)[CC] = lv[k - 1][(u + 2) % R];
