@@ -153,10 +153,7 @@ __device__ __forceinline__ void life_rule(uint32_t (&o)[4], const LifeRow &above
         const uint32_t east = (v[k] >> 8) | ((k == 3 ? vr : v[k + 1]) << 24);
         const uint32_t s = v[k] + west + east;        // 3x3 block sums, <= 9 per byte
         const uint32_t n = s - cur.w[k];              // neighbours only
-        uint32_t x = (n | cur.w[k]) ^ 0x03030303u;    // zero byte <=> alive next
-        x |= x >> 2;
-        x |= x >> 1;
-        o[k] = ~x & 0x01010101u;
+        o[k] = zero_bytes((n | cur.w[k]) ^ 0x03030303u);    // zero byte <=> alive next
     }
 }
 

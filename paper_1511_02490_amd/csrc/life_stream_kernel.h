@@ -167,10 +167,7 @@ __device__ __forceinline__ void life_stream_body(const TileArgs<OpLife, HaloC<1,
                     const uint32_t east = (v[w] >> 8) | (next << 24);
                     const uint32_t s = v[w] + west + east;         // 3x3 block sums, <= 9 per byte
                     const uint32_t n = s - mid[w];                 // neighbours only
-                    uint32_t x = (n | mid[w]) ^ 0x03030303u;       // zero byte <=> alive next (B3/S23)
-                    x |= x >> 2;
-                    x |= x >> 1;
-                    res[w] = ~x & 0x01010101u;
+                    res[w] = zero_bytes((n | mid[w]) ^ 0x03030303u);   // zero byte <=> alive next (B3/S23)
                 }
                 const int gr = r0 - DEPTH + t - k;      // the matrix row just produced
                 if (k < DEPTH) {

@@ -156,6 +156,12 @@ struct out_type_of { using type = typename Op::T; };
 template <class Op>
 struct out_type_of<Op, decltype(void(sizeof(typename Op::O)))> { using type = typename Op::O; };
 
+// Packed bytes, each below 0x80: 0x01 in every byte of the result whose byte of x is zero.
+// (Adding 0x7f carries into a byte's top bit exactly when the byte is not zero, and never beyond.)
+__device__ __forceinline__ uint32_t zero_bytes(uint32_t x) {
+    return ~((x + 0x7f7f7f7fu) >> 7) & 0x01010101u;
+}
+
 // ---- Conway's Game of Life, B3/S23 ("gol") -------------------------------------------------
 struct OpLife {
     static constexpr bool kRowFold = false;
