@@ -47,7 +47,7 @@ def flops_per_cell_update(w):
 # ... or ("temporal", cells_rows, 4, applications per launch) for the iterated heat workload
 MAPPINGS = {
     "weighted_sum": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("direct", 1, 4), ("direct", 2, 4),
-                     ("direct", 4, 4), ("stream", 10, 4), ("stream", 20, 4)],
+                     ("direct", 4, 4), ("stream", 5, 4), ("stream", 10, 4), ("stream", 20, 4)],
     "heat": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("direct", 1, 4), ("direct", 2, 4),
              ("temporal", 2, 4, 2), ("temporal", 4, 4, 2), ("temporal", 4, 4, 3), ("temporal", 2, 4, 4),
              ("temporal", 4, 4, 4), ("temporal", 8, 4, 4),
@@ -133,7 +133,7 @@ STRONG_CONFIGS = {
                      ("direct", 4, 4, 0, (4, 128)), ("local", 4, 4, 0, (16, 8)), ("stream", 10, 4, 0, (1, 64)),
                      # the same with non-temporal output stores (numbering as is)
                      ("local", 2, 4, 0, (16, 8), -1, 1), ("direct", 2, 4, 0, (8, 16), -1, 1),
-                     ("stream", 10, 4, 0, (1, 64), -1, 1)],
+                     ("stream", 10, 4, 0, (1, 64), -1, 1), ("stream", 5, 4, 0, (1, 64), -1, 1)],
     "life": [("direct", 2, 16, 0, (2, 128)), ("direct", 4, 16, 0, (1, 256)), ("temporal", 2, 16, 4, (64, 8)), ("stream", 40, 4, 8, (1, 64)),
              ("stream", 40, 4, 8, (4, 64)), ("stream", 40, 4, 6, (1, 64))],
     "heat": [("direct", 2, 4, 0, (4, 16)), ("temporal", 2, 4, 4, (32, 32)), ("stream", 38, 4, 8, (1, 64)),

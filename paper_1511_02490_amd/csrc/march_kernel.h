@@ -154,6 +154,11 @@ __device__ __forceinline__ void march_body(const TileArgs<Op, Halo> &a, const in
                 // this input row is region row dr of output row j = t - N - dr
 #pragma unroll
                 for (int dr = -N; dr <= S; ++dr) {
+                    // Output rows above or below the segment belong to other wavefronts: nothing has
+                    // to be folded for them (a wavefront-uniform test).  Worth it for short segments
+                    // of a light function (5x5 sum, 10 rows: a quarter of the folds); the sin/cos
+                    // stencil marches tall segments and keeps its straight-line code.
+                    if (!Op::kRowFold && (unsigned)(t - N - dr) >= (unsigned)H) continue;
                     constexpr int kBig = 64 * R;    // keeps the remainder's operand positive
                     const int slot = (u - N - dr + kBig) % R;
 #pragma unroll
