@@ -54,7 +54,7 @@ MAPPINGS = {
              ("stream", 16, 4, 4), ("stream", 36, 4, 4), ("stream", 40, 4, 6), ("stream", 38, 4, 8),
              ("stream", 74, 4, 8)],
     "sincos": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("local", 8, 4),
-               ("stream", 64, 4), ("stream", 89, 4), ("stream", 134, 4)],
+               ("stream", 64, 4), ("stream", 67, 4), ("stream", 89, 4), ("stream", 134, 4)],
     "life": [("local", 1, 1), ("local", 1, 16), ("local", 2, 16), ("direct", 1, 16), ("direct", 2, 16),
              ("direct", 4, 16), ("temporal", 2, 16, 2), ("temporal", 4, 16, 2), ("temporal", 2, 16, 4), ("temporal", 4, 16, 4),
              ("temporal", 8, 16, 4), ("stream", 16, 4, 4), ("stream", 40, 4, 6), ("stream", 40, 4, 8),
@@ -140,7 +140,8 @@ STRONG_CONFIGS = {
              ("stream", 38, 4, 8, (2, 64)), ("stream", 40, 4, 6, (1, 64))],
     "sincos": [("local", 4, 4, 0, (8, 32)), ("local", 2, 4, 0, (18, 14)), ("stream", 89, 4, 0, (4, 64)),
                ("stream", 134, 4, 0, (32, 8)), ("stream", 134, 4, 0, (1, 64)),
-               ("stream", 134, 4, 0, (32, 8), -1, 1), ("stream", 89, 4, 0, (4, 64), -1, 1)],
+               ("stream", 134, 4, 0, (32, 8), -1, 1), ("stream", 89, 4, 0, (4, 64), -1, 1),
+               ("stream", 67, 4, 0, (32, 8), -1, 1)],
 }
 
 
