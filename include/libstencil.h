@@ -224,7 +224,9 @@ int stencil_enumerate_wg(int mode, int max_threads, int *rows, int *cols, int ca
  * and kept until destroy.  Asynchronous on `stream` (a hipStream_t; NULL = default stream),
  * no host synchronisation - except in the first run after stencil_set_kernel replaced a
  * weight table that was already on the device, which waits for the device to go idle
- * before it uploads the new table.
+ * before it uploads the new table.  Calls that allocate nothing (a second run of the same
+ * kind on the same handle) can be captured into a HIP graph; make that first run outside
+ * the capture.
  * wg_rows = wg_cols = 0 lets the library choose (Section 2: selecting the size is the
  * implementation's responsibility): the best size of the handle's last sweep, else a
  * built-in default.  Illegal sizes return STENCIL_E_REFUSED without launching. */
