@@ -258,7 +258,6 @@ def cpu_baseline(wl_mod, w, target_seconds):
     """The oracle, as it stands, on the first rows of the workload's matrix for a bounded
     number of iterations (the sample is sized from a short calibration run)."""
     from oracle import stencil as oracle
-    import numpy as np
     threads = oracle.max_threads()
     g = w.grid()
     rows = w.rows

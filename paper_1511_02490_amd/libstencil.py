@@ -7,7 +7,6 @@ module loads the shared library and raises if it has not been built - there is n
 from __future__ import annotations
 
 import ctypes
-import math
 import os
 from typing import List, Optional, Sequence, Tuple
 
