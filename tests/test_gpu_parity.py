@@ -148,6 +148,26 @@ def test_sincos_borders(ls, border):
                 check(ls, w, wg, blocking=blocking)
 
 
+def test_border_regions_at_the_papers_maximum(ls):
+    """The synthetic template's largest border regions (30 cells, Section 5) in every direction, for
+    both synthetic functions, under the paper's mapping and a blocked one; some sizes are then
+    refused because the tile no longer fits local memory."""
+    for halo in [(30, 1, 1, 30), (1, 30, 30, 1), (30, 30, 30, 30), (32, 32, 32, 32)]:
+        for kernel, border in ((wl.WEIGHTED_SUM, "clamp"), (wl.SINCOS, "wrap")):
+            w = custom(kernel, 150, 170, halo, border, pad=0.3, seed=sum(halo))
+            check(ls, w, (8, 8), blocking=(1, 1))
+            check(ls, w, (4, 16), blocking=(2, 4))
+    w = custom(wl.SINCOS, 150, 170, (30, 30, 30, 30), "constant", pad=0.3, seed=1)
+    st = ls.Stencil.from_workload(w)
+    assert st.is_legal(32, 32) and st.tile_bytes(32, 32) == 92 * 92 * 8
+    st.set_blocking(8, 4)
+    assert not st.is_legal(16, 16)            # (128 + 60) x (64 + 64) x 8 bytes: beyond 160 KiB
+    tin = torch.zeros(150 * 170, device="cuda")
+    with pytest.raises(ls.Refused):
+        st.run(tin, torch.empty_like(tin), 1, (16, 16))
+    st.close()
+
+
 def test_region_alignments_of_the_vector_walk(ls):
     """Run-time regions are walked four window columns at a time from the staged tile's aligned
     west edge: every residue of the west and east extents, against the oracle, and bit for bit
