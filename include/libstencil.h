@@ -69,7 +69,8 @@ enum stencil_border { STENCIL_CLAMP = 0, STENCIL_WRAP = 1, STENCIL_CONSTANT = 2 
  *                 exactly, then the fp32 fma chain; the padding value is a byte.  Exactly one
  *                 application per stencil_run / sweep sample; local-memory tile only, cells
  *                 per work-item (1,1), (4,1), (1,4), (2,4), (4,4), (1,16) or (2,16).
- *   LIFE (u8):    Conway B3/S23 on cells 0/1, region 1/1/1/1 - "gol".
+ *   LIFE (u8):    Conway B3/S23 on cells 0/1, region 1/1/1/1 - "gol".  Precondition: every cell
+ *                 is 0 or 1 (the kernels add packed bytes); a padding value above 1 is rejected.
  *   HEAT (f32):   u + alpha * (((n + s) + (e + w)) - 4u), region 1/1/1/1, every operation
  *                 rounded to fp32 in this order - "he".  scalars[0] = alpha.
  *   SINCOS (f32): sum over the region of w * sin(V) + cos(V) - a compute-intensive
@@ -158,7 +159,8 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            mode: one application per launch, each input row is loaded and pre-processed once
  *            and folded into the N+S+1 output rows it belongs to.
  *            The workgroup only groups wavefronts: w_r*w_c must be a multiple of 64 (other
- *            sizes are refused) and at most 256.
+ *            sizes are refused) and at most 256.  Not available for a matrix whose rows are 4 GiB
+ *            or longer (cells within a row are addressed by 32-bit byte offsets).
  * Output values never depend on the mapping.  Heavily blocked variants have a lower per-kernel
  * W_max (Section 3.1), see stencil_max_wg_size. */
 enum stencil_staging {

@@ -77,6 +77,8 @@ const Variant *find_variant(const stencil *s) {
 }
 
 bool mapping_supported(const stencil *s, int staging, int cr, int cc) {
+    // the register-streaming kernels address a row's cells by 32-bit byte offsets
+    if (staging == STENCIL_STAGING_STREAM && (uint64_t)s->cols * s->elem() >= (1ull << 32)) return false;
     for (const Variant &v : registry())
         if (v.kernel == variant_kernel(s) && v.border == s->border && v.staging == staging && rows_match(v, cr) && v.cc == cc &&
             (v.hn < 0 || (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw)))
@@ -259,6 +261,10 @@ int stencil_set_kernel(stencil_t *s, int kernel_id, const float *weights, int n_
     case STENCIL_LIFE:
         if (s->dtype != STENCIL_U8) return fail(STENCIL_E_INVALID, "LIFE needs a U8 matrix");
         if (!unit_region) return fail(STENCIL_E_INVALID, "LIFE needs border region 1/1/1/1");
+        // the packed-byte kernels add cells without carries between bytes: every cell, the padding
+        // value included, must be 0 or 1
+        if (s->pad != 0.0 && s->pad != 1.0)
+            return fail(STENCIL_E_INVALID, "LIFE needs a padding value of 0 or 1 (it is %g)", s->pad);
         s->weights.clear();
         break;
     case STENCIL_HEAT:
@@ -301,6 +307,8 @@ int stencil_set_border_value(stencil_t *s, double value) {
         return fail(STENCIL_E_INVALID, "padding value of an I32 matrix must be an integer that fits");
     if (s->dtype == STENCIL_U8 && (value < 0 || value > 255 || value != std::floor(value)))
         return fail(STENCIL_E_INVALID, "padding value of a U8 matrix must be an integer in [0, 255]");
+    if (s->kernel == STENCIL_LIFE && value > 1)
+        return fail(STENCIL_E_INVALID, "LIFE cells are 0 or 1: the padding value must be too");
     s->pad = value;
     return STENCIL_OK;
 }

@@ -67,6 +67,28 @@ def test_create_validates_arguments():
     assert "weights" in ls.last_error()
 
 
+def test_life_rejects_cells_that_are_not_0_or_1_and_streaming_rejects_4gib_rows():
+    st = ls.Stencil(8, 8, "u8", (1, 1, 1, 1), "constant")
+    st.set_border_value(3.0)                              # fine for a byte matrix as such ...
+    with pytest.raises(ls.StencilError) as e:
+        st.set_kernel("life")                             # ... but not for the packed-byte Life kernels
+    assert e.value.code == ls.E_INVALID and "0 or 1" in ls.last_error()
+    st.set_border_value(1.0)
+    st.set_kernel("life")
+    with pytest.raises(ls.StencilError):
+        st.set_border_value(2.0)
+    st.set_border_value(0.0)
+    # a near-one-row matrix whose rows are 4 GiB long: the streaming kernels' 32-bit offsets would wrap
+    st = ls.Stencil(1, 1 << 30, "f32", (1, 1, 1, 1), "wrap")
+    st.set_kernel("heat", scalars=(0.2,))
+    st.set_mapping("direct", 1, 4)
+    with pytest.raises(ls.StencilError):
+        st.set_mapping("stream", 8, 4)
+    st = ls.Stencil(1, (1 << 30) - 4, "f32", (1, 1, 1, 1), "wrap")
+    st.set_kernel("heat", scalars=(0.2,))
+    st.set_mapping("stream", 8, 4)
+
+
 def test_legality_eq1():
     st = ls.Stencil.from_workload(wl.config(1))          # 5x5 gaussian, halo 2
     assert st.max_wg_size() == 1024
