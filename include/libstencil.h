@@ -224,9 +224,11 @@ int stencil_enumerate_wg(int mode, int max_threads, int *rows, int *cols, int ca
  * never written; the final matrix is always in `out`; iters = 0 copies.  A scratch matrix
  * for the intermediate steps is allocated by the first run that takes more than one launch
  * and kept until destroy.  Asynchronous on `stream` (a hipStream_t; NULL = default stream),
- * no host synchronisation - except in the first run after stencil_set_kernel replaced a
- * weight table that was already on the device, which waits for the device to go idle
- * before it uploads the new table.  Calls that allocate nothing (a second run of the same
+ * no host synchronisation: the weight table of a run-time region travels to the device in small
+ * launches ordered on `stream` ahead of the stencil's, and a table that stencil_set_kernel
+ * replaced goes into the other of two device tables, so launches already queued keep theirs
+ * (with launches of more than one earlier table still in flight on other streams, order them
+ * yourself).  Calls that allocate nothing (a second run of the same
  * kind on the same handle) can be captured into a HIP graph; make that first run outside
  * the capture.
  * wg_rows = wg_cols = 0 lets the library choose (Section 2: selecting the size is the

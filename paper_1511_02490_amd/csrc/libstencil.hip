@@ -47,6 +47,27 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ in,
         reinterpret_cast<unsigned char *>(out)[tail] = reinterpret_cast<const unsigned char *>(in)[tail];
 }
 
+// A weight table travels to the device inside kernel arguments, 512 floats per launch: ordered on
+// the caller's stream like the stencil launches that read it, no staging buffer, no allocation.
+struct TableChunk { float v[512]; };
+__global__ __launch_bounds__(512) void table_upload_kernel(float *dst, const TableChunk c, int offset, int n) {
+    const int i = (int)threadIdx.x;
+    if (i < n) dst[offset + i] = c.v[i];
+}
+
+hipError_t upload_table(float *dst, const std::vector<float> &w, hipStream_t stream) {
+    for (size_t at = 0; at < w.size(); at += 512) {
+        TableChunk c;
+        const int n = (int)std::min<size_t>(512, w.size() - at);
+        std::memcpy(c.v, w.data() + at, (size_t)n * sizeof(float));
+        hipLaunchKernelGGL(table_upload_kernel, dim3(1), dim3(512), 0, stream, dst, c, (int)at, n);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+constexpr size_t kStaticTableBytes = 32768;                       // 8192 weights (the largest region has 65 x 65)
 
 const std::vector<Variant> &registry() {
     static const std::vector<Variant> reg = [] {
@@ -106,24 +127,21 @@ int check_legal(const stencil *s, const Variant *v, int wr, int wc) {
     return STENCIL_OK;
 }
 
-int ensure_device_state(stencil *s, const Variant *v, bool need_scratch) {
+int ensure_device_state(stencil *s, const Variant *v, bool need_scratch, hipStream_t stream) {
     if (v->hn < 0 && !s->weights_uploaded) {
-        const size_t n = std::max<size_t>(1, s->weights.size());
-        if (!s->d_weights) {
-            hipError_t e = hipMalloc((void **)&s->d_weights, n * sizeof(float));
+        // A replaced table goes into the other of two device tables, by launches ordered on this
+        // run's stream: earlier launches (on any stream) keep reading the table they were given.
+        const int slot = s->d_weights == s->d_tables[0] && s->d_tables[0] ? 1 : 0;
+        if (!s->d_tables[slot]) {
+            hipError_t e = hipMalloc((void **)&s->d_tables[slot], kStaticTableBytes);
             if (e != hipSuccess) return fail(STENCIL_E_RESOURCES, "hipMalloc(weights): %s", hipGetErrorString(e));
-        } else {
-            // launches still in flight (on any stream) may be reading the table about to be replaced
-            hipError_t e = hipDeviceSynchronize();
-            if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
         }
-        if (!s->weights.empty()) {
-            hipError_t e = hipMemcpy(s->d_weights, s->weights.data(), s->weights.size() * sizeof(float),
-                                     hipMemcpyHostToDevice);
-            if (e != hipSuccess) return fail_hip(e, "hipMemcpy(weights)");
-        }
+        hipError_t e = upload_table(s->d_tables[slot], s->weights, stream);
+        if (e != hipSuccess) return fail_hip(e, "weight table upload");
+        s->d_weights = s->d_tables[slot];
         s->weights_uploaded = true;
     }
+    s->table_in_use = s->d_weights;
     if (need_scratch && !s->scratch) {
         hipError_t e = hipMalloc(&s->scratch, s->bytes());
         if (e != hipSuccess) {
@@ -142,7 +160,7 @@ int launches_of(const stencil *s, const Variant *v, int iters) {
 }
 
 // `iters` out-of-place applications ending in `out`, never writing `in`.
-int run_checked(stencil *s, const Variant *v, const void *in, void *out, int iters, int wr, int wc,
+int run_checked(stencil *s, const Variant *v, const void *in, void *out, void *pingpong, int iters, int wr, int wc,
                 hipStream_t stream) {
     if (s->out_dtype() != s->dtype && iters != 1)
         return fail(STENCIL_E_INVALID, "the output is of another element type than the input: exactly one application");
@@ -155,14 +173,14 @@ int run_checked(stencil *s, const Variant *v, const void *in, void *out, int ite
     const int per = v->fuses ? s->temporal_depth : 1;
     const int launches = launches_of(s, v, iters);
     const void *src = in;
-    void *dst = (launches % 2 == 1) ? out : s->scratch;
+    void *dst = (launches % 2 == 1) ? out : pingpong;
     for (int done = 0; done < iters;) {
         const int now = std::min(per, iters - done);
         hipError_t e = v->launch(s, src, dst, wr, wc, now, stream);
         if (e != hipSuccess) return fail_hip(e, "kernel launch");
         done += now;
         src = dst;
-        dst = (dst == out) ? s->scratch : out;
+        dst = (dst == out) ? pingpong : out;
     }
     return STENCIL_OK;
 }
@@ -236,7 +254,8 @@ void stencil_destroy(stencil_t *s) {
     if (!s) return;
     for (hipEvent_t e : s->events) (void)hipEventDestroy(e);
     if (s->scratch) (void)hipFree(s->scratch);
-    if (s->d_weights) (void)hipFree(s->d_weights);
+    for (float *t : s->d_tables)
+        if (t) (void)hipFree(t);
     delete s;
 }
 
@@ -414,9 +433,9 @@ int stencil_run(stencil_t *s, const void *in, void *out, int iters, int wg_rows,
     if (wg_rows == 0 && wg_cols == 0) default_wg(s, v, &wg_rows, &wg_cols);
     rc = check_legal(s, v, wg_rows, wg_cols);
     if (rc != STENCIL_OK) return rc;
-    rc = ensure_device_state(s, v, launches_of(s, v, iters) > 1);
+    rc = ensure_device_state(s, v, launches_of(s, v, iters) > 1, (hipStream_t)stream);
     if (rc != STENCIL_OK) return rc;
-    rc = run_checked(s, v, in, out, iters, wg_rows, wg_cols, (hipStream_t)stream);
+    rc = run_checked(s, v, in, out, s->scratch, iters, wg_rows, wg_cols, (hipStream_t)stream);
     if (rc == STENCIL_OK) g_err[0] = '\0';
     return rc;
 }
@@ -434,7 +453,7 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
     if (!v) return fail(STENCIL_E_INVALID, "no kernel selected for this scenario");
     if (reps <= 0) reps = 30;
     hipStream_t stream = (hipStream_t)stream_;
-    rc = ensure_device_state(s, v, launches_of(s, v, iters) > 1);
+    rc = ensure_device_state(s, v, launches_of(s, v, iters) > 1, stream);
     if (rc != STENCIL_OK) return rc;
     while ((int)s->events.size() < 2 * reps) {
         hipEvent_t e;
@@ -465,7 +484,7 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
             for (int i = from; i < to; ++i) {
                 hipError_t e = hipEventRecord(s->events[2 * i], stream);
                 if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
-                int r = run_checked(s, v, in, out, iters, wr, wc, stream);
+                int r = run_checked(s, v, in, out, s->scratch, iters, wr, wc, stream);
                 if (r != STENCIL_OK) return r;
                 e = hipEventRecord(s->events[2 * i + 1], stream);
                 if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
@@ -484,7 +503,7 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
         };
         const int taken = probe_only ? std::min(2, reps) : reps;
         for (int w = 0; w < (probe_only ? 1 : kWarmup); ++w) {
-            int r = run_checked(s, v, in, out, iters, wr, wc, stream);
+            int r = run_checked(s, v, in, out, s->scratch, iters, wr, wc, stream);
             if (r != STENCIL_OK) return r;
         }
         {

@@ -56,7 +56,9 @@ struct stencil {
     int best_rows = 0, best_cols = 0;
     // device-side state, created on first use
     void *scratch = nullptr;
-    float *d_weights = nullptr;
+    float *d_tables[2] = {nullptr, nullptr};   // weight tables of a run-time region; a replaced table goes into the other one
+    float *d_weights = nullptr;                // the current one of the two
+    const float *table_in_use = nullptr;       // what the launchers hand to the kernels
     bool weights_uploaded = false;
     std::vector<hipEvent_t> events;
     size_t elem() const { return dtype == STENCIL_U8 ? 1 : (dtype == STENCIL_F64 ? 8 : 4); }
@@ -170,7 +172,7 @@ sk::TileArgs<Op, Halo> make_args(const stencil *s, int staging, const void *in, 
         a.halo.s_ = s->hs;
         a.halo.e_ = s->he;
         a.halo.w_ = s->hw;
-        a.w.v = s->d_weights;
+        a.w.v = s->table_in_use;
     }
     *blocks = (unsigned)a.n_tiles;
     a.xcd_chunk = 0;
