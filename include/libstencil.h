@@ -237,6 +237,24 @@ int stencil_enumerate_wg(int mode, int max_threads, int *rows, int *cols, int ca
 int stencil_run(stencil_t *st, const void *in, void *out, int iters,
                 int wg_rows, int wg_cols, void *stream);
 
+/* stencil_run for callers that cannot allocate device memory - code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: the same kernels, but the device memory a run
+ * needs beyond `in` and `out` (the weight table of a run-time border region; the matrix that a run
+ * of more than one launch ping-pongs through) lies in one fixed buffer that is part of the
+ * library's code object, STENCIL_STATIC_MATRIX_BYTES (+ 32 KiB for the table) per GPU, held from
+ * the library's load until the process ends.  Calls no hipMalloc / hipFree and no allocating
+ * routine; the first call on a device looks up the buffer's address (make it outside a capture).
+ * STENCIL_E_INVALID, with nothing launched, if the run needs more than the buffer holds: a
+ * matrix above STENCIL_STATIC_MATRIX_BYTES with more than one launch (one launch never needs
+ * the matrix), or a weight table above 8192 entries.  Everything else as for stencil_run
+ * (arguments, legality, asynchronous on `stream`); the handle's own scratch matrix and tables are
+ * neither used nor created.  All handles and all calls on one GPU share the buffer, which keeps
+ * the last call's contents: each call uploads its table and overwrites the matrix before reading
+ * it, and calls that overlap on one GPU (different streams or threads) race - serialise them. */
+#define STENCIL_STATIC_MATRIX_BYTES (16 << 20)
+int stencil_run_static(stencil_t *st, const void *in, void *out, int iters,
+                       int wg_rows, int wg_cols, void *stream);
+
 /* Section 5's measurement: for each of the n sizes, 3 untimed runs and then `reps` timed
  * samples (reps <= 0 means 30), each sample one stencil_run(iters) bracketed by events on
  * `stream`.  Outputs (host arrays of n, each may be NULL): mean / min / median / sample

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <limits>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -67,7 +68,37 @@ hipError_t upload_table(float *dst, const std::vector<float> &w, hipStream_t str
     return hipSuccess;
 }
 
+// ---- the buffer of stencil_run_static ---------------------------------------------------------
+// Device memory the library needs beyond `in` and `out` - the run-time region's weight table and
+// the matrix that iterated runs ping-pong through - for callers that must not allocate: one array
+// per GPU, part of the code object, held until the process ends.  Host code never passes the
+// array's name to the device (on the host it is only a stand-in for the symbol): the address is
+// asked for once per device and kept.
 constexpr size_t kStaticTableBytes = 32768;                       // 8192 weights (the largest region has 65 x 65)
+constexpr size_t kStaticMatrixBytes = STENCIL_STATIC_MATRIX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticTableBytes + kStaticMatrixBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+// The calling thread's current device's copy of `scratch` (each GPU holds its own, at its own address).
+int static_scratch(unsigned char **ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(STENCIL_E_INVALID, "device index %d beyond %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    *ptr = g_scratch_ptr[dev];
+    return STENCIL_OK;
+}
+
 
 const std::vector<Variant> &registry() {
     static const std::vector<Variant> reg = [] {
@@ -436,6 +467,45 @@ int stencil_run(stencil_t *s, const void *in, void *out, int iters, int wg_rows,
     rc = ensure_device_state(s, v, launches_of(s, v, iters) > 1, (hipStream_t)stream);
     if (rc != STENCIL_OK) return rc;
     rc = run_checked(s, v, in, out, s->scratch, iters, wg_rows, wg_cols, (hipStream_t)stream);
+    if (rc == STENCIL_OK) g_err[0] = '\0';
+    return rc;
+}
+
+int stencil_run_static(stencil_t *s, const void *in, void *out, int iters, int wg_rows, int wg_cols, void *stream_) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    if (iters < 0) return fail(STENCIL_E_INVALID, "iters must be >= 0");
+    int rc = validate_buffers(s, in, out);
+    if (rc != STENCIL_OK) return rc;
+    const Variant *v = find_variant(s);
+    if (!v) return fail(STENCIL_E_INVALID, "no kernel selected for this scenario");
+    if (wg_rows == 0 && wg_cols == 0) default_wg(s, v, &wg_rows, &wg_cols);
+    rc = check_legal(s, v, wg_rows, wg_cols);
+    if (rc != STENCIL_OK) return rc;
+    // what this run needs beyond in / out must fit the fixed buffer
+    const bool needs_matrix = launches_of(s, v, iters) > 1;
+    if (needs_matrix && s->bytes() > kStaticMatrixBytes)
+        return fail(STENCIL_E_INVALID, "stencil_run_static: a run of %d launches ping-pongs through a matrix of %zu bytes, "
+                                       "the fixed buffer holds %zu", launches_of(s, v, iters), s->bytes(), kStaticMatrixBytes);
+    const bool needs_table = v->hn < 0;
+    if (needs_table && s->weights.size() * sizeof(float) > kStaticTableBytes)
+        return fail(STENCIL_E_INVALID, "stencil_run_static: weight table of %zu bytes, the fixed buffer holds %zu",
+                    s->weights.size() * sizeof(float), kStaticTableBytes);
+    unsigned char *buf = nullptr;
+    rc = static_scratch(&buf);
+    if (rc != STENCIL_OK) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    float *table = reinterpret_cast<float *>(buf);
+    void *matrix = buf + kStaticTableBytes;
+    if (needs_table) {
+        // the buffer keeps whatever the last call (of any handle) left: this run's table goes in
+        // first, ordered on the stream before the launches that read it
+        hipError_t e = upload_table(table, s->weights, stream);
+        if (e != hipSuccess) return fail_hip(e, "weight table upload");
+    }
+    // every launch writes its whole destination matrix before the next reads it: nothing to clear
+    s->table_in_use = table;
+    rc = run_checked(s, v, in, out, matrix, iters, wg_rows, wg_cols, stream);
+    s->table_in_use = s->d_weights;
     if (rc == STENCIL_OK) g_err[0] = '\0';
     return rc;
 }

@@ -23,6 +23,7 @@ OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF, OPT_NT_STORE = 0, 1, 2, 3
 _STAGINGS = {"local": STAGING_LOCAL, "direct": STAGING_DIRECT, "temporal": STAGING_TEMPORAL,
              "stream": STAGING_STREAM}
 N_FEATURES = 13
+STATIC_MATRIX_BYTES = 16 << 20      # STENCIL_STATIC_MATRIX_BYTES
 
 _DTYPES = {"f32": F32, "u8": U8, "i32": I32, "f64": F64}
 _BORDERS = {"clamp": CLAMP, "wrap": WRAP, "constant": CONSTANT}
@@ -68,6 +69,7 @@ def _load() -> ctypes.CDLL:
         "stencil_is_legal": (c_int, [vp, c_int, c_int]),
         "stencil_enumerate_wg": (c_int, [c_int, c_int, ip, ip, c_int]),
         "stencil_run": (c_int, [vp, vp, vp, c_int, c_int, c_int, vp]),
+        "stencil_run_static": (c_int, [vp, vp, vp, c_int, c_int, c_int, vp]),
         "stencil_sweep_wg": (c_int, [vp, vp, vp, c_int, ip, ip, c_int, c_int, c_int, c_int,
                                      dp, dp, dp, dp, ip, ip, dp, vp]),
         "stencil_sweep_configs": (c_int, [vp, vp, vp, c_int, vp, c_int, c_int, dp, ip, ip, vp]),
@@ -99,6 +101,7 @@ _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
            "stencil_set_mapping", "stencil_get_mapping", "stencil_output_dtype", "stencil_set_option",
            "stencil_max_wg_size", "stencil_tile_bytes", "stencil_is_legal", "stencil_enumerate_wg", "stencil_run",
+           "stencil_run_static",
            "stencil_sweep_wg", "stencil_sweep_configs", "stencil_device_copy", "stencil_time_copy",
            "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
@@ -319,6 +322,13 @@ class Stencil:
         self._check_tensors(tin, tout)
         _check(_lib.stencil_run(self._h, ctypes.c_void_p(tin.data_ptr()), ctypes.c_void_p(tout.data_ptr()),
                                 int(iters), int(wg[0]), int(wg[1]), self._stream_ptr(stream)))
+        return tout
+
+    def run_static(self, tin, tout, iters: int = 1, wg: Tuple[int, int] = (0, 0), stream=None):
+        """stencil_run out of the library's fixed device buffer (allocates nothing)."""
+        self._check_tensors(tin, tout)
+        _check(_lib.stencil_run_static(self._h, ctypes.c_void_p(tin.data_ptr()), ctypes.c_void_p(tout.data_ptr()),
+                                       int(iters), int(wg[0]), int(wg[1]), self._stream_ptr(stream)))
         return tout
 
     def sweep(self, tin, tout, sizes: Sequence[Tuple[int, int]], iters: int = 1,
