@@ -5,13 +5,18 @@ One "step" = one pass of the stencil over the workload's matrix (all of its iter
 the workgroup size the sweep found best.  Before the timed region the script runs the sweep
 of Section 5 over the workload's whole size list (every size: 3 warm-ups + `--reps` samples),
 reduces it (best size, speedup over the fixed sizes 4x4 and 32x4 / 4x32, best/worst) and asks
-the predictor for a size.  Inputs are generated on the host from a seed and are resident in
-HBM before anything is timed.
+the predictor for a size.  Inputs are generated from a seed and are resident in HBM before
+anything is timed.
+
+The default workload is C5 (8192^2, 256 MiB each way): the one configuration that no cache
+holds, so its bandwidth figure is an HBM figure.  The other workloads, and one heat step on
+8192^2 and 16384^2 matrices, follow as sub-records with the same fields.
 
 Prints ONE JSON line.  `value` = Gcells/s (cell updates per second) of the timed steps;
 `roofline` prices the stencil kernel's algorithmic bytes (one read + one write per cell
-update) over its HIP-event-measured launch time against the 8 TB/s HBM peak; `cpu_baseline`
-is the CPU oracle timed on a bounded sample of the same workload on the host cores.
+update) over its HIP-event-measured launch time against the 8 TB/s HBM peak, with the
+arithmetic views beside it; `cpu_baseline` is the CPU oracle timed on a bounded sample of the
+same workload on the host cores.
 """
 from __future__ import annotations
 
@@ -28,6 +33,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 FP32_VECTOR_PEAK_TFLOPS = 157.3      # published: packed fp32 fma on 256 CUs x 4 SIMDs x 16 lanes at 2.4 GHz
+# vector instructions the chip can issue per second, one lane each: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+VALU_LANE_ISSUE_PEAK = 256 * 4 * 16 * 2.4e9
+
+WORKLOADS = ["C1", "C2", "C3", "C4", "C5", "H8192", "H16384", "W8192"]
 
 
 def flops_per_cell_update(w):
@@ -67,19 +76,52 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = per-workload default)")
     ap.add_argument("--warmup", type=int, default=-1)
-    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C5", choices=WORKLOADS,
+                    help="C1..C5; one heat step on a 8192^2 / 16384^2 matrix (H8192, H16384); a 28-tap weighted sum "
+                         "with C5's border region, given at run time, on C5's matrix (W8192)")
     ap.add_argument("--reps", type=int, default=30, help="timed samples per workgroup size in the sweep")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-predictor", action="store_true", help="skip the leave-one-out predictor study")
+    ap.add_argument("--no-others", action="store_true", help="skip the sub-records of the other workloads")
     ap.add_argument("--quick", action="store_true", help="sweep a thinned size list (development only)")
     ap.add_argument("--wg", default="", help="R,C: skip the sweep and time this workgroup size (profiling runs)")
-    ap.add_argument("--mapping", default="", help="staging,cells_rows,cells_cols to go with --wg, e.g. direct,2,4")
+    ap.add_argument("--mapping", default="", help="staging,cells_rows,cells_cols[,depth] to go with --wg, e.g. direct,2,4")
     ap.add_argument("--nt-store", default=None, choices=["0", "1"],
                     help="force plain (0) or non-temporal (1) output stores instead of timing both")
+    ap.add_argument("--xcd-remap", default=None, choices=["0", "1"], help="workgroup numbering to go with --wg")
     ap.add_argument("--copy-only", action="store_true",
                     help="launch only the plain copy kernel on the workload's matrix (counter calibration)")
     return ap.parse_args()
+
+
+def named_workload(wl, name):
+    if name.startswith("C"):
+        return wl.config(int(name[1]) - 1)
+    n = int(name[1:])
+    if name.startswith("W"):
+        # the lightweight synthetic stencil (Section 3.3) with C5's region: a border region the
+        # library has no compiled variant for, so the run-time-region kernels serve it
+        c5 = wl.config(4)
+        weights = c5.weights / c5.weights.sum()
+        return wl.Workload("%s weighted_sum N1S5E3W0 %dx%d f32 const0" % (name, n, n), n, n, "f32", c5.halo, "constant",
+                           0.0, wl.WEIGHTED_SUM, 1, c5.seed, "pow2", weights=weights.astype("float32"))
+    w = wl.config(3, rows=n, cols=n, iters=1)
+    w.name = "%s heat %dx%d f32 wrap x1" % (name, n, n)
+    return w
+
+
+def device_matrices(torch, w):
+    """(in, out) tensors of the workload, resident on the device.  The two matrices larger than C5
+    are drawn on the device (the same distribution as C4's uniform fill)."""
+    if w.rows * w.cols > 8192 * 8192:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(w.seed)
+        a = torch.rand(w.rows * w.cols, generator=gen, device="cuda", dtype=torch.float32) * 100.0
+    else:
+        a = torch.from_numpy(w.grid()).cuda()
+    types = {"f32": torch.float32, "u8": torch.uint8, "i32": torch.int32, "f64": torch.float64}
+    return a, torch.empty(a.shape, dtype=types[w.out_dtype], device="cuda")
 
 
 def sweep_summary(res, cells_per_sample):
@@ -103,12 +145,12 @@ def sweep_summary(res, cells_per_sample):
 
 def apply_mapping(st, mapping):
     st.set_mapping(*mapping[:3])
-    if len(mapping) > 3:
+    if len(mapping) > 3 and mapping[3]:
         st.set_option(1, mapping[3])      # STENCIL_OPT_TEMPORAL_DEPTH
 
 
 def mapping_name(mapping):
-    return "%s %dx%d" % tuple(mapping[:3]) + (" depth %d" % mapping[3] if len(mapping) > 3 else "")
+    return "%s %dx%d" % tuple(mapping[:3]) + (" depth %d" % mapping[3] if len(mapping) > 3 and mapping[3] else "")
 
 
 def sweep_burst(w):
@@ -125,49 +167,24 @@ FAST_MAPPING = {"weighted_sum": ("local", 2, 4), "heat": ("direct", 2, 4), "sinc
                 "life": ("direct", 2, 16)}
 
 
-# strong configurations of each kernel, swept together (stencil_sweep_configs) for the per-workload
-# figures of the workloads that are not the one being benchmarked:
-# (staging, cells_rows, cells_cols, applications per launch or 0, workgroup size)
+# strong configurations of each kernel, swept together (stencil_sweep_configs) for the sub-records:
+# (staging, cells_rows, cells_cols, applications per launch or 0, workgroup size[, numbering, non-temporal stores])
 STRONG_CONFIGS = {
     "weighted_sum": [("local", 2, 4, 0, (16, 8)), ("local", 2, 4, 0, (8, 8)), ("direct", 2, 4, 0, (8, 16)),
                      ("direct", 4, 4, 0, (4, 128)), ("local", 4, 4, 0, (16, 8)), ("stream", 10, 4, 0, (1, 64)),
                      # the same with non-temporal output stores (numbering as is)
                      ("local", 2, 4, 0, (16, 8), -1, 1), ("direct", 2, 4, 0, (8, 16), -1, 1),
                      ("stream", 10, 4, 0, (1, 64), -1, 1), ("stream", 5, 4, 0, (1, 64), -1, 1)],
-    "life": [("direct", 2, 16, 0, (2, 128)), ("direct", 4, 16, 0, (1, 256)), ("temporal", 2, 16, 4, (64, 8)), ("stream", 40, 4, 8, (1, 64)),
-             ("stream", 40, 4, 8, (4, 64)), ("stream", 40, 4, 6, (1, 64))],
+    "life": [("direct", 2, 16, 0, (2, 128)), ("direct", 4, 16, 0, (1, 256)), ("direct", 4, 16, 0, (1, 256), -1, 1),
+             ("temporal", 2, 16, 4, (64, 8)), ("stream", 40, 4, 8, (1, 64)),
+             ("stream", 20, 8, 8, (1, 64)), ("stream", 40, 4, 8, (4, 64)), ("stream", 40, 4, 6, (1, 64))],
     "heat": [("direct", 2, 4, 0, (4, 16)), ("temporal", 2, 4, 4, (32, 32)), ("stream", 38, 4, 8, (1, 64)),
-             ("stream", 38, 4, 8, (2, 64)), ("stream", 40, 4, 6, (1, 64))],
+             ("stream", 38, 4, 8, (2, 64)), ("stream", 38, 4, 8, (1, 128)), ("stream", 40, 4, 6, (1, 64))],
     "sincos": [("local", 4, 4, 0, (8, 32)), ("local", 2, 4, 0, (18, 14)), ("stream", 89, 4, 0, (4, 64)),
                ("stream", 134, 4, 0, (32, 8)), ("stream", 134, 4, 0, (1, 64)),
                ("stream", 134, 4, 0, (32, 8), -1, 1), ("stream", 89, 4, 0, (4, 64), -1, 1),
                ("stream", 67, 4, 0, (32, 8), -1, 1)],
 }
-
-
-def best_known_configuration(ls, torch, o, reps):
-    """The fastest of the kernel's strong configurations on workload `o`, per application."""
-    st = ls.Stencil.from_workload(o)
-    a = torch.from_numpy(o.grid()).cuda()
-    b = torch.empty_like(a)
-    burst = sweep_burst(o)
-    configs = STRONG_CONFIGS[o.kernel]
-    mean, status, best = st.sweep_configs(a, b, configs, iters=burst, reps=reps)
-    st.close()
-    del a, b
-    if best < 0:
-        return None
-    c = configs[best]
-    per_app_ms = mean[best] / burst
-    fused = max(1, c[3])
-    # a launch moves the matrix once whatever it fuses: bytes per launch over the launch's time
-    gbs = o.cells * o.bytes_per_cell_update / (per_app_ms * fused) / 1e6
-    return {"mapping": mapping_name((c[0], c[1], c[2]) + ((c[3],) if c[3] else ())), "wg": list(c[4]),
-            "nt_store": c[6] if len(c) > 6 else 0, "applications_per_launch": fused, "ms_per_application": per_app_ms,
-            "gcells_s": o.cells / per_app_ms / 1e6, "algorithmic_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
-            "configurations_swept": len(configs)}
-
-
 # one application of the heat step on matrices that no cache holds (256 MiB and 1 GiB each way): the
 # workgroup sizes that win there are not those of the 4096^2 matrix, and the workgroup numbering and
 # non-temporal output stores matter the other way round - the reason to sweep per dataset
@@ -177,36 +194,273 @@ LARGE_HEAT_CONFIGS = [(m, cr, 4, 0, wg, remap, nt)
                       for remap in (1, 0) for nt in (0, 1)]
 
 
-def larger_matrices(ls, wl, torch, reps):
-    out = {}
-    for n in (8192, 16384):
-        o = wl.config(3, rows=n, cols=n, iters=1)
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(o.seed)
-        a = torch.rand(n * n, generator=gen, device="cuda", dtype=torch.float32) * 100.0
-        b = torch.empty_like(a)
-        st = ls.Stencil.from_workload(o)
-        burst = 4
-        mean, status, best = st.sweep_configs(a, b, LARGE_HEAT_CONFIGS, iters=burst, reps=reps)
-        copy_ms, _ = ls.time_copy(a, b, burst=burst, reps=reps)
-        fixed = LARGE_HEAT_CONFIGS.index(("direct", 2, 4, 0, (4, 16), 1, 0))   # the 4096^2 matrix's best
-        st.close()
-        del a, b
-        c = LARGE_HEAT_CONFIGS[best]
-        gbs = lambda ms: n * n * 8 / (ms / burst) / 1e6
-        out["heat %dx%d" % (n, n)] = {
-            "best": {"mapping": mapping_name(c[:3]), "wg": list(c[4]), "xcd_remap": c[5], "nt_store": c[6]},
-            "ms_per_application": mean[best] / burst, "algorithmic_gbs": gbs(mean[best]),
-            "frac_of_hbm_peak": gbs(mean[best]) / HBM_PEAK_GBS,
-            "with_the_4096_best": {"algorithmic_gbs": gbs(mean[fixed]), "frac_of_hbm_peak": gbs(mean[fixed]) / HBM_PEAK_GBS},
-            "copy_kernel_gbs": 2.0 * n * n * 4 / copy_ms / 1e6, "configurations_swept": len(LARGE_HEAT_CONFIGS)}
+def strong_configs(w):
+    if w.name.startswith("W"):
+        return [("local", cr, 4, 0, wg, -1, nt) for cr in (2, 4) for wg in ((8, 32), (4, 64), (8, 16)) for nt in (0, 1)]
+    return LARGE_HEAT_CONFIGS if w.name.startswith("H") else STRONG_CONFIGS[w.kernel]
+
+
+def kernel_label(w, mapping, size, depth, nt, remap=1):
+    """Name under which a kernel's rocprofv3 counters are kept in profiles/traffic.json."""
+    family = {"local": "tile", "direct": "direct", "temporal": "temporal", "stream": "stream"}[mapping[0]]
+    if mapping[0] == "stream" and depth == 0:
+        family = "march"            # register streaming, one application per launch
+    return "%s: %s_kernel<%s> %dx%d cells/work-item, wg %dx%d" % (
+        w.name.split()[0], family, w.kernel, mapping[1], mapping[2], size[0], size[1]) + (
+        ", %d applications/launch" % depth if depth > 1 else "") + (", non-temporal stores" if nt else "") + (
+        "" if remap else ", plain workgroup numbering")
+
+
+def recorded_counters(label):
+    """What the committed rocprofv3 summaries hold for this kernel (HBM bytes per launch, vector
+    instructions), or None when there is nothing for it or the kernel's sources have changed since
+    the counters were taken."""
+    from paper_1511_02490_amd import rocprof_summary as rs
+    import re
+    try:
+        with open(rs.TRAFFIC_JSON) as fh:
+            table = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    rec = table.get(label)
+    if rec is None and ("stream_kernel" in label or "march_kernel" in label):
+        # in the streaming kernels a wavefront's accesses do not depend on how wavefronts are grouped
+        # into workgroups: a record taken with another workgroup size of the same mapping serves
+        strip = lambda k: re.sub(r", wg \d+x\d+", "", k)
+        rec = next((v for k, v in sorted(table.items()) if strip(k) == strip(label)), None)
+    if not rec or rec.get("source_hash") != rs.kernel_source_hash(rs.family_of(label)):
+        return None
+    return rec
+
+
+def cpu_baseline(w, target_seconds):
+    """The oracle, as it stands, on (the first rows of) the workload's matrix: whole passes of a
+    bounded number of iterations, repeated until about `target_seconds` of CPU time have gone by
+    (never less than one second), the sample sized from a short calibration run."""
+    from oracle import stencil as oracle
+    import copy
+    threads = oracle.max_threads()
+    ws = copy.copy(w)
+    ws.rows = min(w.rows, 8192)            # the matrices beyond C5: their first 8192 rows
+    g = ws.grid()
+    run = lambda it, grid=g, th=0: oracle.apply(grid, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, it, th)
+    run(1, g[:64])                         # load the library, spawn the threads
+    iters, dt = 1, 0.0
+    while True:                            # calibration: the iterations one pass makes
+        t0 = time.perf_counter()
+        run(iters)
+        dt = time.perf_counter() - t0
+        if dt >= target_seconds / 3 or iters >= w.iters:
+            break
+        iters = int(min(w.iters, max(2 * iters, iters * 0.8 * target_seconds / max(dt, 1e-3))))
+    passes = int(max(1, min(100000, math.ceil(max(1.0, 0.7 * target_seconds) / max(dt, 1e-6)))))
+    t0 = time.perf_counter()
+    for _ in range(passes):
+        run(iters)
+    dt = time.perf_counter() - t0
+    # the same oracle on one thread, on a sample a tenth the size (context for the threaded figure)
+    it1 = max(1, iters // 10)
+    rows1 = ws.rows if iters >= 10 else max(64, ws.rows // 10)
+    t1 = time.perf_counter()
+    n1 = 0
+    while True:
+        run(it1, g[:rows1], 1)
+        n1 += 1
+        if time.perf_counter() - t1 >= min(1.0, target_seconds / 8):
+            break
+    dt1 = time.perf_counter() - t1
+    run(1, g[:8], threads)                 # thread count back
+    return {
+        "value": ws.rows * w.cols * iters * passes / dt / 1e9,
+        "unit": "Gcells/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": "%s %d x %d matrix, %d of %d iterations, %d passes, %.1f s" % (
+            "whole" if ws.rows == w.rows else "first %d rows of the" % ws.rows, w.rows, w.cols, iters, w.iters, passes, dt),
+        "single_thread": {"value": rows1 * w.cols * it1 * n1 / dt1 / 1e9, "unit": "Gcells/s", "cores": 1,
+                          "sample": "first %d rows, %d iterations, %d passes, %.1f s" % (rows1, it1, n1, dt1)},
+    }
+
+
+class Bench:
+    """One workload on the device: its handle, matrices and the measurements made on them."""
+
+    def __init__(self, ls, torch, w, args):
+        self.ls, self.torch, self.w, self.args = ls, torch, w, args
+        self.st = ls.Stencil.from_workload(w)
+        self.tin, self.tout = device_matrices(torch, w)
+        self.cells = w.rows * w.cols
+        self.burst = 4 if w.name.startswith("H") else sweep_burst(w)
+        self.alg_bytes = self.cells * w.bytes_per_cell_update
+
+    def close(self):
+        self.st.close()
+        del self.tin, self.tout
+
+    def copy_reference(self, n=20):
+        """GB/s of the plain copy kernel on this matrix (read + write), timed like a sweep sample."""
+        mean_ms, _ = self.ls.time_copy(self.tin, self.tin.new_empty(self.tin.shape), burst=max(self.burst, 2), reps=n)
+        return 2.0 * self.tin.numel() * self.tin.element_size() / (mean_ms * 1e-3) / 1e9
+
+    def choose_stores(self, mapping, size):
+        """Plain or non-temporal output stores for this configuration, whichever the sweep's clock
+        prefers (forced by --nt-store); leaves the handle on that choice."""
+        a, st, ls = self.args, self.st, self.ls
+        if a.nt_store is not None:
+            nt = int(a.nt_store)
+        elif a.wg or mapping[2] == 1:      # one cell per work-item: no 16-byte stores to switch
+            nt = 0
+        else:
+            depth = mapping[3] if len(mapping) > 3 else 0
+            pair = [(mapping[0], mapping[1], mapping[2], depth, size, -1, flag) for flag in (0, 1)]
+            mean, status, _ = st.sweep_configs(self.tin, self.tout, pair, iters=self.burst, reps=a.reps)
+            # plain stores unless the others win by more than the run-to-run noise
+            nt = 1 if (status[0] == ls.OK and status[1] == ls.OK and mean[1] < 0.98 * mean[0]) else 0
+        apply_mapping(st, mapping)
+        st.set_option(ls.OPT_NT_STORE, nt)
+        return nt
+
+    def choose_stores_for_steps(self, mapping, size):
+        """The same choice for the timed steps, made on whole steps (all iterations of the workload):
+        a short burst does not show what the stores do to a long chain of dependent launches."""
+        a, st, ls, w, torch = self.args, self.st, self.ls, self.w, self.torch
+        if a.nt_store is not None or a.wg or mapping[2] == 1 or w.iters == 1:
+            return self.choose_stores(mapping, size)
+        apply_mapping(st, mapping)
+        took = []
+        per_trial = 1
+        for flag in (0, 1):
+            st.set_option(ls.OPT_NT_STORE, flag)
+            t_a = time.perf_counter()
+            st.run(self.tin, self.tout, w.iters, size)
+            torch.cuda.synchronize()
+            if flag == 0:     # a trial lasts a few milliseconds, so that the host's part does not decide
+                per_trial = max(1, min(500, int(0.004 / max(time.perf_counter() - t_a, 1e-6))))
+            trials = []
+            for _ in range(3):
+                t_a = time.perf_counter()
+                for _ in range(per_trial):
+                    st.run(self.tin, self.tout, w.iters, size)
+                torch.cuda.synchronize()
+                trials.append(time.perf_counter() - t_a)
+            took.append(min(trials))
+        nt = 1 if took[1] < 0.98 * took[0] else 0
+        st.set_option(ls.OPT_NT_STORE, nt)
+        return nt
+
+    def timed_steps(self, size, steps, warmup):
+        """(ms per step, Gcells/s) of `steps` whole passes, the handle as configured."""
+        st, w, torch = self.st, self.w, self.torch
+        for _ in range(warmup):
+            st.run(self.tin, self.tout, w.iters, size)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            st.run(self.tin, self.tout, w.iters, size)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        return dt / steps * 1e3, self.cells * w.iters * steps / dt / 1e9
+
+    def kernel_roofline(self, mapping, size, nt=None, remap=1):
+        """Launch duration of one kernel by HIP events on the launch stream (the sweep's own clock)
+        against what a launch must move: the matrix once each way, whatever the number of
+        applications it fuses."""
+        w, st, a = self.w, self.st, self.args
+        if nt is None:
+            nt = self.choose_stores(mapping, size)
+        else:
+            apply_mapping(st, mapping)
+            st.set_option(self.ls.OPT_NT_STORE, nt)
+        depth = mapping[3] if len(mapping) > 3 and mapping[3] else 1
+        k_res = st.sweep(self.tin, self.tout, [size], iters=self.burst, fixed=(0, 0), reps=max(a.reps, 30))
+        launches = -(-self.burst // depth)
+        kernel_ms = k_res.mean_ms[0] / launches
+        achieved = self.alg_bytes / (kernel_ms * 1e-3) / 1e9
+        label = kernel_label(w, mapping, size, depth if len(mapping) > 3 and mapping[3] else 0, nt, remap)
+        rec = recorded_counters(label)
+        out = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+               "frac": achieved / HBM_PEAK_GBS, "traffic": rec["traffic_bytes_per_launch"] if rec else None,
+               "kernel": label, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": self.alg_bytes,
+               "applications_per_launch": depth, "nt_store": nt,
+               "gcells_s": self.cells * depth / (kernel_ms * 1e-3) / 1e9}
+        # the arithmetic views: algorithmic fp32 operations against the published vector peak ...
+        flops = flops_per_cell_update(w)
+        if flops:
+            tflops = flops * self.cells * depth / (kernel_ms * 1e-3) / 1e12
+            out["alu"] = {"bound": "alu", "achieved": tflops, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "frac": tflops / FP32_VECTOR_PEAK_TFLOPS, "flops_per_cell_update": flops}
+        # ... and vector instructions issued (rocprofv3 SQ_INSTS_VALU, 64 lanes each; an instruction of
+        # the transcendental unit holds its issue slot four times as long) against the chip's issue rate
+        if rec and rec.get("valu_insts_per_launch"):
+            slots = (rec["valu_insts_per_launch"] + 3.0 * rec.get("valu_trans_insts_per_launch", 0.0)) * 64.0
+            rate = slots / (kernel_ms * 1e-3)
+            out["valu_issue"] = {"bound": "alu", "achieved": rate / 1e12, "peak": VALU_LANE_ISSUE_PEAK / 1e12,
+                                 "unit": "T lane-instructions/s", "frac": rate / VALU_LANE_ISSUE_PEAK,
+                                 "valu_insts_per_cell_update": rec["valu_insts_per_launch"] * 64.0 / (self.cells * depth),
+                                 "issue_slots_per_cell_update": slots / (self.cells * depth),
+                                 "valu_busy_frac_in_profile": rec.get("valu_busy_frac")}
+        return out
+
+
+def sub_record(ls, torch, wl, name, args):
+    """A workload other than the benchmarked one, with the same fields: the fastest of its strong
+    configurations (stencil_sweep_configs), timed steps with it, the roofline of its best kernel
+    that makes one application per launch (and of the fused one the steps used), the oracle."""
+    w = named_workload(wl, name)
+    b = Bench(ls, torch, w, args)
+    reps = max(5, args.reps // 3)
+    configs = strong_configs(w)
+    mean, status, best = b.st.sweep_configs(b.tin, b.tout, configs, iters=b.burst, reps=reps)
+    ok = [k for k in range(len(configs)) if status[k] == ls.OK]
+    if not ok:
+        b.close()
+        return None
+    as_mapping = lambda c: (c[0], c[1], c[2]) + ((c[3],) if c[3] else ())
+    flags = lambda c: (c[5] if len(c) > 5 else -1, c[6] if len(c) > 6 and c[6] >= 0 else 0)
+    c = configs[best]
+    single = [k for k in ok if not configs[k][3]]
+    c1 = configs[min(single, key=lambda k: mean[k])] if single else None
+
+    def configure(cfg):
+        apply_mapping(b.st, as_mapping(cfg))
+        remap, nt = flags(cfg)
+        if remap >= 0:
+            b.st.set_option(ls.OPT_XCD_REMAP, remap)
+        b.st.set_option(ls.OPT_NT_STORE, nt)
+        return nt
+
+    nt = configure(c)
+    steps = {"C1": 200, "C2": 200, "C3": 10, "C4": 3, "C5": 30, "H8192": 50, "H16384": 20, "W8192": 30}[name]
+    ms_per_step, value = b.timed_steps(c[4], steps, max(1, steps // 10))
+    out = {"workload": w.name, "metric": "Gcells/s", "value": value, "unit": "Gcells/s", "ms_per_step": ms_per_step,
+           "steps": steps, "dtype": w.dtype,
+           "config": {"rows": w.rows, "cols": w.cols, "iters": w.iters, "mapping": mapping_name(as_mapping(c)),
+                      "wg": list(c[4]), "xcd_remap": flags(c)[0], "nt_store": nt,
+                      "applications_per_launch": max(1, c[3]), "configurations_swept": len(configs)}}
+    if c1 is not None:
+        nt1 = configure(c1)
+        out["roofline"] = b.kernel_roofline(as_mapping(c1), c1[4], nt=nt1, remap=0 if flags(c1)[0] == 0 else 1)
+        out["roofline"]["xcd_remap"] = flags(c1)[0]
+    if c[3]:
+        nt = configure(c)
+        out["roofline_timed_kernel"] = b.kernel_roofline(as_mapping(c), c[4], nt=nt)
+    if "roofline" in out:
+        out["roofline"]["copy_kernel_gbs"] = b.copy_reference()
+        if name.startswith("H"):
+            at = configs.index(("direct", 2, 4, 0, (4, 16), 1, 0))          # the 4096^2 matrix's best
+            if status[at] == ls.OK:
+                gbs = b.alg_bytes / (mean[at] / b.burst) / 1e6
+                out["with_the_4096_best"] = {"algorithmic_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    b.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, min(3.0, args.cpu_seconds))
     return out
 
 
 def leave_one_out_prediction(ls, wl, torch, index, mapping_of, reps):
     """Section 7's leave-one-out evaluation in miniature: sweep the other four workloads, train
     the classifier on their (f(s), Omega(s)) pairs, predict for workload `index` with the
-    NearestNeighbour fallback of Algorithm 1.  Returns (predicted size, training table)."""
+    NearestNeighbour fallback of Algorithm 1.  Returns (predictor, training table)."""
     pred = ls.Predictor()
     table = []
     for i in range(5):
@@ -222,72 +476,11 @@ def leave_one_out_prediction(ls, wl, torch, index, mapping_of, reps):
         res = st.sweep(a, b, o.wg_sizes(), iters=burst, fixed=(0, 0), reps=reps)
         if res.best:
             pred.add(st.features(), res.best)
-            per_app_ms = res.best_ms / burst
             table.append({"workload": o.name.split()[0], "oracle_wg": list(res.best),
-                          "mapping": mapping_name(mapping_of(o)), "ms_per_application": per_app_ms,
-                          "gcells_s": o.cells / per_app_ms / 1e6,
-                          "algorithmic_gbs": o.cells * o.bytes_per_cell_update / per_app_ms / 1e6,
-                          "frac_of_hbm_peak": o.cells * o.bytes_per_cell_update / per_app_ms / 1e6 / HBM_PEAK_GBS})
+                          "mapping": mapping_name(mapping_of(o)), "ms_per_application": res.best_ms / burst})
         st.close()
         del a, b
     return pred, table
-
-
-def recorded_traffic(kernel_label):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, or None when there is
-    none for this kernel or the kernel sources have changed since the counters were taken."""
-    from paper_1511_02490_amd import rocprof_summary as rs
-    import re
-    try:
-        with open(rs.TRAFFIC_JSON) as fh:
-            table = json.load(fh)
-    except (OSError, ValueError):
-        return None
-    rec = table.get(kernel_label)
-    if rec is None and kernel_label.startswith(("stream_kernel", "march_kernel")):
-        # in the streaming kernels a wavefront's accesses do not depend on how wavefronts are grouped
-        # into workgroups: a record taken with another workgroup size of the same mapping serves
-        strip = lambda k: re.sub(r", wg \d+x\d+", "", k)
-        rec = next((v for k, v in sorted(table.items()) if strip(k) == strip(kernel_label)), None)
-    if not rec or rec.get("source_hash") != rs.kernel_source_hash():
-        return None
-    return rec["traffic_bytes_per_launch"]
-
-
-def cpu_baseline(wl_mod, w, target_seconds):
-    """The oracle, as it stands, on the first rows of the workload's matrix for a bounded
-    number of iterations (the sample is sized from a short calibration run)."""
-    from oracle import stencil as oracle
-    threads = oracle.max_threads()
-    g = w.grid()
-    rows = w.rows
-    run = lambda it: oracle.apply(g, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, it)
-    oracle.apply(g[:64], w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1)   # load library, spawn threads
-    iters, dt = 1, 0.0
-    while True:
-        t0 = time.perf_counter()
-        run(iters)
-        dt = time.perf_counter() - t0
-        if dt >= target_seconds / 3 or iters >= w.iters:
-            break
-        iters = int(min(w.iters, max(2 * iters, iters * 0.8 * target_seconds / max(dt, 1e-3))))
-    # the same oracle on one thread, on a sample a tenth the size (context for the threaded figure)
-    it1 = max(1, iters // 10)
-    rows1 = rows if iters >= 10 else max(64, rows // 10)
-    g1 = g[:rows1]
-    t0 = time.perf_counter()
-    oracle.apply(g1, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, it1, threads=1)
-    dt1 = time.perf_counter() - t0
-    oracle.apply(g[:8], w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1, threads=threads)   # thread count back
-    return {
-        "value": rows * w.cols * iters / dt / 1e9,
-        "unit": "Gcells/s",
-        "cores": threads,
-        "kind": "oracle",
-        "sample": "whole %d x %d matrix, %d of %d iterations, %.1f s" % (w.rows, w.cols, iters, w.iters, dt),
-        "single_thread": {"value": rows1 * w.cols * it1 / dt1 / 1e9, "unit": "Gcells/s", "cores": 1,
-                          "sample": "first %d rows, %d iterations, %.1f s" % (rows1, it1, dt1)},
-    }
 
 
 def main():
@@ -305,46 +498,39 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
 
-    index = int(args.workload[1]) - 1
-    w = wl.config(index)
+    w = named_workload(wl, args.workload)
+    index = int(args.workload[1]) - 1 if args.workload.startswith("C") else -1
     sizes = w.wg_sizes()
     if args.quick:
         sizes = sizes[::5]
-    g = w.grid()
-    tin = torch.from_numpy(g).cuda()
-    tout = torch.empty_like(tin)
-    cells = w.rows * w.cols
-
-    burst = sweep_burst(w)
+    b = Bench(ls, torch, w, args)
+    st, tin, tout, burst, cells = b.st, b.tin, b.tout, b.burst, b.cells
     cells_per_sample = cells * burst
 
-    steps = args.steps if args.steps > 0 else {0: 200, 1: 200, 2: 20, 3: 5, 4: 100}[index]
+    steps = args.steps if args.steps > 0 else {"C1": 200, "C2": 200, "C3": 20, "C4": 5, "C5": 100, "H8192": 100,
+                                               "H16384": 30, "W8192": 100}[args.workload]
     warmup = args.warmup if args.warmup >= 0 else max(1, steps // 10)
 
-    def copy_reference(n=20):
-        """GB/s of the plain copy kernel on this matrix (read + write), timed like a sweep sample."""
-        mean_ms, _ = ls.time_copy(tin, tout, burst=max(burst, 2), reps=n)
-        return 2.0 * tin.numel() * tin.element_size() / (mean_ms * 1e-3) / 1e9
-
     if args.copy_only:
-        gbs = copy_reference(max(steps, 20))
+        gbs = b.copy_reference(max(steps, 20))
         print(json.dumps({"metric": "plain copy kernel GB/s (read+write)", "value": gbs, "unit": "GB/s",
                           "config": {"workload": w.name, "bytes_each_way": tin.numel() * tin.element_size()}}))
         return
 
-    st = ls.Stencil.from_workload(w)
-    sweeps, sweep_seconds, predictor, others = {}, 0.0, {}, {}
+    sweeps, sweep_seconds, predictor, best_vs_fixed = {}, 0.0, {}, None
     if args.wg:
         wg = tuple(int(x) for x in args.wg.split(","))
         m = args.mapping.split(",") if args.mapping else ["local", "1", "1"]
         blocking = (m[0],) + tuple(int(x) for x in m[1:])
         apply_mapping(st, blocking)
-        best = (float("nan"), blocking, wg)
-        best1 = best
+        if args.xcd_remap is not None:
+            st.set_option(ls.OPT_XCD_REMAP, int(args.xcd_remap))
+        best1 = (float("nan"), blocking, wg) if len(blocking) == 3 else None
     else:
         t_sweep0 = time.perf_counter()
         best = None    # (ms per sample, mapping, wg) over every mapping
         best1 = None   # the same over the mappings that make one application per launch
+        best_wg_tuned = None   # ... and over those in which the workgroup size is the tunable (local, direct)
         for mapping in MAPPINGS[w.kernel]:
             try:
                 apply_mapping(st, mapping)
@@ -358,31 +544,41 @@ def main():
                 best = (res.best_ms, mapping, res.best)
             if res.best and len(mapping) == 3 and (best1 is None or res.best_ms < best1[0]):
                 best1 = (res.best_ms, mapping, res.best)
+            if res.best and mapping[0] in ("local", "direct") and (best_wg_tuned is None or res.best_ms < best_wg_tuned[0]):
+                best_wg_tuned = (res.best_ms, mapping, res.best)
         sweep_seconds = time.perf_counter() - t_sweep0
         assert best is not None, "no legal workgroup size"
         _, blocking, wg = best
         apply_mapping(st, blocking)
+        # The paper's question - what the best workgroup size is worth over a fixed one - put to the
+        # mappings in which the workgroup size decides the decomposition (in the register-streaming
+        # mappings it only groups wavefronts and most sizes are refused): the paper's own mapping
+        # first, then the fastest of them.
+        if best_wg_tuned is not None:
+            pick = lambda name: {k: sweeps[name][k] for k in (
+                "sizes", "refused", "best_wg", "best_gcells_s", "best_over_worst", "speedup_over_4x4", "gcells_s_4x4",
+                "speedup_over_32x4", "speedup_over_4x32")}
+            best_vs_fixed = {"paper_mapping": dict(mapping="local 1x1", **pick("local 1x1")) if "local 1x1" in sweeps else None,
+                             "fastest_tile_or_direct_mapping": dict(mapping=mapping_name(best_wg_tuned[1]),
+                                                                    **pick(mapping_name(best_wg_tuned[1])))}
 
         # Algorithm 1 on this scenario, for the best mapping's family and for the paper's
         # mapping: train on the other four workloads' sweeps, predict, repair an illegal
         # prediction (NearestNeighbour), and score it on this workload's own sweep table.
-        if not args.no_predictor:
+        if not args.no_predictor and index >= 0:
             for tag, mapping_of in (("fast", lambda o: FAST_MAPPING[o.kernel]), ("paper", lambda o: ("local", 1, 1))):
                 pred, table = leave_one_out_prediction(ls, wl, torch, index, mapping_of, max(5, args.reps // 3))
                 mine = mapping_of(w)
                 apply_mapping(st, mine)
-                res = st.sweep(tin, tout, sizes, iters=burst, fixed=(4, 4), reps=args.reps)
+                res = st.sweep(tin, tout, sizes, iters=burst, fixed=(4, 4), reps=max(5, args.reps // 3))
                 p = st.predict(pred, sizes)
                 t_p = res.ms_of(p)
                 if math.isnan(t_p) and st.is_legal(*p):
                     t_p = st.sweep(tin, tout, [p], iters=burst, fixed=(0, 0), reps=args.reps).mean_ms[0]
                 t4 = res.ms_of((4, 4))
-                if tag == "fast":
-                    others = {t["workload"]: {k: v for k, v in t.items() if k != "workload"} for t in table}
                 pretrained = None
                 if mine == ("local", 1, 1):
-                    # the classifier shipped with the library (trained offline on the 128-scenario study,
-                    # which contains this kernel on other matrix sizes and, for C4, on this one)
+                    # the classifier shipped with the library (trained offline on the 128-scenario study)
                     shipped = ls.pretrained_predictor("local,1,1")
                     q = st.predict(shipped, sizes)
                     shipped.close()
@@ -390,112 +586,13 @@ def main():
                     pretrained = {"predicted_wg": list(q),
                                   "performance": (res.best_ms / t_q) if not math.isnan(t_q) else None}
                 predictor[tag] = {"mapping": mapping_name(mine), "pretrained": pretrained,
-                                  "trained_on": [{"workload": t["workload"], "oracle_wg": t["oracle_wg"]} for t in table],
-                                  "predicted_wg": list(p),
+                                  "trained_on": table, "predicted_wg": list(p),
                                   "oracle_wg": list(res.best), "performance": res.best_ms / t_p,
                                   "speedup_over_4x4": (t4 / t_p) if not math.isnan(t4) else None}
             apply_mapping(st, blocking)
-            # the other workloads with the fastest kernels known for them (any mapping)
-            for i in range(5):
-                if i != index:
-                    o = wl.config(i)
-                    others.setdefault(o.name.split()[0], {})["best_known"] = best_known_configuration(
-                        ls, torch, o, max(5, args.reps // 3))
 
-    def choose_stores(mapping, size):
-        """Plain or non-temporal output stores for this configuration, whichever the sweep's clock
-        prefers (forced by --nt-store); leaves the handle on that choice."""
-        if args.nt_store is not None:
-            nt = int(args.nt_store)
-        elif args.wg or mapping[2] == 1:      # one cell per work-item: no 16-byte stores to switch
-            nt = 0
-        else:
-            depth = mapping[3] if len(mapping) > 3 else 0
-            pair = [(mapping[0], mapping[1], mapping[2], depth, size, -1, flag) for flag in (0, 1)]
-            mean, status, pick = st.sweep_configs(tin, tout, pair, iters=burst, reps=args.reps)
-            # plain stores unless the others win by more than the run-to-run noise
-            nt = 1 if (status[0] == ls.OK and status[1] == ls.OK and mean[1] < 0.98 * mean[0]) else 0
-        apply_mapping(st, mapping)
-        st.set_option(ls.OPT_NT_STORE, nt)
-        return nt
-
-    def choose_stores_for_steps():
-        """The same choice for the timed steps, made on whole steps (all iterations of the workload):
-        a short burst does not show what the stores do to a long chain of dependent launches."""
-        if args.nt_store is not None or args.wg or blocking[2] == 1:
-            return choose_stores(blocking, wg)
-        apply_mapping(st, blocking)
-        took = []
-        per_trial = 1
-        for flag in (0, 1):
-            st.set_option(ls.OPT_NT_STORE, flag)
-            t_a = time.perf_counter()
-            st.run(tin, tout, w.iters, wg)
-            torch.cuda.synchronize()
-            if flag == 0:     # a trial lasts a few milliseconds, so that the host's part does not decide
-                per_trial = max(1, min(500, int(0.004 / max(time.perf_counter() - t_a, 1e-6))))
-            trials = []
-            for _ in range(3):
-                t_a = time.perf_counter()
-                for _ in range(per_trial):
-                    st.run(tin, tout, w.iters, wg)
-                torch.cuda.synchronize()
-                trials.append(time.perf_counter() - t_a)
-            took.append(min(trials))
-        nt = 1 if took[1] < 0.98 * took[0] else 0
-        st.set_option(ls.OPT_NT_STORE, nt)
-        return nt
-
-    nt_store = choose_stores_for_steps()
-    for _ in range(warmup):
-        st.run(tin, tout, w.iters, wg)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        st.run(tin, tout, w.iters, wg)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / steps * 1e3
-    value = cells * w.iters * steps / dt / 1e9
-
-    # kernel launch duration by HIP events on the launch stream (the sweep's own clock).  A
-    # launch moves the matrix once (read + write) whatever the number of applications it fuses.
-    alg_bytes = cells * w.bytes_per_cell_update
-
-    def kernel_roofline(mapping, size):
-        nt = choose_stores(mapping, size)
-        depth = mapping[3] if len(mapping) > 3 else 1
-        k_res = st.sweep(tin, tout, [size], iters=burst, fixed=(0, 0), reps=max(args.reps, 30))
-        launches = -(-burst // depth)
-        kernel_ms = k_res.mean_ms[0] / launches
-        achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
-        family = {"local": "tile", "direct": "direct", "temporal": "temporal", "stream": "stream"}[mapping[0]]
-        if mapping[0] == "stream" and len(mapping) == 3:
-            family = "march"            # register streaming, one application per launch
-        label = "%s_kernel<%s> %dx%d cells/work-item, wg %dx%d" % (
-            family, w.kernel, mapping[1], mapping[2], size[0], size[1]) + (
-            ", %d applications/launch" % depth if depth > 1 else "") + (", non-temporal stores" if nt else "")
-        out = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-               "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(label),
-               "kernel": label, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg_bytes,
-               "applications_per_launch": depth, "nt_store": nt,
-               "gcells_s": cells * depth / (kernel_ms * 1e-3) / 1e9}
-        # kernels that vector arithmetic bounds rather than memory (the sin/cos stencil; fused
-        # applications): algorithmic fp32 operations against the published vector peak
-        flops = flops_per_cell_update(w)
-        if flops and (w.kernel == "sincos" or depth > 1):
-            tflops = flops * cells * depth / (kernel_ms * 1e-3) / 1e12
-            alu = {"bound": "alu", "achieved": tflops, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-                   "frac": tflops / FP32_VECTOR_PEAK_TFLOPS, "flops_per_cell_update": flops}
-            if w.kernel == "sincos":
-                # measured to be bound by vector-ALU issue in every mapping: the arithmetic view leads,
-                # the memory view stays beside it
-                hbm = {k: out[k] for k in ("bound", "achieved", "peak", "unit", "frac")}
-                out.update(alu)
-                out["hbm"] = hbm
-            else:
-                out["alu"] = alu
-        return out
+    nt_store = b.choose_stores_for_steps(blocking, wg)
+    ms_per_step, value = b.timed_steps(wg, steps, warmup)
 
     # `roofline` prices the best kernel that makes ONE application per launch: that is the
     # kernel whose bytes are all compulsory.  A temporally blocked kernel moves the matrix once
@@ -503,17 +600,20 @@ def main():
     # beside it as `roofline_timed_kernel` when it is the one the timed steps used.
     roofline_timed = None
     if len(blocking) > 3 and best1 is not None:
-        roofline = kernel_roofline(best1[1], best1[2])
-        roofline_timed = kernel_roofline(blocking, wg)
+        roofline = b.kernel_roofline(best1[1], best1[2])
+        roofline_timed = b.kernel_roofline(blocking, wg)
         roofline["note"] = ("single-application kernel; the timed steps used the temporally blocked kernel "
                             "in roofline_timed_kernel")
     else:
-        roofline = kernel_roofline(blocking, wg)
-    roofline["copy_kernel_gbs"] = copy_reference()
-    apply_mapping(st, blocking)
-    st.set_option(ls.OPT_NT_STORE, nt_store)
+        roofline = b.kernel_roofline(blocking, wg, nt=nt_store, remap=0 if args.xcd_remap == "0" else 1)
+    roofline["copy_kernel_gbs"] = b.copy_reference()
+    b.close()
 
-    larger = larger_matrices(ls, wl, torch, max(5, args.reps // 3)) if (index == 3 and not args.wg and not args.quick) else {}
+    others = {}
+    if not (args.wg or args.quick or args.no_others):
+        for name in ("C4", "H8192", "H16384", "C3", "C2", "C1", "C5", "W8192"):
+            if name != args.workload:
+                others[name] = sub_record(ls, torch, wl, name, args)
 
     out = {
         "metric": "Gcells/s at best swept workgroup size (achieved HBM GB/s in roofline)",
@@ -527,14 +627,13 @@ def main():
                    "nt_store": nt_store, "sweep_burst": burst, "sweep_reps": args.reps},
         "roofline": roofline,
         "roofline_timed_kernel": roofline_timed,
+        "best_vs_fixed": best_vs_fixed,
         "sweep": {"seconds": sweep_seconds, "by_blocking": sweeps},
         "predictor": predictor,
         "other_workloads": others,
-        "larger_matrices": larger,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, w, args.cpu_seconds)
-    st.close()
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
     print(json.dumps(out))
 
 
