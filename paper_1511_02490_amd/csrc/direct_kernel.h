@@ -108,7 +108,7 @@ __global__ __launch_bounds__(MAXT) void direct_kernel(const TileArgs<Op, Halo> a
 #pragma unroll
             for (int cc = 0; cc < CC; ++cc)
                 fold_row<Op>(
-                    st[cr][cc], dr, W, E, [&](int dc) { return a.w[(dr + N) * WCOLS + dc + W]; },
+                    st[cr][cc], dr, dr + N, N + S + 1, W, E, [&](int dc) { return a.w[(dr + N) * WCOLS + dc + W]; },
                     [&](int dc) { return row[W + cc + dc]; });
         }
     }

@@ -135,7 +135,12 @@ __device__ __forceinline__ void life_stream_body(const TileArgs<OpLife, HaloC<1,
             for (int w = 0; w < WORDS; ++w) lv[k][s][w] = 0;
     uint32_t pf[PF][WORDS];   // rows on their way from memory, PF time steps ahead
 #pragma unroll
-    for (int s = 0; s < PF; ++s) load_row(s, pf[s]);
+    for (int s = 0; s < PF; ++s) {
+        load_row(s, pf[s]);
+        // in the order the march consumes them: were the scheduler to issue the first-needed row
+        // last, every round of the loop would begin by waiting for all loads in flight
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     for (int round = 0; round < kRounds; ++round) {
 #pragma unroll

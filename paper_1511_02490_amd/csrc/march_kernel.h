@@ -115,9 +115,15 @@ __device__ __forceinline__ void march_body(const TileArgs<Op, Halo> &a, const in
     // rows on their way from memory, R time steps ahead; output rows being accumulated
     T pf[R][CC];
     typename Op::State st[R][CC];
+    [[maybe_unused]] float ring[3][R][CC] = {};   // operators with a tree of row sums: see below
 #pragma unroll
     for (int u = 0; u < R; ++u) {
         load_row(u, pf[u]);
+        // Keep these loads in the order the march consumes them.  Left to itself the scheduler may
+        // issue them last-needed first; the march's first step would then have to wait for every
+        // load in flight, and since waits are counted in issue order that wait (for all loads rather
+        // than for the oldest) would stand at the head of every round of the loop.
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int cc = 0; cc < CC; ++cc) Op::init(st[u][cc]);
     }
@@ -151,6 +157,20 @@ __device__ __forceinline__ void march_body(const TileArgs<Op, Halo> &a, const in
                     for (int p = 0; p < NP; ++p) parts[p] = row[p][i];
                     return Op::combine(parts);
                 };
+                // Operators that fold a row at a time and sum one of its parts as a tree of row sums
+                // (the cosines): the row sum h(t) of every cell, the pair h(t-1) + h(t) and the four
+                // pair(t-2) + pair(t) are formed once per input row and serve all the output rows
+                // whose trees contain them; ring[level][t mod R].
+                if constexpr (Op::kRowFold) {
+#pragma unroll
+                    for (int cc = 0; cc < CC; ++cc) {
+                        const float h = Op::row_cos(W, E, [&](int dc) { return value_at(W + cc + dc); });
+                        const float pair = __fadd_rn(ring[0][(u + R - 1) % R][cc], h);
+                        ring[0][u][cc] = h;
+                        ring[2][u][cc] = __fadd_rn(ring[1][(u + R - 2) % R][cc], pair);
+                        ring[1][u][cc] = pair;
+                    }
+                }
                 // this input row is region row dr of output row j = t - N - dr
 #pragma unroll
                 for (int dr = -N; dr <= S; ++dr) {
@@ -164,9 +184,19 @@ __device__ __forceinline__ void march_body(const TileArgs<Op, Halo> &a, const in
 #pragma unroll
                     for (int cc = 0; cc < CC; ++cc) {
                         if (dr == -N) Op::init(st[slot][cc]);
-                        fold_row<Op>(
-                            st[slot][cc], dr, W, E, [&](int dc) { return a.w[(dr + N) * WCOLS + dc + W]; },
-                            [&](int dc) { return value_at(W + cc + dc); });
+                        if constexpr (Op::kRowFold) {
+                            Op::fold_sines(
+                                st[slot][cc], W, E, [&](int dc) { return a.w[(dr + N) * WCOLS + dc + W]; },
+                                [&](int dc) { return value_at(W + cc + dc); });
+                            if (dr == S)
+                                Op::set_cos(st[slot][cc], Op::template window_cos<R>([&](int level, int back) {
+                                                return ring[level][(u + R - back) % R][cc];
+                                            }));
+                        } else {
+                            fold_row<Op>(
+                                st[slot][cc], dr, dr + N, R, W, E, [&](int dc) { return a.w[(dr + N) * WCOLS + dc + W]; },
+                                [&](int dc) { return value_at(W + cc + dc); });
+                        }
                     }
                     if (dr == S) {
                         const int gr = r0 + t - N - S;      // the output row that is complete now

@@ -291,9 +291,14 @@ struct OpNms {
 
 // ---- compute-intensive synthetic stencil: sum of w * sin(x) + cos(x) over the region ------
 // sin and cos are evaluated once per staged cell (fp32) and kept side by side in local
-// memory (one plane each).  The fold keeps one fma chain for the sines; the cosines of one region row are
-// summed pairwise from the west end ((c0 + c1) + (c2 + c3) + ...), so that neighbouring
-// cells of one work-item share their pair sums, and the row sums are added north to south.
+// memory (one plane each).  The fold keeps one fma chain for the sines.  The cosines are summed
+// as a fixed tree, the same for every cell whatever kernel computes it, whose inner nodes
+// neighbouring cells have in common: the cosines of one region row pairwise from the west end
+// ((c0 + c1) + (c2 + c3) + ...), so that the cells of a work-item share pair sums; the row sums
+// h(0), h(1), ... (north to south) in chunks of four rows, ((h0 + h1) + (h2 + h3)), then a pair
+// (h + h') and a single row for what is left, the chunks added north to south.  Pairs and
+// fours of rows that start an even number of rows apart are the same for output rows below
+// each other, so a kernel that marches down the matrix forms each of them once.
 
 // sin and cos of x in fp32 for |x| <= 2^16, absolute error below 2e-7: x / (2 pi) is formed
 // as a two-term product (1 / (2 pi) split into an fp32 head and tail, fma for the exact
@@ -324,7 +329,8 @@ struct OpSinCos {
     static constexpr int kPlanes = 2;   // a plane of sines and a plane of cosines
     static constexpr bool kWeights = true;
     static constexpr bool kRowFold = true;
-    struct State { float s, c; };
+    // s: the sines' fma chain; c: the chunks of cosine row sums added so far; p, q: the chunk being formed
+    struct State { float s, c, p, q; };
     // which routine serves an element depends on that element alone, so every mapping computes
     // the same bits for it
     __device__ static __forceinline__ void stage(T v, L (&out)[2]) {
@@ -365,11 +371,19 @@ struct OpSinCos {
         }
     }
     __device__ static __forceinline__ V combine(const L (&p)[2]) { return make_float2(p[0], p[1]); }
-    __device__ static __forceinline__ void init(State &s) { s.s = 0.0f; s.c = 0.0f; }
-    // one row of the region: w(dc) and v(dc) give weight and staged value at column offset dc
+    // The chain starts from -0, the one value that x + (-0) = x holds for with every x, signed
+    // zeros included: its first fma is then a plain product and needs no register cleared.
+    __device__ static __forceinline__ void init(State &s) { s.s = -0.0f; s.c = s.p = s.q = 0.0f; }
+
+    // The sines of one region row into the fma chain: w(dc) and v(dc) give weight and staged
+    // value at column offset dc.
     template <class WAcc, class VAcc>
-    __device__ static __forceinline__ void visit_row(State &s, int, int W, int E, WAcc w, VAcc v) {
+    __device__ static __forceinline__ void fold_sines(State &s, int W, int E, WAcc w, VAcc v) {
         for (int dc = -W; dc <= E; ++dc) s.s = __fmaf_rn(w(dc), v(dc).x, s.s);
+    }
+    // h: the cosines of one region row, summed pairwise from the west end.
+    template <class VAcc>
+    __device__ static __forceinline__ float row_cos(int W, int E, VAcc v) {
         int dc = -W;
         float h;
         if (dc + 1 <= E) {
@@ -381,33 +395,84 @@ struct OpSinCos {
         }
         for (; dc + 1 <= E; dc += 2) h = __fadd_rn(h, __fadd_rn(v(dc).y, v(dc + 1).y));
         if (dc <= E) h = __fadd_rn(h, v(dc).y);
-        s.c = __fadd_rn(s.c, h);
+        return h;
     }
-    // The same row fold, one value at a time (k = 0, 1, ... counts the row's cells from its west
+    // Row sum h of region row k (0 = northernmost) of R into the tree: chunks of four rows
+    // ((h + h) + (h + h)), then a pair and a single row for what is left; chunks added north to south.
+    __device__ static __forceinline__ void push_cos(State &s, int k, int R, float h) {
+        const int m = k & 3;
+        if (m == 0) {
+            s.p = h;
+        } else if (m == 1) {
+            s.p = __fadd_rn(s.p, h);
+        } else if (m == 2) {
+            s.q = h;
+        } else {
+            s.q = __fadd_rn(s.q, h);
+            s.p = __fadd_rn(s.p, s.q);
+            s.c = k == 3 ? s.p : __fadd_rn(s.c, s.p);
+        }
+        if (k == R - 1 && (R & 3) != 0) {
+            // one, two or three rows after the last whole chunk: p holds the row or the pair, q a third row
+            s.c = R < 4 ? s.p : __fadd_rn(s.c, s.p);
+            if ((R & 3) == 3) s.c = __fadd_rn(s.c, s.q);
+        }
+    }
+    // The same tree for a kernel that keeps, for every input row t it has seen, h(t), the pair
+    // h(t-1) + h(t) and the four (pair(t-2) + pair(t)): the sum over the R rows that end at the
+    // current one.  get(level, back) = level 0 / 1 / 2: row sum / pair / four ending `back` rows
+    // before the current row.
+    template <int R, class Get>
+    __device__ static __forceinline__ float window_cos(Get get) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int i = 0; i < R / 4; ++i) {                   // rows 4i .. 4i + 3
+            const float chunk = get(2, R - 4 - 4 * i);
+            acc = i == 0 ? chunk : __fadd_rn(acc, chunk);
+        }
+        if constexpr ((R & 2) != 0) {                       // the pair after the last four
+            const float chunk = get(1, R & 1);
+            acc = R < 4 ? chunk : __fadd_rn(acc, chunk);
+        }
+        if constexpr ((R & 1) != 0) {                       // the last row
+            const float chunk = get(0, 0);
+            acc = R == 1 ? chunk : __fadd_rn(acc, chunk);
+        }
+        return acc;
+    }
+    __device__ static __forceinline__ void set_cos(State &s, float c) { s.c = c; }
+
+    // one row of the region, k-th of R from the north
+    template <class WAcc, class VAcc>
+    __device__ static __forceinline__ void visit_row(State &s, int k, int R, int W, int E, WAcc w, VAcc v) {
+        fold_sines(s, W, E, w, v);
+        push_cos(s, k, R, row_cos(W, E, v));
+    }
+    // The same row fold, one value at a time (j = 0, 1, ... counts the row's cells from its west
     // end): the operations, and so the bits, of visit_row.
     struct RowState { float pending, h; };
-    __device__ static __forceinline__ void row_visit(State &s, RowState &rs, int k, float w, V v) {
+    __device__ static __forceinline__ void row_visit(State &s, RowState &rs, int j, float w, V v) {
         s.s = __fmaf_rn(w, v.x, s.s);
-        if (k & 1) {
+        if (j & 1) {
             const float pair = __fadd_rn(rs.pending, v.y);
-            rs.h = k == 1 ? pair : __fadd_rn(rs.h, pair);
+            rs.h = j == 1 ? pair : __fadd_rn(rs.h, pair);
         } else {
             rs.pending = v.y;
         }
     }
-    __device__ static __forceinline__ void row_end(State &s, const RowState &rs, int count) {
+    __device__ static __forceinline__ void row_end(State &s, const RowState &rs, int count, int k, int R) {
         float h = rs.h;
         if (count & 1) h = count == 1 ? rs.pending : __fadd_rn(rs.h, rs.pending);
-        s.c = __fadd_rn(s.c, h);
+        push_cos(s, k, R, h);
     }
     __device__ static __forceinline__ T finish(const State &s, float) { return __fadd_rn(s.s, s.c); }
 };
 
-// One row of the region folded into a cell's state.
+// One row of the region - row dr, the k-th of R from the north - folded into a cell's state.
 template <class Op, class WAcc, class VAcc>
-__device__ __forceinline__ void fold_row(typename Op::State &st, int dr, int W, int E, WAcc w, VAcc v) {
+__device__ __forceinline__ void fold_row(typename Op::State &st, int dr, int k, int R, int W, int E, WAcc w, VAcc v) {
     if constexpr (Op::kRowFold) {
-        Op::visit_row(st, dr, W, E, w, v);
+        Op::visit_row(st, k, R, W, E, w, v);
     } else {
         for (int dc = -W; dc <= E; ++dc) Op::visit(st, dr, dc, w(dc), v(dc));
     }

@@ -113,7 +113,12 @@ __device__ __forceinline__ void stream_body(const TileArgs<Op, HaloC<1, 1, 1, 1>
             for (int j = 0; j < CC; ++j) lv[k][s][j] = 0;
     T pf[PF][CC];         // rows on their way from memory, PF time steps ahead
 #pragma unroll
-    for (int s = 0; s < PF; ++s) load_row(s, pf[s]);
+    for (int s = 0; s < PF; ++s) {
+        load_row(s, pf[s]);
+        // in the order the march consumes them: were the scheduler to issue the first-needed row
+        // last, every round of the loop would begin by waiting for all loads in flight
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     for (int round = 0; round < kRounds; ++round) {
 #pragma unroll
@@ -144,7 +149,7 @@ __device__ __forceinline__ void stream_body(const TileArgs<Op, HaloC<1, 1, 1, 1>
 #pragma unroll
                     for (int cc = 0; cc < CC; ++cc)
                         fold_row<Op>(
-                            st[cc], dr, 1, 1, [&](int dc) { return a.w[(dr + 1) * 3 + dc + 1]; },
+                            st[cc], dr, dr + 1, 3, 1, 1, [&](int dc) { return a.w[(dr + 1) * 3 + dc + 1]; },
                             [&](int dc) { return row[1 + cc + dc]; });
                 }
                 T res[CC];

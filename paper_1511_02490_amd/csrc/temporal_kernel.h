@@ -55,7 +55,7 @@ __device__ __forceinline__ void temporal_quad(typename Op::T (&res)[4], const Qu
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc)
             fold_row<Op>(
-                st[cc], dr, 1, 1, [&](int dc) { return w[(dr + 1) * 3 + dc + 1]; },
+                st[cc], dr, dr + 1, 3, 1, 1, [&](int dc) { return w[(dr + 1) * 3 + dc + 1]; },
                 [&](int dc) { return row[1 + cc + dc]; });
     }
 #pragma unroll

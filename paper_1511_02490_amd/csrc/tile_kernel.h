@@ -274,7 +274,7 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
 #pragma unroll
                 for (int cc = 0; cc < CC; ++cc)
                     fold_row<Op>(
-                        st[cr][cc], dr, W, E, [&](int dc) { return a.w[(dr + N) * WCOLS + dc + W]; },
+                        st[cr][cc], dr, dr + N, N + S + 1, W, E, [&](int dc) { return a.w[(dr + N) * WCOLS + dc + W]; },
                         [&](int dc) { return value_at(HWA - LO + cc + dc); });
             }
         }
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
 #pragma unroll
                     for (int cr = 0; cr < CR; ++cr)
 #pragma unroll
-                        for (int cc = 0; cc < CC; ++cc) Op::row_end(st[cr][cc], rs[cr][cc], wcols);
+                        for (int cc = 0; cc < CC; ++cc) Op::row_end(st[cr][cc], rs[cr][cc], wcols, i, wrows);
                 }
             }
         } else {
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(MAXT) void tile_kernel(const TileArgs<Op, Halo> a) 
 #pragma unroll
                     for (int cr = 0; cr < CR; ++cr)
 #pragma unroll
-                        for (int cc = 0; cc < CC; ++cc) Op::row_end(st[cr][cc], rs[cr][cc], wcols);
+                        for (int cc = 0; cc < CC; ++cc) Op::row_end(st[cr][cc], rs[cr][cc], wcols, i, wrows);
                 }
             }
         }
