@@ -3,7 +3,7 @@
 // at the size the sweep found.  No Python, no PyTorch: device memory comes from the HIP runtime.
 //
 //   hipcc -O2 examples/heat_sweep.cpp -Iinclude -Lpaper_1511_02490_amd/_lib -lstencil \
-//         -Wl,-rpath,$PWD/paper_1511_02490_amd/_lib -o heat_sweep && ./heat_sweep
+//         -Wl,-rpath,$PWD/paper_1511_02490_amd/_lib -o heat_sweep && ./heat_sweep [training pairs]
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -28,7 +28,7 @@
         }                                                                               \
     } while (0)
 
-int main() {
+int main(int argc, char **argv) {
     const int rows = 1024, cols = 1024, steps = 1000;
     std::vector<float> host((size_t)rows * cols, 1.0f);
     for (int r = 400; r < 432; ++r)
@@ -47,6 +47,19 @@ int main() {
     const float alpha = 0.2f;
     STENCIL_OK_OR_DIE(stencil_set_kernel(st, STENCIL_HEAT, nullptr, 0, &alpha, 1));
     STENCIL_OK_OR_DIE(stencil_set_mapping(st, STENCIL_STAGING_DIRECT, 2, 4));
+
+    // Before anything is swept the library chooses by itself (wg 0x0): with training pairs recorded
+    // on this device (argv[1], e.g. paper_1511_02490_amd/tuning_data/mi355x_local_2_4.txt) it asks
+    // a decision tree over the scenario's features, otherwise it takes its built-in default.
+    stencil_predictor_t *pred = nullptr;
+    if (argc > 1) {
+        STENCIL_OK_OR_DIE(stencil_predictor_load(&pred, argv[1], STENCIL_CLASSIFIER_TREE));
+        STENCIL_OK_OR_DIE(stencil_attach_predictor(st, pred, STENCIL_FALLBACK_NEAREST));
+    }
+    int guess_r = 0, guess_c = 0;
+    STENCIL_OK_OR_DIE(stencil_default_wg(st, &guess_r, &guess_c));
+    STENCIL_OK_OR_DIE(stencil_run(st, in, out, 10, 0, 0, nullptr));
+    std::printf("%s size before any sweep: %dx%d\n", pred ? "predicted" : "default", guess_r, guess_c);
 
     // every power-of-two workgroup size up to the kernel's limit, 30 samples of 10 steps each
     const int w_max = stencil_max_wg_size(st);
@@ -78,6 +91,7 @@ int main() {
     // periodic borders conserve the total; diffusion has flattened the square
     std::printf("total %.1f -> %.1f, hottest cell 1000 -> %.2f after %d steps\n", before, after, peak, steps);
     stencil_destroy(st);
+    stencil_predictor_destroy(pred);
     HIP_OK(hipFree(in));
     HIP_OK(hipFree(out));
     return (std::fabs(after - before) <= 1e-4 * before && peak < 500.0f) ? 0 : 2;

@@ -101,7 +101,11 @@ enum stencil_enum_mode {
 };
 
 #define STENCIL_MAX_HALO 32            /* Table 2's border sizes go up to 30 */
-#define STENCIL_MAX_WG_SIZE 1024       /* device limit on work-items per workgroup */
+/* The device's limits as far as they are known without asking it (an MI355X's).  The first call
+ * that uses the GPU asks the device (work-items per workgroup, local memory, compute units) and,
+ * per compiled kernel, the runtime (Section 3.1: W_max(s) depends on device and kernel); from then
+ * on legality and f(s) use those answers. */
+#define STENCIL_MAX_WG_SIZE 1024       /* work-items per workgroup */
 #define STENCIL_LOCAL_MEM_BYTES 163840 /* local memory one workgroup may allocate (160 KiB) */
 
 /* ---- scenario ---------------------------------------------------------------------- */
@@ -191,11 +195,16 @@ int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int 
  * non-temporal stores (the output is not read again by the launch that writes it); narrower
  * stores (unaligned rows, one cell per work-item, the threshold stencil) stay plain.  Same
  * results, different cache behaviour: it pays on matrices beyond the caches and costs where
- * the next application would have found its input in a cache. */
+ * the next application would have found its input in a cache.
+ * STENCIL_OPT_FAIL_LAUNCH (default 0 = off) is a testing aid for the handling of refused parameters
+ * that only show when a launch fails (Section 3.1): with value (w_r << 16) | w_c every launch with
+ * that workgroup size - with -1 every launch - is not made and reports the runtime's
+ * out-of-resources error instead, which stencil_run returns as STENCIL_E_REFUSED and the sweeps
+ * record as a refused size. */
 #define STENCIL_MAX_TEMPORAL_DEPTH 4   /* STENCIL_STAGING_TEMPORAL */
 #define STENCIL_MAX_STREAM_DEPTH 8     /* STENCIL_STAGING_STREAM */
 enum stencil_option { STENCIL_OPT_XCD_REMAP = 0, STENCIL_OPT_TEMPORAL_DEPTH = 1, STENCIL_OPT_SWEEP_CUTOFF = 2,
-                      STENCIL_OPT_NT_STORE = 3 };
+                      STENCIL_OPT_NT_STORE = 3, STENCIL_OPT_FAIL_LAUNCH = 4 };
 int stencil_set_option(stencil_t *st, int option, int value);
 
 /* ---- legality (Section 3.1) ---------------------------------------------------------- */
@@ -208,7 +217,9 @@ int stencil_max_wg_size(const stencil_t *st);
 int64_t stencil_tile_bytes(const stencil_t *st, int wg_rows, int wg_cols);
 
 /* Eq. 1: 1 if (wg_rows, wg_cols) is legal for this scenario (w_r*w_c <= W_max(s) and not a
- * refused parameter, i.e. its tile fits local memory), else 0. */
+ * refused parameter, i.e. its tile fits local memory), else 0.  What can be decided before a
+ * launch; a size may still be refused by the launch itself (stencil_run then returns
+ * STENCIL_E_REFUSED with the runtime's text, the sweeps record the size as refused and go on). */
 int stencil_is_legal(const stencil_t *st, int wg_rows, int wg_cols);
 
 /* Section 5's enumeration.  Writes up to `cap` pairs to rows[]/cols[] (may be NULL when
@@ -232,8 +243,10 @@ int stencil_enumerate_wg(int mode, int max_threads, int *rows, int *cols, int ca
  * kind on the same handle) can be captured into a HIP graph; make that first run outside
  * the capture.
  * wg_rows = wg_cols = 0 lets the library choose (Section 2: selecting the size is the
- * implementation's responsibility): the best size of the handle's last sweep, else a
- * built-in default.  Illegal sizes return STENCIL_E_REFUSED without launching. */
+ * implementation's responsibility): the best size of the handle's last sweep; else the
+ * prediction of the classifier given to stencil_attach_predictor (Algorithm 1 over the
+ * power-of-two sizes); else a built-in default.  Illegal sizes return STENCIL_E_REFUSED without
+ * launching; so does a size that the runtime refuses at launch. */
 int stencil_run(stencil_t *st, const void *in, void *out, int iters,
                 int wg_rows, int wg_cols, void *stream);
 
@@ -322,12 +335,16 @@ int stencil_baseline_wg(const double *performance, int n_scenarios, int n_sizes,
 
 /* ---- prediction (Section 3.2, Section 4.1, Algorithm 1) ---------------------------------- */
 
-#define STENCIL_N_FEATURES 13
+#define STENCIL_N_FEATURES 16
 
 /* f(s): dataset, kernel and device features of the scenario, STENCIL_N_FEATURES doubles:
  * rows, cols, input element bytes, north, south, east, west, region cells, compute-intensive
  * flag, compute units, local memory bytes, max workgroup size, output element bytes
- * (Section 3.2: "the input and output data types"). */
+ * (Section 3.2: "the input and output data types"), operations per cell that the customising
+ * function states (arithmetic and comparisons; the paper counts compiled instructions, these are
+ * filled in by hand per kernel), those of them on the transcendental unit, border mode.  The
+ * three device features are the constants above until a GPU has been used, the device's own
+ * answers after. */
 int stencil_features(const stencil_t *st, double *features);
 
 /* A classifier over (f(s), Omega(s)) pairs (Section 4.1's D_training):
@@ -362,6 +379,23 @@ int stencil_predict_wg(const stencil_t *st, const stencil_predictor_t *p,
                        const int *cand_rows, const int *cand_cols, int n_cand,
                        int handler, int baseline_rows, int baseline_cols, uint64_t random,
                        int *wg_rows, int *wg_cols);
+
+/* The classifier stencil_run(st, ..., 0, 0, ...) consults when the handle has no sweep to go by:
+ * Algorithm 1 with `handler` over the power-of-two sizes (STENCIL_FALLBACK_BASELINE falls back to
+ * the built-in default size).  The predictor stays the caller's and must outlive its use;
+ * NULL detaches. */
+int stencil_attach_predictor(stencil_t *st, const stencil_predictor_t *p, int handler);
+
+/* The size stencil_run(st, ..., 0, 0, ...) would use now: the last sweep's best, else the attached
+ * classifier's prediction repaired by its handler, else the built-in default.  No GPU call. */
+int stencil_default_wg(const stencil_t *st, int *wg_rows, int *wg_cols);
+
+/* A classifier from a text file of training pairs (Section 4.1: collected offline, used at run
+ * time): '#' starts a comment line; the first other line reads "features <n>"; every further line
+ * holds n feature values, then w_r and w_c, separated by blanks.  The files under
+ * paper_1511_02490_amd/tuning_data/ (written by autotune_study --export-training) are of this form.
+ * STENCIL_E_INVALID if the file cannot be read or a line does not parse. */
+int stencil_predictor_load(stencil_predictor_t **out, const char *path, int classifier);
 
 /* ---- prediction with regressors (Sections 4.2 and 4.3, Algorithm 2) -------------------------- */
 

@@ -9,7 +9,7 @@ the sweep's oracle sizes with the metrics of Section 7.
 A large study can be split: `--json FILE --sweep-only` on the GPU records the sweeps, `--from-json
 FILE` (same --synthetic and --mapping) evaluates them anywhere - legality, features and the
 predictors make no GPU call.  `--export-training FILE` writes the (f(s), oracle size) pairs of the
-sweeps: the files under tuning_data/ that `libstencil.pretrained_predictor` loads were made so.
+sweeps as text: the files under tuning_data/ that `stencil_predictor_load` reads were made so.
 
 Everything measured goes through the C ABI (sweeps, legality, features, predictor, baseline);
 this script only builds the scenario list and the tables.  Prints a markdown report.
@@ -54,8 +54,12 @@ def main():
         if recorded["scenarios"] != [w.name for w in scen] or [tuple(x) for x in recorded["sizes"]] != sizes \
                 or recorded.get("mapping", a.mapping) != a.mapping:
             raise SystemExit("%s was recorded for another scenario list, size list or mapping" % a.from_json)
-        times, status, feats = recorded["times_ms"], recorded["status"], recorded["features"]
+        times, status = recorded["times_ms"], recorded["status"]
         a.reps = recorded.get("reps", a.reps)
+        for w in scen:            # f(s) needs no GPU: taken afresh, so that recorded sweeps outlive a change of features
+            st = ls.Stencil.from_workload(w)
+            feats.append(st.features())
+            st.close()
     else:
         import torch
     for w in ([] if recorded else scen):
@@ -91,11 +95,16 @@ def main():
         oracle.append(b)
         perf.append(p)
     if a.export_training:
+        # stencil_predictor_load's format: "features <n>", then n feature values and the oracle size per line
         with open(a.export_training, "w") as fh:
-            pairs = [json.dumps({"scenario": scen[i].name, "features": feats[i], "wg": list(sizes[oracle[i]])})
-                     for i in range(n_s) if oracle[i] >= 0]
-            fh.write('{"device": "MI355X", "mapping": "%s", "samples_per_size": %d, "pairs": [\n%s\n]}\n'
-                     % (a.mapping, a.reps, ",\n".join(pairs)))
+            fh.write("# (f(s), oracle workgroup size) pairs: device MI355X, mapping %s, %d samples per size, %d scenarios\n"
+                     % (a.mapping, a.reps, sum(1 for i in range(n_s) if oracle[i] >= 0)))
+            fh.write("# scenario i of the study's list is named in the comment above its line\n")
+            fh.write("features %d\n" % len(feats[0]))
+            for i in range(n_s):
+                if oracle[i] >= 0:
+                    fh.write("# %s\n" % scen[i].name)
+                    fh.write(" ".join("%.17g" % x for x in feats[i]) + " %d %d\n" % tuple(sizes[oracle[i]]))
         return
     base = ls.baseline_wg(perf)                      # best fixed size that is legal everywhere
     idx = {s: j for j, s in enumerate(sizes)}

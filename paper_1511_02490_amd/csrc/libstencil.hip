@@ -11,6 +11,7 @@
 #include <mutex>
 #include <new>
 #include <type_traits>
+#include <unordered_map>
 #include <vector>
 
 #include "host_tuning.h"
@@ -32,7 +33,40 @@ int fail_hip(hipError_t e, const char *what) {
     return fail(STENCIL_E_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// Section 3.1 takes W_max(s) from the device and the compiled kernel, Section 3.2 takes the
+// device's features from the OpenCL device API.  Here: hipGetDeviceProperties at the first call
+// that uses the GPU (of the device current then), hipFuncGetAttributes per kernel after that.
+// Before any GPU use - and on a machine without one - the header's constants stand in.
+struct DeviceLimits {
+    int compute_units = 256;
+    int64_t local_memory = STENCIL_LOCAL_MEM_BYTES;
+    int max_wg = STENCIL_MAX_WG_SIZE;
+    bool queried = false;
+};
+DeviceLimits g_limits;
+std::mutex g_limits_mutex;
+std::unordered_map<const void *, int> g_kernel_max_threads;
+
+void query_device_limits() {
+    std::lock_guard<std::mutex> lock(g_limits_mutex);
+    if (g_limits.queried) return;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return;                       // keep the constants; a launch will report what is wrong
+    }
+    if (prop.multiProcessorCount > 0) g_limits.compute_units = prop.multiProcessorCount;
+    if (prop.maxThreadsPerBlock > 0) g_limits.max_wg = prop.maxThreadsPerBlock;
+    // what one workgroup can be given once a kernel's dynamic limit is raised: all of a compute unit's
+    const int64_t lds = std::max<int64_t>((int64_t)prop.maxSharedMemoryPerMultiProcessor, (int64_t)prop.sharedMemPerBlock);
+    if (lds > 0) g_limits.local_memory = lds;
+    g_limits.queried = true;
+}
+
 }  // namespace
+
+int64_t stencil_local_memory_limit() { return g_limits.local_memory; }
 
 namespace {
 
@@ -138,13 +172,34 @@ bool mapping_supported(const stencil *s, int staging, int cr, int cc) {
     return false;
 }
 
+// W_max(s): the kernel's own limit (its launch bounds; once the GPU is in use, what the runtime
+// reports for the compiled kernel) within the device's.
+int kernel_max_threads(const stencil *s, const Variant *v) {
+    int lim = std::min(v->max_threads, g_limits.max_wg);
+    if (!g_limits.queried || !v->kernel_of) return lim;
+    const void *k = v->kernel_of(s);
+    if (!k) return lim;
+    std::lock_guard<std::mutex> lock(g_limits_mutex);
+    auto it = g_kernel_max_threads.find(k);
+    if (it == g_kernel_max_threads.end()) {
+        hipFuncAttributes attr;
+        int reported = lim;
+        if (hipFuncGetAttributes(&attr, k) == hipSuccess && attr.maxThreadsPerBlock > 0)
+            reported = attr.maxThreadsPerBlock;
+        else
+            (void)hipGetLastError();
+        it = g_kernel_max_threads.emplace(k, reported).first;
+    }
+    return std::min(lim, it->second);
+}
+
 int check_legal(const stencil *s, const Variant *v, int wr, int wc) {
     if (!v) return fail(STENCIL_E_INVALID, "no kernel variant for this scenario");
     if (wr < 1 || wc < 1)
         return fail(STENCIL_E_REFUSED, "workgroup size %dx%d: dimensions must be >= 1", wr, wc);
-    if ((int64_t)wr * wc > v->max_threads)
-        return fail(STENCIL_E_REFUSED, "workgroup size %dx%d exceeds W_max = %d work-items", wr, wc,
-                    v->max_threads);
+    const int w_max = kernel_max_threads(s, v);
+    if ((int64_t)wr * wc > w_max)
+        return fail(STENCIL_E_REFUSED, "workgroup size %dx%d exceeds W_max = %d work-items", wr, wc, w_max);
     if (v->staging == STENCIL_STAGING_TEMPORAL && s->temporal_depth > STENCIL_MAX_TEMPORAL_DEPTH)
         return fail(STENCIL_E_INVALID, "the local-memory temporal kernels fuse at most %d applications (depth is %d)",
                     STENCIL_MAX_TEMPORAL_DEPTH, s->temporal_depth);
@@ -152,13 +207,14 @@ int check_legal(const stencil *s, const Variant *v, int wr, int wc) {
         return fail(STENCIL_E_REFUSED, "workgroup size %dx%d refused: this mapping gives each wavefront a strip, the "
                                        "workgroup must be whole wavefronts of 64 work-items", wr, wc);
     const TileGeom g = tile_geom(s, *v, wr, wc);
-    if (g.lds_bytes > STENCIL_LOCAL_MEM_BYTES)
-        return fail(STENCIL_E_REFUSED, "workgroup size %dx%d refused: tile needs %lld bytes of local memory (limit %d)",
-                    wr, wc, (long long)g.lds_bytes, STENCIL_LOCAL_MEM_BYTES);
+    if (g.lds_bytes > g_limits.local_memory)
+        return fail(STENCIL_E_REFUSED, "workgroup size %dx%d refused: tile needs %lld bytes of local memory (limit %lld)",
+                    wr, wc, (long long)g.lds_bytes, (long long)g_limits.local_memory);
     return STENCIL_OK;
 }
 
 int ensure_device_state(stencil *s, const Variant *v, bool need_scratch, hipStream_t stream) {
+    query_device_limits();
     if (v->hn < 0 && !s->weights_uploaded) {
         // A replaced table goes into the other of two device tables, by launches ordered on this
         // run's stream: earlier launches (on any stream) keep reading the table they were given.
@@ -190,6 +246,23 @@ int launches_of(const stencil *s, const Variant *v, int iters) {
     return (iters + per - 1) / per;
 }
 
+// A launch the runtime turned down.  Section 3.1: some sizes within W_max are refused all the same
+// and "can only be discovered emergently", by the launch failing; the caller takes another size
+// (Section 4.2).  The errors that mean "not this configuration" - resources, configuration,
+// argument - become STENCIL_E_REFUSED with the runtime's text; anything else is a runtime error.
+int launch_failure(hipError_t e, int wr, int wc) {
+    switch (e) {
+    case hipErrorLaunchOutOfResources:
+    case hipErrorInvalidConfiguration:
+    case hipErrorInvalidValue:
+    case hipErrorOutOfMemory:
+    case hipErrorSharedObjectInitFailed:
+        return fail(STENCIL_E_REFUSED, "workgroup size %dx%d refused at launch: %s", wr, wc, hipGetErrorString(e));
+    default:
+        return fail_hip(e, "kernel launch");
+    }
+}
+
 // `iters` out-of-place applications ending in `out`, never writing `in`.
 int run_checked(stencil *s, const Variant *v, const void *in, void *out, void *pingpong, int iters, int wr, int wc,
                 hipStream_t stream) {
@@ -207,8 +280,9 @@ int run_checked(stencil *s, const Variant *v, const void *in, void *out, void *p
     void *dst = (launches % 2 == 1) ? out : pingpong;
     for (int done = 0; done < iters;) {
         const int now = std::min(per, iters - done);
-        hipError_t e = v->launch(s, src, dst, wr, wc, now, stream);
-        if (e != hipSuccess) return fail_hip(e, "kernel launch");
+        const bool injected = s->fail_rows == -1 || (s->fail_rows == wr && s->fail_cols == wc);
+        hipError_t e = injected ? hipErrorLaunchOutOfResources : v->launch(s, src, dst, wr, wc, now, stream);
+        if (e != hipSuccess) return launch_failure(e, wr, wc);
         done += now;
         src = dst;
         dst = (dst == out) ? pingpong : out;
@@ -224,6 +298,87 @@ int validate_buffers(const stencil *s, const void *in, const void *out) {
     return STENCIL_OK;
 }
 
+// f(s) (Section 3.2): dataset, kernel and device features.
+void scenario_features(const stencil *s, double *f) {
+    const double taps = (double)(s->hn + s->hs + 1) * (s->he + s->hw + 1);
+    f[0] = (double)s->rows;
+    f[1] = (double)s->cols;
+    f[2] = (double)s->elem();
+    f[3] = s->hn;
+    f[4] = s->hs;
+    f[5] = s->he;
+    f[6] = s->hw;
+    f[7] = taps;
+    f[8] = s->kernel == STENCIL_SINCOS ? 1.0 : 0.0;
+    f[9] = (double)g_limits.compute_units;
+    f[10] = (double)g_limits.local_memory;
+    f[11] = (double)g_limits.max_wg;
+    f[12] = (double)s->out_elem();
+    // The paper counts a kernel's instructions in its compiled form; here the operations each
+    // customising function states per cell, filled in by hand: arithmetic and comparisons ...
+    double ops = 0.0, special = 0.0;
+    switch (s->kernel) {
+    case STENCIL_WEIGHTED_SUM: ops = 2.0 * taps - 1.0; break;           // a product per tap, the sum
+    case STENCIL_LIFE: ops = 11.0; break;                               // 7 adds for 8 neighbours, two compares, and, or
+    case STENCIL_HEAT: ops = 7.0; break;                                // three adds, 4u, the difference, alpha t, the sum
+    case STENCIL_SINCOS: ops = 3.0 * taps + 1.0; special = 2.0; break;  // w sin + cos and the sums; one sine, one cosine
+    case STENCIL_SOBEL: ops = 17.0; special = 1.0; break;               // 8 differences / sums, 2 fma, 2 squares, a sum; a root
+    case STENCIL_NMS: ops = 8.0; break;                                 // four compares, two ands, an or, the selection
+    case STENCIL_THRESHOLD: ops = 1.0; break;
+    default: break;
+    }
+    f[13] = ops;
+    f[14] = special;                                                    // ... of which on the transcendental unit
+    f[15] = (double)s->border;
+}
+
+int classify_and_repair(const stencil *s, const Variant *v, const host_tuning::Classifier *c, const int *cand_rows,
+                        const int *cand_cols, int n_cand, int handler, int baseline_rows, int baseline_cols,
+                        uint64_t random, int *wg_rows, int *wg_cols) {
+    double f[STENCIL_N_FEATURES];
+    scenario_features(s, f);
+    int wr = 0, wc = 0;
+    if (!c->classify(f, STENCIL_N_FEATURES, &wr, &wc))
+        return fail(STENCIL_E_INVALID, "classifier has no training pairs, or feature count differs");
+    // Algorithm 1: a legal prediction is kept; otherwise the handler chooses
+    if (check_legal(s, v, wr, wc) != STENCIL_OK) {
+        if (handler == STENCIL_FALLBACK_BASELINE) {
+            if (check_legal(s, v, baseline_rows, baseline_cols) != STENCIL_OK)
+                return fail(STENCIL_E_REFUSED, "the baseline size %dx%d is not legal for this scenario", baseline_rows,
+                            baseline_cols);
+            wr = baseline_rows;
+            wc = baseline_cols;
+        } else {
+            std::vector<int> legal;
+            for (int k = 0; k < n_cand; ++k)
+                if (check_legal(s, v, cand_rows[k], cand_cols[k]) == STENCIL_OK) legal.push_back(k);
+            if (legal.empty()) return fail(STENCIL_E_REFUSED, "no legal candidate workgroup size");
+            int pick = legal[0];
+            if (handler == STENCIL_FALLBACK_RANDOM) {
+                pick = legal[(size_t)(random % legal.size())];
+            } else {
+                double d_min = std::numeric_limits<double>::infinity();
+                for (int k : legal) {
+                    const double dr = cand_rows[k] - wr, dc = cand_cols[k] - wc;
+                    const double d = std::sqrt(dr * dr + dc * dc);
+                    if (d < d_min) {
+                        d_min = d;
+                        pick = k;
+                    }
+                }
+            }
+            wr = cand_rows[pick];
+            wc = cand_cols[pick];
+        }
+    }
+    *wg_rows = wr;
+    *wg_cols = wc;
+    return STENCIL_OK;
+}
+
+// The size stencil_run(0, 0) takes (Section 2: choosing it is the implementation's job): the best
+// of the handle's last sweep; else what the attached classifier predicts for the scenario
+// (Algorithm 1 over the power-of-two sizes); else a wave64-shaped default.
 void default_wg(const stencil *s, const Variant *v, int *wr, int *wc) {
     if (s->best_rows > 0 && check_legal(s, v, s->best_rows, s->best_cols) == STENCIL_OK) {
         *wr = s->best_rows;
@@ -234,6 +389,22 @@ void default_wg(const stencil *s, const Variant *v, int *wr, int *wc) {
     int r = 4, c = 64;
     while (check_legal(s, v, r, c) != STENCIL_OK && (r > 1 || c > 1)) {
         if (r > 1) r /= 2; else c /= 2;
+    }
+    if (s->predictor) {
+        std::vector<int> vals, cr, cc;
+        host_tuning::size_values(STENCIL_ENUM_POW2, STENCIL_MAX_WG_SIZE, vals);
+        for (int a : vals)
+            for (int b : vals)
+                if ((int64_t)a * b <= STENCIL_MAX_WG_SIZE) {
+                    cr.push_back(a);
+                    cc.push_back(b);
+                }
+        int pr = 0, pc = 0;
+        if (classify_and_repair(s, v, reinterpret_cast<const host_tuning::Classifier *>(s->predictor), cr.data(), cc.data(),
+                                (int)cr.size(), s->predictor_handler, r, c, 0, &pr, &pc) == STENCIL_OK) {
+            r = pr;
+            c = pc;
+        }
     }
     *wr = r;
     *wc = c;
@@ -412,6 +583,18 @@ int stencil_set_option(stencil_t *s, int option, int value) {
         s->temporal_depth = value;
         s->best_rows = s->best_cols = 0;
         return STENCIL_OK;
+    case STENCIL_OPT_FAIL_LAUNCH:
+        if (value == 0) {
+            s->fail_rows = s->fail_cols = 0;
+        } else if (value == -1) {
+            s->fail_rows = s->fail_cols = -1;
+        } else {
+            if (value < 0 || (value >> 16) < 1 || (value & 0xffff) < 1)
+                return fail(STENCIL_E_INVALID, "STENCIL_OPT_FAIL_LAUNCH takes (w_r << 16) | w_c, -1 or 0");
+            s->fail_rows = value >> 16;
+            s->fail_cols = value & 0xffff;
+        }
+        return STENCIL_OK;
     default:
         return fail(STENCIL_E_INVALID, "unknown option %d", option);
     }
@@ -421,7 +604,7 @@ int stencil_max_wg_size(const stencil_t *s) {
     if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
     const Variant *v = find_variant(s);
     if (!v) return fail(STENCIL_E_INVALID, "no kernel variant for this scenario");
-    return v->max_threads;
+    return kernel_max_threads(s, v);
 }
 
 int64_t stencil_tile_bytes(const stencil_t *s, int wg_rows, int wg_cols) {
@@ -461,6 +644,7 @@ int stencil_run(stencil_t *s, const void *in, void *out, int iters, int wg_rows,
     if (rc != STENCIL_OK) return rc;
     const Variant *v = find_variant(s);
     if (!v) return fail(STENCIL_E_INVALID, "no kernel selected for this scenario");
+    query_device_limits();
     if (wg_rows == 0 && wg_cols == 0) default_wg(s, v, &wg_rows, &wg_cols);
     rc = check_legal(s, v, wg_rows, wg_cols);
     if (rc != STENCIL_OK) return rc;
@@ -478,6 +662,7 @@ int stencil_run_static(stencil_t *s, const void *in, void *out, int iters, int w
     if (rc != STENCIL_OK) return rc;
     const Variant *v = find_variant(s);
     if (!v) return fail(STENCIL_E_INVALID, "no kernel selected for this scenario");
+    query_device_limits();
     if (wg_rows == 0 && wg_cols == 0) default_wg(s, v, &wg_rows, &wg_cols);
     rc = check_legal(s, v, wg_rows, wg_cols);
     if (rc != STENCIL_OK) return rc;
@@ -525,12 +710,16 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
     hipStream_t stream = (hipStream_t)stream_;
     rc = ensure_device_state(s, v, launches_of(s, v, iters) > 1, stream);
     if (rc != STENCIL_OK) return rc;
-    while ((int)s->events.size() < 2 * reps) {
-        hipEvent_t e;
-        hipError_t he = hipEventCreate(&e);
-        if (he != hipSuccess) return fail_hip(he, "hipEventCreate");
-        s->events.push_back(e);
-    }
+    // event pairs for the samples, made when the first size is actually timed
+    auto need_events = [&]() -> int {
+        while ((int)s->events.size() < 2 * reps) {
+            hipEvent_t e;
+            hipError_t he = hipEventCreate(&e);
+            if (he != hipSuccess) return fail_hip(he, "hipEventCreate");
+            s->events.push_back(e);
+        }
+        return STENCIL_OK;
+    };
     const double nan = std::numeric_limits<double>::quiet_NaN();
     std::vector<double> samples((size_t)reps);
 
@@ -540,15 +729,19 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
     // times one size into slot k; returns STENCIL_OK also when the size is refused
     // probe_only: one warm-up and two samples instead of three warm-ups and `reps` samples
     auto time_size = [&](int wr, int wc, int k, bool probe_only) -> int {
-        if (check_legal(s, v, wr, wc) != STENCIL_OK) {
+        // a size that is not legal, or that the runtime refuses when it is launched (Section 3.1's
+        // refused parameters show only then): recorded, and the sweep goes on
+        auto refused = [&]() -> int {
             stat[k] = STENCIL_E_REFUSED;
+            means[k] = nan;
             if (k < n) {
                 if (min_ms) min_ms[k] = nan;
                 if (median_ms) median_ms[k] = nan;
                 if (stddev_ms) stddev_ms[k] = nan;
             }
             return STENCIL_OK;
-        }
+        };
+        if (check_legal(s, v, wr, wc) != STENCIL_OK) return refused();
         // samples [from, to) into the event pairs, then wait for them and read the times
         auto take = [&](int from, int to) -> int {
             for (int i = from; i < to; ++i) {
@@ -574,10 +767,13 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
         const int taken = probe_only ? std::min(2, reps) : reps;
         for (int w = 0; w < (probe_only ? 1 : kWarmup); ++w) {
             int r = run_checked(s, v, in, out, s->scratch, iters, wr, wc, stream);
+            if (r == STENCIL_E_REFUSED) return refused();
             if (r != STENCIL_OK) return r;
         }
         {
-            int r = take(0, taken);
+            int r = need_events();
+            if (r == STENCIL_OK) r = take(0, taken);
+            if (r == STENCIL_E_REFUSED) return refused();
             if (r != STENCIL_OK) return r;
         }
         samples.resize((size_t)taken);
@@ -765,19 +961,7 @@ int stencil_baseline_wg(const double *performance, int n_scenarios, int n_sizes,
 
 int stencil_features(const stencil_t *s, double *f) {
     if (!s || !f) return fail(STENCIL_E_INVALID, "NULL argument");
-    f[0] = (double)s->rows;
-    f[1] = (double)s->cols;
-    f[2] = (double)s->elem();
-    f[3] = s->hn;
-    f[4] = s->hs;
-    f[5] = s->he;
-    f[6] = s->hw;
-    f[7] = (double)(s->hn + s->hs + 1) * (s->he + s->hw + 1);
-    f[8] = s->kernel == STENCIL_SINCOS ? 1.0 : 0.0;
-    f[9] = 256.0;                              // compute units of an MI355X
-    f[10] = (double)STENCIL_LOCAL_MEM_BYTES;
-    f[11] = (double)STENCIL_MAX_WG_SIZE;
-    f[12] = (double)s->out_elem();
+    scenario_features(s, f);
     return STENCIL_OK;
 }
 
@@ -818,47 +1002,74 @@ int stencil_predict_wg(const stencil_t *s, const stencil_predictor_t *p, const i
         return fail(STENCIL_E_INVALID, "bad arguments");
     if (handler < STENCIL_FALLBACK_NEAREST || handler > STENCIL_FALLBACK_RANDOM)
         return fail(STENCIL_E_INVALID, "unknown fallback handler %d", handler);
-    double f[STENCIL_N_FEATURES];
-    int rc = stencil_features(s, f);
-    if (rc != STENCIL_OK) return rc;
-    int wr = 0, wc = 0;
-    rc = stencil_predictor_classify(p, f, STENCIL_N_FEATURES, &wr, &wc);
-    if (rc != STENCIL_OK) return rc;
     const Variant *v = find_variant(s);
-    // Algorithm 1: a legal prediction is kept; otherwise the handler chooses
-    if (check_legal(s, v, wr, wc) != STENCIL_OK) {
-        if (handler == STENCIL_FALLBACK_BASELINE) {
-            if (check_legal(s, v, baseline_rows, baseline_cols) != STENCIL_OK)
-                return fail(STENCIL_E_REFUSED, "the baseline size %dx%d is not legal for this scenario", baseline_rows,
-                            baseline_cols);
-            wr = baseline_rows;
-            wc = baseline_cols;
-        } else {
-            std::vector<int> legal;
-            for (int k = 0; k < n_cand; ++k)
-                if (check_legal(s, v, cand_rows[k], cand_cols[k]) == STENCIL_OK) legal.push_back(k);
-            if (legal.empty()) return fail(STENCIL_E_REFUSED, "no legal candidate workgroup size");
-            int pick = legal[0];
-            if (handler == STENCIL_FALLBACK_RANDOM) {
-                pick = legal[(size_t)(random % legal.size())];
-            } else {
-                double d_min = std::numeric_limits<double>::infinity();
-                for (int k : legal) {
-                    const double dr = cand_rows[k] - wr, dc = cand_cols[k] - wc;
-                    const double d = std::sqrt(dr * dr + dc * dc);
-                    if (d < d_min) {
-                        d_min = d;
-                        pick = k;
-                    }
-                }
-            }
-            wr = cand_rows[pick];
-            wc = cand_cols[pick];
-        }
-    }
+    int wr = 0, wc = 0;
+    int rc = classify_and_repair(s, v, reinterpret_cast<const host_tuning::Classifier *>(p), cand_rows, cand_cols, n_cand,
+                                 handler, baseline_rows, baseline_cols, random, &wr, &wc);
+    if (rc != STENCIL_OK) return rc;
     g_err[0] = '\0';
     *wg_rows = wr;
     *wg_cols = wc;
+    return STENCIL_OK;
+}
+
+int stencil_attach_predictor(stencil_t *s, const stencil_predictor_t *p, int handler) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    if (handler < STENCIL_FALLBACK_NEAREST || handler > STENCIL_FALLBACK_RANDOM)
+        return fail(STENCIL_E_INVALID, "unknown fallback handler %d", handler);
+    s->predictor = p;
+    s->predictor_handler = handler;
+    return STENCIL_OK;
+}
+
+int stencil_default_wg(const stencil_t *s, int *wg_rows, int *wg_cols) {
+    if (!s || !wg_rows || !wg_cols) return fail(STENCIL_E_INVALID, "NULL argument");
+    const Variant *v = find_variant(s);
+    if (!v) return fail(STENCIL_E_INVALID, "no kernel selected for this scenario");
+    default_wg(s, v, wg_rows, wg_cols);
+    return STENCIL_OK;
+}
+
+int stencil_predictor_load(stencil_predictor_t **out, const char *path, int classifier) {
+    if (!out || !path) return fail(STENCIL_E_INVALID, "NULL argument");
+    *out = nullptr;
+    FILE *fh = std::fopen(path, "r");
+    if (!fh) return fail(STENCIL_E_INVALID, "cannot open %s", path);
+    stencil_predictor_t *p = nullptr;
+    int rc = stencil_predictor_create(&p, classifier);
+    int n_features = 0, line_no = 0, pairs = 0;
+    char line[8192];
+    while (rc == STENCIL_OK && std::fgets(line, sizeof(line), fh)) {
+        ++line_no;
+        char *at = line;
+        while (*at == ' ' || *at == '\t') ++at;
+        if (*at == '#' || *at == '\n' || *at == '\r' || *at == '\0') continue;
+        if (n_features == 0) {
+            if (std::sscanf(at, "features %d", &n_features) != 1 || n_features < 1 || n_features > 256)
+                rc = fail(STENCIL_E_INVALID, "%s:%d: expected \"features <count>\"", path, line_no);
+            continue;
+        }
+        std::vector<double> row;
+        char *end = at;
+        for (;;) {
+            const double x = std::strtod(at, &end);
+            if (end == at) break;
+            row.push_back(x);
+            at = end;
+        }
+        if ((int)row.size() != n_features + 2 || row[(size_t)n_features] < 1 || row[(size_t)n_features + 1] < 1)
+            rc = fail(STENCIL_E_INVALID, "%s:%d: expected %d features and a workgroup size", path, line_no, n_features);
+        else
+            rc = stencil_predictor_add(p, row.data(), n_features, (int)row[(size_t)n_features], (int)row[(size_t)n_features + 1]);
+        ++pairs;
+    }
+    std::fclose(fh);
+    if (rc == STENCIL_OK && pairs == 0) rc = fail(STENCIL_E_INVALID, "%s holds no training pairs", path);
+    if (rc != STENCIL_OK) {
+        stencil_predictor_destroy(p);
+        return rc;
+    }
+    *out = p;
     return STENCIL_OK;
 }
 
@@ -917,7 +1128,7 @@ int stencil_predict_wg_regression(const stencil_t *s, const stencil_regressor_t 
     std::vector<int> pool;
     std::vector<double> fit;
     for (int k = 0; k < n_cand; ++k) {
-        if (cand_rows[k] < 1 || cand_cols[k] < 1 || (int64_t)cand_rows[k] * cand_cols[k] > v->max_threads) continue;
+        if (cand_rows[k] < 1 || cand_cols[k] < 1 || (int64_t)cand_rows[k] * cand_cols[k] > kernel_max_threads(s, v)) continue;
         const double y = reg->predict(f, cand_rows[k], cand_cols[k]);
         if (std::isnan(y)) continue;
         pool.push_back(k);

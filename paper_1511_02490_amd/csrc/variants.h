@@ -34,6 +34,8 @@ struct Variant {
     int staged_bytes;     // bytes per staged element in LDS
     bool fuses = false;   // a launch makes `temporal_depth` applications instead of one
     LaunchFn launch;
+    // the compiled kernel a launch of this scenario would start (what hipFuncGetAttributes is asked about)
+    const void *(*kernel_of)(const stencil *) = nullptr;
 };
 constexpr int kMaxSegmentRows = 4096;
 inline bool rows_match(const Variant &v, int cr) { return v.cr == cr || (v.cr == 0 && cr >= 1 && cr <= kMaxSegmentRows); }
@@ -54,6 +56,10 @@ struct stencil {
     int temporal_depth = 2;   // applications per launch under STENCIL_STAGING_TEMPORAL
     int sweep_cutoff_pct = 0; // > 0: sizes slower than this percentage of the best so far are cut short
     int best_rows = 0, best_cols = 0;
+    int fail_rows = 0, fail_cols = 0;   // testing aid: launches of this workgroup size fail (-1: every launch)
+    // the classifier stencil_run(0, 0) asks when no sweep has been made (not owned), and its fallback handler
+    const stencil_predictor_t *predictor = nullptr;
+    int predictor_handler = 0;
     // device-side state, created on first use
     void *scratch = nullptr;
     float *d_tables[2] = {nullptr, nullptr};   // weight tables of a run-time region; a replaced table goes into the other one
@@ -77,6 +83,10 @@ struct stencil {
 // Variant keys of WEIGHTED_SUM on the other element types (internal: the public kernel id is
 // STENCIL_WEIGHTED_SUM, the matrix dtype selects the variant).
 enum { STENCIL_WEIGHTED_SUM_F64 = 100, STENCIL_WEIGHTED_SUM_I32 = 101, STENCIL_WEIGHTED_SUM_U8 = 102 };
+
+// Local memory a workgroup may allocate: the device's own figure once a GPU has been used, the
+// header's constant before that (defined in libstencil.hip).
+int64_t stencil_local_memory_limit();
 
 namespace {
 
@@ -192,7 +202,7 @@ hipError_t allow_large_tiles(const void *kernel, size_t lds, int *raised_on) {
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (*raised_on != dev) {
-        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, STENCIL_LOCAL_MEM_BYTES);
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)stencil_local_memory_limit());
         if (e != hipSuccess) return e;
         *raised_on = dev;
     }
@@ -388,6 +398,50 @@ hipError_t launch_life_direct(const stencil *s, const void *in, void *out, int w
 }
 
 
+// The kernel behind each launcher (the variant with whole aligned vectors where there are two).
+template <class Op, int B, class Halo, int CR, int CC, int MAXT>
+const void *kernel_tile(const stencil *) { return reinterpret_cast<const void *>(&sk::tile_kernel<Op, B, Halo, CR, CC, MAXT>); }
+template <class Op, int B, class Halo, int CR, int CC, int MAXT>
+const void *kernel_direct(const stencil *) { return reinterpret_cast<const void *>(&sk::direct_kernel<Op, B, Halo, CR, CC, MAXT>); }
+template <int B, int CR, int MAXT>
+const void *kernel_life_direct(const stencil *) { return reinterpret_cast<const void *>(&sk::life_direct_kernel<B, CR, MAXT>); }
+template <class Op, int B, int CR, int MAXT>
+const void *kernel_temporal(const stencil *) { return reinterpret_cast<const void *>(&sk::temporal_kernel<Op, B, CR, MAXT>); }
+template <int B, int CR, int MAXT>
+const void *kernel_life_temporal(const stencil *) { return reinterpret_cast<const void *>(&sk::life_temporal_kernel<B, CR, MAXT>); }
+template <int CR, int CC>
+const void *kernel_threshold(const stencil *) { return reinterpret_cast<const void *>(&sk::threshold_kernel<CR, CC, STENCIL_MAX_WG_SIZE>); }
+template <class Op, int B, class Halo>
+const void *kernel_march(const stencil *) { return reinterpret_cast<const void *>(&sk::march_kernel<Op, B, Halo, true, 256>); }
+template <class Op, int B>
+const void *kernel_stream(const stencil *s) {
+    switch (s->temporal_depth) {
+    case 1: return reinterpret_cast<const void *>(&sk::stream_kernel<Op, B, 1, true, 256>);
+    case 2: return reinterpret_cast<const void *>(&sk::stream_kernel<Op, B, 2, true, 256>);
+    case 3: return reinterpret_cast<const void *>(&sk::stream_kernel<Op, B, 3, true, 256>);
+    case 4: return reinterpret_cast<const void *>(&sk::stream_kernel<Op, B, 4, true, 256>);
+    case 5: return reinterpret_cast<const void *>(&sk::stream_kernel<Op, B, 5, true, 256>);
+    case 6: return reinterpret_cast<const void *>(&sk::stream_kernel<Op, B, 6, true, 256>);
+    case 7: return reinterpret_cast<const void *>(&sk::stream_kernel<Op, B, 7, true, 256>);
+    case 8: return reinterpret_cast<const void *>(&sk::stream_kernel<Op, B, 8, true, 256>);
+    default: return nullptr;
+    }
+}
+template <int B, int WORDS>
+const void *kernel_life_stream(const stencil *s) {
+    switch (s->temporal_depth) {
+    case 1: return reinterpret_cast<const void *>(&sk::life_stream_kernel<B, 1, WORDS, true, 256>);
+    case 2: return reinterpret_cast<const void *>(&sk::life_stream_kernel<B, 2, WORDS, true, 256>);
+    case 3: return reinterpret_cast<const void *>(&sk::life_stream_kernel<B, 3, WORDS, true, 256>);
+    case 4: return reinterpret_cast<const void *>(&sk::life_stream_kernel<B, 4, WORDS, true, 256>);
+    case 5: return reinterpret_cast<const void *>(&sk::life_stream_kernel<B, 5, WORDS, true, 256>);
+    case 6: return reinterpret_cast<const void *>(&sk::life_stream_kernel<B, 6, WORDS, true, 256>);
+    case 7: return reinterpret_cast<const void *>(&sk::life_stream_kernel<B, 7, WORDS, true, 256>);
+    case 8: return reinterpret_cast<const void *>(&sk::life_stream_kernel<B, 8, WORDS, true, 256>);
+    default: return nullptr;
+    }
+}
+
 // Per-kernel workgroup-size limit (Section 3.1: the registers a kernel needs bound its
 // maximum workgroup size).  The heavily blocked variants are compiled for 256 work-items so
 // that their register windows stay out of scratch memory.
@@ -416,6 +470,7 @@ void reg_one(std::vector<Variant> &r) {
     v.max_threads = kMaxT;
     v.staged_bytes = (int)sizeof(typename Op::L) * Op::kPlanes;
     v.launch = &launch_tile<Op, B, Halo, CR, CC, kMaxT>;
+    v.kernel_of = &kernel_tile<Op, B, Halo, CR, CC, kMaxT>;
     r.push_back(v);
 }
 
@@ -431,6 +486,7 @@ void reg_direct_one(std::vector<Variant> &r) {
     v.max_threads = STENCIL_MAX_WG_SIZE;
     v.staged_bytes = 0;
     v.launch = &launch_direct<Op, B, Halo, CR, CC, STENCIL_MAX_WG_SIZE>;
+    v.kernel_of = &kernel_direct<Op, B, Halo, CR, CC, STENCIL_MAX_WG_SIZE>;
     r.push_back(v);
 }
 
@@ -460,6 +516,7 @@ void reg_temporal_one(std::vector<Variant> &r) {
     v.staged_bytes = 4;
     v.fuses = true;
     v.launch = &launch_temporal<Op, B, CR, STENCIL_MAX_WG_SIZE>;
+    v.kernel_of = &kernel_temporal<Op, B, CR, STENCIL_MAX_WG_SIZE>;
     r.push_back(v);
 }
 
@@ -483,6 +540,7 @@ void reg_stream_one(std::vector<Variant> &r) {
     v.staged_bytes = 0;
     v.fuses = true;
     v.launch = &launch_stream<Op, B>;
+    v.kernel_of = &kernel_stream<Op, B>;
     r.push_back(v);
 }
 
@@ -505,6 +563,7 @@ void reg_life_stream_one(std::vector<Variant> &r) {
     v.staged_bytes = 0;
     v.fuses = true;
     v.launch = &launch_life_stream<B, WORDS>;
+    v.kernel_of = &kernel_life_stream<B, WORDS>;
     r.push_back(v);
 }
 
@@ -526,6 +585,7 @@ void reg_threshold_one(std::vector<Variant> &r) {
     v.max_threads = STENCIL_MAX_WG_SIZE;
     v.staged_bytes = 0;
     v.launch = &launch_threshold<CR, CC>;
+    v.kernel_of = &kernel_threshold<CR, CC>;
     r.push_back(v);
 }
 
@@ -552,6 +612,7 @@ void reg_march_one(std::vector<Variant> &r) {
     v.staged_bytes = 0;
     v.fuses = false;
     v.launch = &launch_march<Op, B, Halo>;
+    v.kernel_of = &kernel_march<Op, B, Halo>;
     r.push_back(v);
 }
 
@@ -575,6 +636,7 @@ void reg_life_temporal_one(std::vector<Variant> &r) {
     v.staged_bytes = 1;
     v.fuses = true;
     v.launch = &launch_life_temporal<B, CR, STENCIL_MAX_WG_SIZE>;
+    v.kernel_of = &kernel_life_temporal<B, CR, STENCIL_MAX_WG_SIZE>;
     r.push_back(v);
 }
 
@@ -597,6 +659,7 @@ void reg_life_direct_one(std::vector<Variant> &r) {
     v.max_threads = STENCIL_MAX_WG_SIZE;
     v.staged_bytes = 0;
     v.launch = &launch_life_direct<B, CR, STENCIL_MAX_WG_SIZE>;
+    v.kernel_of = &kernel_life_direct<B, CR, STENCIL_MAX_WG_SIZE>;
     r.push_back(v);
 }
 

@@ -19,10 +19,10 @@ CLAMP, WRAP, CONSTANT = 0, 1, 2
 WEIGHTED_SUM, LIFE, HEAT, SINCOS, SOBEL, NMS, THRESHOLD = 0, 1, 2, 3, 4, 5, 6
 ENUM_POW2, ENUM_EVEN = 0, 1
 STAGING_LOCAL, STAGING_DIRECT, STAGING_TEMPORAL, STAGING_STREAM = 0, 1, 2, 3
-OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF, OPT_NT_STORE = 0, 1, 2, 3
+OPT_XCD_REMAP, OPT_TEMPORAL_DEPTH, OPT_SWEEP_CUTOFF, OPT_NT_STORE, OPT_FAIL_LAUNCH = 0, 1, 2, 3, 4
 _STAGINGS = {"local": STAGING_LOCAL, "direct": STAGING_DIRECT, "temporal": STAGING_TEMPORAL,
              "stream": STAGING_STREAM}
-N_FEATURES = 13
+N_FEATURES = 16
 STATIC_MATRIX_BYTES = 16 << 20      # STENCIL_STATIC_MATRIX_BYTES
 
 _DTYPES = {"f32": F32, "u8": U8, "i32": I32, "f64": F64}
@@ -83,6 +83,9 @@ def _load() -> ctypes.CDLL:
         "stencil_predictor_add": (c_int, [vp, dp, c_int, c_int, c_int]),
         "stencil_predictor_classify": (c_int, [vp, dp, c_int, ip, ip]),
         "stencil_predict_wg": (c_int, [vp, vp, ip, ip, c_int, c_int, c_int, c_int, ctypes.c_uint64, ip, ip]),
+        "stencil_attach_predictor": (c_int, [vp, vp, c_int]),
+        "stencil_default_wg": (c_int, [vp, ip, ip]),
+        "stencil_predictor_load": (c_int, [ctypes.POINTER(vp), ctypes.c_char_p, c_int]),
         "stencil_regressor_create": (c_int, [ctypes.POINTER(vp)]),
         "stencil_regressor_destroy": (None, [vp]),
         "stencil_regressor_add": (c_int, [vp, dp, c_int, c_int, c_int, c_dbl]),
@@ -105,7 +108,7 @@ EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_s
            "stencil_sweep_wg", "stencil_sweep_configs", "stencil_device_copy", "stencil_time_copy",
            "stencil_sweep_reduce", "stencil_baseline_wg", "stencil_features", "stencil_predictor_create",
            "stencil_predictor_destroy", "stencil_predictor_add", "stencil_predictor_classify",
-           "stencil_predict_wg", "stencil_regressor_create", "stencil_regressor_destroy",
+           "stencil_predict_wg", "stencil_attach_predictor", "stencil_default_wg", "stencil_predictor_load", "stencil_regressor_create", "stencil_regressor_destroy",
            "stencil_regressor_add", "stencil_regressor_predict", "stencil_regressor_fit_forest",
            "stencil_predict_wg_regression",
            "stencil_last_error")
@@ -368,6 +371,19 @@ class Stencil:
                                           ctypes.byref(best), self._stream_ptr(stream)))
         return list(mean)[:n], list(status)[:n], best.value
 
+    def attach_predictor(self, predictor: Optional["Predictor"], handler: str = "nearest"):
+        """The classifier run(..., wg=(0, 0)) consults when no sweep has been made (None detaches).
+        The handle keeps a reference, so the predictor outlives its use."""
+        h = {"nearest": 0, "baseline": 1, "random": 2}[handler]
+        _check(_lib.stencil_attach_predictor(self._h, predictor._h if predictor is not None else None, h))
+        self._predictor = predictor
+
+    def default_wg(self) -> Tuple[int, int]:
+        """The size run(..., wg=(0, 0)) would use now."""
+        wr, wc = ctypes.c_int(), ctypes.c_int()
+        _check(_lib.stencil_default_wg(self._h, ctypes.byref(wr), ctypes.byref(wc)))
+        return wr.value, wc.value
+
     def predict_regression(self, regressor: "Regressor", candidates: Sequence[Tuple[int, int]],
                            fitness: str = "reciprocal") -> Tuple[Tuple[int, int], int]:
         """Algorithm 2: ((wg_rows, wg_cols), number of refused candidates struck on the way)."""
@@ -438,21 +454,23 @@ class Regressor:
         return y.value
 
 
+_CLASSIFIERS = {"nearest": 0, "tree": 1, "zeror": 2}
+
+
+def tuning_data_path(mapping: str = "local,1,1") -> str:
+    """The training pairs recorded on an MI355X under a mapping ("local,1,1": the paper's; "local,2,4")."""
+    path = os.path.join(_HERE, "tuning_data", "mi355x_%s.txt" % mapping.replace(",", "_"))
+    if not os.path.exists(path):
+        raise ValueError("no training data for mapping %r (have: local,1,1 and local,2,4)" % mapping)
+    return path
+
+
 def pretrained_predictor(mapping: str = "local,1,1", classifier: str = "tree") -> "Predictor":
     """A classifier already trained on this device (Section 4.1: training data is collected
     offline, prediction happens at run time): the (f(s), oracle size) pairs of the 128-scenario
-    sweeps that autotune_study recorded on an MI355X under the mapping "local,1,1" (the paper's)
-    or "local,2,4".  Use with Stencil.predict(predictor, candidate sizes)."""
-    import json
-    path = os.path.join(_HERE, "tuning_data", "mi355x_%s.json" % mapping.replace(",", "_"))
-    if not os.path.exists(path):
-        raise ValueError("no training data for mapping %r (have: local,1,1 and local,2,4)" % mapping)
-    with open(path) as fh:
-        data = json.load(fh)
-    pred = Predictor(classifier)
-    for pair in data["pairs"]:
-        pred.add(pair["features"], tuple(pair["wg"]))
-    return pred
+    sweeps that autotune_study recorded on an MI355X, loaded by stencil_predictor_load.  Use with
+    Stencil.predict(predictor, candidate sizes) or Stencil.attach_predictor(predictor)."""
+    return Predictor.load(tuning_data_path(mapping), classifier)
 
 
 class Predictor:
@@ -460,8 +478,15 @@ class Predictor:
 
     def __init__(self, classifier: str = "nearest"):
         self._h = ctypes.c_void_p()
-        kind = {"nearest": 0, "tree": 1, "zeror": 2}[classifier]
-        _check(_lib.stencil_predictor_create(ctypes.byref(self._h), kind))
+        _check(_lib.stencil_predictor_create(ctypes.byref(self._h), _CLASSIFIERS[classifier]))
+
+    @classmethod
+    def load(cls, path: str, classifier: str = "tree") -> "Predictor":
+        """Training pairs from a text file (stencil_predictor_load's format)."""
+        self = cls.__new__(cls)
+        self._h = ctypes.c_void_p()
+        _check(_lib.stencil_predictor_load(ctypes.byref(self._h), os.fsencode(path), _CLASSIFIERS[classifier]))
+        return self
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:

@@ -186,6 +186,20 @@ def test_features_and_prediction_algorithm1():
     feats = [s.features() for s in scen]
     assert feats[1][:9] == [2048.0, 2048.0, 4.0, 2.0, 2.0, 2.0, 2.0, 25.0, 0.0]
     assert feats[2][2] == 1.0 and feats[4][8] == 1.0 and feats[4][7] == 28.0
+    # kernel descriptors (operations per cell stated by the customising function, of which on the
+    # transcendental unit) and the border mode tell apart scenarios whose dataset features coincide
+    assert len(feats[0]) == ls.N_FEATURES == 16
+    assert feats[0][13:16] == [17.0, 0.0, 0.0] and feats[1][13:16] == [49.0, 0.0, 0.0]
+    assert feats[2][13:16] == [11.0, 0.0, 1.0] and feats[3][13:16] == [7.0, 0.0, 1.0] and feats[4][13:16] == [85.0, 2.0, 2.0]
+    same_data = []
+    for kernel in ("weighted_sum", "heat", "sobel", "nms"):
+        st = ls.Stencil(1024, 1024, "f32", (1, 1, 1, 1), "clamp")
+        st.set_kernel(kernel, np.zeros((3, 3), np.float32), scalars=(0.2,))
+        same_data.append(tuple(st.features()))
+    assert len(set(same_data)) == 4 and len({f[:13] for f in same_data}) == 1
+    if not _gpu_visible():
+        # no GPU has been asked: the device features are the header's constants
+        assert feats[0][9:12] == [256.0, 163840.0, 1024.0]
     labels = [(8, 8), (4, 64), (16, 16), (2, 128), (64, 32)]      # the last is above any W_max
     pred = ls.Predictor()
     for f, w in zip(feats, labels):
@@ -216,6 +230,111 @@ def test_features_and_prediction_algorithm1():
         probe2.predict(pred, [(2048, 1)])
     with pytest.raises(ls.StencilError):
         ls.Predictor().classify(feats[0])
+
+
+def _gpu_visible():
+    try:
+        import torch
+        return torch.cuda.is_available()
+    except ImportError:
+        return False
+
+
+def _fake_device_pointers():
+    import ctypes
+    return ctypes.c_void_p(0x10000000), ctypes.c_void_p(0x30000000)     # never dereferenced: no launch is made
+
+
+def test_sweep_records_launch_failures_as_refused_and_finishes():
+    """Section 3.1: some sizes are refused only when launched; Section 4.2: the tuner strikes them and
+    goes on.  With every launch made to fail (STENCIL_OPT_FAIL_LAUNCH, a testing aid that puts the
+    runtime's out-of-resources error in the launch's place) the sweep still visits every size,
+    records each as refused and returns; no GPU is needed since nothing is launched."""
+    import ctypes
+    w = wl.config(1, rows=256, cols=256)
+    st = ls.Stencil.from_workload(w)
+    st.set_option(ls.OPT_FAIL_LAUNCH, -1)
+    sizes = [(4, 4), (8, 8), (64, 32), (16, 16)]            # the third is beyond W_max anyway
+    n = len(sizes)
+    a, b = _fake_device_pointers()
+    mean = (ctypes.c_double * n)(*([7.0] * n))
+    status = (ctypes.c_int * n)(*([9] * n))
+    best, sp = ctypes.c_int(5), ctypes.c_double(1.0)
+    rc = ls._lib.stencil_sweep_wg(st._h, a, b, 1, ls._ints([r for r, _ in sizes]), ls._ints([c for _, c in sizes]), n,
+                                  4, 4, 5, mean, None, None, None, status, ctypes.byref(best), ctypes.byref(sp), None)
+    assert rc == ls.OK
+    assert list(status) == [ls.E_REFUSED] * n and all(math.isnan(x) for x in mean)
+    assert best.value == -1 and math.isnan(sp.value)
+    assert "refused at launch" in ls.last_error() and "16x16" in ls.last_error()
+    # the same failure from a plain run is the refusal code, with the runtime's text
+    assert ls._lib.stencil_run(st._h, a, b, 1, 8, 8, None) == ls.E_REFUSED
+    assert "8x8 refused at launch" in ls.last_error()
+    # only one size made to fail: the others are no longer touched by the aid (they would launch)
+    st.set_option(ls.OPT_FAIL_LAUNCH, (8 << 16) | 8)
+    assert ls._lib.stencil_run(st._h, a, b, 1, 8, 8, None) == ls.E_REFUSED
+    with pytest.raises(ls.StencilError):
+        st.set_option(ls.OPT_FAIL_LAUNCH, -7)
+    st.set_option(ls.OPT_FAIL_LAUNCH, 0)
+    st.close()
+
+
+def test_predictor_from_a_text_file_and_inside_the_librarys_own_choice(tmp_path):
+    """stencil_predictor_load reads (f(s), size) pairs from text; an attached classifier decides
+    what stencil_run(0, 0) launches when the handle has no sweep to go by (Section 2: choosing the
+    size is the implementation's job).  The chosen size shows in the text of a launch made to fail."""
+    scen = [ls.Stencil.from_workload(wl.config(i)) for i in range(5)]
+    labels = [(8, 8), (4, 64), (16, 16), (2, 128), (64, 32)]
+    path = tmp_path / "pairs.txt"
+    with open(path, "w") as fh:
+        fh.write("# five pairs\n\nfeatures %d\n" % ls.N_FEATURES)
+        for st, (r, c) in zip(scen, labels):
+            fh.write("# a comment between the pairs\n" + " ".join(repr(x) for x in st.features()) + " %d %d\n" % (r, c))
+    by_hand = ls.Predictor("nearest")
+    for st, lab in zip(scen, labels):
+        by_hand.add(st.features(), lab)
+    for kind in ("nearest", "tree", "zeror"):
+        pred = ls.Predictor.load(str(path), kind)
+        for st, lab in zip(scen, labels):
+            assert pred.classify(st.features()) == (lab if kind != "zeror" else (8, 8))
+        pred.close()
+    pred = ls.Predictor.load(str(path), "nearest")
+    probe = ls.Stencil(2000, 2100, "f32", (2, 2, 2, 2), "clamp")
+    probe.set_kernel("weighted_sum", np.zeros((5, 5), np.float32))
+    assert pred.classify(probe.features()) == by_hand.classify(probe.features()) == (4, 64)
+    a, b = _fake_device_pointers()
+
+    def chosen(st):
+        # the size shows in the text of a launch made to fail, and stencil_default_wg names the same
+        st.set_option(ls.OPT_FAIL_LAUNCH, -1)
+        assert ls._lib.stencil_run(st._h, a, b, 1, 0, 0, None) == ls.E_REFUSED
+        st.set_option(ls.OPT_FAIL_LAUNCH, 0)
+        seen = tuple(int(x) for x in re.search(r"workgroup size (\d+)x(\d+) refused at launch", ls.last_error()).groups())
+        assert st.default_wg() == seen
+        return seen
+
+    assert chosen(probe) == (4, 64)                         # nothing attached: the built-in default (also 4x64)
+    probe2 = ls.Stencil(300, 300, "f32", (1, 1, 1, 1), "clamp")
+    probe2.set_kernel("weighted_sum", np.zeros((3, 3), np.float32))
+    assert chosen(probe2) == (4, 64)
+    probe2.attach_predictor(pred)
+    assert chosen(probe2) == pred.classify(probe2.features()) == (8, 8)      # nearest: C1
+    # an illegal prediction is repaired by the attached handler (Algorithm 1)
+    probe3 = ls.Stencil(8000, 8000, "f32", (1, 5, 3, 0), "constant")
+    probe3.set_kernel("sincos", np.zeros((7, 4), np.float32))
+    probe3.attach_predictor(pred, "nearest")
+    assert pred.classify(probe3.features()) == (64, 32) and chosen(probe3) == (64, 16)
+    probe3.attach_predictor(pred, "baseline")
+    assert chosen(probe3) == (4, 64)                        # the baseline handler falls back to the built-in default
+    probe3.attach_predictor(None)
+    assert chosen(probe3) == (4, 64)
+    # files that do not parse
+    for text in ("", "features 3\n", "1 2 3 4 5\n", "features 3\n1 2 3 4\n", "features 3\n1 2 3 0 4\n", "features 2\n1 x 3 4\n"):
+        bad = tmp_path / "bad.txt"
+        bad.write_text(text)
+        with pytest.raises(ls.StencilError):
+            ls.Predictor.load(str(bad))
+    with pytest.raises(ls.StencilError):
+        ls.Predictor.load(str(tmp_path / "missing.txt"))
 
 
 def test_pretrained_predictor_ships_with_the_library():
