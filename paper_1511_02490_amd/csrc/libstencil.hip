@@ -143,6 +143,7 @@ const std::vector<Variant> &registry() {
         register_direct_and_temporal(r);
         register_streams(r);
         register_life_streams(r);
+        register_wide_regions(r);
         return r;
     }();
     return reg;

@@ -10,8 +10,8 @@
 // southernmost region row is finished and stored.  A cell therefore sees the rows of its
 // region north to south and, inside a row, west to east - the order of the fold everywhere else,
 // so results are bit-identical to the other mappings.  Lanes at a strip's end whose neighbour
-// sits in another wavefront only feed their neighbours (one rim lane per side that has a border
-// region), so strips advance by 62, 63 or 64 vectors.
+// sits in another wavefront only feed their neighbours (one rim lane per side for up to four
+// cells of border region there, two for up to eight), so strips advance by 60 to 64 vectors.
 //
 // All three border modes: a single application never needs a cell's new value, only resolved
 // loads.
@@ -20,8 +20,10 @@
 
 namespace sk {
 
-// vectors of a strip that are written, given the region's west / east extents
-__host__ __device__ constexpr int march_vectors(int W, int E) { return 64 - (W > 0 ? 1 : 0) - (E > 0 ? 1 : 0); }
+// Rim lanes at a side whose region extent is h cells (four cells per lane), and the vectors of a
+// strip that are written, given the region's west / east extents.
+__host__ __device__ constexpr int march_rim(int h) { return (h + 3) / 4; }
+__host__ __device__ constexpr int march_vectors(int W, int E) { return 64 - march_rim(W) - march_rim(E); }
 
 // FAST: rows are whole aligned vectors (cols % 4 == 0, 16-byte aligned pointers).  A lane's four
 // columns then lie either all inside the matrix or all outside it, every row is one vector load
@@ -35,11 +37,11 @@ __device__ __forceinline__ void march_body(const TileArgs<Op, Halo> &a, const in
     static_assert(sizeof(T) == 4 && sizeof(L) == 4, "32-bit elements");
     constexpr int N = Halo::N, S = Halo::S, E = Halo::E, W = Halo::W;
     constexpr int CC = 4;
-    static_assert(E <= CC && W <= CC, "row neighbours come from the adjacent lane only");
+    static_assert(E <= 2 * CC && W <= 2 * CC, "row neighbours come from the two adjacent lanes at each side");
     constexpr int NP = Op::kPlanes;
     constexpr int R = N + S + 1;          // output rows in flight = rows of the region
     constexpr int WCOLS = E + W + 1;
-    constexpr int kRimW = W > 0 ? 1 : 0;
+    constexpr int kRimW = march_rim(W);
     constexpr int kCols = march_vectors(W, E) * CC;
 
     const int tid = (int)threadIdx.y * (int)blockDim.x + (int)threadIdx.x;
@@ -143,13 +145,22 @@ __device__ __forceinline__ void march_body(const TileArgs<Op, Halo> &a, const in
 #pragma unroll
                 for (int p = 0; p < NP; ++p) {
 #pragma unroll
-                    for (int k = 0; k < W; ++k)
-                        row[p][k] = __uint_as_float(from_lane_below(__float_as_uint(sv[p][CC - W + k])));
+                    for (int k = 0; k < W; ++k) {
+                        // the cell d columns west of this lane's first: in the lane one below, or (d > 4) two below
+                        const int d = W - k, hops = (d + CC - 1) / CC;
+                        uint32_t x = from_lane_below(__float_as_uint(sv[p][hops * CC - d]));
+                        if (hops == 2) x = from_lane_below(x);
+                        row[p][k] = __uint_as_float(x);
+                    }
 #pragma unroll
                     for (int k = 0; k < CC; ++k) row[p][W + k] = sv[p][k];
 #pragma unroll
-                    for (int k = 0; k < E; ++k)
-                        row[p][W + CC + k] = __uint_as_float(from_lane_above(__float_as_uint(sv[p][k])));
+                    for (int k = 0; k < E; ++k) {
+                        const int hops = k / CC + 1;
+                        uint32_t x = from_lane_above(__float_as_uint(sv[p][k - (hops - 1) * CC]));
+                        if (hops == 2) x = from_lane_above(x);
+                        row[p][W + CC + k] = __uint_as_float(x);
+                    }
                 }
                 auto value_at = [&](int i) {
                     L parts[NP];

@@ -698,3 +698,4 @@ void register_unit_region_tiles(std::vector<Variant> &r);
 void register_direct_and_temporal(std::vector<Variant> &r);
 void register_streams(std::vector<Variant> &r);
 void register_life_streams(std::vector<Variant> &r);
+void register_wide_regions(std::vector<Variant> &r);

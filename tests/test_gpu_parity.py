@@ -121,10 +121,10 @@ DIRECT_U8 = [("direct", 1, 16), ("direct", 2, 16), ("direct", 4, 16)]
 
 
 @pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
-@pytest.mark.parametrize("halo", [(1, 1, 1, 1), (2, 2, 2, 2), (2, 1, 2, 2), (0, 0, 0, 0), (7, 3, 9, 5)])
+@pytest.mark.parametrize("halo", [(1, 1, 1, 1), (2, 2, 2, 2), (3, 3, 3, 3), (4, 4, 4, 4), (2, 1, 2, 2), (0, 0, 0, 0), (7, 3, 9, 5)])
 def test_weighted_sum_borders_and_regions(ls, border, halo):
     w = custom(wl.WEIGHTED_SUM, 131, 157, halo, border, pad=0.5, seed=sum(halo))
-    direct = DIRECT_F32 if halo in [(1, 1, 1, 1), (2, 2, 2, 2)] else []
+    direct = DIRECT_F32 if halo in [(1, 1, 1, 1), (2, 2, 2, 2), (3, 3, 3, 3), (4, 4, 4, 4)] else []
     for blocking in BLOCKINGS_F32 + direct:
         for wg in [(4, 4), (16, 16), (3, 21), (2, 64)]:
             check(ls, w, wg, blocking=blocking)
@@ -441,12 +441,14 @@ def test_register_streaming_temporal_kernel_bit_exact(ls, border):
 @pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
 def test_register_marching_single_application_kernels(ls, border):
     """One application marched down the matrix in registers (sin/cos stencil N1 S5 E3 W0 and the
-    5x5 weighted sum): matrices wider than one strip (252 / 248 columns), ragged ones, ones smaller
+    5x5 to 11x11 weighted sums, the last with row neighbours two lanes away): matrices wider than
+    one strip (252 / 248 / 240 columns), ragged ones, ones smaller
     than a strip or than the region, unaligned rows, segment heights that do and do not divide
     the rows, and the output bits of the local-memory mapping."""
     shapes = [(70, 600), (37, 252), (41, 256), (130, 83), (64, 1024), (5, 3), (1, 1), (9, 508)]
-    for kernel, halo in [(wl.SINCOS, (1, 5, 3, 0)), (wl.WEIGHTED_SUM, (2, 2, 2, 2))]:
-        for rows, cols in shapes:
+    for kernel, halo in [(wl.SINCOS, (1, 5, 3, 0)), (wl.WEIGHTED_SUM, (2, 2, 2, 2)), (wl.WEIGHTED_SUM, (3, 3, 3, 3)),
+                         (wl.WEIGHTED_SUM, (4, 4, 4, 4)), (wl.WEIGHTED_SUM, (5, 5, 5, 5))]:
+        for rows, cols in shapes + [(23, 241), (12, 484)]:
             w = custom(kernel, rows, cols, halo, border, pad=0.3, seed=rows + cols)
             ref = None
             for h, wg in [(64, (1, 64)), (8, (2, 64)), (1, (4, 64)), (29, (8, 8)), (4096, (2, 32))]:
