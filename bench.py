@@ -37,7 +37,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3      # published: packed fp32 fma on 256 CUs x 4
 VALU_LANE_ISSUE_PEAK = 256 * 4 * 16 * 2.4e9
 PRECONDITION_SECONDS = 0.06          # continuous untimed work ahead of every timed region (clock ramp)
 
-WORKLOADS = ["C1", "C2", "C3", "C4", "C5", "H8192", "H16384", "W8192", "G5", "G7"]
+WORKLOADS = ["C1", "C2", "C3", "C4", "C5", "H8192", "H16384", "W8192", "G5", "G7", "D5", "I5"]
 
 
 def flops_per_cell_update(w):
@@ -80,7 +80,8 @@ def parse_args():
     ap.add_argument("--workload", default="C5", choices=WORKLOADS,
                     help="C1..C5; one heat step on a 8192^2 / 16384^2 matrix (H8192, H16384); a 28-tap weighted sum "
                          "with C5's border region, given at run time, on C5's matrix (W8192); a 5x5 / 7x7 Gaussian blur "
-                         "of a 8192^2 matrix (G5, G7)")
+                         "of a 8192^2 matrix (G5, G7); the 5x5 blur of a 4096^2 matrix of doubles / of 32-bit "
+                         "integers with binomial weights (D5, I5)")
     ap.add_argument("--reps", type=int, default=30, help="timed samples per workgroup size in the sweep")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -100,6 +101,15 @@ def parse_args():
 def named_workload(wl, name):
     if name.startswith("C"):
         return wl.config(int(name[1]) - 1)
+    if name in ("D5", "I5"):
+        # the synthetic template's other element types (Section 3.3) on the paper's largest matrix
+        import numpy as np
+        if name == "D5":
+            return wl.Workload("D5 gaussian5x5 4096x4096 f64 clamp", 4096, 4096, "f64", (2, 2, 2, 2), "clamp", 0.0,
+                               wl.WEIGHTED_SUM, 1, wl.BASE_SEED + 20, "pow2", weights=wl.gaussian_weights(2, 1.0))
+        b = np.array([1.0, 4.0, 6.0, 4.0, 1.0])
+        return wl.Workload("I5 binomial5x5 4096x4096 i32 clamp", 4096, 4096, "i32", (2, 2, 2, 2), "clamp", 0.0,
+                           wl.WEIGHTED_SUM, 1, wl.BASE_SEED + 21, "pow2", weights=np.outer(b, b).astype(np.float32))
     if name.startswith("G"):
         # Table 2's gaussian goes beyond C2's 5x5: the same blur, and the next size up, on a matrix no cache holds
         radius = {"G5": 2, "G7": 3}[name]
@@ -207,6 +217,11 @@ LARGE_HEAT_CONFIGS = [(m, cr, 4, 0, wg, remap, nt)
 def strong_configs(w):
     if w.name.startswith("W"):
         return [("local", cr, 4, 0, wg, -1, nt) for cr in (2, 4) for wg in ((8, 32), (4, 64), (8, 16)) for nt in (0, 1)]
+    if w.name.startswith(("D5", "I5")):
+        cc = 2 if w.dtype == "f64" else 4
+        return ([("local", cr, cc, 0, wg, -1, nt) for cr in (2, 4) for wg in ((8, 32), (4, 64), (16, 16)) for nt in (0, 1)] +
+                [("direct", cr, cc, 0, wg, -1, nt) for cr in (2, 4) for wg in ((4, 64), (4, 16)) for nt in (0, 1)] +
+                [("local", 1, 1, 0, (16, 32), -1, 0)])
     if w.name.startswith("G"):
         return ([("local", cr, 4, 0, wg, remap, 1) for cr in (2, 4) for wg in ((8, 32), (4, 64), (8, 64)) for remap in (1, 0)] +
                 [("direct", cr, 4, 0, wg, remap, 1) for cr in (2, 4) for wg in ((4, 64), (1, 512)) for remap in (1, 0)] +
@@ -458,7 +473,7 @@ def sub_record(ls, torch, wl, name, args):
         return nt
 
     nt = configure(c)
-    steps = {"C1": 200, "C2": 200, "C3": 10, "C4": 3, "C5": 30, "H8192": 50, "H16384": 20, "W8192": 30, "G5": 30, "G7": 30}[name]
+    steps = {"C1": 200, "C2": 200, "C3": 10, "C4": 3, "C5": 30, "H8192": 50, "H16384": 20, "W8192": 30, "G5": 30, "G7": 30, "D5": 50, "I5": 50}[name]
     ms_per_step, value = b.timed_steps(c[4], steps, max(1, steps // 10))
     out = {"workload": w.name, "metric": "Gcells/s", "value": value, "unit": "Gcells/s", "ms_per_step": ms_per_step,
            "steps": steps, "dtype": w.dtype,
@@ -536,7 +551,7 @@ def main():
     cells_per_sample = cells * burst
 
     steps = args.steps if args.steps > 0 else {"C1": 200, "C2": 200, "C3": 20, "C4": 5, "C5": 100, "H8192": 100,
-                                               "H16384": 30, "W8192": 100, "G5": 100, "G7": 100}[args.workload]
+                                               "H16384": 30, "W8192": 100, "G5": 100, "G7": 100, "D5": 100, "I5": 100}[args.workload]
     warmup = args.warmup if args.warmup >= 0 else max(1, steps // 10)
 
     if args.copy_only:
@@ -640,7 +655,7 @@ def main():
 
     others = {}
     if not (args.wg or args.quick or args.no_others):
-        for name in ("C4", "H8192", "H16384", "C3", "C2", "C1", "C5", "W8192", "G5", "G7"):
+        for name in ("C4", "H8192", "H16384", "C3", "C2", "C1", "C5", "W8192", "G5", "G7", "D5", "I5"):
             if name != args.workload:
                 others[name] = sub_record(ls, torch, wl, name, args)
 

@@ -63,7 +63,9 @@ enum stencil_border { STENCIL_CLAMP = 0, STENCIL_WRAP = 1, STENCIL_CONSTANT = 2 
  *   WEIGHTED_SUM: sum of w * V over the region - "gaussian" - in (dr, dc) row-major order.
  *                 F32: fp32 fma chain.  F64: fp64 fma chain (weights widened).  I32: 32-bit
  *                 wrap-around arithmetic; the weights must be integers.  F64 / I32 run with
- *                 the local-memory tile only, cells per work-item (1,1) or (2,2) / (2,4).
+ *                 the local-memory tile, cells per work-item (1,1), (1,2), (2,2), (4,2) / (1,1),
+ *                 (1,4), (2,4), (4,4), and with regions 1/1/1/1 and 2/2/2/2 also DIRECT, cells_rows
+ *                 in {1,2,4}, cells_cols = 2 / 4 (a 16-byte vector of the element type).
  *                 U8: a byte matrix in, an F32 matrix out (input and output types differ,
  *                 Section 3.3) - an 8-bit image blurred into floats; cells are converted
  *                 exactly, then the fp32 fma chain; the padding value is a byte.  Exactly one

@@ -230,17 +230,23 @@ def test_heat_conserves_total_and_long_run(ls):
 @pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
 def test_weighted_sum_on_double_and_int32_matrices(ls, border):
     rng = np.random.default_rng(41)
-    for halo in [(1, 1, 1, 1), (2, 1, 2, 2), (0, 3, 4, 1)]:
+    for halo in [(1, 1, 1, 1), (2, 2, 2, 2), (2, 1, 2, 2), (0, 3, 4, 1)]:
         n, s, e, w_ = halo
+        compiled = halo in [(1, 1, 1, 1), (2, 2, 2, 2)]          # regions with variants of their own, direct ones too
         wf = rng.random((n + s + 1, e + w_ + 1), dtype=np.float32)
         wd = wl.Workload("f64", 77, 90, "f64", halo, border, 0.5, wl.WEIGHTED_SUM, 2, 5, "pow2", weights=wf)
-        for blocking, wg in [((1, 1), (4, 16)), ((2, 2), (8, 32)), ((2, 2), (3, 5))]:
+        for blocking, wg in [((1, 1), (4, 16)), ((2, 2), (8, 32)), ((2, 2), (3, 5)), ((1, 2), (4, 16)), ((4, 2), (8, 8))] + (
+                [(("direct", cr, 2), wg) for cr in (1, 2, 4) for wg in ((4, 16), (3, 5))] if compiled else []):
             check(ls, wd, wg, blocking=blocking)
         check(ls, wd, (4, 8), blocking=(2, 2), offset=1)
         wi = rng.integers(-5, 6, size=wf.shape).astype(np.float32)
         wi32 = wl.Workload("i32", 77, 90, "i32", halo, border, 3.0, wl.WEIGHTED_SUM, 3, 6, "pow2", weights=wi)
-        for blocking, wg in [((1, 1), (4, 16)), ((2, 4), (8, 32)), ((2, 4), (3, 5))]:
+        for blocking, wg in [((1, 1), (4, 16)), ((2, 4), (8, 32)), ((2, 4), (3, 5)), ((1, 4), (4, 16)), ((4, 4), (8, 8))] + (
+                [(("direct", cr, 4), wg) for cr in (1, 2, 4) for wg in ((4, 16), (3, 5))] if compiled else []):
             check(ls, wi32, wg, blocking=blocking)
+        if compiled:
+            check(ls, wd, (4, 8), blocking=("direct", 2, 2), offset=1)
+            check(ls, wi32, (4, 8), blocking=("direct", 2, 4), offset=1)
     # wrap-around arithmetic
     big = np.full((40, 48), (1 << 20) + 1, np.int32)
     wb = wl.Workload("i32", 40, 48, "i32", (1, 1, 1, 1), border, 0.0, wl.WEIGHTED_SUM, 1, 7, "pow2",
