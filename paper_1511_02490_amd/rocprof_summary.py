@@ -203,8 +203,9 @@ def main():
         out.append("")
         out.append("## Instruction, occupancy and local-memory counters (--pmc, means per dispatch of the stencil kernel)")
         out.append("")
-        out.append("Launch: workgroup of %s work-items, grid of %s, %s vector registers (+%s accumulation), %s scalar registers, "
-                   "%s bytes of local memory per workgroup, %s bytes of scratch per work-item."
+        out.append("Launch as rocprofv3 lists it: workgroup of %s work-items, grid of %s work-items, VGPR_Count %s (+%s "
+                   "accumulation), SGPR_Count %s, LDS_Block_Size %s (the kernels' dynamically sized tile is not in that "
+                   "column), Scratch_Size %s."
                    % (attrs["workgroup"], attrs["grid"], attrs["vgprs"], attrs["agprs"], attrs["sgprs"], attrs["lds_bytes"],
                       attrs["scratch"]))
         out.append("")
@@ -236,9 +237,7 @@ def main():
                 occ = c["SQ_WAVE_CYCLES"] * 4.0 / (N_SIMD * cyc)
                 derived["mean_waves_per_simd"] = occ
                 lines.append("occupancy: %.0f wavefronts per launch, on average %.2f resident per SIMD (SQ_WAVE_CYCLES x 4 / "
-                             "(%d SIMDs x kernel cycles)); the register count allows %d"
-                             % (c.get("SQ_WAVES", float("nan")), occ, N_SIMD,
-                                min(8, 512 // max(1, int(attrs["vgprs"]) + int(attrs["agprs"])))))
+                             "(%d SIMDs x kernel cycles))" % (c.get("SQ_WAVES", float("nan")), occ, N_SIMD))
         if c.get("SQ_LDS_IDX_ACTIVE"):
             derived["lds_bank_conflict_frac"] = c["SQ_LDS_BANK_CONFLICT"] / c["SQ_LDS_IDX_ACTIVE"]
             lines.append("local memory: %.3g instructions per dispatch; bank-conflict cycles / active cycles "
