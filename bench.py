@@ -66,7 +66,7 @@ MAPPINGS = {
     "sincos": [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("local", 8, 4),
                ("stream", 64, 4), ("stream", 67, 4), ("stream", 89, 4), ("stream", 134, 4)],
     "life": [("local", 1, 1), ("local", 1, 16), ("local", 2, 16), ("direct", 1, 16), ("direct", 2, 16),
-             ("direct", 4, 16), ("temporal", 2, 16, 2), ("temporal", 4, 16, 2), ("temporal", 2, 16, 4), ("temporal", 4, 16, 4),
+             ("direct", 4, 16), ("direct", 8, 16), ("temporal", 2, 16, 2), ("temporal", 4, 16, 2), ("temporal", 2, 16, 4), ("temporal", 4, 16, 4),
              ("temporal", 8, 16, 4), ("stream", 16, 4, 4), ("stream", 40, 4, 6), ("stream", 40, 4, 8),
              ("stream", 20, 8, 8)],
 }
@@ -200,6 +200,7 @@ STRONG_CONFIGS = {
                      ("local", 2, 4, 0, (16, 8), -1, 1), ("direct", 2, 4, 0, (8, 16), -1, 1),
                      ("stream", 10, 4, 0, (1, 64), -1, 1), ("stream", 5, 4, 0, (1, 64), -1, 1)],
     "life": [("direct", 2, 16, 0, (2, 128)), ("direct", 4, 16, 0, (1, 256)), ("direct", 4, 16, 0, (1, 256), -1, 1),
+             ("direct", 8, 16, 0, (2, 128), -1, 1), ("direct", 8, 16, 0, (1, 256), -1, 1),
              ("temporal", 2, 16, 4, (64, 8)), ("stream", 40, 4, 8, (1, 64)),
              ("stream", 20, 8, 8, (1, 64)), ("stream", 40, 4, 8, (4, 64)), ("stream", 40, 4, 6, (1, 64))],
     "heat": [("direct", 2, 4, 0, (4, 16)), ("temporal", 2, 4, 4, (32, 32)), ("stream", 38, 4, 8, (1, 64)),

@@ -152,7 +152,7 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            (w_c*cells_cols) elements.  (1,1) is the paper's one element per work-item.
  *            LOCAL: cells_rows in {1,2,4,8}, cells_cols in {1,4} (F32) or {1,16} (U8); THRESHOLD:
  *            (1,1), (2,1), (1,4), (2,4), (4,4), and nothing is staged for want of a border region;
- *            DIRECT: cells_rows in {1,2,4}, cells_cols = 4 (F32) or 16 (U8).
+ *            DIRECT: cells_rows in {1,2,4} (LIFE also 8), cells_cols = 4 (F32) or 16 (U8).
  *            STENCIL_STAGING_STREAM - register streaming, no local memory: each wavefront walks
  *            down a strip of 60 to 64 four-cell vectors (the outermost lanes at a side that has
  *            a border region only feed their neighbours), cells_rows (1..4096) rows at a time,

@@ -22,4 +22,5 @@ void register_direct_and_temporal(std::vector<Variant> &r) {
     reg_life_direct<1>(r);
     reg_life_direct<2>(r);
     reg_life_direct<4>(r);
+    reg_life_direct<8>(r);
 }

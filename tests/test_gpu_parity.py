@@ -117,7 +117,7 @@ def test_c1_all_listed_sizes(ls):
 
 BLOCKINGS_F32 = [(1, 1), (2, 1), (8, 1), (1, 4), (4, 4), (8, 4)]
 DIRECT_F32 = [("direct", 1, 4), ("direct", 2, 4), ("direct", 4, 4)]
-DIRECT_U8 = [("direct", 1, 16), ("direct", 2, 16), ("direct", 4, 16)]
+DIRECT_U8 = [("direct", 1, 16), ("direct", 2, 16), ("direct", 4, 16), ("direct", 8, 16)]
 
 
 @pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
