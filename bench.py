@@ -221,7 +221,9 @@ LARGE_HEAT_CONFIGS = [(m, cr, 4, 0, wg, remap, nt)
 
 def strong_configs(w):
     if w.name.startswith("W"):
-        return [("local", cr, 4, 0, wg, -1, nt) for cr in (2, 4) for wg in ((8, 32), (4, 64), (8, 16)) for nt in (0, 1)]
+        return ([("local", cr, 4, 0, wg, -1, nt) for cr in (2, 4) for wg in ((8, 32), (4, 64), (8, 16)) for nt in (0, 1)] +
+                # marched: 33 strips x segments that fill 2 .. 5 wavefront slots per SIMD
+                [("stream", h, 4, 0, wg, -1, 1) for h in (133, 105, 89, 67, 53) for wg in ((1, 64), (4, 64))])
     if w.name.startswith(("D5", "I5")):
         cc = 2 if w.dtype == "f64" else 4
         return ([("local", cr, cc, 0, wg, -1, nt) for cr in (2, 4) for wg in ((8, 32), (4, 64), (16, 16)) for nt in (0, 1)] +

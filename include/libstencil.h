@@ -153,7 +153,7 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            LOCAL: cells_rows in {1,2,4,8}, cells_cols in {1,4} (F32) or {1,16} (U8); THRESHOLD:
  *            (1,1), (2,1), (1,4), (2,4), (4,4), and nothing is staged for want of a border region;
  *            DIRECT: cells_rows in {1,2,4} (LIFE also 8), cells_cols = 4 (F32) or 16 (U8).
- *            STENCIL_STAGING_STREAM - register streaming, no local memory: each wavefront walks
+ *            STENCIL_STAGING_STREAM - register streaming, no tile in local memory: each wavefront walks
  *            down a strip of 60 to 64 four-cell vectors (the outermost lanes at a side that has
  *            a border region only feed their neighbours), cells_rows (1..4096) rows at a time,
  *            taking row neighbours from adjacent lanes; cells_cols = 4.  Two kernels:
@@ -161,9 +161,13 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            blocking, the last three rows of every time level stay in registers,
  *            STENCIL_OPT_TEMPORAL_DEPTH applications per launch (up to
  *            STENCIL_MAX_STREAM_DEPTH; one rim lane per side up to 4, two beyond);
- *            SINCOS with region N1 S5 E3 W0 and WEIGHTED_SUM with region 2/2/2/2, any border
- *            mode: one application per launch, each input row is loaded and pre-processed once
- *            and folded into the N+S+1 output rows it belongs to.
+ *            SINCOS with region N1 S5 E3 W0 and WEIGHTED_SUM (F32), any border mode: one
+ *            application per launch, each input row is loaded and pre-processed once and folded
+ *            into the N+S+1 output rows it belongs to.  WEIGHTED_SUM regions 2/2/2/2 .. 5/5/5/5
+ *            have kernels of their own; any other region with N, S <= 5 and E, W <= 4 runs a
+ *            kernel compiled for its number of columns E+W+1 and for at most 5 (N, S <= 2) or 11
+ *            rows, which hands row neighbours through local memory (a few KiB per workgroup,
+ *            never a reason for refusal).  Larger regions: not available.
  *            The workgroup only groups wavefronts: w_r*w_c must be a multiple of 64 (other
  *            sizes are refused) and at most 256.  Not available for a matrix whose rows are 4 GiB
  *            or longer (cells within a row are addressed by 32-bit byte offsets).

@@ -144,6 +144,7 @@ const std::vector<Variant> &registry() {
         register_streams(r);
         register_life_streams(r);
         register_wide_regions(r);
+        register_runtime_march(r);
         return r;
     }();
     return reg;
@@ -151,16 +152,23 @@ const std::vector<Variant> &registry() {
 
 // The variant that serves a scenario: a compile-time border region if one matches, else
 // the run-time one.
+// whether a variant compiled for any region within a largest one covers the scenario's region
+bool within(const Variant &v, const stencil *s) {
+    return v.hn == -2 && s->hn <= v.mn && s->hs <= v.ms && s->he <= v.me && s->hw <= v.mw;
+}
+
 const Variant *find_variant(const stencil *s) {
-    const Variant *dyn = nullptr;
+    const Variant *dyn = nullptr, *masked = nullptr;
     for (const Variant &v : registry()) {
         if (v.kernel != variant_kernel(s) || v.border != s->border || !rows_match(v, s->cr) || v.cc != s->cc ||
             v.staging != s->staging)
             continue;
         if (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw) return &v;
-        if (v.hn < 0) dyn = &v;
+        // among the masked variants the one with the smallest largest region
+        if (within(v, s) && (!masked || v.mn + v.ms < masked->mn + masked->ms)) masked = &v;
+        if (v.hn == -1) dyn = &v;
     }
-    return dyn;
+    return masked ? masked : dyn;
 }
 
 bool mapping_supported(const stencil *s, int staging, int cr, int cc) {
@@ -168,7 +176,7 @@ bool mapping_supported(const stencil *s, int staging, int cr, int cc) {
     if (staging == STENCIL_STAGING_STREAM && (uint64_t)s->cols * s->elem() >= (1ull << 32)) return false;
     for (const Variant &v : registry())
         if (v.kernel == variant_kernel(s) && v.border == s->border && v.staging == staging && rows_match(v, cr) && v.cc == cc &&
-            (v.hn < 0 || (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw)))
+            (v.hn == -1 || within(v, s) || (v.hn == s->hn && v.hs == s->hs && v.he == s->he && v.hw == s->hw)))
             return true;
     return false;
 }

@@ -35,6 +35,7 @@ __device__ __forceinline__ int resolve(int i, int n) {
 template <int N_, int S_, int E_, int W_>
 struct HaloC {
     static constexpr bool kStatic = true;
+    static constexpr bool kMasked = false;
     static constexpr int N = N_, S = S_, E = E_, W = W_;
     __host__ __device__ constexpr int n() const { return N_; }
     __host__ __device__ constexpr int s() const { return S_; }
@@ -44,6 +45,7 @@ struct HaloC {
 // ... or one only known at launch.
 struct HaloD {
     static constexpr bool kStatic = false;
+    static constexpr bool kMasked = false;
     static constexpr int N = 0, S = 0, E = 0, W = 0;
     int n_, s_, e_, w_;
     __host__ __device__ int n() const { return n_; }

@@ -17,6 +17,7 @@
 #include "temporal_kernel.h"
 #include "tile_kernel.h"
 #include "march_kernel.h"
+#include "march_masked_kernel.h"
 #include "life_stream_kernel.h"
 #include "pointwise_kernel.h"
 
@@ -28,7 +29,8 @@ using LaunchFn = hipError_t (*)(const stencil *, const void *, void *, int, int,
 struct Variant {
     int staging;          // STENCIL_STAGING_LOCAL, _DIRECT, _TEMPORAL or _STREAM
     int kernel, border;
-    int hn, hs, he, hw;   // -1: run-time border region
+    int hn, hs, he, hw;   // -1: run-time border region; -2: any region within the largest one (mn, ms, me, mw)
+    int mn = 0, ms = 0, me = 0, mw = 0;
     int cr, cc;           // cr = 0 (register-streaming kernels): any segment height up to kMaxSegmentRows
     int max_threads;      // per-kernel workgroup-size limit (Section 3.1)
     int staged_bytes;     // bytes per staged element in LDS
@@ -350,6 +352,36 @@ hipError_t launch_march(const stencil *s, const void *in, void *out, int wr, int
     return hipGetLastError();
 }
 
+// The same for any region within the kernel's largest one (march_masked_kernel.h): the kernel compiled for the
+// region's number of columns.
+template <class Op, int B, class Halo, int WC = 1>
+hipError_t launch_march_masked(const stencil *s, const void *in, void *out, int wr, int wc, int, hipStream_t stream) {
+    constexpr int kMaxT = 256;
+    if constexpr (WC > Halo::E + Halo::W + 1) {
+        return hipErrorInvalidValue;
+    } else {
+        if (s->he + s->hw + 1 != WC) return launch_march_masked<Op, B, Halo, WC + 1>(s, in, out, wr, wc, 0, stream);
+        if (s->hn > Halo::N || s->hs > Halo::S || s->he > Halo::E || s->hw > Halo::W) return hipErrorInvalidValue;
+        unsigned blocks;
+        size_t lds;
+        auto a = make_args<Op, Halo, 0, 4>(s, STENCIL_STAGING_STREAM, in, out, wr, wc, &blocks, &lds);
+        const unsigned waves_per_block = (unsigned)(wr * wc) / 64u;
+        blocks = ((unsigned)a.n_tiles + waves_per_block - 1) / waves_per_block;
+        a.xcd_chunk = 0;
+        if (s->xcd_remap && blocks >= 64) {
+            a.xcd_chunk = (int)((blocks + 7) / 8);
+            blocks = (unsigned)a.xcd_chunk * 8u;
+        }
+        if (a.vec_ok)
+            hipLaunchKernelGGL((sk::march_masked_kernel<Op, B, Halo, WC, true, kMaxT>), dim3(blocks), dim3(wc, wr), 0,
+                               stream, a, s->cr);
+        else
+            hipLaunchKernelGGL((sk::march_masked_kernel<Op, B, Halo, WC, false, kMaxT>), dim3(blocks), dim3(wc, wr), 0,
+                               stream, a, s->cr);
+        return hipGetLastError();
+    }
+}
+
 template <int B, int CR, int MAXT>
 hipError_t launch_life_temporal(const stencil *s, const void *in, void *out, int wr, int wc, int depth,
                                 hipStream_t stream) {
@@ -413,6 +445,15 @@ template <int CR, int CC>
 const void *kernel_threshold(const stencil *) { return reinterpret_cast<const void *>(&sk::threshold_kernel<CR, CC, STENCIL_MAX_WG_SIZE>); }
 template <class Op, int B, class Halo>
 const void *kernel_march(const stencil *) { return reinterpret_cast<const void *>(&sk::march_kernel<Op, B, Halo, true, 256>); }
+template <class Op, int B, class Halo, int WC = 1>
+const void *kernel_march_masked(const stencil *s) {
+    if constexpr (WC > Halo::E + Halo::W + 1)
+        return nullptr;
+    else if (s->he + s->hw + 1 != WC)
+        return kernel_march_masked<Op, B, Halo, WC + 1>(s);
+    else
+        return reinterpret_cast<const void *>(&sk::march_masked_kernel<Op, B, Halo, WC, true, 256>);
+}
 template <class Op, int B>
 const void *kernel_stream(const stencil *s) {
     switch (s->temporal_depth) {
@@ -623,6 +664,34 @@ void reg_march(std::vector<Variant> &r) {
     reg_march_one<Op, KID, sk::kConstant, Halo>(r);
 }
 
+template <class Op, int KID, int B, class Halo>
+void reg_march_masked_one(std::vector<Variant> &r) {
+    Variant v;
+    v.staging = STENCIL_STAGING_STREAM;
+    v.kernel = KID;
+    v.border = B;
+    v.hn = v.hs = v.he = v.hw = -2;
+    v.mn = Halo::N;
+    v.ms = Halo::S;
+    v.me = Halo::E;
+    v.mw = Halo::W;
+    v.cr = 0;
+    v.cc = 4;
+    v.max_threads = 256;
+    v.staged_bytes = 0;
+    v.fuses = false;
+    v.launch = &launch_march_masked<Op, B, Halo>;
+    v.kernel_of = &kernel_march_masked<Op, B, Halo>;
+    r.push_back(v);
+}
+
+template <class Op, int KID, class Halo>
+void reg_march_masked(std::vector<Variant> &r) {
+    reg_march_masked_one<Op, KID, sk::kClamp, Halo>(r);
+    reg_march_masked_one<Op, KID, sk::kWrap, Halo>(r);
+    reg_march_masked_one<Op, KID, sk::kConstant, Halo>(r);
+}
+
 template <int B, int CR>
 void reg_life_temporal_one(std::vector<Variant> &r) {
     Variant v;
@@ -699,3 +768,4 @@ void register_direct_and_temporal(std::vector<Variant> &r);
 void register_streams(std::vector<Variant> &r);
 void register_life_streams(std::vector<Variant> &r);
 void register_wide_regions(std::vector<Variant> &r);
+void register_runtime_march(std::vector<Variant> &r);

@@ -43,7 +43,7 @@ FAMILY_SOURCES = {
     "direct": _COMMON + ["direct_kernel.h"],
     "temporal": _COMMON + ["temporal_kernel.h"],
     "stream": _COMMON + ["stream_kernel.h", "life_stream_kernel.h"],
-    "march": _COMMON + ["march_kernel.h"],
+    "march": _COMMON + ["march_kernel.h", "march_masked_kernel.h"],
 }
 
 

@@ -453,7 +453,13 @@ def test_register_marching_single_application_kernels(ls, border):
     the rows, and the output bits of the local-memory mapping."""
     shapes = [(70, 600), (37, 252), (41, 256), (130, 83), (64, 1024), (5, 3), (1, 1), (9, 508)]
     for kernel, halo in [(wl.SINCOS, (1, 5, 3, 0)), (wl.WEIGHTED_SUM, (2, 2, 2, 2)), (wl.WEIGHTED_SUM, (3, 3, 3, 3)),
-                         (wl.WEIGHTED_SUM, (4, 4, 4, 4)), (wl.WEIGHTED_SUM, (5, 5, 5, 5))]:
+                         (wl.WEIGHTED_SUM, (4, 4, 4, 4)), (wl.WEIGHTED_SUM, (5, 5, 5, 5)),
+                         # regions without a variant of their own: the kernels compiled for a largest region (5 or
+                         # 11 rows) and the region's number of columns
+                         (wl.WEIGHTED_SUM, (1, 5, 3, 0)), (wl.WEIGHTED_SUM, (2, 1, 2, 2)), (wl.WEIGHTED_SUM, (0, 0, 0, 0)),
+                         (wl.WEIGHTED_SUM, (4, 0, 0, 3)), (wl.WEIGHTED_SUM, (0, 5, 4, 0)), (wl.WEIGHTED_SUM, (5, 5, 4, 4)),
+                         (wl.WEIGHTED_SUM, (0, 0, 4, 4)), (wl.WEIGHTED_SUM, (2, 2, 1, 0)), (wl.WEIGHTED_SUM, (0, 3, 0, 1)),
+                         (wl.WEIGHTED_SUM, (1, 0, 3, 3)), (wl.WEIGHTED_SUM, (2, 2, 4, 3)), (wl.WEIGHTED_SUM, (3, 3, 2, 0))]:
         for rows, cols in shapes + [(23, 241), (12, 484)]:
             w = custom(kernel, rows, cols, halo, border, pad=0.3, seed=rows + cols)
             ref = None
@@ -480,6 +486,8 @@ def test_register_marching_single_application_kernels(ls, border):
         st.set_mapping("stream", 5000, 4)                                        # segment height limit
     with pytest.raises(ls.StencilError):
         ls.Stencil.from_workload(custom(wl.SINCOS, 32, 32, (2, 0, 1, 3), border)).set_mapping("stream", 16, 4)
+    with pytest.raises(ls.StencilError):             # beyond the largest region the run-time marching kernel is compiled for
+        ls.Stencil.from_workload(custom(wl.WEIGHTED_SUM, 32, 32, (6, 0, 1, 3), border)).set_mapping("stream", 16, 4)
 
 
 @pytest.mark.parametrize("border", ["wrap", "constant"])

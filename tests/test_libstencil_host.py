@@ -89,6 +89,25 @@ def test_life_rejects_cells_that_are_not_0_or_1_and_streaming_rejects_4gib_rows(
     st.set_mapping("stream", 8, 4)
 
 
+def test_marching_kernel_serves_run_time_regions_within_its_largest():
+    """Weighted sums of floats: a region given at run time is marched if it lies within N5 S5 E4 W4."""
+    for halo, ok in [((1, 5, 3, 0), True), ((0, 0, 0, 0), True), ((5, 5, 4, 4), True), ((2, 1, 2, 2), True),
+                     ((6, 0, 1, 1), False), ((0, 6, 1, 1), False), ((1, 1, 5, 0), False), ((1, 1, 0, 5), False)]:
+        n, s, e, w = halo
+        st = ls.Stencil(64, 300, "f32", halo, "wrap")
+        st.set_kernel("weighted_sum", np.ones((n + s + 1, e + w + 1), np.float32))
+        if ok:
+            st.set_mapping("stream", 16, 4)
+            assert st.max_wg_size() == 256 and st.is_legal(4, 64) and not st.is_legal(4, 4)
+        else:
+            with pytest.raises(ls.StencilError):
+                st.set_mapping("stream", 16, 4)
+    st = ls.Stencil(64, 300, "f64", (1, 1, 1, 1), "wrap")             # floats only
+    st.set_kernel("weighted_sum", np.ones((3, 3), np.float32))
+    with pytest.raises(ls.StencilError):
+        st.set_mapping("stream", 16, 4)
+
+
 def test_legality_eq1():
     st = ls.Stencil.from_workload(wl.config(1))          # 5x5 gaussian, halo 2
     assert st.max_wg_size() == 1024
