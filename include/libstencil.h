@@ -167,7 +167,8 @@ int stencil_set_border_value(stencil_t *st, double value);
  *            have kernels of their own; any other region with N, S <= 5 and E, W <= 4 runs a
  *            kernel compiled for its number of columns E+W+1 and for at most 5 (N, S <= 2) or 11
  *            rows, which hands row neighbours through local memory (a few KiB per workgroup,
- *            never a reason for refusal).  Larger regions: not available.
+ *            never a reason for refusal).  Larger regions: not available (the local-memory
+ *            tile is as fast there: its fold is bound by arithmetic).
  *            The workgroup only groups wavefronts: w_r*w_c must be a multiple of 64 (other
  *            sizes are refused) and at most 256.  Not available for a matrix whose rows are 4 GiB
  *            or longer (cells within a row are addressed by 32-bit byte offsets).

@@ -4,7 +4,12 @@ of synthetic and real stencil scenarios (Section 5), then evaluate workgroup-siz
 fallback; Algorithm 2: nearest-neighbour and random-forest regressors on runtimes and on speedups) against
 the sweep's oracle sizes with the metrics of Section 7.
 
-    python -m paper_1511_02490_amd.autotune_study [--synthetic 32] [--reps 5] [--mapping local,1,1]
+    python -m paper_1511_02490_amd.autotune_study [--synthetic 32] [--reps 5] [--mapping local,1,1 | best]
+
+`--mapping best` extends the space by the kernel family: every scenario is first timed under each
+mapping the library has for it (local-memory tiles of 1x1, 2x4 and 4x4 cells per work-item, the direct
+kernel, the register-marching kernel at a few segment heights) on a short list of workgroup sizes, and
+the full sweep of workgroup sizes then runs under the fastest one, which the report names.
 
 A large study can be split: `--json FILE --sweep-only` on the GPU records the sweeps, `--from-json
 FILE` (same --synthetic and --mapping) evaluates them anywhere - legality, features and the
@@ -39,13 +44,27 @@ def main():
     from paper_1511_02490_amd import libstencil as ls
     from paper_1511_02490_amd import workloads as wl
 
-    m = a.mapping.split(",")
+    pick_best = a.mapping == "best"
+    m = "local,1,1".split(",") if pick_best else a.mapping.split(",")
     mapping = (m[0], int(m[1]), int(m[2]))
+    # the mappings tried per scenario under `best`, and the sizes each is tried on
+    candidates = [("local", 1, 1), ("local", 2, 4), ("local", 4, 4), ("direct", 2, 4), ("direct", 4, 4),
+                  ("stream", 16, 4), ("stream", 32, 4), ("stream", 64, 4), ("stream", 128, 4)]
+    probe_sizes = [(4, 64), (8, 32), (16, 16), (2, 32), (1, 64), (2, 128)]
+
+    def use(st, mp):
+        """Puts a scenario on a mapping, or on the paper's own where the library has no such kernel for it."""
+        try:
+            st.set_mapping(*mp)
+            return tuple(mp)
+        except ls.StencilError:
+            st.set_mapping("local", 1, 1)
+            return ("local", 1, 1)
     sizes = ls.enumerate_wg("pow2", 1024)
     scen = wl.synthetic_scenarios(a.synthetic) + wl.real_scenarios()
     kind = ["synthetic"] * a.synthetic + ["real"] * (len(scen) - a.synthetic)
 
-    feats, times, status = [], [], []
+    feats, times, status, mappings = [], [], [], []
     t0 = time.perf_counter()
     recorded = None
     if a.from_json:
@@ -55,6 +74,7 @@ def main():
                 or recorded.get("mapping", a.mapping) != a.mapping:
             raise SystemExit("%s was recorded for another scenario list, size list or mapping" % a.from_json)
         times, status = recorded["times_ms"], recorded["status"]
+        mappings = [tuple(mp) for mp in recorded.get("mappings", [])]
         a.reps = recorded.get("reps", a.reps)
         for w in scen:            # f(s) needs no GPU: taken afresh, so that recorded sweeps outlive a change of features
             st = ls.Stencil.from_workload(w)
@@ -64,31 +84,40 @@ def main():
         import torch
     for w in ([] if recorded else scen):
         st = ls.Stencil.from_workload(w)
-        try:
-            st.set_mapping(*mapping)
-        except ls.StencilError:
-            st.set_mapping("local", 1, 1)
         tin = torch.from_numpy(w.grid()).cuda()
         tout = torch.empty(tin.shape, dtype=torch.uint8 if w.out_dtype == "u8" else tin.dtype, device="cuda")
+        chosen = mapping
+        if pick_best:
+            best_ms = float("inf")
+            for mp in candidates:
+                if mp[1] > w.rows or use(st, mp) != mp:
+                    continue
+                probe = st.sweep(tin, tout, probe_sizes, iters=max(1, min(w.iters, 10)), fixed=(0, 0), reps=3)
+                if probe.best is not None and probe.best_ms < best_ms:
+                    best_ms, chosen = probe.best_ms, mp
+        mappings.append(use(st, chosen))
         res = st.sweep(tin, tout, sizes, iters=max(1, min(w.iters, 10)), fixed=(0, 0), reps=a.reps)
         feats.append(st.features())
         times.append(res.mean_ms)
         status.append(res.status)
         st.close()
         del tin, tout
-        print("swept %-44s best %-10s %.4f ms  refused %d" % (w.name, res.best, res.best_ms,
-                                                             sum(1 for s in res.status if s != 0)),
+        print("swept %-44s %-14s best %-10s %.4f ms  refused %d" % (w.name, "%s %dx%d" % mappings[-1], res.best, res.best_ms,
+                                                                   sum(1 for s in res.status if s != 0)),
               file=sys.stderr, flush=True)
     sweep_s = recorded["sweep_seconds"] if recorded else time.perf_counter() - t0
     if a.json and not recorded:
         with open(a.json, "w") as fh:
             json.dump({"sizes": sizes, "scenarios": [w.name for w in scen], "times_ms": times, "status": status,
-                       "features": feats, "mapping": a.mapping, "reps": a.reps, "sweep_seconds": sweep_s}, fh)
+                       "features": feats, "mapping": a.mapping, "mappings": mappings, "reps": a.reps,
+                       "sweep_seconds": sweep_s}, fh)
     if a.sweep_only:
         return
 
     n_s, n_w = len(scen), len(sizes)
     nan = float("nan")
+    if len(mappings) != n_s:               # sweeps recorded before the mapping was kept per scenario
+        mappings = [mapping] * n_s
     oracle, perf = [], []
     for i in range(n_s):
         b, p, _ = ls.sweep_reduce(sizes, times[i], status[i], nan)
@@ -127,10 +156,7 @@ def main():
                     pred.add(feats[k], sizes[oracle[k]])
                 raw = pred.classify(feats[i])
                 st = ls.Stencil.from_workload(scen[i])
-                try:
-                    st.set_mapping(*mapping)
-                except ls.StencilError:
-                    st.set_mapping("local", 1, 1)
+                use(st, mappings[i])
                 legal_first = st.is_legal(*raw)
                 j = idx[st.predict(pred, sizes)]
                 st.close()
@@ -165,10 +191,7 @@ def main():
                 bootstrap, masks = wl.forest_draws(30, n_tuples, len(feats[i]) + 2, seed=wl.BASE_SEED + 200 + i)
                 reg.fit_forest(bootstrap, masks, min_leaf=2, max_depth=32)
             st = ls.Stencil.from_workload(scen[i])
-            try:
-                st.set_mapping(*mapping)
-            except ls.StencilError:
-                st.set_mapping("local", 1, 1)
+            use(st, mappings[i])
             (wr, wc), struck = st.predict_regression(reg, sizes, "reciprocal" if target == "runtime" else "identity")
             st.close()
             reg.close()
@@ -213,8 +236,16 @@ def main():
     refused = sum(1 for i in all_i for s in status[i] if s != 0)
     print("# Workgroup-size autotuning study on one MI355X")
     print()
-    print("Mapping `%s %dx%d`; %d scenarios (%d synthetic, %d real), %d workgroup sizes each (powers of two,"
-          " product <= 1024), %d samples per size; sweep time %.0f s." % (mapping + (n_s, len(syn), len(real), n_w, a.reps, sweep_s)))
+    print("Mapping %s; %d scenarios (%d synthetic, %d real), %d workgroup sizes each (powers of two,"
+          " product <= 1024), %d samples per size; sweep time %.0f s." % (
+              "the fastest of the library's for each scenario (named in the table below)" if pick_best
+              else "`%s %dx%d`" % mapping, n_s, len(syn), len(real), n_w, a.reps, sweep_s))
+    if pick_best:
+        count = {}
+        for mp in mappings:
+            count[mp[0]] = count.get(mp[0], 0) + 1
+        print()
+        print("* fastest mapping: " + ", ".join("%s for %d scenarios" % (k, v) for k, v in sorted(count.items())))
     print()
     print("* distinct oracle sizes: %d of %d scenarios; most common: %s" % (
         distinct, n_s, max(set(oracle), key=oracle.count) and sizes[max(set(oracle), key=oracle.count)]))
@@ -234,12 +265,15 @@ def main():
             s["median_speedup_over_baseline"], s["mean_speedup_over_baseline"], s["median_speedup_over_4x4"],
             s["median_speedup_over_32x4"]))
     print()
-    print("| scenario | oracle size | oracle ms | predicted (leave-one-out) | performance |")
-    print("|---|---|---|---|---|")
+    print("| scenario | mapping | oracle size | oracle ms | GB/s read + written | predicted (leave-one-out) | performance |")
+    print("|---|---|---|---|---|---|---|")
     for i, r in enumerate(parts["leave-one-out, 1-NN + NearestNeighbour"]):
-        print("| %s | %dx%d | %.4f | %dx%d | %.2f |" % (r["scenario"], r["oracle"][0], r["oracle"][1],
-                                                       times[i][oracle[i]], r["predicted"][0], r["predicted"][1],
-                                                       r["performance"]))
+        w = scen[i]
+        per_sweep_sample = max(1, min(w.iters, 10))
+        gbs = w.cells * w.bytes_per_cell_update * per_sweep_sample / (times[i][oracle[i]] * 1e-3) / 1e9
+        print("| %s | %s %dx%d | %dx%d | %.4f | %.0f | %dx%d | %.2f |" % (
+            (r["scenario"],) + tuple(mappings[i]) + (r["oracle"][0], r["oracle"][1], times[i][oracle[i]], gbs,
+                                                    r["predicted"][0], r["predicted"][1], r["performance"])))
 
 
 if __name__ == "__main__":

@@ -531,3 +531,12 @@ def test_study_evaluates_a_fabricated_landscape(tmp_path, capsys, monkeypatch):
     assert int(rows["leave-one-out, random forest on speedups (Algorithm 2)"][1].split()[0]) >= 90
     assert rows["ZeroR (always the baseline size)"][1] == "50 %"
     assert all(r[2] == "100 %" for r in rows.values())                                  # every first answer legal
+    # sweeps taken under the fastest mapping of each scenario carry that mapping with them
+    path.write_text(json.dumps({"sizes": sizes, "scenarios": [w.name for w in scen], "times_ms": times, "status": status,
+                                "features": feats, "mapping": "best", "mappings": [["local", 2, 4]] * len(scen), "reps": 3,
+                                "sweep_seconds": 1.0}))
+    monkeypatch.setattr(sys, "argv", ["autotune_study", "--synthetic", "0", "--mapping", "best", "--from-json", str(path)])
+    autotune_study.main()
+    report = capsys.readouterr().out
+    assert "fastest mapping: local for %d scenarios" % len(scen) in report
+    assert sum("| local 2x4 |" in line for line in report.splitlines()) == len(scen)
