@@ -150,13 +150,13 @@ const std::vector<Variant> &registry() {
     return reg;
 }
 
-// The variant that serves a scenario: a compile-time border region if one matches, else
-// the run-time one.
 // whether a variant compiled for any region within a largest one covers the scenario's region
 bool within(const Variant &v, const stencil *s) {
     return v.hn == -2 && s->hn <= v.mn && s->hs <= v.ms && s->he <= v.me && s->hw <= v.mw;
 }
 
+// The variant that serves a scenario: a compile-time border region if one matches, else a kernel
+// compiled for a largest region that holds it, else the run-time one.
 const Variant *find_variant(const stencil *s) {
     const Variant *dyn = nullptr, *masked = nullptr;
     for (const Variant &v : registry()) {
