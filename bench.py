@@ -219,11 +219,20 @@ LARGE_HEAT_CONFIGS = [(m, cr, 4, 0, wg, remap, nt)
                       for remap in (1, 0) for nt in (0, 1)]
 
 
+def marching_heights(w, slots=(2, 3, 4, 5, 6)):
+    """Segment heights at which the marching kernel's wavefronts (strips x segments) just fill so many slots per SIMD."""
+    from paper_1511_02490_amd import libstencil as ls
+    st = ls.Stencil.from_workload(w)
+    st.set_mapping("stream", 64, 4)
+    heights = sorted({st.stream_segment_rows(k) for k in slots}, reverse=True)
+    st.close()
+    return heights
+
+
 def strong_configs(w):
     if w.name.startswith("W"):
         return ([("local", cr, 4, 0, wg, -1, nt) for cr in (2, 4) for wg in ((8, 32), (4, 64), (8, 16)) for nt in (0, 1)] +
-                # marched: 33 strips x segments that fill 2 .. 5 wavefront slots per SIMD
-                [("stream", h, 4, 0, wg, -1, 1) for h in (133, 105, 89, 67, 53) for wg in ((1, 64), (4, 64))])
+                [("stream", h, 4, 0, wg, -1, 1) for h in marching_heights(w) for wg in ((1, 64), (4, 64))])
     if w.name.startswith(("D5", "I5")):
         cc = 2 if w.dtype == "f64" else 4
         return ([("local", cr, cc, 0, wg, -1, nt) for cr in (2, 4) for wg in ((8, 32), (4, 64), (16, 16)) for nt in (0, 1)] +
@@ -232,8 +241,7 @@ def strong_configs(w):
     if w.name.startswith("G"):
         return ([("local", cr, 4, 0, wg, remap, 1) for cr in (2, 4) for wg in ((8, 32), (4, 64), (8, 64)) for remap in (1, 0)] +
                 [("direct", cr, 4, 0, wg, remap, 1) for cr in (2, 4) for wg in ((4, 64), (1, 512)) for remap in (1, 0)] +
-                # segment heights at which the wavefronts (34 strips x segments) just fill 2 .. 6 slots per SIMD
-                [("stream", h, 4, 0, wg, -1, 1) for h in (137, 92, 69, 55, 46, 32) for wg in ((1, 64), (4, 64))])
+                [("stream", h, 4, 0, wg, -1, 1) for h in marching_heights(w, (2, 3, 4, 5, 6, 8)) for wg in ((1, 64), (4, 64))])
     return LARGE_HEAT_CONFIGS if w.name.startswith("H") else STRONG_CONFIGS[w.kernel]
 
 

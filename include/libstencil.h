@@ -188,6 +188,17 @@ int stencil_set_mapping(stencil_t *st, int staging, int cells_rows, int cells_co
 int stencil_output_dtype(const stencil_t *st);
 int stencil_get_mapping(const stencil_t *st, int *staging, int *cells_rows, int *cells_cols);
 
+/* Segment heights worth trying under STENCIL_STAGING_STREAM.  There a wavefront is the unit of work
+ * (one strip of columns x cells_rows rows), a SIMD holds a few of them at a time, and a launch is
+ * fastest when its wavefronts fill a whole number of such slots on every SIMD: one wavefront more
+ * and a last, nearly empty round is added.  For a scenario already on the mapping this returns in
+ * *cells_rows the smallest height at which strips x segments <= 4 x compute units x
+ * wavefronts_per_simd (the compute units: the device's, 256 until a GPU has been used); taller
+ * segments repeat fewer run-in rows, shorter ones hide more latency - 2 to 6 per SIMD are the
+ * values to sweep (stencil_sweep_configs).  STENCIL_E_INVALID on another mapping,
+ * STENCIL_E_REFUSED if the height would exceed the kernels' 4096. */
+int stencil_stream_segment_rows(const stencil_t *st, int wavefronts_per_simd, int *cells_rows);
+
 /* Launch options.  STENCIL_OPT_XCD_REMAP (default 1): workgroups are numbered so that each of
  * the eight XCDs (each with its own L2) works on one contiguous band of tiles.
  * STENCIL_OPT_TEMPORAL_DEPTH (default 2): applications fused into one launch, 1..

@@ -569,6 +569,24 @@ int stencil_get_mapping(const stencil_t *s, int *staging, int *cells_rows, int *
     return STENCIL_OK;
 }
 
+int stencil_stream_segment_rows(const stencil_t *s, int wavefronts_per_simd, int *cells_rows) {
+    if (!s || !cells_rows) return fail(STENCIL_E_INVALID, "NULL argument");
+    if (wavefronts_per_simd < 1) return fail(STENCIL_E_INVALID, "wavefronts per SIMD must be >= 1");
+    const Variant *v = find_variant(s);
+    if (s->staging != STENCIL_STAGING_STREAM || !v)
+        return fail(STENCIL_E_INVALID, "the scenario is not on the register-streaming mapping");
+    const int64_t strip_cols = tile_geom(s, *v, 1, 64).tw;
+    const int64_t strips = (s->cols + strip_cols - 1) / strip_cols;
+    const int64_t slots = (int64_t)g_limits.compute_units * 4 * wavefronts_per_simd;
+    // as many segments per strip as the slots allow, at least one; then the shortest height that needs no more
+    const int64_t segments = std::max<int64_t>(1, std::min<int64_t>(slots / strips, s->rows));
+    const int64_t h = (s->rows + segments - 1) / segments;
+    if (h > kMaxSegmentRows)
+        return fail(STENCIL_E_REFUSED, "segments of %lld rows are beyond the kernels' %d", (long long)h, kMaxSegmentRows);
+    *cells_rows = (int)h;
+    return STENCIL_OK;
+}
+
 int stencil_set_option(stencil_t *s, int option, int value) {
     if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
     switch (option) {

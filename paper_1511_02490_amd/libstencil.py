@@ -62,6 +62,7 @@ def _load() -> ctypes.CDLL:
         "stencil_set_border_value": (c_int, [vp, c_dbl]),
         "stencil_set_mapping": (c_int, [vp, c_int, c_int, c_int]),
         "stencil_get_mapping": (c_int, [vp, ip, ip, ip]),
+        "stencil_stream_segment_rows": (c_int, [vp, c_int, ip]),
         "stencil_output_dtype": (c_int, [vp]),
         "stencil_set_option": (c_int, [vp, c_int, c_int]),
         "stencil_max_wg_size": (c_int, [vp]),
@@ -102,7 +103,7 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
-           "stencil_set_mapping", "stencil_get_mapping", "stencil_output_dtype", "stencil_set_option",
+           "stencil_set_mapping", "stencil_get_mapping", "stencil_stream_segment_rows", "stencil_output_dtype", "stencil_set_option",
            "stencil_max_wg_size", "stencil_tile_bytes", "stencil_is_legal", "stencil_enumerate_wg", "stencil_run",
            "stencil_run_static",
            "stencil_sweep_wg", "stencil_sweep_configs", "stencil_device_copy", "stencil_time_copy",
@@ -279,6 +280,12 @@ class Stencil:
         a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
         _check(_lib.stencil_get_mapping(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
         return a.value, b.value, c.value
+
+    def stream_segment_rows(self, wavefronts_per_simd: int) -> int:
+        """Segment height at which the streaming mapping's wavefronts just fill that many slots per SIMD."""
+        h = ctypes.c_int()
+        _check(_lib.stencil_stream_segment_rows(self._h, int(wavefronts_per_simd), ctypes.byref(h)))
+        return h.value
 
     def get_blocking(self) -> Tuple[int, int]:
         return self.get_mapping()[1:]

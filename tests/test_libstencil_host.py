@@ -108,6 +108,34 @@ def test_marching_kernel_serves_run_time_regions_within_its_largest():
         st.set_mapping("stream", 16, 4)
 
 
+def test_segment_heights_that_fill_whole_wavefront_slots():
+    """8192^2, region N1 S5 E3 W0: 63 vectors of 4 cells per strip -> 33 strips; 1024 SIMDs x 3 slots hold 93
+    segments per strip, i.e. segments of 89 rows (the height the sweeps find fastest for the sin/cos stencil)."""
+    st = ls.Stencil.from_workload(wl.config(4))
+    with pytest.raises(ls.StencilError):
+        st.stream_segment_rows(3)                         # not on the streaming mapping
+    st.set_mapping("stream", 64, 4)
+    assert [st.stream_segment_rows(k) for k in (1, 2, 3, 4, 6)] == [265, 133, 89, 67, 45]
+    with pytest.raises(ls.StencilError):
+        st.stream_segment_rows(0)
+    # a 7x7 sum (3/3/3/3: one rim lane each side, 62 vectors): 34 strips; six slots -> 46 rows
+    g7 = ls.Stencil(8192, 8192, "f32", (3, 3, 3, 3), "clamp")
+    g7.set_kernel("weighted_sum", np.ones((7, 7), np.float32))
+    g7.set_mapping("stream", 64, 4)
+    assert g7.stream_segment_rows(6) == 46 and g7.stream_segment_rows(2) == 137
+    # fewer rows than slots: one row per segment; one narrow tall strip: the kernels' limit
+    small = ls.Stencil(8, 100, "f32", (3, 3, 3, 3), "clamp")
+    small.set_kernel("weighted_sum", np.ones((7, 7), np.float32))
+    small.set_mapping("stream", 4, 4)
+    assert small.stream_segment_rows(2) == 1
+    tall = ls.Stencil(1 << 24, 16, "f32", (3, 3, 3, 3), "clamp")
+    tall.set_kernel("weighted_sum", np.ones((7, 7), np.float32))
+    tall.set_mapping("stream", 4, 4)
+    with pytest.raises(ls.StencilError) as e:
+        tall.stream_segment_rows(1)
+    assert e.value.code == ls.E_REFUSED
+
+
 def test_legality_eq1():
     st = ls.Stencil.from_workload(wl.config(1))          # 5x5 gaussian, halo 2
     assert st.max_wg_size() == 1024
