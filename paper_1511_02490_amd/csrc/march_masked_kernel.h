@@ -51,6 +51,7 @@ __device__ __forceinline__ void march_masked_body(const TileArgs<Op, Halo> &a, c
     static_assert(EM <= kPadLanes * CC && WM <= kPadLanes * CC, "a lane's window stays within the row and its pads");
     constexpr int RM = Halo::N + Halo::S + 1;     // links of the chain
     static_assert(WC >= 1 && WC <= EM + WM + 1, "columns of a region within the largest one");
+    static_assert(RM < 32, "one bit per link");
     constexpr int kTable = (RM * WC + 63) / 64 * 64;
     constexpr int kWindow = WC + CC - 1;
     constexpr int P = 4;                          // input rows requested ahead
@@ -178,8 +179,15 @@ __device__ __forceinline__ void march_masked_body(const TileArgs<Op, Halo> &a, c
             L win[kWindow];
 #pragma unroll
             for (int i = 0; i < kWindow; ++i) win[i] = window[i % CC][i / CC];
-            // this input row is region row k (0 = northernmost) of output row t - k of the segment; a row's
-            // weights are requested kAhead rows ahead, whether the region has those rows or not
+            // This input row is region row k (0 = northernmost) of output row t - k of the segment.  The links
+            // that have something to fold at this step, one bit each: k < r and 0 <= t - k < H.  (Made anew at
+            // every step from the region's numbers: compared once for all steps, the outcomes would be kept as
+            // lane masks in more scalar registers than there are.)
+            int rk = r;
+            asm volatile("" : "+s"(rk));
+            const int k_end = t + 1 < rk ? t + 1 : rk, k_begin = t - H + 1 > 0 ? t - H + 1 : 0;
+            const uint32_t links = k_begin < k_end ? ((~0u >> (32 - (k_end - k_begin))) << k_begin) : 0u;
+            // a row's weights are requested kAhead rows ahead, whether the region has those rows or not
             constexpr int kAhead = 2;
             float wk[kAhead + 1][WC];
 #pragma unroll
@@ -192,12 +200,8 @@ __device__ __forceinline__ void march_masked_body(const TileArgs<Op, Halo> &a, c
 #pragma unroll
                     for (int i = 0; i < WC; ++i) wk[(k - kAhead) % (kAhead + 1)][i] = table[(k - kAhead) * WC + i];
                 }
-                // (the region's number of rows is taken anew for every test: compared once for all steps, the
-                // outcomes would be kept as lane masks in more scalar registers than there are)
-                int rk = r;
-                asm volatile("" : "+s"(rk));
-                if (k >= rk) continue;                              // the region has no such row
-                if ((unsigned)(t - k) >= (unsigned)H) continue;     // another wavefront's output row
+                // the region has no such row, or the output row is another wavefront's
+                if (!((links >> k) & 1u)) continue;
                 typename Op::State(&sum)[CC] = link[k + 1];         // the row's taps carry the sum to the next link
 #pragma unroll
                 for (int cc = 0; cc < CC; ++cc) {
