@@ -595,7 +595,13 @@ def main():
         best1 = None   # the same over the mappings that make one application per launch
         best_wg_tuned = None   # ... and over those in which the workgroup size is the tunable (local, direct)
         candidates = []        # every (ms per sample, mapping, wg) that was timed
-        for mapping in MAPPINGS[w.kernel]:
+        mappings = list(MAPPINGS[w.kernel])
+        if w.kernel == "weighted_sum" and w.dtype == "f32" and w.rows >= 4096:
+            try:        # the marching kernel at the heights that fill whole wavefront slots on a matrix of this size
+                mappings += [("stream", h, 4) for h in marching_heights(w, (2, 3, 4, 6)) if ("stream", h, 4) not in mappings]
+            except ls.StencilError:
+                pass    # a region the marching kernels do not have
+        for mapping in mappings:
             try:
                 apply_mapping(st, mapping)
             except ls.StencilError:
