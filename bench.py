@@ -362,6 +362,7 @@ class Bench:
             pair_bytes = self.tin.numel() * self.tin.element_size() + self.tout.numel() * self.tout.element_size()
             n = int(min(ROTATION_MAX_PAIRS, max(3, 1 + math.ceil(ROTATION_BYTES / pair_bytes))))
             self.pairs += [(self.tin.clone(), self.torch.empty_like(self.tout)) for _ in range(n - 1)]
+            self.st.set_sweep_rotation(self.pairs)       # the library's sweeps go round the same pairs
         return self.pairs
 
     def run_pass(self, k, size):
@@ -526,6 +527,7 @@ def sub_record(ls, torch, wl, name, args):
     b = Bench(ls, torch, w, args)
     reps = max(5, args.reps // 3)
     configs = strong_configs(w)
+    b.rotation()
     mean, status, best = b.st.sweep_configs(b.tin, b.tout, configs, iters=b.burst, reps=reps)
     ok = [k for k in range(len(configs)) if status[k] == ls.OK]
     if not ok:
@@ -542,8 +544,7 @@ def sub_record(ls, torch, wl, name, args):
         return nt
 
     if len(b.rotation()) > 1:
-        # the sweep timed the configurations on one matrix pair (and found the refused ones); the ranking that
-        # counts is on the rotation, where what wins is not always what wins with part of the input in a cache
+        # the sweep's samples are short; the ranking that counts is over longer runs of back-to-back passes
         for k in ok:
             configure(configs[k])
             b.precondition(configs[k][4], 0.01)
@@ -631,6 +632,7 @@ def main():
     if args.quick:
         sizes = sizes[::5]
     b = Bench(ls, torch, w, args)
+    b.rotation()            # single-application workloads: every sweep below goes round fresh matrix pairs
     st, tin, tout, burst, cells = b.st, b.tin, b.tout, b.burst, b.cells
     cells_per_sample = cells * burst
 

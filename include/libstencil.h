@@ -286,6 +286,22 @@ int stencil_run(stencil_t *st, const void *in, void *out, int iters,
 int stencil_run_static(stencil_t *st, const void *in, void *out, int iters,
                        int wg_rows, int wg_cols, void *stream);
 
+/* Matrix pairs for the sweeps to go round.  A sweep's sample is otherwise a chain of `iters`
+ * applications on the caller's one pair (in -> out), and on a device with a large last-level cache
+ * every sample then finds in it what the sample before read or wrote: on MI355X (256 MB, on the
+ * memory side) a single application to a 256 MiB matrix runs up to 25 % faster on a pair it has just
+ * been applied to than on matrices fresh from HBM, and the size that wins is not always the same.
+ * With n >= 1 pairs set, a sample of stencil_sweep_wg / stencil_sweep_configs is `iters` independent
+ * single applications, ins[k] -> outs[k], on the pairs in turn (the sweeps' own in / out arguments
+ * are still validated, and still receive nothing they would not have received).  Device pointers,
+ * each a whole matrix of the scenario's input / output type, kept by reference: they must stay
+ * valid until the rotation is replaced or cleared (n = 0) or the handle destroyed; no output may
+ * overlap any other matrix of the rotation (inputs may be shared).  Enough pairs that their total
+ * size is a few times the cache make every application a cold one.  STENCIL_E_INVALID on a bad
+ * pointer, an overlap, or n outside 0..STENCIL_MAX_ROTATION. */
+#define STENCIL_MAX_ROTATION 64
+int stencil_set_sweep_rotation(stencil_t *st, const void *const *ins, void *const *outs, int n);
+
 /* Section 5's measurement: for each of the n sizes, 3 untimed runs and then `reps` timed
  * samples (reps <= 0 means 30), each sample one stencil_run(iters) bracketed by events on
  * `stream`.  Outputs (host arrays of n, each may be NULL): mean / min / median / sample

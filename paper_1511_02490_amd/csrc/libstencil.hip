@@ -722,6 +722,29 @@ int stencil_run_static(stencil_t *s, const void *in, void *out, int iters, int w
     return rc;
 }
 
+int stencil_set_sweep_rotation(stencil_t *s, const void *const *ins, void *const *outs, int n) {
+    if (!s) return fail(STENCIL_E_INVALID, "handle is NULL");
+    if (n < 0 || n > STENCIL_MAX_ROTATION || (n > 0 && (!ins || !outs)))
+        return fail(STENCIL_E_INVALID, "a rotation has 0..%d matrix pairs", STENCIL_MAX_ROTATION);
+    std::vector<std::pair<const void *, void *>> pairs;
+    for (int k = 0; k < n; ++k) {
+        int rc = validate_buffers(s, ins[k], outs[k]);
+        if (rc != STENCIL_OK) return rc;
+        // an output that another pair reads or writes would make the applications depend on each other
+        const uintptr_t o = (uintptr_t)outs[k], m = s->out_bytes();
+        for (int j = 0; j < n; ++j) {
+            if (j == k) continue;
+            const uintptr_t a = (uintptr_t)ins[j], b = (uintptr_t)outs[j];
+            if ((o < a + s->bytes() && a < o + m) || (o < b + m && b < o + m))
+                return fail(STENCIL_E_INVALID, "output %d overlaps a matrix of pair %d", k, j);
+        }
+        pairs.emplace_back(ins[k], outs[k]);
+    }
+    s->rotation.swap(pairs);
+    s->rotation_at = 0;
+    return STENCIL_OK;
+}
+
 int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const int *wg_rows_list,
                      const int *wg_cols_list, int n, int fixed_rows, int fixed_cols, int reps,
                      double *mean_ms, double *min_ms, double *median_ms, double *stddev_ms, int *status,
@@ -735,7 +758,8 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
     if (!v) return fail(STENCIL_E_INVALID, "no kernel selected for this scenario");
     if (reps <= 0) reps = 30;
     hipStream_t stream = (hipStream_t)stream_;
-    rc = ensure_device_state(s, v, launches_of(s, v, iters) > 1, stream);
+    // (single applications on a rotation of pairs need no ping-pong matrix)
+    rc = ensure_device_state(s, v, s->rotation.empty() && launches_of(s, v, iters) > 1, stream);
     if (rc != STENCIL_OK) return rc;
     // event pairs for the samples, made when the first size is actually timed
     auto need_events = [&]() -> int {
@@ -749,6 +773,17 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
     };
     const double nan = std::numeric_limits<double>::quiet_NaN();
     std::vector<double> samples((size_t)reps);
+    // The applications of one sample: a chain in -> out of `iters` applications, or, with a rotation of
+    // matrix pairs set, `iters` independent single applications, each on the pair whose turn it is.
+    auto run_sample = [&](int wr, int wc) -> int {
+        if (s->rotation.empty()) return run_checked(s, v, in, out, s->scratch, iters, wr, wc, stream);
+        for (int i = 0; i < iters; ++i) {
+            const auto &pair = s->rotation[s->rotation_at++ % s->rotation.size()];
+            int r = run_checked(s, v, pair.first, pair.second, s->scratch, 1, wr, wc, stream);
+            if (r != STENCIL_OK) return r;
+        }
+        return STENCIL_OK;
+    };
 
     std::vector<double> means((size_t)n + 1, nan);
     std::vector<int> stat((size_t)n + 1, STENCIL_E_REFUSED);
@@ -774,7 +809,7 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
             for (int i = from; i < to; ++i) {
                 hipError_t e = hipEventRecord(s->events[2 * i], stream);
                 if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
-                int r = run_checked(s, v, in, out, s->scratch, iters, wr, wc, stream);
+                int r = run_sample(wr, wc);
                 if (r != STENCIL_OK) return r;
                 e = hipEventRecord(s->events[2 * i + 1], stream);
                 if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
@@ -793,7 +828,7 @@ int stencil_sweep_wg(stencil_t *s, const void *in, void *out, int iters, const i
         };
         const int taken = probe_only ? std::min(2, reps) : reps;
         for (int w = 0; w < (probe_only ? 1 : kWarmup); ++w) {
-            int r = run_checked(s, v, in, out, s->scratch, iters, wr, wc, stream);
+            int r = run_sample(wr, wc);
             if (r == STENCIL_E_REFUSED) return refused();
             if (r != STENCIL_OK) return r;
         }

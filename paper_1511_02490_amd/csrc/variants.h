@@ -69,6 +69,9 @@ struct stencil {
     const float *table_in_use = nullptr;       // what the launchers hand to the kernels
     bool weights_uploaded = false;
     std::vector<hipEvent_t> events;
+    // matrix pairs the sweeps' applications go round (stencil_set_sweep_rotation); empty: the caller's pair
+    std::vector<std::pair<const void *, void *>> rotation;
+    size_t rotation_at = 0;
     size_t elem() const { return dtype == STENCIL_U8 ? 1 : (dtype == STENCIL_F64 ? 8 : 4); }
     size_t bytes() const { return (size_t)rows * (size_t)cols * elem(); }
     // the output matrix: the input's element type, except for the threshold stencil (floats in,

@@ -63,6 +63,7 @@ def _load() -> ctypes.CDLL:
         "stencil_set_mapping": (c_int, [vp, c_int, c_int, c_int]),
         "stencil_get_mapping": (c_int, [vp, ip, ip, ip]),
         "stencil_stream_segment_rows": (c_int, [vp, c_int, ip]),
+        "stencil_set_sweep_rotation": (c_int, [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), c_int]),
         "stencil_output_dtype": (c_int, [vp]),
         "stencil_set_option": (c_int, [vp, c_int, c_int]),
         "stencil_max_wg_size": (c_int, [vp]),
@@ -103,7 +104,7 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = ("stencil_create", "stencil_destroy", "stencil_set_kernel", "stencil_set_border_value",
-           "stencil_set_mapping", "stencil_get_mapping", "stencil_stream_segment_rows", "stencil_output_dtype", "stencil_set_option",
+           "stencil_set_mapping", "stencil_get_mapping", "stencil_stream_segment_rows", "stencil_set_sweep_rotation", "stencil_output_dtype", "stencil_set_option",
            "stencil_max_wg_size", "stencil_tile_bytes", "stencil_is_legal", "stencil_enumerate_wg", "stencil_run",
            "stencil_run_static",
            "stencil_sweep_wg", "stencil_sweep_configs", "stencil_device_copy", "stencil_time_copy",
@@ -377,6 +378,18 @@ class Stencil:
                                           int(iters), ctypes.cast(arr, ctypes.c_void_p), n, int(reps), mean, status,
                                           ctypes.byref(best), self._stream_ptr(stream)))
         return list(mean)[:n], list(status)[:n], best.value
+
+    def set_sweep_rotation(self, pairs):
+        """Matrix pairs [(in, out), ...] the sweeps' applications go round instead of chaining on one pair
+        (an empty list clears).  The handle keeps the tensors alive."""
+        pairs = list(pairs)
+        for tin, tout in pairs:
+            self._check_tensors(tin, tout)
+        n = len(pairs)
+        ins = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t, _ in pairs])
+        outs = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for _, t in pairs])
+        _check(_lib.stencil_set_sweep_rotation(self._h, ins, outs, n))
+        self._rotation = pairs
 
     def attach_predictor(self, predictor: Optional["Predictor"], handler: str = "nearest"):
         """The classifier run(..., wg=(0, 0)) consults when no sweep has been made (None detaches).

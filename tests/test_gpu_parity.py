@@ -444,6 +444,37 @@ def test_register_streaming_temporal_kernel_bit_exact(ls, border):
         ls.Stencil.from_workload(clamp).set_mapping("stream", 32, 4)
 
 
+def test_sweeps_over_a_rotation_of_matrix_pairs(ls):
+    """stencil_set_sweep_rotation: a sample is `iters` independent applications on the pairs in turn; every
+    pair's output is the single application of its own input, the sweep's own out argument is not written,
+    refusals are recorded as ever, and clearing the rotation brings the chain on the caller's pair back."""
+    w = wl.config(1, rows=300, cols=520)
+    st = ls.Stencil.from_workload(w)
+    st.set_mapping("local", 2, 4)
+    grids = [w.grid() * np.float32(k + 1) for k in range(3)]
+    pairs = [(torch.from_numpy(g).cuda(), torch.full(g.shape, 7.0, dtype=torch.float32, device="cuda")) for g in grids]
+    tin = torch.from_numpy(w.grid()).cuda()
+    tout = torch.full(w.grid().shape, 7.0, dtype=torch.float32, device="cuda")
+    st.set_sweep_rotation(pairs)
+    sizes = [(4, 16), (8, 8), (64, 32), (2, 64)]
+    res = st.sweep(tin, tout, sizes, iters=4, fixed=(4, 4), reps=5)
+    assert [s_ == ls.OK for s_ in res.status] == [True, True, False, True] and res.best is not None
+    torch.cuda.synchronize()
+    assert float(tout.min()) == 7.0 and float(tout.max()) == 7.0
+    for g, (a, b) in zip(grids, pairs):
+        ref = oracle.apply(g, w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 1)
+        assert rel_err(b.cpu().numpy(), ref) <= 1e-5
+        np.testing.assert_array_equal(a.cpu().numpy(), g)
+    mean, status, best = st.sweep_configs(tin, tout, [("local", 2, 4, 0, (4, 16)), ("direct", 2, 4, 0, (4, 16))], iters=3, reps=5)
+    assert status == [ls.OK, ls.OK] and float(tout.min()) == 7.0
+    st.set_sweep_rotation([])
+    st.sweep(tin, tout, [(4, 16)], iters=4, reps=3)
+    torch.cuda.synchronize()
+    ref = oracle.apply(w.grid(), w.kernel, w.halo, w.border, w.pad, w.weights, w.scalars, 4)
+    assert rel_err(tout.cpu().numpy(), ref) <= 1e-4
+    st.close()
+
+
 @pytest.mark.parametrize("border", ["clamp", "wrap", "constant"])
 def test_register_marching_single_application_kernels(ls, border):
     """One application marched down the matrix in registers (sin/cos stencil N1 S5 E3 W0 and the

@@ -108,6 +108,46 @@ def test_marching_kernel_serves_run_time_regions_within_its_largest():
         st.set_mapping("stream", 16, 4)
 
 
+def test_sweep_rotation_is_validated_and_used_by_the_sweeps():
+    """Matrix pairs for the sweeps to go round: pointers are checked for overlap (an output may not touch any
+    other matrix of the rotation), the number of pairs is bounded, an empty list clears; with every launch made
+    to fail, a sweep over a rotation still visits every size (nothing is launched, so no GPU is needed)."""
+    import ctypes
+    w = wl.config(1, rows=256, cols=256)
+    st = ls.Stencil.from_workload(w)
+    nbytes = 256 * 256 * 4
+    base = 1 << 30
+    vp = ctypes.c_void_p
+
+    def rotation(ins, outs):
+        n = len(ins)
+        return ls._lib.stencil_set_sweep_rotation(st._h, (vp * max(n, 1))(*ins), (vp * max(n, 1))(*outs), n)
+
+    m = [base + k * nbytes for k in range(8)]
+    assert rotation([m[0], m[2], m[4]], [m[1], m[3], m[5]]) == ls.OK
+    assert rotation([m[0], m[0]], [m[1], m[2]]) == ls.OK                    # a shared input is fine
+    assert rotation([m[0], m[1]], [m[1], m[2]]) == ls.E_INVALID             # pair 0 writes what pair 1 reads
+    assert "overlaps" in ls.last_error()
+    assert rotation([m[0], m[2]], [m[1], m[1] + 64]) == ls.E_INVALID        # two outputs overlap
+    assert rotation([m[0]], [m[0] + 128]) == ls.E_INVALID                   # in and out of one pair overlap
+    assert rotation([m[0]], [0]) == ls.E_INVALID
+    assert rotation([m[0]] * 65, [m[1]] * 65) == ls.E_INVALID               # too many
+    assert ls._lib.stencil_set_sweep_rotation(st._h, None, None, 2) == ls.E_INVALID
+    assert rotation([m[0], m[2], m[4]], [m[1], m[3], m[5]]) == ls.OK
+    st.set_option(ls.OPT_FAIL_LAUNCH, -1)
+    sizes = [(4, 4), (8, 8), (16, 16)]
+    n = len(sizes)
+    mean = (ctypes.c_double * n)(*([7.0] * n))
+    status = (ctypes.c_int * n)(*([9] * n))
+    best = ctypes.c_int(5)
+    a, b = _fake_device_pointers()
+    rc = ls._lib.stencil_sweep_wg(st._h, a, b, 4, ls._ints([r for r, _ in sizes]), ls._ints([c for _, c in sizes]), n,
+                                  0, 0, 5, mean, None, None, None, status, ctypes.byref(best), None, None)
+    assert rc == ls.OK and list(status) == [ls.E_REFUSED] * n and best.value == -1
+    assert rotation([], []) == ls.OK
+    st.close()
+
+
 def test_segment_heights_that_fill_whole_wavefront_slots():
     """8192^2, region N1 S5 E3 W0: 63 vectors of 4 cells per strip -> 33 strips; 1024 SIMDs x 3 slots hold 93
     segments per strip, i.e. segments of 89 rows (the height the sweeps find fastest for the sin/cos stencil)."""
