@@ -372,8 +372,8 @@ class Bench:
 
     def timed_kernel(self, size, reps, one_pair=False):
         """Mean milliseconds per pass of the handle's current kernel: `reps` x `burst` passes back to back round
-        the rotation (or on its first pair only) between two events on the launch stream.  Back to back, because a
-        pass on its own between two waits runs 15-20 % slower than in a stream of passes (clocks)."""
+        the rotation (or on its first pair only) between two events on the launch stream.  Back to back: from idle
+        the device needs some 30 ms of continuous work before a kernel's time settles."""
         torch = self.torch
         n_pairs = 1 if one_pair else len(self.rotation())
         n = reps * self.burst
@@ -687,11 +687,11 @@ def main():
                 best_wg_tuned = (res.best_ms, mapping, res.best)
         sweep_seconds = time.perf_counter() - t_sweep0
         assert best is not None, "no legal workgroup size"
-        # Confirmation pass.  A size's samples last a few milliseconds, too short for the clocks to
-        # settle (the sweep's times are 15-20 % above the steady state, and not by the same factor
-        # for every kernel), and near the top the landscape is flat: the best size of every mapping
-        # that came within 15 % of the best, and the three best sizes overall, are timed again, each
-        # after PRECONDITION_SECONDS of its own launches, and the fastest is taken.
+        # Confirmation pass.  A size's samples last a few milliseconds, the sweeps use plain output
+        # stores only, and near the top the landscape is flat: the best size of every mapping that
+        # came within 15 % of the best, and the three best sizes overall, are timed again with both
+        # kinds of store, each over a longer run of back-to-back passes after PRECONDITION_SECONDS
+        # of its own launches, and the fastest is taken.
         per_mapping = {}
         for c in sorted(candidates, key=lambda c: c[0]):
             per_mapping.setdefault(mapping_name(c[1]), c)
