@@ -87,6 +87,7 @@ struct OpWeightedSumF64 {
     using V = double;
     static constexpr int kPlanes = 1;
     static constexpr bool kWeights = true;
+    using Wt = double;
     struct State { double acc; };
     __device__ static __forceinline__ void stage(T v, L (&out)[1]) { out[0] = v; }
     __device__ static __forceinline__ V combine(const L (&p)[1]) { return p[0]; }
@@ -96,8 +97,8 @@ struct OpWeightedSumF64 {
         for (int k = 0; k < CC; ++k) out[0][k] = v[k];
     }
     __device__ static __forceinline__ void init(State &s) { s.acc = 0.0; }
-    __device__ static __forceinline__ void visit(State &s, int, int, float w, V v) {
-        s.acc = __fma_rn((double)w, v, s.acc);
+    __device__ static __forceinline__ void visit(State &s, int, int, double w, V v) {
+        s.acc = __fma_rn(w, v, s.acc);      // (w is a float's value: the conversion is exact wherever it is made)
     }
     __device__ static __forceinline__ T finish(const State &s, float) { return s.acc; }
 };
@@ -151,6 +152,14 @@ struct OpWeightedSumU8 {
     }
     __device__ static __forceinline__ O finish(const State &s, float) { return s.acc; }
 };
+
+// The type in which a compile-time weight table travels in the kernel arguments: Op::Wt where the
+// function names one (doubles for the fp64 sum: a scalar register pair is an operand of the fp64
+// fma, a float would first have to be converted into a pair of vector registers), else float.
+template <class Op, class = void>
+struct weight_type_of { using type = float; };
+template <class Op>
+struct weight_type_of<Op, decltype(void(sizeof(typename Op::Wt)))> { using type = typename Op::Wt; };
 
 // The output element type of a customising function: Op::O where it names one, else Op::T.
 template <class Op, class = void>

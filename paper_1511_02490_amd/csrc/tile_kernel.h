@@ -18,8 +18,9 @@ struct WeightStore;
 template <class Op, class Halo>
 struct WeightStore<Op, Halo, true> {
     static constexpr int kCount = Op::kWeights ? (Halo::N + Halo::S + 1) * (Halo::E + Halo::W + 1) : 1;
-    float v[kCount];
-    __device__ __forceinline__ float operator[](int k) const { return Op::kWeights ? v[k] : 0.0f; }
+    using W = typename weight_type_of<Op>::type;
+    W v[kCount];
+    __device__ __forceinline__ W operator[](int k) const { return Op::kWeights ? v[k] : W(0); }
 };
 // Run-time region: table in device memory (uniform index -> scalar loads).
 template <class Op, class Halo>
