@@ -132,7 +132,8 @@ def main():
     cfg = bench["config"]
     cells = cfg["rows"] * cfg["cols"]
     depth = roof["applications_per_launch"]
-    copy_kib = cells * (4 if bench["dtype"] == "f32" else 1) / 1024.0
+    # the plain copy kernel copies the input matrix: one element of the workload's type per cell
+    copy_kib = cells * {"f32": 4, "i32": 4, "f64": 8, "u8": 1}[bench["dtype"]] / 1024.0
     f_scale = copy_kib / fetch[pick(fetch, "copy_kernel")][0]
     w_scale = copy_kib / write[pick(write, "copy_kernel")][0]
     f_kib = fetch[pick(fetch, a.kernel)][0] * f_scale
