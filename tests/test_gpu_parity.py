@@ -1111,6 +1111,44 @@ def test_c5_full_size_every_cell(ls):
         np.testing.assert_array_equal(got, gpu_apply(ls, w, g, wg, blocking=("stream", h, 4)))
 
 
+def test_weighted_sums_on_8192_squared_every_cell(ls):
+    """The weighted sums bench.py times on 8192^2 - the 28-tap sum with a border region given at run time, the
+    7x7 Gaussian - in its launch configurations: every cell against the oracle's whole-matrix result, and the
+    marching kernels bit for bit against the local-memory tile."""
+    import bench
+    for name, marches in (("W8192", [(133, (4, 64)), (89, (1, 64))]), ("G7", [(69, (4, 64)), (46, (4, 64))])):
+        w = bench.named_workload(wl, name)
+        g = w.grid()
+        ref = oracle.apply_workload(w, g)
+        got = gpu_apply(ls, w, g, (8, 32), blocking=(4, 4))
+        err = rel_err(got, ref)
+        assert err <= REL_1, (name, err)
+        for h, wg in marches:
+            np.testing.assert_array_equal(got, gpu_apply(ls, w, g, wg, blocking=("stream", h, 4)))
+
+
+def test_bench_prints_its_json_line():
+    """bench.py on the small configuration: one JSON line with the contract's fields."""
+    import json
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "C1", "--no-others", "--reps", "5",
+                          "--steps", "5", "--warmup", "1", "--cpu-seconds", "1", "--no-predictor"], cwd=root,
+                         capture_output=True, text=True, timeout=280)
+    assert out.returncode == 0, out.stderr[-2000:]
+    lines = [l for l in out.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    rec = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in rec, key
+    assert rec["n_gpus"] == 1 and rec["steps"] == 5 and rec["value"] > 0 and rec["config"]["workload"].startswith("C1")
+    assert rec["roofline"]["bound"] == "hbm" and 0 < rec["roofline"]["frac"] < 1 and rec["roofline"]["peak"] == 8000.0
+    assert rec["cpu_baseline"]["kind"] == "oracle" and rec["cpu_baseline"]["cores"] >= 1
+    assert rec["config"]["matrix_pairs_in_rotation"] > 1
+
+
 # ---- a matrix whose byte offsets pass 2^32 ------------------------------------------------------
 
 def _window(t, rows, cols, r0, c0, h, w_, margin):

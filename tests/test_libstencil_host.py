@@ -608,3 +608,14 @@ def test_study_evaluates_a_fabricated_landscape(tmp_path, capsys, monkeypatch):
     report = capsys.readouterr().out
     assert "fastest mapping: local for %d scenarios" % len(scen) in report
     assert sum("| local 2x4 |" in line for line in report.splitlines()) == len(scen)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: asked for more it says so and exits before touching a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], cwd=root, capture_output=True,
+                         text=True, timeout=120)
+    assert out.returncode != 0 and "one GPU" in out.stderr and out.stdout.strip() == ""
