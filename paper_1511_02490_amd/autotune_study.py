@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--synthetic", type=int, default=32)
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--mapping", default="local,1,1")
+    ap.add_argument("--fresh-matrices", action="store_true",
+                    help="sweep single-application scenarios over a rotation of matrix pairs (about 512 MiB between two "
+                         "uses of a pair), so that no sample finds its input in the last-level cache")
     ap.add_argument("--json", default="", help="also write the raw sweep tables here")
     ap.add_argument("--sweep-only", action="store_true", help="stop after the sweeps (with --json)")
     ap.add_argument("--from-json", default="", help="evaluate sweeps recorded with --json instead of sweeping")
@@ -86,6 +89,10 @@ def main():
         st = ls.Stencil.from_workload(w)
         tin = torch.from_numpy(w.grid()).cuda()
         tout = torch.empty(tin.shape, dtype=torch.uint8 if w.out_dtype == "u8" else tin.dtype, device="cuda")
+        if a.fresh_matrices and w.iters == 1:
+            pair_bytes = tin.numel() * tin.element_size() + tout.numel() * tout.element_size()
+            n_pairs = int(min(24, max(3, 1 + math.ceil((512 << 20) / pair_bytes))))
+            st.set_sweep_rotation([(tin, tout)] + [(tin.clone(), torch.empty_like(tout)) for _ in range(n_pairs - 1)])
         chosen = mapping
         if pick_best:
             best_ms = float("inf")
@@ -247,6 +254,8 @@ def main():
         print()
         print("* fastest mapping: " + ", ".join("%s for %d scenarios" % (k, v) for k, v in sorted(count.items())))
     print()
+    if a.fresh_matrices:
+        print("* single-application scenarios swept over a rotation of matrix pairs (fresh matrices)")
     print("* distinct oracle sizes: %d of %d scenarios; most common: %s" % (
         distinct, n_s, max(set(oracle), key=oracle.count) and sizes[max(set(oracle), key=oracle.count)]))
     print("* oracle over worst size: mean %.1fx (min %.2fx, max %.1fx)" % (
