@@ -7,15 +7,15 @@
 // an arriving input row is region row k of link k, whose sum then moves on to link k+1 (the links
 // are taken from the last to the first) or, from the region's last row, to the output matrix.
 // The code of a step therefore does not depend on which step it is, and the loop over the steps
-// is unrolled only as far as rows are requested ahead.  Region rows the actual region does not
-// have are skipped by wavefront-uniform tests.  A lane's row neighbours cannot come from
+// is unrolled only as far as rows are requested ahead.  Links the actual region does not have,
+// or whose output row belongs to another wavefront, are skipped by one wavefront-uniform bit test
+// each.  A lane's row neighbours cannot come from
 // cross-lane moves here (their distances are compile-time numbers): the wavefront writes the row
 // to local memory and every lane reads the window that starts at its region's west edge, so the
 // taps of a region row are the window's first E + W + 1 positions: the kernel is compiled once
 // for every such number of columns WC, and only how they divide into east and west is left to the
 // launch.  The weights come from a copy of the table in local memory as well, one copy per
-// wavefront (no barrier anywhere), a region row's weights requested while the row before it is
-// folded.  A cell sees exactly the taps of its region, north to south and west to east: the fold,
+// wavefront (no barrier anywhere), a region row's weights requested two rows ahead of their use.  A cell sees exactly the taps of its region, north to south and west to east: the fold,
 // and the output bits, of every other mapping.  For customising functions that fold tap by tap
 // (the weighted sums).
 #pragma once
